@@ -1,0 +1,191 @@
+/*
+ * CPU oracle for the table-lookup quantized convolution.  TEST INFRASTRUCTURE ONLY:
+ * it is called from tests/, from the smoke check and from the benchmark's cpu_baseline
+ * leg, never from the product path, and it shares no code with the HIP library.
+ *
+ * What it computes is the definition written out, one output element at a time:
+ *
+ *   - The layer is the quantized matrix product of Eq. (3) of the paper (Sec. II) in
+ *     which the product of the two 8-bit codes is replaced by the output of an 8-bit
+ *     multiplier model (Sec. II, the MAC with an 8-bit multiplier and a 32-bit
+ *     accumulator), given as a truth table of 256^2 16-bit entries addressed by the two
+ *     codes stitched into one 16-bit index (Sec. III, matrix multiplication phase).
+ *     Reading taken: index = activation_code * 256 + filter_code.
+ *   - Tensor layouts are those of Sec. III: input N x H x W x C with C fastest, filters
+ *     H x W x C x Count with Count fastest, output laid out like the input.
+ *   - The loop nest (image, output pixel, output channel, kernel tap, input channel) is
+ *     the direct, definition-shaped method that Sec. III describes for the CPU.
+ *   - Dequantization follows the expansion of Eq. (3) into Eq. (4), in its all-integer
+ *     form: with Sp the sum of the activation codes of the patch, Sf the sum of the
+ *     filter codes of the output channel, K the patch length,
+ *         corr = acc - beta2*Sp - beta1*Sf + K*beta1*beta2,   y = alpha1*alpha2*corr.
+ *     (Eq. (4) as printed mixes real-valued and code sums and has a sign that does not
+ *     follow from Eq. (3); the form used here is the exact expansion of Eq. (3) and is
+ *     pinned by a test against a float64 convolution of the dequantized tensors.)
+ *   - Taps outside the image feed the code pad_code (default: the zero point beta1, the
+ *     code of the real value 0, Sec. II) through the table and into Sp.
+ *   - Output size: OH = floor((H + 2*pad_h - KH) / stride_h) + 1, same for OW.
+ *
+ * The accumulator is kept in 64 bits and checked against the int32 range the emulated
+ * accumulator has; y is the double product rounded once to float.
+ */
+#include "ax_oracle.h"
+
+#include <stddef.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static int check_quant(const ax_oracle_quant* q, int* pad_code) {
+  if (!q) return AX_ORACLE_ERR_ARG;
+  if (q->x_zp < 0 || q->x_zp > 255 || q->w_zp < 0 || q->w_zp > 255) return AX_ORACLE_ERR_ARG;
+  if (!(q->x_scale > 0.0f) || !(q->w_scale > 0.0f)) return AX_ORACLE_ERR_ARG;
+  if (q->pad_code < -1 || q->pad_code > 255) return AX_ORACLE_ERR_ARG;
+  *pad_code = (q->pad_code < 0) ? q->x_zp : q->pad_code;
+  return 0;
+}
+
+/* One output element of the convolution.  Returns 0, or AX_ORACLE_ERR_OVERFLOW when the
+ * sum of table entries leaves the int32 range. */
+static int conv_element(const uint8_t* x, int H, int W, int Cin, const uint8_t* w, int KH, int KW,
+                        int Cout, const uint16_t* lut, int stride_h, int stride_w, int pad_h,
+                        int pad_w, const ax_oracle_quant* q, int pad_code, int n, int oy, int ox,
+                        int co, int32_t* acc_out, float* y_out) {
+  int64_t acc = 0; /* sum of table entries                    */
+  int64_t Sp = 0;  /* sum of the activation codes of the patch */
+  int64_t Sf = 0;  /* sum of the filter codes of channel co    */
+  for (int ky = 0; ky < KH; ++ky) {
+    for (int kx = 0; kx < KW; ++kx) {
+      const int iy = oy * stride_h - pad_h + ky;
+      const int ix = ox * stride_w - pad_w + kx;
+      const int inside = (iy >= 0 && iy < H && ix >= 0 && ix < W);
+      for (int ci = 0; ci < Cin; ++ci) {
+        int a = pad_code;
+        if (inside) a = x[(((size_t)n * H + iy) * W + ix) * Cin + ci];
+        const int b = w[(((size_t)ky * KW + kx) * Cin + ci) * Cout + co];
+        acc += lut[a * 256 + b];
+        Sp += a;
+        Sf += b;
+      }
+    }
+  }
+  if (acc > 2147483647LL) return AX_ORACLE_ERR_OVERFLOW;
+  const int64_t K = (int64_t)KH * KW * Cin;
+  const int64_t corr = acc - (int64_t)q->w_zp * Sp - (int64_t)q->x_zp * Sf + K * q->x_zp * q->w_zp;
+  *acc_out = (int32_t)acc;
+  *y_out = (float)((double)q->x_scale * (double)q->w_scale * (double)corr);
+  return 0;
+}
+
+static int conv_shape_ok(int N, int H, int W, int Cin, int KH, int KW, int Cout, int stride_h,
+                         int stride_w, int pad_h, int pad_w, int* OH, int* OW) {
+  if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || KH <= 0 || KW <= 0 || Cout <= 0) return 0;
+  if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0) return 0;
+  if (H + 2 * pad_h < KH || W + 2 * pad_w < KW) return 0;
+  *OH = (H + 2 * pad_h - KH) / stride_h + 1;
+  *OW = (W + 2 * pad_w - KW) / stride_w + 1;
+  return 1;
+}
+
+int ax_oracle_conv2d(const uint8_t* x, int N, int H, int W, int Cin, const uint8_t* w, int KH,
+                     int KW, int Cout, const uint16_t* lut, int stride_h, int stride_w, int pad_h,
+                     int pad_w, const ax_oracle_quant* q, int32_t* acc_out, float* y_out) {
+  int OH, OW, pad_code;
+  if (!x || !w || !lut || !acc_out || !y_out) return AX_ORACLE_ERR_ARG;
+  if (!conv_shape_ok(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &OH, &OW))
+    return AX_ORACLE_ERR_ARG;
+  int rc = check_quant(q, &pad_code);
+  if (rc) return rc;
+  int status = 0;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n) {
+    for (int oy = 0; oy < OH; ++oy) {
+      for (int ox = 0; ox < OW; ++ox) {
+        for (int co = 0; co < Cout; ++co) {
+          const size_t o = (((size_t)n * OH + oy) * OW + ox) * Cout + co;
+          int r = conv_element(x, H, W, Cin, w, KH, KW, Cout, lut, stride_h, stride_w, pad_h, pad_w,
+                               q, pad_code, n, oy, ox, co, &acc_out[o], &y_out[o]);
+          if (r) {
+#pragma omp atomic write
+            status = r;
+          }
+        }
+      }
+    }
+  }
+  return status;
+}
+
+int ax_oracle_conv2d_sample(const uint8_t* x, int N, int H, int W, int Cin, const uint8_t* w,
+                            int KH, int KW, int Cout, const uint16_t* lut, int stride_h,
+                            int stride_w, int pad_h, int pad_w, const ax_oracle_quant* q,
+                            const int64_t* flat_index, int count, int32_t* acc_out, float* y_out) {
+  int OH, OW, pad_code;
+  if (!x || !w || !lut || !acc_out || !y_out || !flat_index || count < 0) return AX_ORACLE_ERR_ARG;
+  if (!conv_shape_ok(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &OH, &OW))
+    return AX_ORACLE_ERR_ARG;
+  int rc = check_quant(q, &pad_code);
+  if (rc) return rc;
+  const int64_t total = (int64_t)N * OH * OW * Cout;
+  for (int i = 0; i < count; ++i) {
+    int64_t o = flat_index[i];
+    if (o < 0 || o >= total) return AX_ORACLE_ERR_ARG;
+    const int co = (int)(o % Cout);
+    o /= Cout;
+    const int ox = (int)(o % OW);
+    o /= OW;
+    const int oy = (int)(o % OH);
+    const int n = (int)(o / OH);
+    rc = conv_element(x, H, W, Cin, w, KH, KW, Cout, lut, stride_h, stride_w, pad_h, pad_w, q,
+                      pad_code, n, oy, ox, co, &acc_out[i], &y_out[i]);
+    if (rc) return rc;
+  }
+  return 0;
+}
+
+/* Dense layer: the matrix product of Eq. (2)/(3) itself, x is M x K, w is K x N, both row
+ * major; out[i][j] = sum_k lut[x[i][k]*256 + w[k][j]], then the same correction. */
+int ax_oracle_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint16_t* lut,
+                    const ax_oracle_quant* q, int32_t* acc_out, float* y_out) {
+  int pad_code;
+  if (!x || !w || !lut || !acc_out || !y_out) return AX_ORACLE_ERR_ARG;
+  if (M <= 0 || K <= 0 || N <= 0) return AX_ORACLE_ERR_ARG;
+  int rc = check_quant(q, &pad_code);
+  if (rc) return rc;
+  int status = 0;
+#pragma omp parallel for schedule(static)
+  for (int i = 0; i < M; ++i) {
+    for (int j = 0; j < N; ++j) {
+      int64_t acc = 0, Sp = 0, Sf = 0;
+      for (int k = 0; k < K; ++k) {
+        const int a = x[(size_t)i * K + k];
+        const int b = w[(size_t)k * N + j];
+        acc += lut[a * 256 + b];
+        Sp += a;
+        Sf += b;
+      }
+      if (acc > 2147483647LL) {
+#pragma omp atomic write
+        status = AX_ORACLE_ERR_OVERFLOW;
+        continue;
+      }
+      const int64_t corr =
+          acc - (int64_t)q->w_zp * Sp - (int64_t)q->x_zp * Sf + (int64_t)K * q->x_zp * q->w_zp;
+      acc_out[(size_t)i * N + j] = (int32_t)acc;
+      y_out[(size_t)i * N + j] = (float)((double)q->x_scale * (double)q->w_scale * (double)corr);
+    }
+  }
+  return status;
+}
+
+int ax_oracle_threads(void) {
+  int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+  {
+#pragma omp single
+    n = omp_get_num_threads();
+  }
+#endif
+  return n;
+}

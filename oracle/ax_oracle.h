@@ -1,0 +1,49 @@
+/*
+ * Interface of the CPU oracle (test infrastructure; see ax_oracle.c).  All pointers are
+ * host pointers owned by the caller.  This header is private to oracle/: the HIP library
+ * does not include it.
+ */
+#ifndef AX_ORACLE_H
+#define AX_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AX_ORACLE_ERR_ARG (-1)      /* null pointer, bad shape or bad quantization value */
+#define AX_ORACLE_ERR_OVERFLOW (-2) /* a sum of table entries left the int32 range       */
+
+typedef struct {
+  float x_scale;    /* alpha_1 > 0                                   */
+  int32_t x_zp;     /* beta_1 in [0,255]                             */
+  float w_scale;    /* alpha_2 > 0                                   */
+  int32_t w_zp;     /* beta_2 in [0,255]                             */
+  int32_t pad_code; /* code of out-of-image taps, -1 = use x_zp      */
+} ax_oracle_quant;
+
+/* x: [N,H,W,Cin]; w: [KH,KW,Cin,Cout]; lut: [65536], index = x_code*256 + w_code;
+ * acc_out, y_out: [N,OH,OW,Cout]. */
+int ax_oracle_conv2d(const uint8_t* x, int N, int H, int W, int Cin, const uint8_t* w, int KH,
+                     int KW, int Cout, const uint16_t* lut, int stride_h, int stride_w, int pad_h,
+                     int pad_w, const ax_oracle_quant* q, int32_t* acc_out, float* y_out);
+
+/* Same definition evaluated only at `count` flat output indices (into [N,OH,OW,Cout]);
+ * results are written to acc_out[i], y_out[i]. */
+int ax_oracle_conv2d_sample(const uint8_t* x, int N, int H, int W, int Cin, const uint8_t* w,
+                            int KH, int KW, int Cout, const uint16_t* lut, int stride_h,
+                            int stride_w, int pad_h, int pad_w, const ax_oracle_quant* q,
+                            const int64_t* flat_index, int count, int32_t* acc_out, float* y_out);
+
+/* x: [M,K]; w: [K,N]; acc_out, y_out: [M,N]. */
+int ax_oracle_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint16_t* lut,
+                    const ax_oracle_quant* q, int32_t* acc_out, float* y_out);
+
+/* Number of threads the parallel loops use. */
+int ax_oracle_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,119 @@
+"""ctypes loader for the C oracle.  Test infrastructure: imported only by tests/, the smoke
+check and the benchmark's cpu_baseline leg.  Takes and returns numpy arrays on the host."""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+class _Quant(ctypes.Structure):
+    _fields_ = [
+        ("x_scale", ctypes.c_float),
+        ("x_zp", ctypes.c_int32),
+        ("w_scale", ctypes.c_float),
+        ("w_zp", ctypes.c_int32),
+        ("pad_code", ctypes.c_int32),
+    ]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        _lib = ctypes.CDLL(path)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        _lib.ax_oracle_conv2d.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, vp]
+        _lib.ax_oracle_conv2d_sample.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, ci, vp, vp]
+        _lib.ax_oracle_dense.argtypes = [vp, ci, ci, vp, ci, vp, vp, vp, vp]
+        for f in (_lib.ax_oracle_conv2d, _lib.ax_oracle_conv2d_sample, _lib.ax_oracle_dense, _lib.ax_oracle_threads):
+            f.restype = ci
+    return _lib
+
+
+def _q(q) -> _Quant:
+    return _Quant(float(q.x_scale), int(q.x_zp), float(q.w_scale), int(q.w_zp), int(q.pad_code))
+
+
+def _chk(a, dtype, ndim):
+    a = np.ascontiguousarray(a)
+    if a.dtype != dtype or a.ndim != ndim:
+        raise TypeError("expected %s array with %d dims, got %s %s" % (dtype, ndim, a.dtype, a.shape))
+    return a
+
+
+def _lut(lut):
+    lut = _chk(np.asarray(lut).reshape(-1), np.uint16, 1)
+    if lut.size != 65536:
+        raise ValueError("table must have 65536 entries")
+    return lut
+
+
+def out_hw(H, W, KH, KW, stride, pad):
+    sh, sw = (stride, stride) if np.isscalar(stride) else stride
+    ph, pw = (pad, pad) if np.isscalar(pad) else pad
+    return (H + 2 * ph - KH) // sh + 1, (W + 2 * pw - KW) // sw + 1, sh, sw, ph, pw
+
+
+def conv2d(x, w, lut, stride, pad, q):
+    x, w, lut = _chk(x, np.uint8, 4), _chk(w, np.uint8, 4), _lut(lut)
+    N, H, W, Cin = x.shape
+    KH, KW, Cin2, Cout = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    OH, OW, sh, sw, ph, pw = out_hw(H, W, KH, KW, stride, pad)
+    if OH <= 0 or OW <= 0:
+        raise ValueError("empty output")
+    acc = np.empty((N, OH, OW, Cout), np.int32)
+    y = np.empty((N, OH, OW, Cout), np.float32)
+    qs = _q(q)
+    rc = lib().ax_oracle_conv2d(x.ctypes.data, N, H, W, Cin, w.ctypes.data, KH, KW, Cout, lut.ctypes.data,
+                                sh, sw, ph, pw, ctypes.addressof(qs), acc.ctypes.data, y.ctypes.data)
+    if rc:
+        raise RuntimeError("ax_oracle_conv2d failed: %d" % rc)
+    return acc, y
+
+
+def conv2d_sample(x, w, lut, stride, pad, q, flat_index):
+    x, w, lut = _chk(x, np.uint8, 4), _chk(w, np.uint8, 4), _lut(lut)
+    idx = _chk(np.asarray(flat_index, dtype=np.int64), np.int64, 1)
+    N, H, W, Cin = x.shape
+    KH, KW, Cin2, Cout = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    OH, OW, sh, sw, ph, pw = out_hw(H, W, KH, KW, stride, pad)
+    acc = np.empty(idx.size, np.int32)
+    y = np.empty(idx.size, np.float32)
+    qs = _q(q)
+    rc = lib().ax_oracle_conv2d_sample(x.ctypes.data, N, H, W, Cin, w.ctypes.data, KH, KW, Cout, lut.ctypes.data,
+                                       sh, sw, ph, pw, ctypes.addressof(qs), idx.ctypes.data, idx.size,
+                                       acc.ctypes.data, y.ctypes.data)
+    if rc:
+        raise RuntimeError("ax_oracle_conv2d_sample failed: %d" % rc)
+    return acc, y
+
+
+def dense(x, w, lut, q):
+    x, w, lut = _chk(x, np.uint8, 2), _chk(w, np.uint8, 2), _lut(lut)
+    M, K = x.shape
+    K2, N = w.shape
+    if K2 != K:
+        raise ValueError("inner dimension mismatch")
+    acc = np.empty((M, N), np.int32)
+    y = np.empty((M, N), np.float32)
+    qs = _q(q)
+    rc = lib().ax_oracle_dense(x.ctypes.data, M, K, w.ctypes.data, N, lut.ctypes.data, ctypes.addressof(qs),
+                               acc.ctypes.data, y.ctypes.data)
+    if rc:
+        raise RuntimeError("ax_oracle_dense failed: %d" % rc)
+    return acc, y
+
+
+def threads() -> int:
+    return int(lib().ax_oracle_threads())
