@@ -1,0 +1,136 @@
+/*
+ * axconv -- table-lookup quantized conv2d / dense for AMD MI355X (gfx950).
+ *
+ * Emulates a DNN accelerator whose MAC unit has an 8-bit (approximate) multiplier and a
+ * 32-bit accumulator: every product of an 8-bit activation code and an 8-bit filter code
+ * is taken from a truth table of 256 x 256 16-bit entries (128 kB), summed exactly in
+ * int32, then dequantized (paper: Sec. II, Eq. (1)-(4) and the MAC model; Sec. III,
+ * tensor layouts and the table addressed by the two stitched codes).
+ *
+ * Conventions for every entry point
+ *   - Tensor pointers (x, w, lut, acc_out, y_out, workspace) are DEVICE pointers owned by
+ *     the caller.  `q` is a HOST pointer and is read before the call returns.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  They never synchronize, allocate or free.
+ *   - Outputs are overwritten completely.  Either of acc_out / y_out may be NULL to skip
+ *     it (not both).  Inputs must not alias outputs or the workspace.
+ *   - `workspace` holds per-call scratch (re-laid-out table, packed operands, partial
+ *     sums).  Its contents need not be preserved between calls, but two calls that run
+ *     concurrently on different streams need separate workspaces.  The required size is
+ *     returned by the matching *_workspace_bytes function; a smaller buffer is an error.
+ *   - Return value: AX_OK (0) or a negative AX_ERR_* code; ax_strerror() gives text.
+ *     Nothing is printed, thrown or aborted.
+ */
+#ifndef AXCONV_H
+#define AXCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AX_OK 0
+#define AX_ERR_NULL (-1)       /* a required pointer is NULL                                   */
+#define AX_ERR_SHAPE (-2)      /* non-positive dimension, stride < 1, pad < 0, empty output,
+                                  or a tensor with 2^31 or more elements                       */
+#define AX_ERR_QUANT (-3)      /* zero point / pad code outside [0,255] (pad_code may be -1),
+                                  scale not finite or not positive                             */
+#define AX_ERR_K_OVERFLOW (-4) /* KH*KW*Cin > 32768: the int32 accumulator could overflow
+                                  (32769 * 65535 > 2^31 - 1)                                   */
+#define AX_ERR_WORKSPACE (-5)  /* workspace NULL, too small or not 256-byte aligned            */
+#define AX_ERR_HIP (-6)        /* a HIP runtime call failed (launch, attribute, event)         */
+#define AX_ERR_ALIGN (-7)      /* a tensor pointer is not aligned to its element size          */
+#define AX_ERR_OPTION (-8)     /* unknown option name or value out of range                    */
+
+/* Affine quantization parameters, real = scale * (code - zero_point)  (Eq. (1)).
+ * x_* are alpha_1 / beta_1 of the activations, w_* are alpha_2 / beta_2 of the filters
+ * (Eq. (3)).  pad_code is the activation code that taps outside the image feed through
+ * the multiplier table; -1 selects x_zp, the code of the real value zero (Sec. II). */
+typedef struct {
+  float x_scale;
+  int32_t x_zp;
+  float w_scale;
+  int32_t w_zp;
+  int32_t pad_code;
+} ax_quant_t;
+
+/*
+ * Approximate 2-D convolution (Sec. III, Algorithm 1 without the float quantization step:
+ * operands arrive as 8-bit codes).
+ *
+ *   x        [N, H, W, Cin]       uint8, channels fastest
+ *   w        [KH, KW, Cin, Cout]  uint8, filter count fastest
+ *   lut      [65536]              uint16, entry index = x_code * 256 + w_code
+ *   acc_out  [N, OH, OW, Cout]    int32:  acc = sum over the KH*KW*Cin taps of lut[...]
+ *   y_out    [N, OH, OW, Cout]    float:  y = x_scale * w_scale *
+ *                (acc - w_zp * Sp - x_zp * Sf + K * x_zp * w_zp),
+ *            Sp = sum of the patch's activation codes (padded taps included), Sf = sum of
+ *            the channel's filter codes, K = KH*KW*Cin: the integer expansion of Eq. (3)
+ *            with the table in place of the product (Eq. (4)).
+ *   OH = floor((H + 2*pad_h - KH) / stride_h) + 1, OW likewise.  Dilation is 1.
+ *
+ * acc_out is bit-exact; y_out is float(corr) * (x_scale * w_scale) in float arithmetic.
+ */
+int ax_conv2d(const uint8_t* x, int N, int H, int W, int Cin, const uint8_t* w, int KH, int KW,
+              int Cout, const uint16_t* lut, int stride_h, int stride_w, int pad_h, int pad_w,
+              const ax_quant_t* q, int32_t* acc_out, float* y_out, void* workspace,
+              size_t workspace_bytes, void* hip_stream);
+
+size_t ax_conv2d_workspace_bytes(int N, int H, int W, int Cin, int KH, int KW, int Cout,
+                                 int stride_h, int stride_w, int pad_h, int pad_w);
+
+/*
+ * Approximate dense layer / matrix product (Eq. (2)-(4)); identical to ax_conv2d with
+ * H = W = KH = KW = 1, Cin = K, Cout = N and M images.
+ *   x [M, K] uint8 row major, w [K, N] uint8 row major, acc_out / y_out [M, N].
+ */
+int ax_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint16_t* lut,
+             const ax_quant_t* q, int32_t* acc_out, float* y_out, void* workspace,
+             size_t workspace_bytes, void* hip_stream);
+
+size_t ax_dense_workspace_bytes(int M, int K, int N);
+
+const char* ax_strerror(int code);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int ax_version(void);
+
+/*
+ * Process-wide tuning / test knobs.  Names:
+ *   "variant"  0 = choose automatically (default)
+ *              1 = direct kernel: one thread per output, table read from global memory
+ *              2 = table-tile kernel, lanes over output pixels
+ *              3 = table-tile kernel, lanes over output channels
+ *   "split_k"  0 = choose automatically, n >= 1 = force n slices of the K loop
+ * Returns AX_OK or AX_ERR_OPTION.  Not thread safe with respect to concurrent calls.
+ */
+int ax_set_option(const char* name, int value);
+int ax_get_option(const char* name, int* value);
+
+/* ---- measurement helpers (not part of the layer path) -------------------------------- */
+
+/*
+ * LDS gather micro-benchmark: one workgroup per compute unit keeps a table of
+ * `table_bytes` in LDS and every lane repeatedly reads `width_bytes` (2, 4, 8 or 16)
+ * from it.  pattern 0: lane l reads consecutive elements (no bank conflict);
+ * pattern 1: every lane reads independent uniformly random aligned elements;
+ * pattern 2: like 1, but half of the lanes (chosen at random) read element 0.
+ * Unlike the layer calls, this one allocates temporary device memory and synchronizes.
+ * Outputs (host pointers): wave_reads = wave-level read
+ * instructions executed per workgroup, cycles = mean shader-clock cycles per workgroup,
+ * seconds = elapsed time of the kernel, workgroups = grid size.
+ */
+int ax_probe_lds_gather(int width_bytes, int pattern, int table_bytes, int threads, int iters,
+                        double* wave_reads, double* cycles, double* seconds, int* workgroups,
+                        void* hip_stream);
+
+/* Plain device-to-device copy kernel of `bytes` (multiple of 16), for the HBM roofline and
+ * for calibrating memory-traffic counters.  Asynchronous. */
+int ax_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AXCONV_H */

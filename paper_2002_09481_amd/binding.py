@@ -1,0 +1,245 @@
+"""ctypes binding of libaxconv.so: the same entry points as include/axconv.h.
+
+Only argument marshalling happens here.  Tensors are torch CUDA tensors (torch provides
+device memory and the stream); every step of the layer runs in the HIP kernels.  There is
+no fallback: a missing library raises at first use.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaxconv.so")
+
+_lib = None
+
+
+class AxError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("axconv error %d: %s" % (code, text))
+        self.code = code
+
+
+class ax_quant_t(ctypes.Structure):
+    _fields_ = [
+        ("x_scale", ctypes.c_float),
+        ("x_zp", ctypes.c_int32),
+        ("w_scale", ctypes.c_float),
+        ("w_zp", ctypes.c_int32),
+        ("pad_code", ctypes.c_int32),
+    ]
+
+
+EXPORTS = [
+    "ax_conv2d", "ax_conv2d_workspace_bytes", "ax_dense", "ax_dense_workspace_bytes", "ax_strerror",
+    "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy",
+]
+
+
+def lib():
+    """Load libaxconv.so (built beforehand by paper_2002_09481_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libaxconv.so is not built: run `python -m paper_2002_09481_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.ax_conv2d.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci,
+                            ctypes.POINTER(ax_quant_t), vp, vp, vp, sz, vp]
+    L.ax_conv2d.restype = ci
+    L.ax_conv2d_workspace_bytes.argtypes = [ci] * 11
+    L.ax_conv2d_workspace_bytes.restype = sz
+    L.ax_dense.argtypes = [vp, ci, ci, vp, ci, vp, ctypes.POINTER(ax_quant_t), vp, vp, vp, sz, vp]
+    L.ax_dense.restype = ci
+    L.ax_dense_workspace_bytes.argtypes = [ci, ci, ci]
+    L.ax_dense_workspace_bytes.restype = sz
+    L.ax_strerror.argtypes = [ci]
+    L.ax_strerror.restype = ctypes.c_char_p
+    L.ax_version.argtypes = []
+    L.ax_version.restype = ci
+    L.ax_set_option.argtypes = [ctypes.c_char_p, ci]
+    L.ax_set_option.restype = ci
+    L.ax_get_option.argtypes = [ctypes.c_char_p, ctypes.POINTER(ci)]
+    L.ax_get_option.restype = ci
+    dp = ctypes.POINTER(ctypes.c_double)
+    L.ax_probe_lds_gather.argtypes = [ci, ci, ci, ci, ci, dp, dp, dp, ctypes.POINTER(ci), vp]
+    L.ax_probe_lds_gather.restype = ci
+    L.ax_probe_copy.argtypes = [vp, vp, sz, vp]
+    L.ax_probe_copy.restype = ci
+    _lib = L
+    return L
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise AxError(rc, lib().ax_strerror(rc).decode())
+
+
+def ax_strerror(code: int) -> str:
+    return lib().ax_strerror(code).decode()
+
+
+def ax_version() -> int:
+    return int(lib().ax_version())
+
+
+def ax_set_option(name: str, value: int) -> None:
+    _check(lib().ax_set_option(name.encode(), int(value)))
+
+
+def ax_get_option(name: str) -> int:
+    v = ctypes.c_int(0)
+    _check(lib().ax_get_option(name.encode(), ctypes.byref(v)))
+    return v.value
+
+
+def _quant(q) -> ax_quant_t:
+    return ax_quant_t(float(q.x_scale), int(q.x_zp), float(q.w_scale), int(q.w_zp), int(q.pad_code))
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a CUDA tensor" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return t
+
+
+def _pair(v) -> Tuple[int, int]:
+    return (int(v), int(v)) if isinstance(v, int) else (int(v[0]), int(v[1]))
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def ax_conv2d_workspace_bytes(x_shape, w_shape, stride=1, pad=0) -> int:
+    N, H, W, Cin = [int(v) for v in x_shape]
+    KH, KW, _, Cout = [int(v) for v in w_shape]
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    return int(lib().ax_conv2d_workspace_bytes(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw))
+
+
+def ax_dense_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(lib().ax_dense_workspace_bytes(int(M), int(K), int(N)))
+
+
+def ax_conv2d(x, w, lut, stride, pad, q, acc_out=None, y_out=None, workspace=None, stream=None):
+    """Enqueue one layer.  x: uint8 [N,H,W,Cin]; w: uint8 [KH,KW,Cin,Cout]; lut: int16/uint16
+    [65536] (bit pattern of the uint16 entries); acc_out: int32 [N,OH,OW,Cout]; y_out: float32.
+    Missing outputs / workspace are allocated with torch (the C call itself never allocates).
+    Returns (acc_out, y_out)."""
+    L = lib()
+    _dev(x, torch.uint8, "x")
+    _dev(w, torch.uint8, "w")
+    if lut.dtype not in (torch.int16, torch.uint16):
+        raise TypeError("lut must be a 16-bit integer tensor")
+    _dev(lut, lut.dtype, "lut")
+    if lut.numel() != 65536:
+        raise ValueError("lut must have 65536 entries")
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
+        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout]")
+    N, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    OH = (H + 2 * ph - KH) // sh + 1
+    OW = (W + 2 * pw - KW) // sw + 1
+    if OH <= 0 or OW <= 0:
+        _check(-2)
+    if acc_out is None:
+        acc_out = torch.empty((N, OH, OW, Cout), dtype=torch.int32, device=x.device)
+    if y_out is None:
+        y_out = torch.empty((N, OH, OW, Cout), dtype=torch.float32, device=x.device)
+    if acc_out is not False:
+        _dev(acc_out, torch.int32, "acc_out")
+    if y_out is not False:
+        _dev(y_out, torch.float32, "y_out")
+    for o in (acc_out, y_out):
+        if o is not False and o.numel() != N * OH * OW * Cout:
+            raise ValueError("output tensor has the wrong number of elements")
+    need = int(L.ax_conv2d_workspace_bytes(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    qs = _quant(q)
+    rc = L.ax_conv2d(_ptr(x), N, H, W, Cin, _ptr(w), KH, KW, Cout, _ptr(lut), sh, sw, ph, pw, ctypes.byref(qs),
+                     _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
+                     _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    _check(rc)
+    return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
+def ax_dense(x, w, lut, q, acc_out=None, y_out=None, workspace=None, stream=None):
+    """x: uint8 [M,K]; w: uint8 [K,N]; outputs [M,N]."""
+    L = lib()
+    _dev(x, torch.uint8, "x")
+    _dev(w, torch.uint8, "w")
+    if lut.dtype not in (torch.int16, torch.uint16):
+        raise TypeError("lut must be a 16-bit integer tensor")
+    _dev(lut, lut.dtype, "lut")
+    if lut.numel() != 65536:
+        raise ValueError("lut must have 65536 entries")
+    if x.dim() != 2 or w.dim() != 2 or w.shape[0] != x.shape[1]:
+        raise ValueError("x must be [M,K] and w [K,N]")
+    M, K = x.shape
+    N = w.shape[1]
+    if acc_out is None:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=x.device)
+    if y_out is None:
+        y_out = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    if acc_out is not False:
+        _dev(acc_out, torch.int32, "acc_out")
+    if y_out is not False:
+        _dev(y_out, torch.float32, "y_out")
+    need = int(L.ax_dense_workspace_bytes(M, K, N))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    qs = _quant(q)
+    rc = L.ax_dense(_ptr(x), M, K, _ptr(w), N, _ptr(lut), ctypes.byref(qs),
+                    _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
+                    _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    _check(rc)
+    return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
+def ax_probe_lds_gather(width_bytes: int, pattern: int, table_bytes: int, threads: int = 1024, iters: int = 2000,
+                        stream=None) -> dict:
+    wr, cy, sec = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    wgs = ctypes.c_int()
+    rc = lib().ax_probe_lds_gather(width_bytes, pattern, table_bytes, threads, iters, ctypes.byref(wr),
+                                   ctypes.byref(cy), ctypes.byref(sec), ctypes.byref(wgs),
+                                   ctypes.c_void_p(_stream_ptr(stream)))
+    _check(rc)
+    return {"wave_reads": wr.value, "cycles": cy.value, "seconds": sec.value, "workgroups": wgs.value}
+
+
+def ax_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("size mismatch")
+    _check(lib().ax_probe_copy(_ptr(dst), _ptr(src), nbytes, ctypes.c_void_p(_stream_ptr(stream))))
+
+
+def lut_to_device(lut_np, device="cuda") -> torch.Tensor:
+    """uint16 numpy table -> device tensor holding the same bit patterns."""
+    import numpy as np
+
+    a = np.ascontiguousarray(lut_np, dtype=np.uint16).reshape(-1)
+    return torch.from_numpy(a.view(np.int16).copy()).to(device)

@@ -1,0 +1,158 @@
+// C ABI of libaxconv: argument validation, dispatch, error text.  No device code here.
+#include <cmath>
+#include <cstring>
+
+#include "ax_internal.h"
+
+namespace ax {
+
+Options g_opt = {0, 0};
+
+static int make_quant(const ax_quant_t* q, QParams* qp) {
+  if (!q) return AX_ERR_NULL;
+  if (q->x_zp < 0 || q->x_zp > 255 || q->w_zp < 0 || q->w_zp > 255) return AX_ERR_QUANT;
+  if (q->pad_code < -1 || q->pad_code > 255) return AX_ERR_QUANT;
+  if (!std::isfinite(q->x_scale) || !std::isfinite(q->w_scale) || !(q->x_scale > 0.f) || !(q->w_scale > 0.f))
+    return AX_ERR_QUANT;
+  qp->x_zp = q->x_zp;
+  qp->w_zp = q->w_zp;
+  qp->pad_code = q->pad_code < 0 ? q->x_zp : q->pad_code;
+  qp->scale = q->x_scale * q->w_scale;
+  return AX_OK;
+}
+
+static int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw,
+                     Geom* g) {
+  if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || KH <= 0 || KW <= 0 || Cout <= 0) return AX_ERR_SHAPE;
+  if (sh < 1 || sw < 1 || ph < 0 || pw < 0) return AX_ERR_SHAPE;
+  if (ph > (1 << 20) || pw > (1 << 20)) return AX_ERR_SHAPE;
+  const long long eh = (long long)H + 2LL * ph - KH, ew = (long long)W + 2LL * pw - KW;
+  if (eh < 0 || ew < 0) return AX_ERR_SHAPE;
+  const long long OH = eh / sh + 1, OW = ew / sw + 1;
+  const long long K = (long long)KH * KW * Cin;
+  if (K > 32768) return AX_ERR_K_OVERFLOW;
+  const long long lim = 0x7fffffffLL;
+  const long long M = (long long)N * OH * OW;
+  if ((long long)N * H * W * Cin > lim || K * Cout > lim || M > lim || M * Cout > lim) return AX_ERR_SHAPE;
+  *g = Geom{N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, (int)OH, (int)OW, (int)M, (int)K};
+  return AX_OK;
+}
+
+// 1 = direct, 2/3 = table-tile kernels
+static int choose_variant(const Geom& g) {
+  if (g_opt.variant == 1) return 1;
+  if (!tab_supported(g)) return 1;
+  if (g_opt.variant == 2 || g_opt.variant == 3) return g_opt.variant;
+  // Tiny problems do not amortize the table set-up.
+  if ((double)g.M * g.K * g.Cout < 4.0e6) return 1;
+  return 0;  // let the tab planner pick the lane assignment
+}
+
+static int run(const Geom& g, const ax_quant_t* q, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
+               int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, void* stream) {
+  if (!x || !w || !lut || (!acc_out && !y_out)) return AX_ERR_NULL;
+  if (((uintptr_t)lut & 1) || ((uintptr_t)acc_out & 3) || ((uintptr_t)y_out & 3)) return AX_ERR_ALIGN;
+  QParams qp;
+  int rc = make_quant(q, &qp);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  const int v = choose_variant(g);
+  hipError_t e;
+  if (v == 1) {
+    e = launch_direct(g, qp, x, w, lut, acc_out, y_out, s);
+  } else {
+    Options o = g_opt;
+    o.variant = v;
+    const TabPlan p = tab_plan(g, o);
+    if (!ws || ws_bytes < p.total || ((uintptr_t)ws & 255)) return AX_ERR_WORKSPACE;
+    e = launch_tab(g, qp, p, x, w, lut, acc_out, y_out, ws, s);
+  }
+  return e == hipSuccess ? AX_OK : AX_ERR_HIP;
+}
+
+static size_t workspace_for(const Geom& g) {
+  // Large enough for whichever variant the options may select later.
+  if (!tab_supported(g)) return 256;
+  size_t need = 256;
+  for (int v = 2; v <= 3; ++v) {
+    Options o = {v, 0};
+    const size_t t = tab_plan(g, o).total;
+    if (t > need) need = t;
+  }
+  return need;
+}
+
+}  // namespace ax
+
+using namespace ax;
+
+extern "C" int ax_conv2d(const uint8_t* x, int N, int H, int W, int Cin, const uint8_t* w, int KH, int KW,
+                         int Cout, const uint16_t* lut, int stride_h, int stride_w, int pad_h, int pad_w,
+                         const ax_quant_t* q, int32_t* acc_out, float* y_out, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  Geom g;
+  int rc = make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g);
+  if (rc) return rc;
+  return run(g, q, x, w, lut, acc_out, y_out, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t ax_conv2d_workspace_bytes(int N, int H, int W, int Cin, int KH, int KW, int Cout, int stride_h,
+                                            int stride_w, int pad_h, int pad_w) {
+  Geom g;
+  if (make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g)) return 0;
+  return workspace_for(g);
+}
+
+extern "C" int ax_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint16_t* lut,
+                        const ax_quant_t* q, int32_t* acc_out, float* y_out, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  Geom g;
+  int rc = make_geom(M, 1, 1, K, 1, 1, N, 1, 1, 0, 0, &g);
+  if (rc) return rc;
+  return run(g, q, x, w, lut, acc_out, y_out, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t ax_dense_workspace_bytes(int M, int K, int N) {
+  Geom g;
+  if (make_geom(M, 1, 1, K, 1, 1, N, 1, 1, 0, 0, &g)) return 0;
+  return workspace_for(g);
+}
+
+extern "C" const char* ax_strerror(int code) {
+  switch (code) {
+    case AX_OK: return "ok";
+    case AX_ERR_NULL: return "required pointer is NULL";
+    case AX_ERR_SHAPE: return "invalid shape, stride or padding";
+    case AX_ERR_QUANT: return "invalid quantization parameters";
+    case AX_ERR_K_OVERFLOW: return "KH*KW*Cin exceeds 32768: int32 accumulator could overflow";
+    case AX_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+    case AX_ERR_HIP: return "HIP runtime call failed";
+    case AX_ERR_ALIGN: return "pointer not aligned";
+    case AX_ERR_OPTION: return "unknown option or value out of range";
+    default: return "unknown error code";
+  }
+}
+
+extern "C" int ax_version(void) { return 100; }
+
+extern "C" int ax_set_option(const char* name, int value) {
+  if (!name) return AX_ERR_OPTION;
+  if (!std::strcmp(name, "variant")) {
+    if (value < 0 || value > 3) return AX_ERR_OPTION;
+    g_opt.variant = value;
+    return AX_OK;
+  }
+  if (!std::strcmp(name, "split_k")) {
+    if (value < 0 || value > 64) return AX_ERR_OPTION;
+    g_opt.split_k = value;
+    return AX_OK;
+  }
+  return AX_ERR_OPTION;
+}
+
+extern "C" int ax_get_option(const char* name, int* value) {
+  if (!name || !value) return AX_ERR_OPTION;
+  if (!std::strcmp(name, "variant")) { *value = g_opt.variant; return AX_OK; }
+  if (!std::strcmp(name, "split_k")) { *value = g_opt.split_k; return AX_OK; }
+  return AX_ERR_OPTION;
+}

@@ -1,0 +1,60 @@
+// Direct kernel: one thread per output element, table read straight from global memory.
+//
+// This is the simplest device formulation of the layer (Sec. II Eq. (3)/(4) with the product
+// replaced by the truth-table entry; Sec. III layouts): consecutive lanes take consecutive
+// output channels of one pixel, so the activation code is wave-uniform, the filter codes
+// are a coalesced 64-byte read and the lookups fall into one 512-byte table row.  It is
+// used for tiny problems and for shapes the table-tile kernels do not take.
+#include "ax_internal.h"
+
+namespace ax {
+
+__global__ __launch_bounds__(256) void direct_kernel(Geom g, QParams qp, const uint8_t* __restrict__ x,
+                                                      const uint8_t* __restrict__ w,
+                                                      const uint16_t* __restrict__ lut,
+                                                      int32_t* __restrict__ acc_out,
+                                                      float* __restrict__ y_out) {
+  const uint32_t total = (uint32_t)g.M * (uint32_t)g.Cout;
+  const uint32_t o = blockIdx.x * 256u + threadIdx.x;
+  if (o >= total) return;
+  const int co = o % (uint32_t)g.Cout;
+  uint32_t m = o / (uint32_t)g.Cout;
+  const int ox = m % (uint32_t)g.OW;
+  m /= (uint32_t)g.OW;
+  const int oy = m % (uint32_t)g.OH;
+  const int n = m / (uint32_t)g.OH;
+
+  uint32_t acc = 0, sp = 0, sf = 0;
+  for (int ky = 0; ky < g.KH; ++ky) {
+    const int iy = oy * g.sh - g.ph + ky;
+    for (int kx = 0; kx < g.KW; ++kx) {
+      const int ix = ox * g.sw - g.pw + kx;
+      const bool inside = (iy >= 0) && (iy < g.H) && (ix >= 0) && (ix < g.W);
+      const uint8_t* xp = x + (((size_t)n * g.H + (inside ? iy : 0)) * g.W + (inside ? ix : 0)) * g.Cin;
+      const uint8_t* wp = w + ((size_t)(ky * g.KW + kx) * g.Cin) * g.Cout + co;
+      for (int ci = 0; ci < g.Cin; ++ci) {
+        const uint32_t a = inside ? (uint32_t)xp[ci] : (uint32_t)qp.pad_code;
+        const uint32_t b = wp[(size_t)ci * g.Cout];
+        acc += lut[a * 256u + b];
+        sp += a;
+        sf += b;
+      }
+    }
+  }
+  if (acc_out) acc_out[o] = (int32_t)acc;
+  if (y_out) {
+    const long long corr = (long long)acc - (long long)qp.w_zp * sp - (long long)qp.x_zp * sf +
+                           (long long)g.K * qp.x_zp * qp.w_zp;
+    y_out[o] = (float)corr * qp.scale;
+  }
+}
+
+hipError_t launch_direct(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w,
+                         const uint16_t* lut, int32_t* acc_out, float* y_out, hipStream_t s) {
+  const uint64_t total = (uint64_t)g.M * g.Cout;
+  const uint32_t blocks = (uint32_t)((total + 255) / 256);
+  hipLaunchKernelGGL(direct_kernel, dim3(blocks), dim3(256), 0, s, g, qp, x, w, lut, acc_out, y_out);
+  return hipGetLastError();
+}
+
+}  // namespace ax

@@ -1,0 +1,58 @@
+// Internal declarations shared by the translation units of libaxconv (HIP, gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "axconv.h"
+
+namespace ax {
+
+// Geometry of one layer call after validation.  A dense layer is a 1x1 convolution over
+// M "images" of one pixel.
+struct Geom {
+  int N, H, W, Cin;
+  int KH, KW, Cout;
+  int sh, sw, ph, pw;
+  int OH, OW;
+  int M;  // N*OH*OW output pixels
+  int K;  // KH*KW*Cin taps per output
+};
+
+// Quantization parameters as the kernels consume them.
+struct QParams {
+  int x_zp, w_zp, pad_code;
+  float scale;  // x_scale * w_scale, rounded to float
+};
+
+struct Options {
+  int variant;  // 0 auto, 1 direct, 2 lanes over pixels, 3 lanes over channels
+  int split_k;  // 0 auto
+};
+extern Options g_opt;
+
+// Direct kernel (ax_direct.hip): needs no workspace.
+hipError_t launch_direct(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w,
+                         const uint16_t* lut, int32_t* acc_out, float* y_out, hipStream_t s);
+
+// Table-tile kernels (ax_tab.hip).
+struct TabPlan {
+  int variant;      // 2 or 3
+  int split_k;      // number of K slices (>= 1)
+  int k_per_split;  // multiple of the kernel's K chunk
+  size_t off_rows;  // workspace offsets (bytes)
+  size_t off_bpack;
+  size_t off_bsum;
+  size_t off_apack;
+  size_t off_part;
+  size_t off_lsum;
+  size_t total;
+};
+bool tab_supported(const Geom& g);
+TabPlan tab_plan(const Geom& g, const Options& o);
+hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const uint8_t* x,
+                      const uint8_t* w, const uint16_t* lut, int32_t* acc_out, float* y_out,
+                      void* ws, hipStream_t s);
+
+}  // namespace ax

@@ -1,0 +1,159 @@
+// Measurement helpers: LDS gather micro-benchmark and a plain copy kernel.  They are not
+// part of the layer path; they measure the denominators its throughput is compared with
+// (LDS lookup rate with and without bank conflicts, HBM stream bandwidth).
+#include <random>
+#include <vector>
+
+#include "ax_internal.h"
+
+namespace ax {
+
+constexpr int kProbeSets = 8;  // independent addresses per lane, cycled through
+
+// The reads of one iteration are issued back to back, then waited for together, so that
+// each wave keeps kProbeSets gathers in flight.
+template <int WIDTH>
+__global__ __launch_bounds__(1024) void probe_lds_kernel(const uint32_t* __restrict__ offs, int iters,
+                                                          int table_bytes, uint32_t* __restrict__ sink,
+                                                          unsigned long long* __restrict__ cycles) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x, nt = blockDim.x;
+  for (int i = tid * 4; i < table_bytes; i += nt * 4) *(uint32_t*)(lds + i) = (uint32_t)i * 2654435761u;
+  __syncthreads();
+  const uint32_t base = (uint32_t)(uintptr_t)lds;
+  uint32_t a[kProbeSets];
+#pragma unroll
+  for (int j = 0; j < kProbeSets; ++j) a[j] = base + offs[(size_t)(blockIdx.x * nt + tid) * kProbeSets + j];
+  uint32_t fold = 0;
+  __syncthreads();
+  const unsigned long long t0 = clock64();
+  for (int it = 0; it < iters; ++it) {
+    if constexpr (WIDTH == 2 || WIDTH == 4) {
+      uint32_t v[kProbeSets];
+#pragma unroll
+      for (int j = 0; j < kProbeSets; ++j) {
+        if constexpr (WIDTH == 2)
+          asm volatile("ds_read_u16 %0, %1" : "=v"(v[j]) : "v"(a[j]));
+        else
+          asm volatile("ds_read_b32 %0, %1" : "=v"(v[j]) : "v"(a[j]));
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < kProbeSets; ++j) fold += v[j];
+    } else if constexpr (WIDTH == 8) {
+      uint2 v[kProbeSets];
+#pragma unroll
+      for (int j = 0; j < kProbeSets; ++j) asm volatile("ds_read_b64 %0, %1" : "=v"(v[j]) : "v"(a[j]));
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < kProbeSets; ++j) fold += v[j].x ^ v[j].y;
+    } else {
+      uint4 v[kProbeSets];
+#pragma unroll
+      for (int j = 0; j < kProbeSets; ++j) asm volatile("ds_read_b128 %0, %1" : "=v"(v[j]) : "v"(a[j]));
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < kProbeSets; ++j) fold += (v[j].x ^ v[j].y) + (v[j].z ^ v[j].w);
+    }
+  }
+  const unsigned long long t1 = clock64();
+  sink[blockIdx.x * nt + tid] = fold;
+  if (tid == 0) cycles[blockIdx.x] = t1 - t0;
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                          size_t n16) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+}  // namespace ax
+
+extern "C" int ax_probe_lds_gather(int width_bytes, int pattern, int table_bytes, int threads, int iters,
+                                   double* wave_reads, double* cycles, double* seconds, int* workgroups,
+                                   void* hip_stream) {
+  using namespace ax;
+  if (!wave_reads || !cycles || !seconds || !workgroups) return AX_ERR_NULL;
+  if (width_bytes != 2 && width_bytes != 4 && width_bytes != 8 && width_bytes != 16) return AX_ERR_OPTION;
+  if (pattern < 0 || pattern > 2 || iters < 1 || iters > (1 << 20)) return AX_ERR_OPTION;
+  if (threads < 64 || threads > 1024 || threads % 64) return AX_ERR_OPTION;
+  if (table_bytes < 1024 || table_bytes > 160 * 1024 || table_bytes % 1024) return AX_ERR_OPTION;
+  hipStream_t s = (hipStream_t)hip_stream;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return AX_ERR_HIP;
+  const int wgs = prop.multiProcessorCount;
+  const size_t nthreads = (size_t)wgs * threads;
+  const uint32_t elems = (uint32_t)(table_bytes / width_bytes);
+
+  std::vector<uint32_t> h(nthreads * kProbeSets);
+  std::mt19937 rng(12345u + 7u * (uint32_t)pattern + (uint32_t)width_bytes);
+  for (size_t t = 0; t < nthreads; ++t) {
+    const uint32_t lane = (uint32_t)(t % (size_t)threads);
+    for (int j = 0; j < kProbeSets; ++j) {
+      uint32_t e;
+      if (pattern == 0) {
+        e = (lane + 64u * (uint32_t)j) % elems;
+      } else {
+        e = rng() % elems;
+        if (pattern == 2 && (rng() & 1u)) e = 0;
+      }
+      h[t * kProbeSets + j] = e * (uint32_t)width_bytes;
+    }
+  }
+  uint32_t *d_offs = nullptr, *d_sink = nullptr;
+  unsigned long long* d_cyc = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = AX_ERR_HIP;
+  std::vector<unsigned long long> hc(wgs);
+  float ms = 0.f;
+  double csum = 0;
+  do {
+    if (hipMalloc(&d_offs, h.size() * 4) != hipSuccess) break;
+    if (hipMalloc(&d_sink, nthreads * 4) != hipSuccess) break;
+    if (hipMalloc(&d_cyc, (size_t)wgs * 8) != hipSuccess) break;
+    if (hipMemcpyAsync(d_offs, h.data(), h.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess) break;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) break;
+    void (*kern)(const uint32_t*, int, int, uint32_t*, unsigned long long*) =
+        width_bytes == 2   ? probe_lds_kernel<2>
+        : width_bytes == 4 ? probe_lds_kernel<4>
+        : width_bytes == 8 ? probe_lds_kernel<8>
+                           : probe_lds_kernel<16>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, table_bytes) != hipSuccess)
+      break;
+    // one untimed launch (code load, clocks), then the timed one
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(threads), table_bytes, s, d_offs, 4, table_bytes, d_sink, d_cyc);
+    if (hipEventRecord(e0, s) != hipSuccess) break;
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(threads), table_bytes, s, d_offs, iters, table_bytes, d_sink, d_cyc);
+    if (hipGetLastError() != hipSuccess) break;
+    if (hipEventRecord(e1, s) != hipSuccess) break;
+    if (hipMemcpyAsync(hc.data(), d_cyc, (size_t)wgs * 8, hipMemcpyDeviceToHost, s) != hipSuccess) break;
+    if (hipStreamSynchronize(s) != hipSuccess) break;
+    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) break;
+    for (int i = 0; i < wgs; ++i) csum += (double)hc[i];
+    rc = AX_OK;
+  } while (0);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (d_offs) (void)hipFree(d_offs);
+  if (d_sink) (void)hipFree(d_sink);
+  if (d_cyc) (void)hipFree(d_cyc);
+  if (rc != AX_OK) return rc;
+  *wave_reads = (double)iters * kProbeSets * (threads / 64);
+  *cycles = csum / wgs;
+  *seconds = ms * 1e-3;
+  *workgroups = wgs;
+  return AX_OK;
+}
+
+extern "C" int ax_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (!dst || !src) return AX_ERR_NULL;
+  if (bytes == 0 || bytes % 16 || ((uintptr_t)dst | (uintptr_t)src) % 16) return AX_ERR_ALIGN;
+  const size_t n16 = bytes / 16;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(ax::probe_copy_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                     (uint4*)dst, (const uint4*)src, n16);
+  return hipGetLastError() == hipSuccess ? AX_OK : AX_ERR_HIP;
+}
