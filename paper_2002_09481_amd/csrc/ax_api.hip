@@ -75,7 +75,7 @@ static size_t workspace_for(const Geom& g) {
   if (!tab_supported(g)) return 256;
   size_t need = 256;
   for (int v = 2; v <= 3; ++v) {
-    Options o = {v, 0};
+    Options o = {v, g_opt.split_k};
     const size_t t = tab_plan(g, o).total;
     if (t > need) need = t;
   }

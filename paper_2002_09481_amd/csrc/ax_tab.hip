@@ -1,8 +1,530 @@
-// placeholder until the table-tile kernels land
+// Table-tile kernels: the LDS-resident, wide-gather formulation of the lookup-MAC loop.
+//
+// The layer is acc[i][j] = sum_k LUT(A[i][k], B[k][j])  (Sec. II Eq. (3) with the product
+// taken from the truth table; Sec. III "matrix multiplication phase").  One operand is put
+// on the lanes (index i, one or more elements per lane), the other on small per-step
+// tables (index j):
+//
+//   for a tap k and a group of 8 columns j..j+7, the workgroup builds in LDS a table of 256
+//   entries of 16 bytes, entry v = the eight 16-bit products LUT(v, B[k][j..j+7]);
+//   every lane then fetches entry A[i][k] with ONE 16-byte LDS read and adds its eight
+//   halves to eight int32 accumulators.
+//
+// So a lookup-MAC costs 2 bytes of LDS read bandwidth and one integer add, instead of one
+// conflict-prone 2-byte gather per MAC.  The 128 kB truth table itself stays in L2: the
+// tables are assembled from a row-major re-layout of it ("rows": for each code of the
+// table-side operand the 256 products against every lane-side code, 512 contiguous bytes),
+// read with coalesced global loads that do not compete with the LDS gathers.
+//
+// Two lane assignments share the kernel:
+//   variant 2  lanes = output pixels   (A = im2col view of x, B = filters, rows = LUT^T)
+//   variant 3  lanes = output channels (A = filters^T, B = im2col(x)^T, rows = LUT)
+// The K loop can be cut into slices (grid.z); partial sums are then combined by a small
+// reduction kernel (integer addition is associative, so the result is the same bits).
+#include <algorithm>
+#include <cmath>
+
 #include "ax_internal.h"
+
 namespace ax {
-bool tab_supported(const Geom&) { return false; }
-TabPlan tab_plan(const Geom&, const Options&) { TabPlan p{}; p.total = 256; return p; }
-hipError_t launch_tab(const Geom&, const QParams&, const TabPlan&, const uint8_t*, const uint8_t*, const uint16_t*,
-                      int32_t*, float*, void*, hipStream_t) { return hipErrorNotSupported; }
+
+constexpr int kThreads = 512;  // 8 waves: 2 per SIMD, up to 256 VGPRs each
+constexpr int kChunk = 16;     // taps per 16-byte lane-operand load
+
+struct TabArgs {
+  // lane-side operand, addressed as an implicit im2col view of an [N,H,W,Cin] tensor
+  const uint8_t* A;
+  int I;  // valid lane elements
+  int H, W, Cin, KW, sh, sw, ph, pw, OHW, OW;
+  uint32_t pad4;  // pad code in all four bytes
+  // table-side operand, packed [Krows][Jpad] with zero fill
+  const uint8_t* Bp;
+  int Jpad, J;
+  const int32_t* bsum;   // [Jpad] column sums of Bp over k < K
+  const uint16_t* rows;  // re-laid-out truth table, 256 rows of 512 bytes
+  int K, k_per_split;
+  int z_lane, z_tab;
+  long long kzz;  // K * z_lane * z_tab
+  float scale;
+  int32_t* acc_out;
+  float* y_out;
+  int32_t* part;  // [split][out_elems] partial accumulators (split mode)
+  int32_t* lsum;  // [split][I] partial lane-operand sums   (split mode)
+  long long out_elems;
+};
+
+__device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
+  const uint32_t w = (kk < 4) ? v.x : (kk < 8) ? v.y : (kk < 12) ? v.z : v.w;
+  return (w >> (8 * (kk & 3))) & 0xffu;
 }
+
+// P lane elements per thread, NG table groups (8 columns each) per workgroup.
+// CH: lanes are output channels (output index j*I + i) instead of pixels (i*J + j).
+// SPLIT: write partial sums instead of final outputs.
+// WIDE: K > 16384, the correction needs 64-bit arithmetic.
+template <int P, int NG, bool CH, bool SPLIT, bool WIDE>
+__global__ __launch_bounds__(kThreads) void tab_kernel(const TabArgs a) {
+  constexpr int JT = NG * 8;
+  constexpr int IT = P * kThreads;
+  constexpr int UNITS = NG / 4;  // half-tables built per wave per step
+  static_assert(NG == 4 || NG == 8, "8 waves build NG tables of two halves each");
+
+  __shared__ uint4 tab[2][NG][256];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i0 = blockIdx.x * IT;
+  const int j0 = blockIdx.y * JT;
+  const int kbeg = blockIdx.z * a.k_per_split;
+  const int kend = min(a.K, kbeg + a.k_per_split);
+
+  // ---- lane elements -------------------------------------------------------------------
+  int li[P], by[P], bx[P], nb[P];
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    li[p] = i0 + p * kThreads + tid;
+    const int i = min(li[p], a.I - 1);
+    const int n = i / a.OHW;
+    const int r = i - n * a.OHW;
+    const int oy = r / a.OW;
+    const int ox = r - oy * a.OW;
+    by[p] = oy * a.sh - a.ph;
+    bx[p] = ox * a.sw - a.pw;
+    nb[p] = n * a.H;
+  }
+  auto load_chunk = [&](int k0, uint4 (&v)[P]) {
+    const int tap = k0 / a.Cin;
+    const int ci0 = k0 - tap * a.Cin;
+    const int ky = tap / a.KW;
+    const int kx = tap - ky * a.KW;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      const int iy = by[p] + ky, ix = bx[p] + kx;
+      const bool inside = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+      const uint32_t off = ((uint32_t)(nb[p] + iy) * (uint32_t)a.W + (uint32_t)ix) * (uint32_t)a.Cin + (uint32_t)ci0;
+      v[p] = make_uint4(a.pad4, a.pad4, a.pad4, a.pad4);
+      if (inside) v[p] = *reinterpret_cast<const uint4*>(a.A + off);
+    }
+  };
+
+  // ---- table building ------------------------------------------------------------------
+  const int g_build = wave % NG;
+  const int h_base = (wave / NG) * UNITS;
+  const uint8_t* bcol = a.Bp + j0 + 8 * g_build;
+  uint32_t d[UNITS][8];
+  // The eight table-side codes of a step are wave-uniform: they are fetched with scalar
+  // loads, a whole chunk ahead, so that no step waits for them.
+  auto load_codes = [&](int k) { return *reinterpret_cast<const uint2*>(bcol + (size_t)k * a.Jpad); };
+  auto build_issue = [&](const uint2 tv) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const uint32_t b = ((c < 4 ? tv.x : tv.y) >> (8 * (c & 3))) & 0xffu;
+      const uint32_t* rp = reinterpret_cast<const uint32_t*>(a.rows + b * 256u);
+#pragma unroll
+      for (int u = 0; u < UNITS; ++u) d[u][c] = rp[lane + 64 * (h_base + u)];
+    }
+  };
+  auto build_commit = [&](int buf) {
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) {
+      uint4 lo, hi;
+      lo.x = __builtin_amdgcn_perm(d[u][1], d[u][0], 0x05040100u);
+      lo.y = __builtin_amdgcn_perm(d[u][3], d[u][2], 0x05040100u);
+      lo.z = __builtin_amdgcn_perm(d[u][5], d[u][4], 0x05040100u);
+      lo.w = __builtin_amdgcn_perm(d[u][7], d[u][6], 0x05040100u);
+      hi.x = __builtin_amdgcn_perm(d[u][1], d[u][0], 0x07060302u);
+      hi.y = __builtin_amdgcn_perm(d[u][3], d[u][2], 0x07060302u);
+      hi.z = __builtin_amdgcn_perm(d[u][5], d[u][4], 0x07060302u);
+      hi.w = __builtin_amdgcn_perm(d[u][7], d[u][6], 0x07060302u);
+      const int e = lane + 64 * (h_base + u);
+      tab[buf][g_build][e] = lo;
+      tab[buf][g_build][e + 128] = hi;
+    }
+  };
+
+  // ---- main loop -----------------------------------------------------------------------
+  uint32_t acc[P][JT];
+  uint32_t sl[P];
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    sl[p] = 0;
+#pragma unroll
+    for (int j = 0; j < JT; ++j) acc[p][j] = 0;
+  }
+
+  uint4 xa[P], xn[P];
+  const int nchunks = (kend - kbeg + kChunk - 1) / kChunk;
+  if (nchunks > 0) {
+    load_chunk(kbeg, xn);
+    build_issue(load_codes(kbeg));
+    build_commit(0);
+  }
+  __syncthreads();
+  uint2 tv_cur[kChunk], tv_nxt[kChunk];  // codes of steps k0+1 .. k0+16 (row K exists: zero fill)
+  const int klast = ((a.K + kChunk - 1) / kChunk) * kChunk;  // last row of Bp
+#pragma unroll
+  for (int kk = 0; kk < kChunk; ++kk) tv_nxt[kk] = load_codes(min(kbeg + kk + 1, klast));
+  for (int c = 0; c < nchunks; ++c) {
+    const int k0 = kbeg + c * kChunk;
+    const int klen = min(kChunk, kend - k0);
+#pragma unroll
+    for (int p = 0; p < P; ++p) xa[p] = xn[p];
+#pragma unroll
+    for (int kk = 0; kk < kChunk; ++kk) tv_cur[kk] = tv_nxt[kk];
+    if (c + 1 < nchunks) {
+      load_chunk(k0 + kChunk, xn);
+#pragma unroll
+      for (int kk = 0; kk < kChunk; ++kk) tv_nxt[kk] = load_codes(min(k0 + kChunk + kk + 1, klast));
+    }
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      sl[p] = __builtin_amdgcn_sad_u8(xa[p].x, 0u, sl[p]);
+      sl[p] = __builtin_amdgcn_sad_u8(xa[p].y, 0u, sl[p]);
+      sl[p] = __builtin_amdgcn_sad_u8(xa[p].z, 0u, sl[p]);
+      sl[p] = __builtin_amdgcn_sad_u8(xa[p].w, 0u, sl[p]);
+    }
+#pragma unroll
+    for (int kk = 0; kk < kChunk; ++kk) {
+      if (kk < klen) {  // uniform
+        build_issue(tv_cur[kk]);  // table of step k0+kk+1
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+          const uint32_t v = byte_of(xa[p], kk);
+          const uint4* tp = &tab[kk & 1][0][v];
+#pragma unroll
+          for (int g = 0; g < NG; ++g) {
+            const uint4 e = tp[g * 256];
+            acc[p][g * 8 + 0] += e.x & 0xffffu;
+            acc[p][g * 8 + 1] += e.x >> 16;
+            acc[p][g * 8 + 2] += e.y & 0xffffu;
+            acc[p][g * 8 + 3] += e.y >> 16;
+            acc[p][g * 8 + 4] += e.z & 0xffffu;
+            acc[p][g * 8 + 5] += e.z >> 16;
+            acc[p][g * 8 + 6] += e.w & 0xffffu;
+            acc[p][g * 8 + 7] += e.w >> 16;
+          }
+        }
+        build_commit((kk + 1) & 1);
+        __syncthreads();
+      }
+    }
+  }
+
+  // ---- epilogue ------------------------------------------------------------------------
+  if constexpr (SPLIT) {
+    int32_t* part = a.part + (size_t)blockIdx.z * a.out_elems;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      const int i = li[p];
+      if (i >= a.I) continue;
+      if (blockIdx.y == 0) a.lsum[(size_t)blockIdx.z * a.I + i] = (int32_t)sl[p];
+#pragma unroll
+      for (int j = 0; j < JT; ++j) {
+        if (j0 + j < a.J) {
+          const size_t o = CH ? (size_t)(j0 + j) * a.I + i : (size_t)i * a.J + (j0 + j);
+          part[o] = (int32_t)acc[p][j];
+        }
+      }
+    }
+  } else {
+    // corr = acc - z_tab*Sl - z_lane*Sb[j] + K*z_lane*z_tab.  Each of the four terms is below
+    // 2^31 in magnitude; for K <= 16384 so is every partial sum, and 32-bit wrap-around
+    // arithmetic is exact.  Longer K takes the 64-bit form.
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      const int i = li[p];
+      if (i >= a.I) continue;
+      const uint32_t lterm = (uint32_t)a.z_tab * sl[p];
+#pragma unroll
+      for (int j = 0; j < JT; ++j) {
+        if (j0 + j < a.J) {
+          const size_t o = CH ? (size_t)(j0 + j) * a.I + i : (size_t)i * a.J + (j0 + j);
+          if (a.acc_out) a.acc_out[o] = (int32_t)acc[p][j];
+          if (a.y_out) {
+            const long long cj64 = a.kzz - (long long)a.z_lane * a.bsum[j0 + j];  // uniform
+            if constexpr (WIDE) {
+              const long long corr = (long long)(int32_t)(acc[p][j] - lterm) + cj64;
+              a.y_out[o] = (float)corr * a.scale;
+            } else {
+              const int32_t corr = (int32_t)(acc[p][j] - lterm + (uint32_t)cj64);
+              a.y_out[o] = (float)corr * a.scale;
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// Combine the K slices: out = sum of partials, then the correction and dequantization.
+template <bool CH>
+__global__ __launch_bounds__(256) void tab_reduce_kernel(const TabArgs a, int nsplit) {
+  const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (o >= a.out_elems) return;
+  int i, j;
+  if (CH) {
+    j = (int)(o / a.I);
+    i = (int)(o - (long long)j * a.I);
+  } else {
+    i = (int)(o / a.J);
+    j = (int)(o - (long long)i * a.J);
+  }
+  uint32_t acc = 0, sl = 0;
+  for (int s = 0; s < nsplit; ++s) {
+    acc += (uint32_t)a.part[(size_t)s * a.out_elems + o];
+    sl += (uint32_t)a.lsum[(size_t)s * a.I + i];
+  }
+  if (a.acc_out) a.acc_out[o] = (int32_t)acc;
+  if (a.y_out) {
+    const long long corr =
+        (long long)acc - (long long)a.z_tab * sl - (long long)a.z_lane * a.bsum[j] + a.kzz;
+    a.y_out[o] = (float)corr * a.scale;
+  }
+}
+
+// ---- operand preparation ---------------------------------------------------------------
+
+// rows[t][2P] = R[t][P], rows[t][2P+1] = R[t][P+128]  (P < 128), where R[t][v] is the
+// product of table-side code t and lane-side code v.  A lane that loads dword P of a row
+// gets the entries for v = P and v = P + 128, so consecutive lanes later write consecutive
+// 16-byte table entries (no LDS write conflicts).
+__global__ __launch_bounds__(512) void prep_rows_kernel(const uint16_t* __restrict__ lut,
+                                                         uint32_t* __restrict__ rows32, int lanes_are_channels) {
+  const int dw = blockIdx.x * 512 + threadIdx.x;  // 0 .. 32767
+  const int t = dw >> 7, P = dw & 127;
+  uint32_t lo, hi;
+  if (lanes_are_channels) {  // table side = activation code t, lane side = filter code v
+    lo = lut[t * 256 + P];
+    hi = lut[t * 256 + P + 128];
+  } else {  // table side = filter code t, lane side = activation code v
+    lo = lut[P * 256 + t];
+    hi = lut[(P + 128) * 256 + t];
+  }
+  rows32[dw] = lo | (hi << 16);
+}
+
+struct ConvView {  // im2col addressing of x
+  const uint8_t* x;
+  int H, W, Cin, KW, sh, sw, ph, pw, OH, OW, M, K, pad_code;
+};
+
+__device__ __forceinline__ uint32_t im2col_code(const ConvView& v, int m, int k) {
+  const int ohw = v.OH * v.OW;
+  const int n = m / ohw;
+  const int r = m - n * ohw;
+  const int oy = r / v.OW, ox = r - (r / v.OW) * v.OW;
+  const int tap = k / v.Cin, ci = k - tap * v.Cin;
+  const int ky = tap / v.KW, kx = tap - ky * v.KW;
+  const int iy = oy * v.sh - v.ph + ky, ix = ox * v.sw - v.pw + kx;
+  if ((unsigned)iy >= (unsigned)v.H || (unsigned)ix >= (unsigned)v.W) return (uint32_t)v.pad_code;
+  return v.x[((size_t)(n * v.H + iy) * v.W + ix) * v.Cin + ci];
+}
+
+// Pack the table-side operand into Bp[krows][Jpad] (zero fill outside k < K, j < J) and sum
+// its columns.  One block per 64 columns; thread = (4 columns, one of 64 row phases).
+// FROM_X: B[k][j] = im2col(x)[j][k] (lanes are channels) else B[k][j] = w[k*J + j].
+template <bool FROM_X>
+__global__ __launch_bounds__(1024) void prep_pack_kernel(const uint8_t* __restrict__ w, ConvView cv, int K, int J,
+                                                          int krows, int Jpad, uint8_t* __restrict__ Bp,
+                                                          int32_t* __restrict__ bsum) {
+  __shared__ int32_t red[64][65];
+  const int c4 = threadIdx.x & 15, r = threadIdx.x >> 4;
+  const int j = blockIdx.x * 64 + c4 * 4;
+  int32_t s[4] = {0, 0, 0, 0};
+  for (int k = r; k < krows; k += 64) {
+    uint32_t pk = 0;
+    if (k < K) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        uint32_t b = 0;
+        if (j + e < J) b = FROM_X ? im2col_code(cv, j + e, k) : (uint32_t)w[(size_t)k * J + j + e];
+        s[e] += (int32_t)b;
+        pk |= b << (8 * e);
+      }
+    }
+    *reinterpret_cast<uint32_t*>(Bp + (size_t)k * Jpad + j) = pk;
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) red[r][c4 * 4 + e] = s[e];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    int32_t t = 0;
+    for (int q = 0; q < 64; ++q) t += red[q][threadIdx.x];
+    bsum[blockIdx.x * 64 + threadIdx.x] = t;
+  }
+}
+
+// Materialized im2col, Ap[m][Kp] (zero fill for k >= K): used when the implicit view cannot be
+// read in aligned 16-byte pieces (Cin not a multiple of 16, or a misaligned base pointer).
+__global__ __launch_bounds__(256) void prep_im2col_kernel(ConvView cv, int Kp, uint8_t* __restrict__ Ap) {
+  const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int kq = Kp / 4;
+  if (q >= (long long)cv.M * kq) return;
+  const int m = (int)(q / kq);
+  const int k = (int)(q - (long long)m * kq) * 4;
+  uint32_t pk = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (k + e < cv.K) pk |= im2col_code(cv, m, k + e) << (8 * e);
+  *reinterpret_cast<uint32_t*>(Ap + (size_t)m * Kp + k) = pk;
+}
+
+// Ap[j][k] = w[k][j] (zero fill for k >= K), 64x64 tiles through LDS.
+__global__ __launch_bounds__(256) void prep_transpose_kernel(const uint8_t* __restrict__ w, int K, int J, int Kp,
+                                                              uint8_t* __restrict__ Ap) {
+  __shared__ uint8_t tile[64][68];
+  const int k0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  const int t = threadIdx.x;
+  {
+    const int r = t >> 2, seg = (t & 3) * 16;
+    const int k = k0 + r;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int j = j0 + seg + e;
+      tile[r][seg + e] = (k < K && j < J) ? w[(size_t)k * J + j] : (uint8_t)0;
+    }
+  }
+  __syncthreads();
+  {
+    const int c = t >> 2, seg = (t & 3) * 16;
+    const int j = j0 + c;
+    if (j < J && k0 + seg < Kp) {
+      uint32_t pk[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) pk[e >> 2] |= (uint32_t)tile[seg + e][c] << (8 * (e & 3));
+      *reinterpret_cast<uint4*>(Ap + (size_t)j * Kp + k0 + seg) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+    }
+  }
+}
+
+// ---- host side -------------------------------------------------------------------------
+
+static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+constexpr int kP = 2, kNG = 8;
+constexpr int kIT = kP * kThreads, kJT = kNG * 8;
+
+bool tab_supported(const Geom&) { return true; }
+
+static double padded_work(long long I, long long J) {
+  return (double)cdiv(I, kIT) * kIT * (double)cdiv(J, kJT) * kJT;
+}
+
+TabPlan tab_plan(const Geom& g, const Options& o) {
+  TabPlan p{};
+  int v = o.variant;
+  if (v != 2 && v != 3) v = padded_work(g.M, g.Cout) <= padded_work(g.Cout, g.M) ? 2 : 3;
+  p.variant = v;
+  const long long I = (v == 2) ? g.M : g.Cout;
+  const long long J = (v == 2) ? g.Cout : g.M;
+  const int tiles = cdiv(I, kIT) * cdiv(J, kJT);
+  const int nchunks = cdiv(g.K, kChunk);
+  int S = o.split_k;
+  if (S <= 0) {
+    // Fill the 256 compute units: pick the slice count with the best machine occupancy,
+    // charging a little for every extra slice (partial sums are written and re-read).
+    const int smax = (int)std::max(1LL, std::min<long long>(64, nchunks / 4));
+    double best = 1e30;
+    S = 1;
+    for (int s = 1; s <= smax; ++s) {
+      const double wgs = (double)tiles * s;
+      const double eff = wgs / (std::ceil(wgs / 256.0) * 256.0);
+      const double cost = 1.0 / eff + 0.03 * (s - 1);
+      if (cost < best - 1e-9) { best = cost; S = s; }
+    }
+  }
+  S = std::max(1, std::min(S, nchunks));
+  p.k_per_split = cdiv(nchunks, S) * kChunk;
+  p.split_k = cdiv(g.K, p.k_per_split);
+
+  const size_t Kp = (size_t)nchunks * kChunk;
+  const size_t Jpad = (size_t)cdiv(J, kJT) * kJT;
+  size_t off = 0;
+  p.off_rows = off;   off += up256(131072);
+  p.off_bpack = off;  off += up256((Kp + 1) * Jpad);
+  p.off_bsum = off;   off += up256(Jpad * 4);
+  p.off_apack = off;  off += up256((size_t)I * Kp);  // only used when the lane operand is materialized
+  p.off_lsum = off;   off += up256((size_t)p.split_k * I * 4);
+  p.off_part = off;
+  if (p.split_k > 1) off += up256((size_t)p.split_k * (size_t)g.M * g.Cout * 4);
+  p.total = off;
+  return p;
+}
+
+template <bool CH>
+static void launch_main(const TabArgs& a, dim3 grid, bool split, hipStream_t s) {
+  if (split)
+    hipLaunchKernelGGL((tab_kernel<kP, kNG, CH, true, false>), grid, dim3(kThreads), 0, s, a);
+  else if (a.K > 16384)
+    hipLaunchKernelGGL((tab_kernel<kP, kNG, CH, false, true>), grid, dim3(kThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL((tab_kernel<kP, kNG, CH, false, false>), grid, dim3(kThreads), 0, s, a);
+}
+
+hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const uint8_t* x, const uint8_t* w,
+                      const uint16_t* lut, int32_t* acc_out, float* y_out, void* ws, hipStream_t s) {
+  uint8_t* wsb = static_cast<uint8_t*>(ws);
+  const bool ch = (p.variant == 3);
+  const int I = ch ? g.Cout : g.M;
+  const int J = ch ? g.M : g.Cout;
+  const int nchunks = cdiv(g.K, kChunk);
+  const int Kp = nchunks * kChunk;
+  const int Jpad = cdiv(J, kJT) * kJT;
+  uint16_t* rows = reinterpret_cast<uint16_t*>(wsb + p.off_rows);
+  uint8_t* Bp = wsb + p.off_bpack;
+  int32_t* bsum = reinterpret_cast<int32_t*>(wsb + p.off_bsum);
+  uint8_t* Ap = wsb + p.off_apack;
+
+  ConvView cv{x, g.H, g.W, g.Cin, g.KW, g.sh, g.sw, g.ph, g.pw, g.OH, g.OW, g.M, g.K, qp.pad_code};
+
+  hipLaunchKernelGGL(prep_rows_kernel, dim3(64), dim3(512), 0, s, lut, reinterpret_cast<uint32_t*>(rows), ch ? 1 : 0);
+  if (ch)
+    hipLaunchKernelGGL((prep_pack_kernel<true>), dim3(Jpad / 64), dim3(1024), 0, s, w, cv, g.K, J, Kp + 1, Jpad, Bp, bsum);
+  else
+    hipLaunchKernelGGL((prep_pack_kernel<false>), dim3(Jpad / 64), dim3(1024), 0, s, w, cv, g.K, J, Kp + 1, Jpad, Bp, bsum);
+
+  TabArgs a{};
+  a.I = I;
+  if (ch) {
+    hipLaunchKernelGGL(prep_transpose_kernel, dim3(cdiv(Kp, 64), cdiv(g.Cout, 64)), dim3(256), 0, s, w, g.K,
+                       g.Cout, Kp, Ap);
+    a.A = Ap;
+    a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
+  } else if (g.Cin % 16 == 0 && ((uintptr_t)x & 15) == 0) {
+    a.A = x;
+    a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.KW = g.KW; a.sh = g.sh; a.sw = g.sw; a.ph = g.ph; a.pw = g.pw;
+    a.OHW = g.OH * g.OW; a.OW = g.OW;
+  } else {
+    const long long quads = (long long)g.M * (Kp / 4);
+    hipLaunchKernelGGL(prep_im2col_kernel, dim3((unsigned)cdiv(quads, 256)), dim3(256), 0, s, cv, Kp, Ap);
+    a.A = Ap;
+    a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
+  }
+  a.pad4 = (uint32_t)qp.pad_code * 0x01010101u;
+  a.Bp = Bp; a.Jpad = Jpad; a.J = J; a.bsum = bsum; a.rows = rows;
+  a.K = g.K; a.k_per_split = p.k_per_split;
+  a.z_lane = ch ? qp.w_zp : qp.x_zp;
+  a.z_tab = ch ? qp.x_zp : qp.w_zp;
+  a.kzz = (long long)g.K * qp.x_zp * qp.w_zp;
+  a.scale = qp.scale;
+  a.acc_out = acc_out; a.y_out = y_out;
+  a.part = reinterpret_cast<int32_t*>(wsb + p.off_part);
+  a.lsum = reinterpret_cast<int32_t*>(wsb + p.off_lsum);
+  a.out_elems = (long long)g.M * g.Cout;
+
+  const dim3 grid(cdiv(I, kIT), Jpad / kJT, p.split_k);
+  const bool split = p.split_k > 1;
+  if (ch) launch_main<true>(a, grid, split, s); else launch_main<false>(a, grid, split, s);
+  if (split) {
+    const unsigned blocks = (unsigned)cdiv(a.out_elems, 256);
+    if (ch)
+      hipLaunchKernelGGL((tab_reduce_kernel<true>), dim3(blocks), dim3(256), 0, s, a, p.split_k);
+    else
+      hipLaunchKernelGGL((tab_reduce_kernel<false>), dim3(blocks), dim3(256), 0, s, a, p.split_k);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace ax
