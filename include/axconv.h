@@ -104,6 +104,8 @@ int ax_version(void);
  *              2 = table-tile kernel, lanes over output pixels
  *              3 = table-tile kernel, lanes over output channels
  *   "split_k"  0 = choose automatically, n >= 1 = force n slices of the K loop
+ *   "tile"     index of the table-tile configuration (threads, lane elements per thread,
+ *              table groups, taps per barrier); 0 = default
  * Returns AX_OK or AX_ERR_OPTION.  Not thread safe with respect to concurrent calls.
  */
 int ax_set_option(const char* name, int value);
@@ -125,6 +127,16 @@ int ax_get_option(const char* name, int* value);
 int ax_probe_lds_gather(int width_bytes, int pattern, int table_bytes, int threads, int iters,
                         double* wave_reads, double* cycles, double* seconds, int* workgroups,
                         void* hip_stream);
+
+/*
+ * Instruction-mix micro-benchmark.  mode 0: independent integer adds only (ops = lane adds);
+ * modes 1..4: the inner loop of the table-tile kernels without table building or barriers,
+ * for (threads, lane elements per thread, table groups) = (512,2,8), (1024,1,8), (512,4,4),
+ * (1024,2,4) (ops = lookup-MACs).  pattern 1: uniform random codes, 2: half of the codes zero.
+ * Allocates temporary device memory and synchronizes.  Outputs are host pointers.
+ */
+int ax_probe_mac(int mode, int pattern, int iters, int wgs_per_cu, double* ops, double* seconds,
+                 void* hip_stream);
 
 /* Plain device-to-device copy kernel of `bytes` (multiple of 16), for the HBM roofline and
  * for calibrating memory-traffic counters.  Asynchronous. */

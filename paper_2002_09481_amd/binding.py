@@ -37,7 +37,7 @@ class ax_quant_t(ctypes.Structure):
 
 EXPORTS = [
     "ax_conv2d", "ax_conv2d_workspace_bytes", "ax_dense", "ax_dense_workspace_bytes", "ax_strerror",
-    "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy",
+    "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac",
 ]
 
 
@@ -71,6 +71,8 @@ def lib():
     dp = ctypes.POINTER(ctypes.c_double)
     L.ax_probe_lds_gather.argtypes = [ci, ci, ci, ci, ci, dp, dp, dp, ctypes.POINTER(ci), vp]
     L.ax_probe_lds_gather.restype = ci
+    L.ax_probe_mac.argtypes = [ci, ci, ci, ci, dp, dp, vp]
+    L.ax_probe_mac.restype = ci
     L.ax_probe_copy.argtypes = [vp, vp, sz, vp]
     L.ax_probe_copy.restype = ci
     _lib = L
@@ -228,6 +230,13 @@ def ax_probe_lds_gather(width_bytes: int, pattern: int, table_bytes: int, thread
                                    ctypes.c_void_p(_stream_ptr(stream)))
     _check(rc)
     return {"wave_reads": wr.value, "cycles": cy.value, "seconds": sec.value, "workgroups": wgs.value}
+
+
+def ax_probe_mac(mode: int, pattern: int = 1, iters: int = 200, wgs_per_cu: int = 1, stream=None) -> dict:
+    ops, sec = ctypes.c_double(), ctypes.c_double()
+    _check(lib().ax_probe_mac(mode, pattern, iters, wgs_per_cu, ctypes.byref(ops), ctypes.byref(sec),
+                              ctypes.c_void_p(_stream_ptr(stream))))
+    return {"ops": ops.value, "seconds": sec.value, "ops_per_s": ops.value / sec.value}
 
 
 def ax_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

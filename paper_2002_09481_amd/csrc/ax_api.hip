@@ -6,7 +6,7 @@
 
 namespace ax {
 
-Options g_opt = {0, 0};
+Options g_opt = {0, 0, 0};
 
 static int make_quant(const ax_quant_t* q, QParams* qp) {
   if (!q) return AX_ERR_NULL;
@@ -75,7 +75,7 @@ static size_t workspace_for(const Geom& g) {
   if (!tab_supported(g)) return 256;
   size_t need = 256;
   for (int v = 2; v <= 3; ++v) {
-    Options o = {v, g_opt.split_k};
+    Options o = {v, g_opt.split_k, g_opt.tile};
     const size_t t = tab_plan(g, o).total;
     if (t > need) need = t;
   }
@@ -147,6 +147,11 @@ extern "C" int ax_set_option(const char* name, int value) {
     g_opt.split_k = value;
     return AX_OK;
   }
+  if (!std::strcmp(name, "tile")) {
+    if (value < 0 || value >= tab_num_tiles()) return AX_ERR_OPTION;
+    g_opt.tile = value;
+    return AX_OK;
+  }
   return AX_ERR_OPTION;
 }
 
@@ -154,5 +159,6 @@ extern "C" int ax_get_option(const char* name, int* value) {
   if (!name || !value) return AX_ERR_OPTION;
   if (!std::strcmp(name, "variant")) { *value = g_opt.variant; return AX_OK; }
   if (!std::strcmp(name, "split_k")) { *value = g_opt.split_k; return AX_OK; }
+  if (!std::strcmp(name, "tile")) { *value = g_opt.tile; return AX_OK; }
   return AX_ERR_OPTION;
 }

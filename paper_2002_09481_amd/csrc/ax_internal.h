@@ -29,6 +29,7 @@ struct QParams {
 struct Options {
   int variant;  // 0 auto, 1 direct, 2 lanes over pixels, 3 lanes over channels
   int split_k;  // 0 auto
+  int tile;     // index of the table-tile configuration (0 = default)
 };
 extern Options g_opt;
 
@@ -50,6 +51,7 @@ struct TabPlan {
   size_t total;
 };
 bool tab_supported(const Geom& g);
+int tab_num_tiles();
 TabPlan tab_plan(const Geom& g, const Options& o);
 hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const uint8_t* x,
                       const uint8_t* w, const uint16_t* lut, int32_t* acc_out, float* y_out,

@@ -68,6 +68,87 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(uint4* __restrict__ dst
   for (; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Inner loop of the table-tile kernels in isolation: per tap one 16-byte gather per table
+// group and eight adds per gather, no table building and no barrier.  It bounds what that
+// instruction mix can reach when LDS gathers and integer adds overlap perfectly.
+template <int THREADS, int P, int NG>
+__global__ __launch_bounds__(THREADS) void probe_mac_kernel(const uint4* __restrict__ codes, int iters,
+                                                             uint32_t* __restrict__ sink) {
+  __shared__ uint4 tab[NG][256];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < NG * 256; i += THREADS) {
+    const uint32_t v = (uint32_t)i * 2654435761u;
+    (&tab[0][0])[i] = make_uint4(v, v ^ 0x9e3779b9u, v * 3u, v * 7u);
+  }
+  __syncthreads();
+  uint4 x[P];
+#pragma unroll
+  for (int p = 0; p < P; ++p) x[p] = codes[(size_t)(blockIdx.x * P + p) * THREADS + tid];
+  uint32_t acc[P][NG * 8];
+#pragma unroll
+  for (int p = 0; p < P; ++p)
+#pragma unroll
+    for (int j = 0; j < NG * 8; ++j) acc[p][j] = 0;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+#pragma unroll
+      for (int p = 0; p < P; ++p) {
+        const uint32_t w = (kk < 4) ? x[p].x : (kk < 8) ? x[p].y : (kk < 12) ? x[p].z : x[p].w;
+        const uint32_t v = (w >> (8 * (kk & 3))) & 0xffu;
+        const uint4* tp = &tab[0][v];
+        uint4 e[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) e[g] = tp[g * 256];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+          acc[p][g * 8 + 0] += e[g].x & 0xffffu;
+          acc[p][g * 8 + 1] += e[g].x >> 16;
+          acc[p][g * 8 + 2] += e[g].y & 0xffffu;
+          acc[p][g * 8 + 3] += e[g].y >> 16;
+          acc[p][g * 8 + 4] += e[g].z & 0xffffu;
+          acc[p][g * 8 + 5] += e[g].z >> 16;
+          acc[p][g * 8 + 6] += e[g].w & 0xffffu;
+          acc[p][g * 8 + 7] += e[g].w >> 16;
+        }
+      }
+    }
+    // keep the loop from being collapsed: the codes change a little every iteration
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      x[p].x = x[p].x * 1664525u + 1013904223u;
+      x[p].y = x[p].y * 1664525u + 1013904223u;
+      x[p].z = x[p].z * 1664525u + 1013904223u;
+      x[p].w = x[p].w * 1664525u + 1013904223u;
+    }
+  }
+  uint32_t f = 0;
+#pragma unroll
+  for (int p = 0; p < P; ++p)
+#pragma unroll
+    for (int j = 0; j < NG * 8; ++j) f ^= acc[p][j];
+  sink[(size_t)blockIdx.x * THREADS + tid] = f;
+}
+
+// Integer-add throughput: independent accumulators, no memory traffic in the loop.
+__global__ __launch_bounds__(1024) void probe_valu_kernel(int iters, uint32_t* __restrict__ sink) {
+  uint32_t a[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) a[j] = threadIdx.x + j;
+  uint32_t s = blockIdx.x + 1;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int j = 0; j < 32; ++j) a[j] += (j & 1) ? (s >> 16) : (s & 0xffffu);
+    s = s * 1664525u + a[0];
+  }
+  uint32_t f = 0;
+#pragma unroll
+  for (int j = 0; j < 32; ++j) f ^= a[j];
+  sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = f;
+}
+
 }  // namespace ax
 
 extern "C" int ax_probe_lds_gather(int width_bytes, int pattern, int table_bytes, int threads, int iters,
@@ -156,4 +237,74 @@ extern "C" int ax_probe_copy(void* dst, const void* src, size_t bytes, void* hip
   hipLaunchKernelGGL(ax::probe_copy_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)hip_stream,
                      (uint4*)dst, (const uint4*)src, n16);
   return hipGetLastError() == hipSuccess ? AX_OK : AX_ERR_HIP;
+}
+
+// mode 0: probe_valu (128 adds per lane and iteration); mode 1..4: probe_mac with
+// (threads, lane elements, groups) = (512,2,8), (1024,1,8), (512,4,4), (1024,2,4).
+// pattern as in ax_probe_lds_gather (1 = uniform random codes, 2 = half of them zero).
+extern "C" int ax_probe_mac(int mode, int pattern, int iters, int wgs_per_cu, double* ops, double* seconds,
+                            void* hip_stream) {
+  using namespace ax;
+  if (!ops || !seconds) return AX_ERR_NULL;
+  if (mode < 0 || mode > 4 || pattern < 1 || pattern > 2 || iters < 1 || iters > (1 << 20) || wgs_per_cu < 1 ||
+      wgs_per_cu > 8)
+    return AX_ERR_OPTION;
+  hipStream_t s = (hipStream_t)hip_stream;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return AX_ERR_HIP;
+  const int wgs = prop.multiProcessorCount * wgs_per_cu;
+  const int threads = (mode == 0 || mode == 2 || mode == 4) ? 1024 : 512;
+  const int P = (mode == 1 || mode == 4) ? 2 : (mode == 3 ? 4 : 1);
+  const size_t lanes = (size_t)wgs * threads * P;
+  std::vector<uint4> h(lanes);
+  std::mt19937 rng(999u + (uint32_t)pattern);
+  for (size_t i = 0; i < lanes; ++i) {
+    uint32_t w[4];
+    for (int c = 0; c < 4; ++c) {
+      w[c] = rng();
+      if (pattern == 2) {
+        const uint32_t m = rng();
+        for (int b = 0; b < 4; ++b)
+          if ((m >> b) & 1u) w[c] &= ~(0xffu << (8 * b));
+      }
+    }
+    h[i] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  uint4* d_codes = nullptr;
+  uint32_t* d_sink = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = AX_ERR_HIP;
+  float ms = 0.f;
+  do {
+    if (hipMalloc(&d_codes, lanes * 16) != hipSuccess) break;
+    if (hipMalloc(&d_sink, (size_t)wgs * threads * 4) != hipSuccess) break;
+    if (hipMemcpyAsync(d_codes, h.data(), lanes * 16, hipMemcpyHostToDevice, s) != hipSuccess) break;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) break;
+    for (int rep = 0; rep < 2; ++rep) {
+      const int n = rep == 0 ? 2 : iters;
+      if (rep == 1 && hipEventRecord(e0, s) != hipSuccess) break;
+      switch (mode) {
+        case 0: hipLaunchKernelGGL(probe_valu_kernel, dim3(wgs), dim3(1024), 0, s, n, d_sink); break;
+        case 1: hipLaunchKernelGGL((probe_mac_kernel<512, 2, 8>), dim3(wgs), dim3(512), 0, s, d_codes, n, d_sink); break;
+        case 2: hipLaunchKernelGGL((probe_mac_kernel<1024, 1, 8>), dim3(wgs), dim3(1024), 0, s, d_codes, n, d_sink); break;
+        case 3: hipLaunchKernelGGL((probe_mac_kernel<512, 4, 4>), dim3(wgs), dim3(512), 0, s, d_codes, n, d_sink); break;
+        default: hipLaunchKernelGGL((probe_mac_kernel<1024, 2, 4>), dim3(wgs), dim3(1024), 0, s, d_codes, n, d_sink); break;
+      }
+    }
+    if (hipGetLastError() != hipSuccess) break;
+    if (hipEventRecord(e1, s) != hipSuccess) break;
+    if (hipStreamSynchronize(s) != hipSuccess) break;
+    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) break;
+    rc = AX_OK;
+  } while (0);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (d_codes) (void)hipFree(d_codes);
+  if (d_sink) (void)hipFree(d_sink);
+  if (rc != AX_OK) return rc;
+  const int NG = (mode == 1 || mode == 2) ? 8 : 4;
+  *ops = mode == 0 ? (double)wgs * 1024 * 128.0 * iters : (double)lanes * 16.0 * NG * 8 * iters;
+  *seconds = ms * 1e-3;
+  return AX_OK;
 }

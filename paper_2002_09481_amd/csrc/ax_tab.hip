@@ -28,7 +28,7 @@
 
 namespace ax {
 
-constexpr int kThreads = 512;  // 8 waves: 2 per SIMD, up to 256 VGPRs each
+
 constexpr int kChunk = 16;     // taps per 16-byte lane-operand load
 
 struct TabArgs {
@@ -51,6 +51,7 @@ struct TabArgs {
   int32_t* part;  // [split][out_elems] partial accumulators (split mode)
   int32_t* lsum;  // [split][I] partial lane-operand sums   (split mode)
   long long out_elems;
+  int vec_out;  // outputs may be written in aligned 16-byte pieces along j
 };
 
 __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
@@ -58,18 +59,29 @@ __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
   return (w >> (8 * (kk & 3))) & 0xffu;
 }
 
-// P lane elements per thread, NG table groups (8 columns each) per workgroup.
+// THREADS threads, P lane elements per thread, NG table groups (8 columns each) per
+// workgroup, KS taps per barrier phase.
 // CH: lanes are output channels (output index j*I + i) instead of pixels (i*J + j).
 // SPLIT: write partial sums instead of final outputs.
 // WIDE: K > 16384, the correction needs 64-bit arithmetic.
-template <int P, int NG, bool CH, bool SPLIT, bool WIDE>
-__global__ __launch_bounds__(kThreads) void tab_kernel(const TabArgs a) {
+//
+// LDS holds two phase buffers of KS*NG tables.  In every phase each wave (a) issues the
+// global loads of the table rows for the NEXT phase, (b) gathers from the current buffer and
+// accumulates, (c) interleaves the loaded rows into 16-byte entries and stores them into
+// the other buffer, (d) joins the barrier.
+template <int THREADS, int P, int NG, int KS, bool CH, bool SPLIT, bool WIDE>
+__global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
   constexpr int JT = NG * 8;
-  constexpr int IT = P * kThreads;
-  constexpr int UNITS = NG / 4;  // half-tables built per wave per step
-  static_assert(NG == 4 || NG == 8, "8 waves build NG tables of two halves each");
+  constexpr int IT = P * THREADS;
+  constexpr int WAVES = THREADS / 64;
+  constexpr int HALVES = 2 * NG * KS;  // half-tables (128 entries) to build per phase
+  constexpr int UNITS = (HALVES + WAVES - 1) / WAVES;
+  constexpr int PHASES = kChunk / KS;
+  constexpr int CODES = (UNITS + 1) / 2;  // units 2c and 2c+1 are the two halves of one table
+  static_assert(UNITS == 1 || UNITS % 2 == 0, "units of a wave must pair up");
+  static_assert(kChunk % KS == 0 && PHASES % 2 == 0, "a chunk must hold an even number of phases");
 
-  __shared__ uint4 tab[2][NG][256];
+  __shared__ uint4 tab[2][KS][NG][256];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -78,12 +90,13 @@ __global__ __launch_bounds__(kThreads) void tab_kernel(const TabArgs a) {
   const int j0 = blockIdx.y * JT;
   const int kbeg = blockIdx.z * a.k_per_split;
   const int kend = min(a.K, kbeg + a.k_per_split);
+  const int klast = ((a.K + kChunk - 1) / kChunk) * kChunk;  // last (zero) row of Bp
 
   // ---- lane elements -------------------------------------------------------------------
   int li[P], by[P], bx[P], nb[P];
 #pragma unroll
   for (int p = 0; p < P; ++p) {
-    li[p] = i0 + p * kThreads + tid;
+    li[p] = i0 + p * THREADS + tid;
     const int i = min(li[p], a.I - 1);
     const int n = i / a.OHW;
     const int r = i - n * a.OHW;
@@ -109,25 +122,41 @@ __global__ __launch_bounds__(kThreads) void tab_kernel(const TabArgs a) {
   };
 
   // ---- table building ------------------------------------------------------------------
-  const int g_build = wave % NG;
-  const int h_base = (wave / NG) * UNITS;
-  const uint8_t* bcol = a.Bp + j0 + 8 * g_build;
+  // Unit q of a phase = (tap s of the phase, table g, half h).  The eight table-side codes of
+  // a unit are wave-uniform and come through scalar loads; the rows are read with buffer
+  // loads whose scalar offset selects the row (code * 512 bytes) and whose per-lane offset
+  // selects dword `lane` (+64 for the second half): 256 contiguous bytes per wave.
+  const __amdgpu_buffer_rsrc_t rows_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.rows), 0, 131072, 0x00020000);
+  int us[UNITS], ug[UNITS], uh[UNITS];
+  bool uvalid[UNITS];
+#pragma unroll
+  for (int u = 0; u < UNITS; ++u) {
+    const int q = wave * UNITS + u;
+    uvalid[u] = q < HALVES;
+    const int qq = uvalid[u] ? q : 0;
+    us[u] = qq / (2 * NG);
+    ug[u] = (qq >> 1) % NG;
+    uh[u] = qq & 1;
+  }
   uint32_t d[UNITS][8];
-  // The eight table-side codes of a step are wave-uniform: they are fetched with scalar
-  // loads, a whole chunk ahead, so that no step waits for them.
-  auto load_codes = [&](int k) { return *reinterpret_cast<const uint2*>(bcol + (size_t)k * a.Jpad); };
-  auto build_issue = [&](const uint2 tv) {
+  auto load_codes = [&](int cu, int k) {  // codes of unit pair cu for the phase that starts at tap k
+    return *reinterpret_cast<const uint2*>(a.Bp + (size_t)min(k + us[2 * cu < UNITS ? 2 * cu : 0], klast) * a.Jpad + j0 +
+                                           8 * ug[2 * cu < UNITS ? 2 * cu : 0]);
+  };
+  auto build_issue = [&](int u, const uint2 tv) {
+    if (!uvalid[u]) return;
+    const int voff = (lane + 64 * uh[u]) * 4;
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       const uint32_t b = ((c < 4 ? tv.x : tv.y) >> (8 * (c & 3))) & 0xffu;
-      const uint32_t* rp = reinterpret_cast<const uint32_t*>(a.rows + b * 256u);
-#pragma unroll
-      for (int u = 0; u < UNITS; ++u) d[u][c] = rp[lane + 64 * (h_base + u)];
+      d[u][c] = __builtin_amdgcn_raw_buffer_load_b32(rows_rsrc, voff, (int)(b * 512u), 0);
     }
   };
   auto build_commit = [&](int buf) {
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) {
+      if (!uvalid[u]) continue;
       uint4 lo, hi;
       lo.x = __builtin_amdgcn_perm(d[u][1], d[u][0], 0x05040100u);
       lo.y = __builtin_amdgcn_perm(d[u][3], d[u][2], 0x05040100u);
@@ -137,9 +166,9 @@ __global__ __launch_bounds__(kThreads) void tab_kernel(const TabArgs a) {
       hi.y = __builtin_amdgcn_perm(d[u][3], d[u][2], 0x07060302u);
       hi.z = __builtin_amdgcn_perm(d[u][5], d[u][4], 0x07060302u);
       hi.w = __builtin_amdgcn_perm(d[u][7], d[u][6], 0x07060302u);
-      const int e = lane + 64 * (h_base + u);
-      tab[buf][g_build][e] = lo;
-      tab[buf][g_build][e + 128] = hi;
+      const int e = lane + 64 * uh[u];
+      tab[buf][us[u]][ug[u]][e] = lo;
+      tab[buf][us[u]][ug[u]][e + 128] = hi;
     }
   };
 
@@ -155,27 +184,33 @@ __global__ __launch_bounds__(kThreads) void tab_kernel(const TabArgs a) {
 
   uint4 xa[P], xn[P];
   const int nchunks = (kend - kbeg + kChunk - 1) / kChunk;
-  if (nchunks > 0) {
-    load_chunk(kbeg, xn);
-    build_issue(load_codes(kbeg));
-    build_commit(0);
-  }
-  __syncthreads();
-  uint2 tv_cur[kChunk], tv_nxt[kChunk];  // codes of steps k0+1 .. k0+16 (row K exists: zero fill)
-  const int klast = ((a.K + kChunk - 1) / kChunk) * kChunk;  // last row of Bp
+  load_chunk(kbeg, xn);
 #pragma unroll
-  for (int kk = 0; kk < kChunk; ++kk) tv_nxt[kk] = load_codes(min(kbeg + kk + 1, klast));
+  for (int u = 0; u < UNITS; ++u) build_issue(u, load_codes(u >> 1, kbeg));
+  build_commit(0);
+  __syncthreads();
+  // codes of the phases that follow: tv[u][ph] belongs to taps k0 + (ph+1)*KS ...
+  uint2 tv_cur[CODES][PHASES], tv_nxt[CODES][PHASES];
+#pragma unroll
+  for (int u = 0; u < CODES; ++u)
+#pragma unroll
+    for (int ph = 0; ph < PHASES; ++ph) tv_nxt[u][ph] = load_codes(u, kbeg + (ph + 1) * KS);
+
   for (int c = 0; c < nchunks; ++c) {
     const int k0 = kbeg + c * kChunk;
     const int klen = min(kChunk, kend - k0);
 #pragma unroll
     for (int p = 0; p < P; ++p) xa[p] = xn[p];
 #pragma unroll
-    for (int kk = 0; kk < kChunk; ++kk) tv_cur[kk] = tv_nxt[kk];
+    for (int u = 0; u < CODES; ++u)
+#pragma unroll
+      for (int ph = 0; ph < PHASES; ++ph) tv_cur[u][ph] = tv_nxt[u][ph];
     if (c + 1 < nchunks) {
       load_chunk(k0 + kChunk, xn);
 #pragma unroll
-      for (int kk = 0; kk < kChunk; ++kk) tv_nxt[kk] = load_codes(min(k0 + kChunk + kk + 1, klast));
+      for (int u = 0; u < CODES; ++u)
+#pragma unroll
+        for (int ph = 0; ph < PHASES; ++ph) tv_nxt[u][ph] = load_codes(u, k0 + kChunk + (ph + 1) * KS);
     }
 #pragma unroll
     for (int p = 0; p < P; ++p) {
@@ -185,34 +220,109 @@ __global__ __launch_bounds__(kThreads) void tab_kernel(const TabArgs a) {
       sl[p] = __builtin_amdgcn_sad_u8(xa[p].w, 0u, sl[p]);
     }
 #pragma unroll
-    for (int kk = 0; kk < kChunk; ++kk) {
-      if (kk < klen) {  // uniform
-        build_issue(tv_cur[kk]);  // table of step k0+kk+1
+    for (int ph = 0; ph < PHASES; ++ph) {
+      if (ph * KS < klen) {  // uniform
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
-          const uint32_t v = byte_of(xa[p], kk);
-          const uint4* tp = &tab[kk & 1][0][v];
+        for (int u = 0; u < UNITS; ++u) build_issue(u, tv_cur[u >> 1][ph]);
 #pragma unroll
-          for (int g = 0; g < NG; ++g) {
-            const uint4 e = tp[g * 256];
-            acc[p][g * 8 + 0] += e.x & 0xffffu;
-            acc[p][g * 8 + 1] += e.x >> 16;
-            acc[p][g * 8 + 2] += e.y & 0xffffu;
-            acc[p][g * 8 + 3] += e.y >> 16;
-            acc[p][g * 8 + 4] += e.z & 0xffffu;
-            acc[p][g * 8 + 5] += e.z >> 16;
-            acc[p][g * 8 + 6] += e.w & 0xffffu;
-            acc[p][g * 8 + 7] += e.w >> 16;
+        for (int s = 0; s < KS; ++s) {
+          if (s == 0 || ph * KS + s < klen) {
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+              const uint32_t v = byte_of(xa[p], ph * KS + s);
+              const uint4* tp = &tab[ph & 1][s][0][v];
+              uint4 e[NG];
+#pragma unroll
+              for (int g = 0; g < NG; ++g) e[g] = tp[g * 256];
+#pragma unroll
+              for (int g = 0; g < NG; ++g) {
+                acc[p][g * 8 + 0] += e[g].x & 0xffffu;
+                acc[p][g * 8 + 1] += e[g].x >> 16;
+                acc[p][g * 8 + 2] += e[g].y & 0xffffu;
+                acc[p][g * 8 + 3] += e[g].y >> 16;
+                acc[p][g * 8 + 4] += e[g].z & 0xffffu;
+                acc[p][g * 8 + 5] += e[g].z >> 16;
+                acc[p][g * 8 + 6] += e[g].w & 0xffffu;
+                acc[p][g * 8 + 7] += e[g].w >> 16;
+              }
+            }
           }
         }
-        build_commit((kk + 1) & 1);
+        build_commit((ph + 1) & 1);
         __syncthreads();
       }
     }
   }
 
   // ---- epilogue ------------------------------------------------------------------------
-  if constexpr (SPLIT) {
+  // corr = acc - z_tab*Sl - z_lane*Sb[j] + K*z_lane*z_tab.  Each of the four terms is below
+  // 2^31 in magnitude; for K <= 16384 so is every partial sum, and 32-bit wrap-around
+  // arithmetic is exact.  Longer K takes the 64-bit form.
+  auto dequant = [&](uint32_t accv, uint32_t lterm, int j) -> float {
+    const long long cj64 = a.kzz - (long long)a.z_lane * a.bsum[j];
+    if constexpr (WIDE) {
+      return (float)((long long)(int32_t)(accv - lterm) + cj64) * a.scale;
+    } else {
+      return (float)(int32_t)(accv - lterm + (uint32_t)cj64) * a.scale;
+    }
+  };
+
+  if (!CH && a.vec_out) {
+    // Lanes hold whole rows of JT consecutive outputs of one pixel.  Stage 128 pixels at a time
+    // in LDS (rows padded by 4 dwords: conflict-free 16-byte writes) and read them back so
+    // that consecutive lanes store consecutive 16-byte pieces: full-line coalesced stores.
+    constexpr int PX = 128;
+    constexpr int ROW = JT + 4;
+    constexpr int NPASS = IT / PX;
+    constexpr int PIECES = PX * (JT / 4);
+    static_assert(PX * ROW * 4 <= 2 * KS * NG * 4096, "stage must fit in the table buffers");
+    uint32_t* stage = reinterpret_cast<uint32_t*>(&tab[0][0][0][0]);
+    int32_t* part = SPLIT ? a.part + (size_t)blockIdx.z * a.out_elems : nullptr;
+#pragma unroll
+    for (int q = 0; q < NPASS; ++q) {
+      const int p_own = (q * PX) / THREADS;
+      const int t0 = q * PX - p_own * THREADS;
+      __syncthreads();
+      if (tid >= t0 && tid < t0 + PX) {
+        uint32_t* row = stage + (tid - t0) * ROW;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+          if (p == p_own) {
+#pragma unroll
+            for (int j4 = 0; j4 < JT / 4; ++j4)
+              *reinterpret_cast<uint4*>(row + 4 * j4) =
+                  make_uint4(acc[p][4 * j4], acc[p][4 * j4 + 1], acc[p][4 * j4 + 2], acc[p][4 * j4 + 3]);
+            row[JT] = sl[p];
+          }
+        }
+      }
+      __syncthreads();
+      for (int idx = tid; idx < PIECES; idx += THREADS) {
+        const int r = idx / (JT / 4), c4 = idx - r * (JT / 4);
+        const int i = i0 + q * PX + r, j = j0 + 4 * c4;
+        if (i < a.I && j < a.J) {
+          const uint4 v = *reinterpret_cast<const uint4*>(stage + r * ROW + 4 * c4);
+          const uint32_t slv = stage[r * ROW + JT];
+          const size_t o = (size_t)i * a.J + j;
+          if constexpr (SPLIT) {
+            *reinterpret_cast<uint4*>(part + o) = v;
+            if (blockIdx.y == 0 && c4 == 0) a.lsum[(size_t)blockIdx.z * a.I + i] = (int32_t)slv;
+          } else {
+            if (a.acc_out) *reinterpret_cast<uint4*>(a.acc_out + o) = v;
+            if (a.y_out) {
+              const uint32_t lterm = (uint32_t)a.z_tab * slv;
+              float4 y;
+              y.x = dequant(v.x, lterm, j);
+              y.y = dequant(v.y, lterm, j + 1);
+              y.z = dequant(v.z, lterm, j + 2);
+              y.w = dequant(v.w, lterm, j + 3);
+              *reinterpret_cast<float4*>(a.y_out + o) = y;
+            }
+          }
+        }
+      }
+    }
+  } else if constexpr (SPLIT) {
     int32_t* part = a.part + (size_t)blockIdx.z * a.out_elems;
 #pragma unroll
     for (int p = 0; p < P; ++p) {
@@ -228,9 +338,6 @@ __global__ __launch_bounds__(kThreads) void tab_kernel(const TabArgs a) {
       }
     }
   } else {
-    // corr = acc - z_tab*Sl - z_lane*Sb[j] + K*z_lane*z_tab.  Each of the four terms is below
-    // 2^31 in magnitude; for K <= 16384 so is every partial sum, and 32-bit wrap-around
-    // arithmetic is exact.  Longer K takes the 64-bit form.
 #pragma unroll
     for (int p = 0; p < P; ++p) {
       const int i = li[p];
@@ -241,16 +348,7 @@ __global__ __launch_bounds__(kThreads) void tab_kernel(const TabArgs a) {
         if (j0 + j < a.J) {
           const size_t o = CH ? (size_t)(j0 + j) * a.I + i : (size_t)i * a.J + (j0 + j);
           if (a.acc_out) a.acc_out[o] = (int32_t)acc[p][j];
-          if (a.y_out) {
-            const long long cj64 = a.kzz - (long long)a.z_lane * a.bsum[j0 + j];  // uniform
-            if constexpr (WIDE) {
-              const long long corr = (long long)(int32_t)(acc[p][j] - lterm) + cj64;
-              a.y_out[o] = (float)corr * a.scale;
-            } else {
-              const int32_t corr = (int32_t)(acc[p][j] - lterm + (uint32_t)cj64);
-              a.y_out[o] = (float)corr * a.scale;
-            }
-          }
+          if (a.y_out) a.y_out[o] = dequant(acc[p][j], lterm, j0 + j);
         }
       }
     }
@@ -403,12 +501,25 @@ __global__ __launch_bounds__(256) void prep_transpose_kernel(const uint8_t* __re
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 
-constexpr int kP = 2, kNG = 8;
-constexpr int kIT = kP * kThreads, kJT = kNG * 8;
+// Tile configurations selectable with the "tile" option (0 = default).
+struct TileCfg { int threads, P, NG, KS; };
+static const TileCfg kTiles[] = {
+    {512, 2, 8, 1},   // 0: 1024 x 64 tile, 8 waves
+    {1024, 1, 8, 1},  // 1: 1024 x 64 tile, 16 waves
+    {512, 2, 8, 2},   // 2: two taps per barrier
+    {1024, 1, 8, 2},  // 3
+    {512, 4, 4, 1},   // 4: 2048 x 32 tile
+    {512, 4, 4, 2},   // 5
+    {1024, 2, 4, 2},  // 6: 2048 x 32 tile, 16 waves
+};
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+static const TileCfg& tile_cfg() { return kTiles[(g_opt.tile >= 0 && g_opt.tile < kNumTiles) ? g_opt.tile : 0]; }
+int tab_num_tiles() { return kNumTiles; }
 
 bool tab_supported(const Geom&) { return true; }
 
 static double padded_work(long long I, long long J) {
+  const int kIT = tile_cfg().threads * tile_cfg().P, kJT = tile_cfg().NG * 8;
   return (double)cdiv(I, kIT) * kIT * (double)cdiv(J, kJT) * kJT;
 }
 
@@ -419,6 +530,7 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   p.variant = v;
   const long long I = (v == 2) ? g.M : g.Cout;
   const long long J = (v == 2) ? g.Cout : g.M;
+  const int kIT = tile_cfg().threads * tile_cfg().P, kJT = tile_cfg().NG * 8;
   const int tiles = cdiv(I, kIT) * cdiv(J, kJT);
   const int nchunks = cdiv(g.K, kChunk);
   int S = o.split_k;
@@ -440,7 +552,7 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   p.split_k = cdiv(g.K, p.k_per_split);
 
   const size_t Kp = (size_t)nchunks * kChunk;
-  const size_t Jpad = (size_t)cdiv(J, kJT) * kJT;
+  const size_t Jpad = (size_t)cdiv(J, 64) * 64;
   size_t off = 0;
   p.off_rows = off;   off += up256(131072);
   p.off_bpack = off;  off += up256((Kp + 1) * Jpad);
@@ -453,14 +565,30 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   return p;
 }
 
+template <int THREADS, int P, int NG, int KS, bool CH>
+static void launch_cfg(const TabArgs& a, dim3 grid, bool split, hipStream_t s) {
+  if (split)
+    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, CH, true, false>), grid, dim3(THREADS), 0, s, a);
+  else if (a.K > 16384)
+    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, CH, false, true>), grid, dim3(THREADS), 0, s, a);
+  else
+    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, CH, false, false>), grid, dim3(THREADS), 0, s, a);
+}
+
 template <bool CH>
 static void launch_main(const TabArgs& a, dim3 grid, bool split, hipStream_t s) {
-  if (split)
-    hipLaunchKernelGGL((tab_kernel<kP, kNG, CH, true, false>), grid, dim3(kThreads), 0, s, a);
-  else if (a.K > 16384)
-    hipLaunchKernelGGL((tab_kernel<kP, kNG, CH, false, true>), grid, dim3(kThreads), 0, s, a);
-  else
-    hipLaunchKernelGGL((tab_kernel<kP, kNG, CH, false, false>), grid, dim3(kThreads), 0, s, a);
+  const TileCfg& t = tile_cfg();
+  const int key = t.threads * 1000 + t.P * 100 + t.NG * 10 + t.KS;
+  switch (key) {
+    case 512 * 1000 + 281: launch_cfg<512, 2, 8, 1, CH>(a, grid, split, s); break;
+    case 1024 * 1000 + 181: launch_cfg<1024, 1, 8, 1, CH>(a, grid, split, s); break;
+    case 512 * 1000 + 282: launch_cfg<512, 2, 8, 2, CH>(a, grid, split, s); break;
+    case 1024 * 1000 + 182: launch_cfg<1024, 1, 8, 2, CH>(a, grid, split, s); break;
+    case 512 * 1000 + 441: launch_cfg<512, 4, 4, 1, CH>(a, grid, split, s); break;
+    case 512 * 1000 + 442: launch_cfg<512, 4, 4, 2, CH>(a, grid, split, s); break;
+    case 1024 * 1000 + 242: launch_cfg<1024, 2, 4, 2, CH>(a, grid, split, s); break;
+    default: break;
+  }
 }
 
 hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const uint8_t* x, const uint8_t* w,
@@ -471,7 +599,8 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   const int J = ch ? g.M : g.Cout;
   const int nchunks = cdiv(g.K, kChunk);
   const int Kp = nchunks * kChunk;
-  const int Jpad = cdiv(J, kJT) * kJT;
+  const int kIT = tile_cfg().threads * tile_cfg().P, kJT = tile_cfg().NG * 8;
+  const int Jpad = cdiv(J, 64) * 64;
   uint16_t* rows = reinterpret_cast<uint16_t*>(wsb + p.off_rows);
   uint8_t* Bp = wsb + p.off_bpack;
   int32_t* bsum = reinterpret_cast<int32_t*>(wsb + p.off_bsum);
@@ -513,8 +642,9 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.part = reinterpret_cast<int32_t*>(wsb + p.off_part);
   a.lsum = reinterpret_cast<int32_t*>(wsb + p.off_lsum);
   a.out_elems = (long long)g.M * g.Cout;
+  a.vec_out = (!ch && J % 4 == 0 && (((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
 
-  const dim3 grid(cdiv(I, kIT), Jpad / kJT, p.split_k);
+  const dim3 grid(cdiv(I, kIT), cdiv(J, kJT), p.split_k);
   const bool split = p.split_k > 1;
   if (ch) launch_main<true>(a, grid, split, s); else launch_main<false>(a, grid, split, s);
   if (split) {

@@ -21,6 +21,7 @@ def _reset_options():
     yield
     ax.ax_set_option("variant", 0)
     ax.ax_set_option("split_k", 0)
+    ax.ax_set_option("tile", 0)
 
 
 def L(N, H, W, Cin, KH, KW, Cout, s=1, p=0, dense=False, x_dist="uniform", w_dist="uniform", name=None):
@@ -77,6 +78,24 @@ def test_forced_k_slices(variant, split_k):
     ax.ax_set_option("split_k", split_k)
     G.check_layer(L(1, 14, 14, 64, 3, 3, 72, 1, 1, x_dist="relu", w_dist="normal"), 5, I.lut_random_error(3))
     G.check_layer(L(40, 1, 1, 1000, 1, 1, 130, dense=True), 6, I.lut_truncated(6))
+
+
+TILES = list(range(1, 7))
+
+
+@pytest.mark.parametrize("variant", [2, 3])
+@pytest.mark.parametrize("tile", TILES)
+def test_tile_configurations(variant, tile):
+    """Every table-tile configuration (threads, lane elements, groups, taps per barrier)."""
+    ax.ax_set_option("variant", variant)
+    ax.ax_set_option("tile", tile)
+    lut = I.lut_random(21)
+    G.check_layer(L(2, 30, 33, 32, 3, 3, 72, 1, 1), 31, lut)           # ragged pixel and channel tiles
+    G.check_layer(L(1, 20, 20, 48, 1, 1, 30, 2, 0), 32, lut)           # Cout not a multiple of 4: scalar stores
+    G.check_layer(L(3, 9, 9, 7, 3, 3, 16, 1, 1), 33, lut)              # materialized patches, K tail
+    ax.ax_set_option("split_k", 3)
+    G.check_layer(L(1, 16, 16, 64, 3, 3, 40, 1, 1), 34, lut)
+    G.check_layer(L(50, 1, 1, 200, 1, 1, 64, dense=True), 35, lut)
 
 
 RESNET_SLICES = [
