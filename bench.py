@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the table-lookup conv2d hot path on one MI355X.
+
+One "step" is one pass over the ResNet-50-shaped workload (53 convolutions + the 2048x1000
+classifier, batch 32, every layer on its own seeded synthetic input resident in HBM, the
+truncated-multiplier table with the 6 low partial-product columns removed).  Prints ONE JSON
+line: whole-job LUT-MACs/s, the roofline of the dominant kernel (measured live with HIP
+events around that kernel on the launch stream) and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--cpu-batch", type=int, default=32, help="images per layer for the oracle timing (0 = skip)")
+    ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2002_09481_amd import binding as ax
+    from paper_2002_09481_amd import inputs as I
+
+    if not os.path.exists(ax.LIB_PATH):
+        from paper_2002_09481_amd import build as hip_build
+        hip_build.build()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    layers = I.config_resnet50(args.batch)
+    lut = I.lut_truncated(6)
+    lut_d = ax.lut_to_device(lut)
+
+    # ---- operands resident in HBM before anything is timed --------------------------------
+    t_gen = time.time()
+    calls = []
+    host = []
+    for idx, l in enumerate(layers):
+        x, w, q = I.make_operands(l, I.layer_seed(3, idx))
+        xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
+        if l.dense:
+            xd, wd = xd.view(l.N, l.K), wd.view(l.K, l.Cout)
+            acc = torch.empty((l.N, l.Cout), dtype=torch.int32, device=dev)
+            ws = torch.empty(max(256, ax.ax_dense_workspace_bytes(l.N, l.K, l.Cout)), dtype=torch.uint8, device=dev)
+        else:
+            acc = torch.empty((l.N, l.OH, l.OW, l.Cout), dtype=torch.int32, device=dev)
+            ws = torch.empty(max(256, ax.ax_conv2d_workspace_bytes(x.shape, w.shape, l.stride, l.pad)),
+                             dtype=torch.uint8, device=dev)
+        y = torch.empty(acc.shape, dtype=torch.float32, device=dev)
+        calls.append((l, xd, wd, q, acc, y, ws))
+        host.append((x, w, q) if not args.no_check else None)
+    t_gen = time.time() - t_gen
+    total_macs = sum(l.macs for l in layers)
+
+    def step():
+        for l, xd, wd, q, acc, y, ws in calls:
+            if l.dense:
+                ax.ax_dense(xd, wd, lut_d, q, acc, y, ws)
+            else:
+                ax.ax_conv2d(xd, wd, lut_d, l.stride, l.pad, q, acc, y, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    value = total_macs / (ms_per_step * 1e-3)
+
+    # ---- dominant kernel: HIP events around the main kernel of every layer call ------------
+    ax.ax_set_option("timing", 1)
+    kern_ms = []
+    for rep in range(3):
+        per = []
+        for l, xd, wd, q, acc, y, ws in calls:
+            if l.dense:
+                ax.ax_dense(xd, wd, lut_d, q, acc, y, ws)
+            else:
+                ax.ax_conv2d(xd, wd, lut_d, l.stride, l.pad, q, acc, y, ws)
+            per.append(ax.ax_last_kernel_ms())
+        kern_ms.append(per)
+    ax.ax_set_option("timing", 0)
+    kern_ms = np.median(np.array(kern_ms), axis=0)
+    main_ms = float(kern_ms.sum())
+    n_launch = len(calls)
+
+    # measured denominators: LDS lookup rates and copy bandwidth on this device
+    r_cf = ax.ax_probe_lds_gather(2, 0, 131072, 1024, 20000)
+    r_rand = ax.ax_probe_lds_gather(2, 1, 131072, 1024, 8000)
+    lookups = lambda r: r["wave_reads"] * r["workgroups"] * 64 / r["seconds"]
+    lds_peak, lds_rand = lookups(r_cf), lookups(r_rand)
+    nb = 1 << 30
+    a = torch.empty(nb, dtype=torch.uint8, device=dev)
+    b = torch.empty(nb, dtype=torch.uint8, device=dev)
+    ax.ax_probe_copy(b, a)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        ax.ax_probe_copy(b, a)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * nb * 5 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del a, b
+
+    alg_bytes = sum(l.algorithmic_bytes for l in layers)
+    kern_rate = total_macs / (main_ms * 1e-3)  # lookup-MACs per second inside the dominant kernel
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = {
+        "kernel": "tab_kernel (table-tile lookup-MAC kernel), %d launches per step" % n_launch,
+        "bound": "lds",
+        "achieved": kern_rate / 1e9,
+        "peak": lds_peak / 1e9,
+        "unit": "Glookup/s",
+        "frac": kern_rate / lds_peak,
+        "peak_source": "measured on this device: conflict-free 2-byte LDS gathers, 128 KB table resident",
+        "avg_launch_ms": main_ms / n_launch,
+        "algorithmic_lookups_per_launch": total_macs / n_launch,
+        "traffic": traffic,
+        "frac_of_random_gather_rate": kern_rate / lds_rand,
+        "alu": {"achieved": kern_rate / 1e12, "peak": 39.32, "unit": "Tint32-add/s", "frac": kern_rate / 39.32e12},
+        "hbm": {"achieved": alg_bytes / (main_ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                "frac": alg_bytes / (main_ms * 1e-3) / 8e12, "measured_copy_GBps": copy_gbs,
+                "algorithmic_bytes_per_launch": alg_bytes / n_launch},
+    }
+
+    # ---- sampled parity against the oracle, in the configuration that was timed -------------
+    parity = None
+    if not args.no_check:
+        from oracle import oracle
+        rng = np.random.default_rng(0)
+        parity = True
+        for (l, xd, wd, q, acc, y, ws), (x, w, qq) in zip(calls, host):
+            n_out = l.M * l.Cout
+            idx = rng.integers(0, n_out, size=48)
+            a_s, y_s = oracle.conv2d_sample(x, w, lut, l.stride, l.pad, qq, idx)
+            ti = torch.from_numpy(idx).to(dev)
+            a_g = acc.view(-1)[ti].cpu().numpy()
+            y_g = y.view(-1)[ti].cpu().numpy()
+            ok = np.array_equal(a_g, a_s) and np.all(np.abs(y_g.astype(np.float64) - y_s) <= 1e-5 * np.abs(y_s) + 1e-6)
+            if not ok:
+                parity = False
+                print("bench.py: PARITY FAILURE in layer %s" % l.name, file=sys.stderr)
+
+    # ---- the oracle, as it stands, on the host cores (bounded sample) ------------------------
+    cpu = None
+    if args.cpu_batch > 0:
+        from oracle import oracle
+        cl = I.config_resnet50(args.cpu_batch)
+        if args.cpu_batch == args.batch and not args.no_check:
+            ops = host  # the very tensors the GPU consumed
+        else:
+            ops = [I.make_operands(l, I.layer_seed(3, idx)) for idx, l in enumerate(cl)]
+        t = time.perf_counter()
+        for l, (x, w, q) in zip(cl, ops):
+            if l.dense:
+                oracle.dense(x.reshape(l.N, l.K), w.reshape(l.K, l.Cout), lut, q)
+            else:
+                oracle.conv2d(x, w, lut, l.stride, l.pad, q)
+        dt = time.perf_counter() - t
+        cmacs = sum(l.macs for l in cl)
+        cpu = {"value": cmacs / dt, "unit": "LUT-MAC/s", "cores": oracle.threads(), "kind": "oracle",
+               "sample": "all 54 layers of the same workload at batch %d (%.2f G lookups, %.1f s)" % (
+                   args.cpu_batch, cmacs / 1e9, dt),
+               "images_per_s": args.cpu_batch / dt}
+
+    out = {
+        "metric": "LUT-MACs/s (ResNet-50 shapes)",
+        "value": value,
+        "unit": "LUT-MAC/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8 codes x u16 table -> int32",
+        "data": "synthetic",
+        "config": {"workload": "configs[2]: ResNet-50-shaped inference, 53 conv + FC, batch %d, 224x224x3, "
+                               "truncated-multiplier table (6 low partial-product columns removed)" % args.batch,
+                   "global_batch": args.batch, "layers": len(layers), "lut_macs_per_step": total_macs},
+        "images_per_s": args.batch / (ms_per_step * 1e-3),
+        "frac_of_lds_lookup_roofline": value / lds_peak,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "parity_sampled": parity,
+        "wall_s_timed_region": wall,
+        "input_generation_s": t_gen,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

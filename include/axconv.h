@@ -104,12 +104,20 @@ int ax_version(void);
  *              2 = table-tile kernel, lanes over output pixels
  *              3 = table-tile kernel, lanes over output channels
  *   "split_k"  0 = choose automatically, n >= 1 = force n slices of the K loop
- *   "tile"     index of the table-tile configuration (threads, lane elements per thread,
- *              table groups, taps per barrier); 0 = default
+ *   "tile"     0 = choose the table-tile configuration automatically (default), n >= 1 =
+ *              force configuration n (threads, lane elements per thread, table groups,
+ *              taps per barrier)
+ *   "timing"   1 = record a HIP event pair around the main kernel of every layer call on
+ *              the call's stream (see ax_last_kernel_ms); 0 = off (default)
  * Returns AX_OK or AX_ERR_OPTION.  Not thread safe with respect to concurrent calls.
  */
 int ax_set_option(const char* name, int value);
 int ax_get_option(const char* name, int* value);
+
+/* Duration in milliseconds of the main kernel of the most recent layer call made while the
+ * "timing" option was on (operand preparation and the K-slice reduction are not included).
+ * Waits for that kernel to finish.  AX_ERR_OPTION if no timed call has been made. */
+int ax_last_kernel_ms(float* ms);
 
 /* ---- measurement helpers (not part of the layer path) -------------------------------- */
 

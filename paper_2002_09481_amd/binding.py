@@ -37,7 +37,7 @@ class ax_quant_t(ctypes.Structure):
 
 EXPORTS = [
     "ax_conv2d", "ax_conv2d_workspace_bytes", "ax_dense", "ax_dense_workspace_bytes", "ax_strerror",
-    "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac",
+    "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_last_kernel_ms",
 ]
 
 
@@ -73,6 +73,8 @@ def lib():
     L.ax_probe_lds_gather.restype = ci
     L.ax_probe_mac.argtypes = [ci, ci, ci, ci, dp, dp, vp]
     L.ax_probe_mac.restype = ci
+    L.ax_last_kernel_ms.argtypes = [ctypes.POINTER(ctypes.c_float)]
+    L.ax_last_kernel_ms.restype = ci
     L.ax_probe_copy.argtypes = [vp, vp, sz, vp]
     L.ax_probe_copy.restype = ci
     _lib = L
@@ -100,6 +102,12 @@ def ax_get_option(name: str) -> int:
     v = ctypes.c_int(0)
     _check(lib().ax_get_option(name.encode(), ctypes.byref(v)))
     return v.value
+
+
+def ax_last_kernel_ms() -> float:
+    v = ctypes.c_float(0.0)
+    _check(lib().ax_last_kernel_ms(ctypes.byref(v)))
+    return float(v.value)
 
 
 def _quant(q) -> ax_quant_t:

@@ -6,7 +6,24 @@
 
 namespace ax {
 
-Options g_opt = {0, 0, 0};
+Options g_opt = {0, 0, 0, 0};
+
+static hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
+static bool g_ev_valid = false;
+
+void timing_begin(hipStream_t s) {
+  if (!g_opt.timing) return;
+  if (!g_ev0 && (hipEventCreate(&g_ev0) != hipSuccess || hipEventCreate(&g_ev1) != hipSuccess)) {
+    g_ev0 = g_ev1 = nullptr;
+    return;
+  }
+  g_ev_valid = hipEventRecord(g_ev0, s) == hipSuccess;
+}
+
+void timing_end(hipStream_t s) {
+  if (!g_opt.timing || !g_ev0) return;
+  g_ev_valid = g_ev_valid && hipEventRecord(g_ev1, s) == hipSuccess;
+}
 
 static int make_quant(const ax_quant_t* q, QParams* qp) {
   if (!q) return AX_ERR_NULL;
@@ -75,7 +92,7 @@ static size_t workspace_for(const Geom& g) {
   if (!tab_supported(g)) return 256;
   size_t need = 256;
   for (int v = 2; v <= 3; ++v) {
-    Options o = {v, g_opt.split_k, g_opt.tile};
+    Options o = {v, g_opt.split_k, g_opt.tile, 0};
     const size_t t = tab_plan(g, o).total;
     if (t > need) need = t;
   }
@@ -148,8 +165,13 @@ extern "C" int ax_set_option(const char* name, int value) {
     return AX_OK;
   }
   if (!std::strcmp(name, "tile")) {
-    if (value < 0 || value >= tab_num_tiles()) return AX_ERR_OPTION;
+    if (value < 0 || value > tab_num_tiles()) return AX_ERR_OPTION;
     g_opt.tile = value;
+    return AX_OK;
+  }
+  if (!std::strcmp(name, "timing")) {
+    if (value < 0 || value > 1) return AX_ERR_OPTION;
+    g_opt.timing = value;
     return AX_OK;
   }
   return AX_ERR_OPTION;
@@ -160,5 +182,13 @@ extern "C" int ax_get_option(const char* name, int* value) {
   if (!std::strcmp(name, "variant")) { *value = g_opt.variant; return AX_OK; }
   if (!std::strcmp(name, "split_k")) { *value = g_opt.split_k; return AX_OK; }
   if (!std::strcmp(name, "tile")) { *value = g_opt.tile; return AX_OK; }
+  if (!std::strcmp(name, "timing")) { *value = g_opt.timing; return AX_OK; }
   return AX_ERR_OPTION;
+}
+
+extern "C" int ax_last_kernel_ms(float* ms) {
+  if (!ms) return AX_ERR_NULL;
+  if (!g_ev_valid || !g_ev0) return AX_ERR_OPTION;
+  if (hipEventSynchronize(g_ev1) != hipSuccess) return AX_ERR_HIP;
+  return hipEventElapsedTime(ms, g_ev0, g_ev1) == hipSuccess ? AX_OK : AX_ERR_HIP;
 }

@@ -53,7 +53,9 @@ hipError_t launch_direct(const Geom& g, const QParams& qp, const uint8_t* x, con
                          const uint16_t* lut, int32_t* acc_out, float* y_out, hipStream_t s) {
   const uint64_t total = (uint64_t)g.M * g.Cout;
   const uint32_t blocks = (uint32_t)((total + 255) / 256);
+  timing_begin(s);
   hipLaunchKernelGGL(direct_kernel, dim3(blocks), dim3(256), 0, s, g, qp, x, w, lut, acc_out, y_out);
+  timing_end(s);
   return hipGetLastError();
 }
 

@@ -501,7 +501,7 @@ __global__ __launch_bounds__(256) void prep_transpose_kernel(const uint8_t* __re
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 
-// Tile configurations selectable with the "tile" option (0 = default).
+// Tile configurations; the "tile" option selects one by index + 1 (0 = automatic choice).
 struct TileCfg { int threads, P, NG, KS; };
 static const TileCfg kTiles[] = {
     {512, 2, 8, 1},   // 0: 1024 x 64 tile, 8 waves
@@ -513,7 +513,8 @@ static const TileCfg kTiles[] = {
     {1024, 2, 4, 2},  // 6: 2048 x 32 tile, 16 waves
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
-static const TileCfg& tile_cfg() { return kTiles[(g_opt.tile >= 0 && g_opt.tile < kNumTiles) ? g_opt.tile : 0]; }
+constexpr int kDefaultTile = 6;
+static const TileCfg& tile_cfg() { return kTiles[(g_opt.tile >= 1 && g_opt.tile <= kNumTiles) ? g_opt.tile - 1 : kDefaultTile]; }
 int tab_num_tiles() { return kNumTiles; }
 
 bool tab_supported(const Geom&) { return true; }
@@ -646,7 +647,9 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
 
   const dim3 grid(cdiv(I, kIT), cdiv(J, kJT), p.split_k);
   const bool split = p.split_k > 1;
+  timing_begin(s);
   if (ch) launch_main<true>(a, grid, split, s); else launch_main<false>(a, grid, split, s);
+  timing_end(s);
   if (split) {
     const unsigned blocks = (unsigned)cdiv(a.out_elems, 256);
     if (ch)
