@@ -40,7 +40,8 @@ struct TabArgs {
   // table-side operand, packed [Krows][Jpad] with zero fill
   const uint8_t* Bp;
   int Jpad, J;
-  const int32_t* bsum;   // [Jpad] column sums of Bp over k < K
+  const int32_t* bsum;   // [nseg][Jpad] partial column sums of Bp (k segments), see prep_kernel
+  int nseg;
   const uint16_t* rows;  // re-laid-out truth table, 256 rows of 512 bytes
   int K, k_per_split;
   int z_lane, z_tab;
@@ -53,6 +54,17 @@ struct TabArgs {
   long long out_elems;
   int vec_out;  // outputs may be written in aligned 16-byte pieces along j
 };
+
+// acc_lo += low half of e, acc_hi += high half of e: one sub-dword-select add each.  Written
+// as instructions because the optimizer otherwise regroups each accumulator's chain of adds
+// across a whole unrolled chunk into a tree, which keeps every gathered value alive at once.
+__device__ __forceinline__ void add_halves(uint32_t& acc_lo, uint32_t& acc_hi, uint32_t e) {
+  asm volatile(
+      "v_add_u32_sdwa %0, %0, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+      "v_add_u32_sdwa %1, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1"
+      : "+v"(acc_lo), "+v"(acc_hi)
+      : "v"(e));
+}
 
 __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
   const uint32_t w = (kk < 4) ? v.x : (kk < 8) ? v.y : (kk < 12) ? v.z : v.w;
@@ -89,8 +101,10 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
   const int i0 = blockIdx.x * IT;
   const int j0 = blockIdx.y * JT;
   const int kbeg = blockIdx.z * a.k_per_split;
-  const int kend = min(a.K, kbeg + a.k_per_split);
-  const int klast = ((a.K + kChunk - 1) / kChunk) * kChunk;  // last (zero) row of Bp
+  const int klast = ((a.K + kChunk - 1) / kChunk) * kChunk;  // padded K = index of the last (zero) row of Bp
+  // Taps K .. klast-1 exist only in materialized operands, where both codes are 0: each adds
+  // the table entry (0,0) to every accumulator, which the epilogue takes off again.
+  const int kend = min(klast, kbeg + a.k_per_split);
 
   // ---- lane elements -------------------------------------------------------------------
   int li[P], by[P], bx[P], nb[P];
@@ -198,7 +212,6 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
 
   for (int c = 0; c < nchunks; ++c) {
     const int k0 = kbeg + c * kChunk;
-    const int klen = min(kChunk, kend - k0);
 #pragma unroll
     for (int p = 0; p < P; ++p) xa[p] = xn[p];
 #pragma unroll
@@ -219,38 +232,43 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
       sl[p] = __builtin_amdgcn_sad_u8(xa[p].z, 0u, sl[p]);
       sl[p] = __builtin_amdgcn_sad_u8(xa[p].w, 0u, sl[p]);
     }
+    // A phase issues ITEMS*NG gathers (item = one tap of one lane element).  They run through
+    // a small ring of registers: gather i+DEPTH is issued before the eight adds of gather i,
+    // so that LDS latency hides behind VALU work without a large register footprint.
+    constexpr int ITEMS = KS * P;
+    constexpr int NR = ITEMS * NG;
+    constexpr int DEPTH = 3;
+    auto issue = [&](int ph, int i, uint4 (&ring)[DEPTH + 1]) {
+      const int it = i / NG, g = i - it * NG;
+      const int s = it / P, p = it - s * P;
+      const uint32_t v = byte_of(xa[p], ph * KS + s);
+      ring[i % (DEPTH + 1)] = tab[ph & 1][s][g][v];
+    };
+    auto retire = [&](int i, const uint4 (&ring)[DEPTH + 1]) {
+      const int it = i / NG, g = i - it * NG;
+      const int p = it % P;
+      const uint4 e = ring[i % (DEPTH + 1)];
+      add_halves(acc[p][g * 8 + 0], acc[p][g * 8 + 1], e.x);
+      add_halves(acc[p][g * 8 + 2], acc[p][g * 8 + 3], e.y);
+      add_halves(acc[p][g * 8 + 4], acc[p][g * 8 + 5], e.z);
+      add_halves(acc[p][g * 8 + 6], acc[p][g * 8 + 7], e.w);
+    };
 #pragma unroll
     for (int ph = 0; ph < PHASES; ++ph) {
-      if (ph * KS < klen) {  // uniform
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) build_issue(u, tv_cur[u >> 1][ph]);
+      for (int u = 0; u < UNITS; ++u) build_issue(u, tv_cur[u >> 1][ph]);
+      uint4 ring[DEPTH + 1];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          if (s == 0 || ph * KS + s < klen) {
+      for (int i = 0; i < DEPTH && i < NR; ++i) issue(ph, i, ring);
 #pragma unroll
-            for (int p = 0; p < P; ++p) {
-              const uint32_t v = byte_of(xa[p], ph * KS + s);
-              const uint4* tp = &tab[ph & 1][s][0][v];
-              uint4 e[NG];
-#pragma unroll
-              for (int g = 0; g < NG; ++g) e[g] = tp[g * 256];
-#pragma unroll
-              for (int g = 0; g < NG; ++g) {
-                acc[p][g * 8 + 0] += e[g].x & 0xffffu;
-                acc[p][g * 8 + 1] += e[g].x >> 16;
-                acc[p][g * 8 + 2] += e[g].y & 0xffffu;
-                acc[p][g * 8 + 3] += e[g].y >> 16;
-                acc[p][g * 8 + 4] += e[g].z & 0xffffu;
-                acc[p][g * 8 + 5] += e[g].z >> 16;
-                acc[p][g * 8 + 6] += e[g].w & 0xffffu;
-                acc[p][g * 8 + 7] += e[g].w >> 16;
-              }
-            }
-          }
-        }
-        build_commit((ph + 1) & 1);
-        __syncthreads();
+      for (int i = 0; i < NR; ++i) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (i + DEPTH < NR) issue(ph, i + DEPTH, ring);
+        retire(i, ring);
       }
+      __builtin_amdgcn_sched_barrier(0);
+      build_commit((ph + 1) & 1);
+      __syncthreads();
     }
   }
 
@@ -258,12 +276,20 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
   // corr = acc - z_tab*Sl - z_lane*Sb[j] + K*z_lane*z_tab.  Each of the four terms is below
   // 2^31 in magnitude; for K <= 16384 so is every partial sum, and 32-bit wrap-around
   // arithmetic is exact.  Longer K takes the 64-bit form.
-  auto dequant = [&](uint32_t accv, uint32_t lterm, int j) -> float {
-    const long long cj64 = a.kzz - (long long)a.z_lane * a.bsum[j];
+  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0];  // see kend above
+  // Column constant K*z_lane*z_tab - z_lane*Sb[j] of this workgroup's JT columns.
+  __shared__ long long cterm[JT];
+  if (!SPLIT && tid < JT) {
+    int32_t sb = 0;
+    for (int q = 0; q < a.nseg; ++q) sb += a.bsum[(size_t)q * a.Jpad + j0 + tid];
+    cterm[tid] = a.kzz - (long long)a.z_lane * sb;
+  }
+  __syncthreads();
+  auto dequant = [&](uint32_t accv, uint32_t lterm, int jl) -> float {  // jl = column within the tile
     if constexpr (WIDE) {
-      return (float)((long long)(int32_t)(accv - lterm) + cj64) * a.scale;
+      return (float)((long long)(int32_t)(accv - lterm) + cterm[jl]) * a.scale;
     } else {
-      return (float)(int32_t)(accv - lterm + (uint32_t)cj64) * a.scale;
+      return (float)(int32_t)(accv - lterm + (uint32_t)cterm[jl]) * a.scale;
     }
   };
 
@@ -301,8 +327,11 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
         const int r = idx / (JT / 4), c4 = idx - r * (JT / 4);
         const int i = i0 + q * PX + r, j = j0 + 4 * c4;
         if (i < a.I && j < a.J) {
-          const uint4 v = *reinterpret_cast<const uint4*>(stage + r * ROW + 4 * c4);
+          uint4 v = *reinterpret_cast<const uint4*>(stage + r * ROW + 4 * c4);
           const uint32_t slv = stage[r * ROW + JT];
+          if constexpr (!SPLIT) {
+            v.x -= padfix; v.y -= padfix; v.z -= padfix; v.w -= padfix;
+          }
           const size_t o = (size_t)i * a.J + j;
           if constexpr (SPLIT) {
             *reinterpret_cast<uint4*>(part + o) = v;
@@ -312,10 +341,10 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
             if (a.y_out) {
               const uint32_t lterm = (uint32_t)a.z_tab * slv;
               float4 y;
-              y.x = dequant(v.x, lterm, j);
-              y.y = dequant(v.y, lterm, j + 1);
-              y.z = dequant(v.z, lterm, j + 2);
-              y.w = dequant(v.w, lterm, j + 3);
+              y.x = dequant(v.x, lterm, 4 * c4);
+              y.y = dequant(v.y, lterm, 4 * c4 + 1);
+              y.z = dequant(v.z, lterm, 4 * c4 + 2);
+              y.w = dequant(v.w, lterm, 4 * c4 + 3);
               *reinterpret_cast<float4*>(a.y_out + o) = y;
             }
           }
@@ -347,8 +376,8 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
       for (int j = 0; j < JT; ++j) {
         if (j0 + j < a.J) {
           const size_t o = CH ? (size_t)(j0 + j) * a.I + i : (size_t)i * a.J + (j0 + j);
-          if (a.acc_out) a.acc_out[o] = (int32_t)acc[p][j];
-          if (a.y_out) a.y_out[o] = dequant(acc[p][j], lterm, j0 + j);
+          if (a.acc_out) a.acc_out[o] = (int32_t)(acc[p][j] - padfix);
+          if (a.y_out) a.y_out[o] = dequant(acc[p][j] - padfix, lterm, j);
         }
       }
     }
@@ -356,51 +385,74 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
 }
 
 // Combine the K slices: out = sum of partials, then the correction and dequantization.
-template <bool CH>
+// VEC outputs per thread, contiguous in the output tensor.  VEC = 4 needs 16-byte aligned
+// pointers and a fastest output dimension that is a multiple of 4, so that the four outputs
+// share their row (pixel lanes: same pixel, columns j..j+3; channel lanes: same pixel j, channels
+// i..i+3).  All index arithmetic is 32-bit: tensors have fewer than 2^31 elements.
+template <bool CH, int VEC>
 __global__ __launch_bounds__(256) void tab_reduce_kernel(const TabArgs a, int nsplit) {
-  const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (o >= a.out_elems) return;
-  int i, j;
-  if (CH) {
-    j = (int)(o / a.I);
-    i = (int)(o - (long long)j * a.I);
-  } else {
-    i = (int)(o / a.J);
-    j = (int)(o - (long long)i * a.J);
-  }
-  uint32_t acc = 0, sl = 0;
+  const uint32_t total = (uint32_t)a.out_elems;
+  const uint32_t o = (blockIdx.x * 256u + threadIdx.x) * VEC;
+  if (o >= total) return;
+  const int klast = ((a.K + kChunk - 1) / kChunk) * kChunk;
+  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0];  // padded taps, see tab_kernel
+  uint32_t acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0u - padfix;
   for (int s = 0; s < nsplit; ++s) {
-    acc += (uint32_t)a.part[(size_t)s * a.out_elems + o];
-    sl += (uint32_t)a.lsum[(size_t)s * a.I + i];
+    const int32_t* src = a.part + (size_t)s * total + o;
+    if constexpr (VEC == 4) {
+      const uint4 v = *reinterpret_cast<const uint4*>(src);
+      acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+    } else {
+      acc[0] += (uint32_t)src[0];
+    }
   }
-  if (a.acc_out) a.acc_out[o] = (int32_t)acc;
+  if (a.acc_out) {
+    if constexpr (VEC == 4)
+      *reinterpret_cast<uint4*>(a.acc_out + o) = make_uint4(acc[0], acc[1], acc[2], acc[3]);
+    else
+      a.acc_out[o] = (int32_t)acc[0];
+  }
   if (a.y_out) {
-    const long long corr =
-        (long long)acc - (long long)a.z_tab * sl - (long long)a.z_lane * a.bsum[j] + a.kzz;
-    a.y_out[o] = (float)corr * a.scale;
+    // fastest output dimension F (columns for pixel lanes, lane elements for channel lanes)
+    const uint32_t F = CH ? (uint32_t)a.I : (uint32_t)a.J;
+    const uint32_t row = o / F, col = o - row * F;
+    uint32_t sl[VEC];
+    int32_t sb[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { sl[e] = 0; sb[e] = 0; }
+    if (CH) {  // row = table column j (pixel), col.. = lane elements i (channels)
+      for (int s = 0; s < nsplit; ++s)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sl[e] += (uint32_t)a.lsum[(size_t)s * a.I + col + e];
+      int32_t t = 0;
+      for (int q = 0; q < a.nseg; ++q) t += a.bsum[(size_t)q * a.Jpad + row];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) sb[e] = t;
+    } else {  // row = lane element i (pixel), col.. = table columns j (channels)
+      uint32_t t = 0;
+      for (int s = 0; s < nsplit; ++s) t += (uint32_t)a.lsum[(size_t)s * a.I + row];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) sl[e] = t;
+      for (int q = 0; q < a.nseg; ++q)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sb[e] += a.bsum[(size_t)q * a.Jpad + col + e];
+    }
+    float y[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const long long corr = (long long)acc[e] - (long long)a.z_tab * sl[e] - (long long)a.z_lane * sb[e] + a.kzz;
+      y[e] = (float)corr * a.scale;
+    }
+    if constexpr (VEC == 4)
+      *reinterpret_cast<float4*>(a.y_out + o) = make_float4(y[0], y[1], y[2], y[3]);
+    else
+      a.y_out[o] = y[0];
   }
 }
 
 // ---- operand preparation ---------------------------------------------------------------
-
-// rows[t][2P] = R[t][P], rows[t][2P+1] = R[t][P+128]  (P < 128), where R[t][v] is the
-// product of table-side code t and lane-side code v.  A lane that loads dword P of a row
-// gets the entries for v = P and v = P + 128, so consecutive lanes later write consecutive
-// 16-byte table entries (no LDS write conflicts).
-__global__ __launch_bounds__(512) void prep_rows_kernel(const uint16_t* __restrict__ lut,
-                                                         uint32_t* __restrict__ rows32, int lanes_are_channels) {
-  const int dw = blockIdx.x * 512 + threadIdx.x;  // 0 .. 32767
-  const int t = dw >> 7, P = dw & 127;
-  uint32_t lo, hi;
-  if (lanes_are_channels) {  // table side = activation code t, lane side = filter code v
-    lo = lut[t * 256 + P];
-    hi = lut[t * 256 + P + 128];
-  } else {  // table side = filter code t, lane side = activation code v
-    lo = lut[P * 256 + t];
-    hi = lut[(P + 128) * 256 + t];
-  }
-  rows32[dw] = lo | (hi << 16);
-}
 
 struct ConvView {  // im2col addressing of x
   const uint8_t* x;
@@ -419,27 +471,60 @@ __device__ __forceinline__ uint32_t im2col_code(const ConvView& v, int m, int k)
   return v.x[((size_t)(n * v.H + iy) * v.W + ix) * v.Cin + ci];
 }
 
-// Pack the table-side operand into Bp[krows][Jpad] (zero fill outside k < K, j < J) and sum
-// its columns.  One block per 64 columns; thread = (4 columns, one of 64 row phases).
+// rows[t][2P] = R[t][P], rows[t][2P+1] = R[t][P+128]  (P < 128), where R[t][v] is the
+// product of table-side code t and lane-side code v.  A lane that loads dword P of a row
+// gets the entries for v = P and v = P + 128, so consecutive lanes later write consecutive
+// 16-byte table entries (no LDS write conflicts).
+//
+// The same launch packs the table-side operand into Bp[krows][Jpad] (zero fill outside k < K,
+// j < J) and sums its columns per segment of `seg_rows` rows: psum[seg][j].  Blocks 0..127 do
+// the rows; block 128 + seg * (Jpad/64) + jb does 64 columns of one segment, thread = (4
+// columns, one of 16 row phases).
 // FROM_X: B[k][j] = im2col(x)[j][k] (lanes are channels) else B[k][j] = w[k*J + j].
+constexpr int kRowBlocks = 128;
 template <bool FROM_X>
-__global__ __launch_bounds__(1024) void prep_pack_kernel(const uint8_t* __restrict__ w, ConvView cv, int K, int J,
-                                                          int krows, int Jpad, uint8_t* __restrict__ Bp,
-                                                          int32_t* __restrict__ bsum) {
-  __shared__ int32_t red[64][65];
+__global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ lut, uint32_t* __restrict__ rows32,
+                                                    const uint8_t* __restrict__ w, ConvView cv, int K, int J, int krows,
+                                                    int Jpad, int seg_rows, uint8_t* __restrict__ Bp,
+                                                    int32_t* __restrict__ psum) {
+  if (blockIdx.x < kRowBlocks) {
+    const int dw = blockIdx.x * 256 + threadIdx.x;  // 0 .. 32767
+    const int t = dw >> 7, P = dw & 127;
+    uint32_t lo, hi;
+    if (FROM_X) {  // table side = activation code t, lane side = filter code v
+      lo = lut[t * 256 + P];
+      hi = lut[t * 256 + P + 128];
+    } else {  // table side = filter code t, lane side = activation code v
+      lo = lut[P * 256 + t];
+      hi = lut[(P + 128) * 256 + t];
+    }
+    rows32[dw] = lo | (hi << 16);
+    return;
+  }
+  __shared__ int32_t red[16][65];
+  const int b = blockIdx.x - kRowBlocks;
+  const int jblocks = Jpad / 64;
+  const int seg = b / jblocks, jb = b - seg * jblocks;
   const int c4 = threadIdx.x & 15, r = threadIdx.x >> 4;
-  const int j = blockIdx.x * 64 + c4 * 4;
+  const int j = jb * 64 + c4 * 4;
+  const int kbeg = seg * seg_rows, kend = min(krows, kbeg + seg_rows);
+  const bool fast = !FROM_X && (J % 4 == 0) && (((uintptr_t)w & 3) == 0) && (j + 3 < J);
   int32_t s[4] = {0, 0, 0, 0};
-  for (int k = r; k < krows; k += 64) {
+  for (int k = kbeg + r; k < kend; k += 16) {
     uint32_t pk = 0;
     if (k < K) {
+      if (fast) {
+        pk = *reinterpret_cast<const uint32_t*>(w + (size_t)k * J + j);
+      } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        uint32_t b = 0;
-        if (j + e < J) b = FROM_X ? im2col_code(cv, j + e, k) : (uint32_t)w[(size_t)k * J + j + e];
-        s[e] += (int32_t)b;
-        pk |= b << (8 * e);
+        for (int e = 0; e < 4; ++e) {
+          uint32_t bb = 0;
+          if (j + e < J) bb = FROM_X ? im2col_code(cv, j + e, k) : (uint32_t)w[(size_t)k * J + j + e];
+          pk |= bb << (8 * e);
+        }
       }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s[e] += (int32_t)((pk >> (8 * e)) & 0xffu);
     }
     *reinterpret_cast<uint32_t*>(Bp + (size_t)k * Jpad + j) = pk;
   }
@@ -448,8 +533,9 @@ __global__ __launch_bounds__(1024) void prep_pack_kernel(const uint8_t* __restri
   __syncthreads();
   if (threadIdx.x < 64) {
     int32_t t = 0;
-    for (int q = 0; q < 64; ++q) t += red[q][threadIdx.x];
-    bsum[blockIdx.x * 64 + threadIdx.x] = t;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) t += red[q][threadIdx.x];
+    psum[(size_t)seg * Jpad + jb * 64 + threadIdx.x] = t;
   }
 }
 
@@ -498,6 +584,7 @@ __global__ __launch_bounds__(256) void prep_transpose_kernel(const uint8_t* __re
 
 // ---- host side -------------------------------------------------------------------------
 
+constexpr int kMaxSeg = 8;  // segments of the table-side column sums
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 
@@ -511,9 +598,11 @@ static const TileCfg kTiles[] = {
     {512, 4, 4, 1},   // 4: 2048 x 32 tile
     {512, 4, 4, 2},   // 5
     {1024, 2, 4, 2},  // 6: 2048 x 32 tile, 16 waves
+    {1024, 2, 4, 4},  // 7: four taps per barrier (128 KB of tables)
+    {512, 4, 4, 4},   // 8
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
-constexpr int kDefaultTile = 6;
+constexpr int kDefaultTile = 7;
 static const TileCfg& tile_cfg() { return kTiles[(g_opt.tile >= 1 && g_opt.tile <= kNumTiles) ? g_opt.tile - 1 : kDefaultTile]; }
 int tab_num_tiles() { return kNumTiles; }
 
@@ -557,7 +646,7 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   size_t off = 0;
   p.off_rows = off;   off += up256(131072);
   p.off_bpack = off;  off += up256((Kp + 1) * Jpad);
-  p.off_bsum = off;   off += up256(Jpad * 4);
+  p.off_bsum = off;   off += up256(Jpad * 4 * kMaxSeg);
   p.off_apack = off;  off += up256((size_t)I * Kp);  // only used when the lane operand is materialized
   p.off_lsum = off;   off += up256((size_t)p.split_k * I * 4);
   p.off_part = off;
@@ -588,6 +677,8 @@ static void launch_main(const TabArgs& a, dim3 grid, bool split, hipStream_t s) 
     case 512 * 1000 + 441: launch_cfg<512, 4, 4, 1, CH>(a, grid, split, s); break;
     case 512 * 1000 + 442: launch_cfg<512, 4, 4, 2, CH>(a, grid, split, s); break;
     case 1024 * 1000 + 242: launch_cfg<1024, 2, 4, 2, CH>(a, grid, split, s); break;
+    case 1024 * 1000 + 244: launch_cfg<1024, 2, 4, 4, CH>(a, grid, split, s); break;
+    case 512 * 1000 + 444: launch_cfg<512, 4, 4, 4, CH>(a, grid, split, s); break;
     default: break;
   }
 }
@@ -609,11 +700,17 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
 
   ConvView cv{x, g.H, g.W, g.Cin, g.KW, g.sh, g.sw, g.ph, g.pw, g.OH, g.OW, g.M, g.K, qp.pad_code};
 
-  hipLaunchKernelGGL(prep_rows_kernel, dim3(64), dim3(512), 0, s, lut, reinterpret_cast<uint32_t*>(rows), ch ? 1 : 0);
+  // Column sums are produced per segment of rows so that more than Jpad/64 blocks share the work.
+  const int krows = Kp + 1;
+  const int nseg = std::max(1, std::min(kMaxSeg, cdiv(krows, 256)));
+  const int seg_rows = cdiv(cdiv(krows, nseg), 16) * 16;
+  const dim3 pgrid(kRowBlocks + nseg * (Jpad / 64));
   if (ch)
-    hipLaunchKernelGGL((prep_pack_kernel<true>), dim3(Jpad / 64), dim3(1024), 0, s, w, cv, g.K, J, Kp + 1, Jpad, Bp, bsum);
+    hipLaunchKernelGGL((prep_kernel<true>), pgrid, dim3(256), 0, s, lut, reinterpret_cast<uint32_t*>(rows), w, cv, g.K, J,
+                       krows, Jpad, seg_rows, Bp, bsum);
   else
-    hipLaunchKernelGGL((prep_pack_kernel<false>), dim3(Jpad / 64), dim3(1024), 0, s, w, cv, g.K, J, Kp + 1, Jpad, Bp, bsum);
+    hipLaunchKernelGGL((prep_kernel<false>), pgrid, dim3(256), 0, s, lut, reinterpret_cast<uint32_t*>(rows), w, cv, g.K, J,
+                       krows, Jpad, seg_rows, Bp, bsum);
 
   TabArgs a{};
   a.I = I;
@@ -633,7 +730,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
     a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
   }
   a.pad4 = (uint32_t)qp.pad_code * 0x01010101u;
-  a.Bp = Bp; a.Jpad = Jpad; a.J = J; a.bsum = bsum; a.rows = rows;
+  a.Bp = Bp; a.Jpad = Jpad; a.J = J; a.bsum = bsum; a.nseg = cdiv(krows, seg_rows); a.rows = rows;
   a.K = g.K; a.k_per_split = p.k_per_split;
   a.z_lane = ch ? qp.w_zp : qp.x_zp;
   a.z_tab = ch ? qp.x_zp : qp.w_zp;
@@ -651,11 +748,19 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   if (ch) launch_main<true>(a, grid, split, s); else launch_main<false>(a, grid, split, s);
   timing_end(s);
   if (split) {
-    const unsigned blocks = (unsigned)cdiv(a.out_elems, 256);
-    if (ch)
-      hipLaunchKernelGGL((tab_reduce_kernel<true>), dim3(blocks), dim3(256), 0, s, a, p.split_k);
-    else
-      hipLaunchKernelGGL((tab_reduce_kernel<false>), dim3(blocks), dim3(256), 0, s, a, p.split_k);
+    const bool vec = (a.out_elems % 4 == 0) && (ch || J % 4 == 0) && ((((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0);
+    const unsigned blocks = (unsigned)cdiv(cdiv(a.out_elems, vec ? 4 : 1), 256);
+    if (ch) {
+      if (vec && I % 4 == 0)
+        hipLaunchKernelGGL((tab_reduce_kernel<true, 4>), dim3(blocks), dim3(256), 0, s, a, p.split_k);
+      else
+        hipLaunchKernelGGL((tab_reduce_kernel<true, 1>), dim3((unsigned)cdiv(a.out_elems, 256)), dim3(256), 0, s, a, p.split_k);
+    } else {
+      if (vec)
+        hipLaunchKernelGGL((tab_reduce_kernel<false, 4>), dim3(blocks), dim3(256), 0, s, a, p.split_k);
+      else
+        hipLaunchKernelGGL((tab_reduce_kernel<false, 1>), dim3((unsigned)cdiv(a.out_elems, 256)), dim3(256), 0, s, a, p.split_k);
+    }
   }
   return hipGetLastError();
 }
