@@ -26,8 +26,11 @@
 
 #include "ax_internal.h"
 
-namespace ax {
+#ifndef AX_ADD_SDWA
+#define AX_ADD_SDWA 0
+#endif
 
+namespace ax {
 
 constexpr int kChunk = 16;     // taps per 16-byte lane-operand load
 
@@ -55,15 +58,26 @@ struct TabArgs {
   int vec_out;  // outputs may be written in aligned 16-byte pieces along j
 };
 
-// acc_lo += low half of e, acc_hi += high half of e: one sub-dword-select add each.  Written
-// as instructions because the optimizer otherwise regroups each accumulator's chain of adds
-// across a whole unrolled chunk into a tree, which keeps every gathered value alive at once.
-__device__ __forceinline__ void add_halves(uint32_t& acc_lo, uint32_t& acc_hi, uint32_t e) {
+// acc_lo += low half of e, acc_hi += high half of e.  Written as instructions because the
+// optimizer otherwise regroups each accumulator's chain of adds across a whole unrolled chunk
+// into a tree, which keeps every gathered value alive at once.  The 16-bit dot product with a
+// (1,0) / (0,1) selector is an add of one half; it issues a little faster than the
+// sub-dword-select form of v_add_u32.
+__device__ __forceinline__ void add_halves(uint32_t& acc_lo, uint32_t& acc_hi, uint32_t e, uint32_t sel_hi) {
+#if AX_ADD_SDWA
+  (void)sel_hi;
   asm volatile(
       "v_add_u32_sdwa %0, %0, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
       "v_add_u32_sdwa %1, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1"
       : "+v"(acc_lo), "+v"(acc_hi)
       : "v"(e));
+#else
+  asm volatile(
+      "v_dot2_u32_u16 %0, %2, 1, %0\n\t"
+      "v_dot2_u32_u16 %1, %2, %3, %1"
+      : "+v"(acc_lo), "+v"(acc_hi)
+      : "v"(e), "s"(sel_hi));
+#endif
 }
 
 __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
@@ -244,14 +258,15 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
       const uint32_t v = byte_of(xa[p], ph * KS + s);
       ring[i % (DEPTH + 1)] = tab[ph & 1][s][g][v];
     };
+    const uint32_t sel_hi = 0x00010000u;  // selector of the high half
     auto retire = [&](int i, const uint4 (&ring)[DEPTH + 1]) {
       const int it = i / NG, g = i - it * NG;
       const int p = it % P;
       const uint4 e = ring[i % (DEPTH + 1)];
-      add_halves(acc[p][g * 8 + 0], acc[p][g * 8 + 1], e.x);
-      add_halves(acc[p][g * 8 + 2], acc[p][g * 8 + 3], e.y);
-      add_halves(acc[p][g * 8 + 4], acc[p][g * 8 + 5], e.z);
-      add_halves(acc[p][g * 8 + 6], acc[p][g * 8 + 7], e.w);
+      add_halves(acc[p][g * 8 + 0], acc[p][g * 8 + 1], e.x, sel_hi);
+      add_halves(acc[p][g * 8 + 2], acc[p][g * 8 + 3], e.y, sel_hi);
+      add_halves(acc[p][g * 8 + 4], acc[p][g * 8 + 5], e.z, sel_hi);
+      add_halves(acc[p][g * 8 + 6], acc[p][g * 8 + 7], e.w, sel_hi);
     };
 #pragma unroll
     for (int ph = 0; ph < PHASES; ++ph) {
@@ -541,17 +556,36 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
 
 // Materialized im2col, Ap[m][Kp] (zero fill for k >= K): used when the implicit view cannot be
 // read in aligned 16-byte pieces (Cin not a multiple of 16, or a misaligned base pointer).
+// One thread per 16-byte piece: the pixel is decoded once and the tap index advanced
+// incrementally; consecutive threads write consecutive pieces.
 __global__ __launch_bounds__(256) void prep_im2col_kernel(ConvView cv, int Kp, uint8_t* __restrict__ Ap) {
-  const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
-  const int kq = Kp / 4;
-  if (q >= (long long)cv.M * kq) return;
-  const int m = (int)(q / kq);
-  const int k = (int)(q - (long long)m * kq) * 4;
-  uint32_t pk = 0;
+  const uint32_t nchunk = (uint32_t)Kp / 16u;
+  const uint32_t q = blockIdx.x * 256u + threadIdx.x;
+  if (q >= (uint32_t)cv.M * nchunk) return;  // M * Kp/16 < 2^31: see tab_supported
+  const uint32_t m = q / nchunk;
+  const int k0 = (int)(q - m * nchunk) * 16;
+  const uint32_t ohw = (uint32_t)(cv.OH * cv.OW);
+  const uint32_t n = m / ohw, r = m - n * ohw;
+  const int oy = (int)(r / (uint32_t)cv.OW), ox = (int)(r - (r / (uint32_t)cv.OW) * (uint32_t)cv.OW);
+  const int by = oy * cv.sh - cv.ph, bx = ox * cv.sw - cv.pw;
+  int tap = k0 / cv.Cin, ci = k0 - tap * cv.Cin;
+  int ky = tap / cv.KW, kx = tap - ky * cv.KW;
+  uint32_t pk[4] = {0, 0, 0, 0};
 #pragma unroll
-  for (int e = 0; e < 4; ++e)
-    if (k + e < cv.K) pk |= im2col_code(cv, m, k + e) << (8 * e);
-  *reinterpret_cast<uint32_t*>(Ap + (size_t)m * Kp + k) = pk;
+  for (int e = 0; e < 16; ++e) {
+    if (k0 + e < cv.K) {
+      const int iy = by + ky, ix = bx + kx;
+      uint32_t v = (uint32_t)cv.pad_code;
+      if ((unsigned)iy < (unsigned)cv.H && (unsigned)ix < (unsigned)cv.W)
+        v = cv.x[((size_t)(n * cv.H + iy) * cv.W + ix) * cv.Cin + ci];
+      pk[e >> 2] |= v << (8 * (e & 3));
+      if (++ci == cv.Cin) {
+        ci = 0;
+        if (++kx == cv.KW) { kx = 0; ++ky; }
+      }
+    }
+  }
+  *reinterpret_cast<uint4*>(Ap + (size_t)m * Kp + k0) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
 }
 
 // Ap[j][k] = w[k][j] (zero fill for k >= K), 64x64 tiles through LDS.
@@ -606,7 +640,11 @@ constexpr int kDefaultTile = 7;
 static const TileCfg& tile_cfg() { return kTiles[(g_opt.tile >= 1 && g_opt.tile <= kNumTiles) ? g_opt.tile - 1 : kDefaultTile]; }
 int tab_num_tiles() { return kNumTiles; }
 
-bool tab_supported(const Geom&) { return true; }
+// The preparation kernels index their pieces with 32-bit integers.
+bool tab_supported(const Geom& g) {
+  const long long chunks = cdiv(g.K, kChunk);
+  return (long long)g.M * chunks < (1LL << 31) && (long long)g.Cout * chunks < (1LL << 31);
+}
 
 static double padded_work(long long I, long long J) {
   const int kIT = tile_cfg().threads * tile_cfg().P, kJT = tile_cfg().NG * 8;
@@ -724,8 +762,8 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
     a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.KW = g.KW; a.sh = g.sh; a.sw = g.sw; a.ph = g.ph; a.pw = g.pw;
     a.OHW = g.OH * g.OW; a.OW = g.OW;
   } else {
-    const long long quads = (long long)g.M * (Kp / 4);
-    hipLaunchKernelGGL(prep_im2col_kernel, dim3((unsigned)cdiv(quads, 256)), dim3(256), 0, s, cv, Kp, Ap);
+    const long long pieces = (long long)g.M * (Kp / 16);
+    hipLaunchKernelGGL(prep_im2col_kernel, dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, s, cv, Kp, Ap);
     a.A = Ap;
     a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
   }
