@@ -103,7 +103,8 @@ int ax_version(void);
  *              1 = direct kernel: one thread per output, table read from global memory
  *              2 = table-tile kernel, lanes over output pixels
  *              3 = table-tile kernel, lanes over output channels
- *   "split_k"  0 = choose automatically, n >= 1 = force n slices of the K loop
+ *   "split_k"  0 = choose the work decomposition automatically, n >= 1 = force n equal
+ *              workgroup shares per output tile (n slices of the K loop)
  *   "tile"     0 = choose the table-tile configuration automatically (default), n >= 1 =
  *              force configuration n (threads, lane elements per thread, table groups,
  *              taps per barrier)

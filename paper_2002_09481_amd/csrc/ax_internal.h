@@ -45,8 +45,8 @@ hipError_t launch_direct(const Geom& g, const QParams& qp, const uint8_t* x, con
 // Table-tile kernels (ax_tab.hip).
 struct TabPlan {
   int variant;      // 2 or 3
-  int split_k;      // number of K slices (>= 1)
-  int k_per_split;  // multiple of the kernel's K chunk
+  int G;            // workgroups of the main kernel
+  int partials;     // partial tile pieces that grid produces (0: no fix-up pass)
   size_t off_rows;  // workspace offsets (bytes)
   size_t off_bpack;
   size_t off_bsum;

@@ -19,10 +19,12 @@
 // Two lane assignments share the kernel:
 //   variant 2  lanes = output pixels   (A = im2col view of x, B = filters, rows = LUT^T)
 //   variant 3  lanes = output channels (A = filters^T, B = im2col(x)^T, rows = LUT)
-// The K loop can be cut into slices (grid.z); partial sums are then combined by a small
-// reduction kernel (integer addition is associative, so the result is the same bits).
+// Work is divided over the grid by (tile, chunk) iterations rather than by tiles, so that all
+// compute units stay busy whatever the layer shape; tiles shared by several workgroups are
+// combined by a small fix-up kernel (integer addition is associative: same bits).
 #include <algorithm>
 #include <cmath>
+#include <vector>
 
 #include "ax_internal.h"
 
@@ -46,14 +48,19 @@ struct TabArgs {
   const int32_t* bsum;   // [nseg][Jpad] partial column sums of Bp (k segments), see prep_kernel
   int nseg;
   const uint16_t* rows;  // re-laid-out truth table, 256 rows of 512 bytes
-  int K, k_per_split;
+  int K;
+  // work decomposition: tile t = ti * ntj + tj, nch chunks of 16 taps per tile; workgroup w of G
+  // takes iterations [w*total/G, (w+1)*total/G) of the tile-major iteration space
+  int ntj, nch;
+  long long total_iters;
   int z_lane, z_tab;
   long long kzz;  // K * z_lane * z_tab
   float scale;
   int32_t* acc_out;
   float* y_out;
-  int32_t* part;  // [split][out_elems] partial accumulators (split mode)
-  int32_t* lsum;  // [split][I] partial lane-operand sums   (split mode)
+  int32_t* part;  // [2*G][IT*JT] partial tiles: slot 2w = workgroup w's piece of a tile begun by
+                  // another workgroup, slot 2w+1 = its piece of a tile it begins but does not end
+  int32_t* lsum;  // [2*G][IT] lane-operand sums of the same pieces
   long long out_elems;
   int vec_out;  // outputs may be written in aligned 16-byte pieces along j
 };
@@ -80,6 +87,8 @@ __device__ __forceinline__ void add_halves(uint32_t& acc_lo, uint32_t& acc_hi, u
 #endif
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
   const uint32_t w = (kk < 4) ? v.x : (kk < 8) ? v.y : (kk < 12) ? v.z : v.w;
   return (w >> (8 * (kk & 3))) & 0xffu;
@@ -88,14 +97,19 @@ __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
 // THREADS threads, P lane elements per thread, NG table groups (8 columns each) per
 // workgroup, KS taps per barrier phase.
 // CH: lanes are output channels (output index j*I + i) instead of pixels (i*J + j).
-// SPLIT: write partial sums instead of final outputs.
 // WIDE: K > 16384, the correction needs 64-bit arithmetic.
+//
+// Work is spread over the grid by iterations, not by tiles (G workgroups, one per compute
+// unit, each takes an equal contiguous share of tiles x chunks): a workgroup runs through one or
+// more "segments" (a tile and a chunk range of it).  A segment that covers its tile's whole K
+// range writes final outputs; any other writes a partial tile that tab_fixup_kernel combines.
+// Integer addition is associative, so the decomposition does not change a single bit.
 //
 // LDS holds two phase buffers of KS*NG tables.  In every phase each wave (a) issues the
 // global loads of the table rows for the NEXT phase, (b) gathers from the current buffer and
 // accumulates, (c) interleaves the loaded rows into 16-byte entries and stores them into
 // the other buffer, (d) joins the barrier.
-template <int THREADS, int P, int NG, int KS, bool CH, bool SPLIT, bool WIDE>
+template <int THREADS, int P, int NG, int KS, bool CH, bool WIDE>
 __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
   constexpr int JT = NG * 8;
   constexpr int IT = P * THREADS;
@@ -112,20 +126,28 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int i0 = blockIdx.x * IT;
-  const int j0 = blockIdx.y * JT;
-  const int kbeg = blockIdx.z * a.k_per_split;
-  const int klast = ((a.K + kChunk - 1) / kChunk) * kChunk;  // padded K = index of the last (zero) row of Bp
+  const int klast = a.nch * kChunk;  // padded K = index of the last (zero) row of Bp
   // Taps K .. klast-1 exist only in materialized operands, where both codes are 0: each adds
-  // the table entry (0,0) to every accumulator, which the epilogue takes off again.
-  const int kend = min(klast, kbeg + a.k_per_split);
+  // the table entry (0,0) to every accumulator, which the final epilogue takes off again.
+  long long it_beg = (long long)blockIdx.x * a.total_iters / gridDim.x;
+  const long long it_end = (long long)(blockIdx.x + 1) * a.total_iters / gridDim.x;
+  __shared__ long long cterm[JT];  // column constants of the current tile, see the epilogue
+
+  while (it_beg < it_end) {
+  const int tile = (int)(it_beg / a.nch);
+  const int c_beg = (int)(it_beg - (long long)tile * a.nch);
+  const int c_end = (int)min((long long)a.nch, c_beg + (it_end - it_beg));
+  const bool whole = (c_beg == 0) && (c_end == a.nch);
+  const int ti = tile / a.ntj;
+  const int i0 = ti * IT;
+  const int j0 = (tile - ti * a.ntj) * JT;
+  const int kbeg = c_beg * kChunk, kend = c_end * kChunk;
 
   // ---- lane elements -------------------------------------------------------------------
-  int li[P], by[P], bx[P], nb[P];
+  int by[P], bx[P], nb[P];
 #pragma unroll
   for (int p = 0; p < P; ++p) {
-    li[p] = i0 + p * THREADS + tid;
-    const int i = min(li[p], a.I - 1);
+    const int i = min(i0 + p * THREADS + tid, a.I - 1);
     const int n = i / a.OHW;
     const int r = i - n * a.OHW;
     const int oy = r / a.OW;
@@ -167,7 +189,7 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
     ug[u] = (qq >> 1) % NG;
     uh[u] = qq & 1;
   }
-  uint32_t d[UNITS][8];
+  uint32_t d[8];  // rows of the unit being built (units of a wave take turns within a phase)
   auto load_codes = [&](int cu, int k) {  // codes of unit pair cu for the phase that starts at tap k
     return *reinterpret_cast<const uint2*>(a.Bp + (size_t)min(k + us[2 * cu < UNITS ? 2 * cu : 0], klast) * a.Jpad + j0 +
                                            8 * ug[2 * cu < UNITS ? 2 * cu : 0]);
@@ -178,26 +200,23 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       const uint32_t b = ((c < 4 ? tv.x : tv.y) >> (8 * (c & 3))) & 0xffu;
-      d[u][c] = __builtin_amdgcn_raw_buffer_load_b32(rows_rsrc, voff, (int)(b * 512u), 0);
+      d[c] = __builtin_amdgcn_raw_buffer_load_b32(rows_rsrc, voff, (int)(b * 512u), 0);
     }
   };
-  auto build_commit = [&](int buf) {
-#pragma unroll
-    for (int u = 0; u < UNITS; ++u) {
-      if (!uvalid[u]) continue;
-      uint4 lo, hi;
-      lo.x = __builtin_amdgcn_perm(d[u][1], d[u][0], 0x05040100u);
-      lo.y = __builtin_amdgcn_perm(d[u][3], d[u][2], 0x05040100u);
-      lo.z = __builtin_amdgcn_perm(d[u][5], d[u][4], 0x05040100u);
-      lo.w = __builtin_amdgcn_perm(d[u][7], d[u][6], 0x05040100u);
-      hi.x = __builtin_amdgcn_perm(d[u][1], d[u][0], 0x07060302u);
-      hi.y = __builtin_amdgcn_perm(d[u][3], d[u][2], 0x07060302u);
-      hi.z = __builtin_amdgcn_perm(d[u][5], d[u][4], 0x07060302u);
-      hi.w = __builtin_amdgcn_perm(d[u][7], d[u][6], 0x07060302u);
-      const int e = lane + 64 * uh[u];
-      tab[buf][us[u]][ug[u]][e] = lo;
-      tab[buf][us[u]][ug[u]][e + 128] = hi;
-    }
+  auto build_commit = [&](int u, int buf) {
+    if (!uvalid[u]) return;
+    uint4 lo, hi;
+    lo.x = __builtin_amdgcn_perm(d[1], d[0], 0x05040100u);
+    lo.y = __builtin_amdgcn_perm(d[3], d[2], 0x05040100u);
+    lo.z = __builtin_amdgcn_perm(d[5], d[4], 0x05040100u);
+    lo.w = __builtin_amdgcn_perm(d[7], d[6], 0x05040100u);
+    hi.x = __builtin_amdgcn_perm(d[1], d[0], 0x07060302u);
+    hi.y = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
+    hi.z = __builtin_amdgcn_perm(d[5], d[4], 0x07060302u);
+    hi.w = __builtin_amdgcn_perm(d[7], d[6], 0x07060302u);
+    const int e = lane + 64 * uh[u];
+    tab[buf][us[u]][ug[u]][e] = lo;
+    tab[buf][us[u]][ug[u]][e + 128] = hi;
   };
 
   // ---- main loop -----------------------------------------------------------------------
@@ -214,8 +233,10 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
   const int nchunks = (kend - kbeg + kChunk - 1) / kChunk;
   load_chunk(kbeg, xn);
 #pragma unroll
-  for (int u = 0; u < UNITS; ++u) build_issue(u, load_codes(u >> 1, kbeg));
-  build_commit(0);
+  for (int u = 0; u < UNITS; ++u) {
+    build_issue(u, load_codes(u >> 1, kbeg));
+    build_commit(u, 0);
+  }
   __syncthreads();
   // codes of the phases that follow: tv[u][ph] belongs to taps k0 + (ph+1)*KS ...
   uint2 tv_cur[CODES][PHASES], tv_nxt[CODES][PHASES];
@@ -251,12 +272,20 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
     // so that LDS latency hides behind VALU work without a large register footprint.
     constexpr int ITEMS = KS * P;
     constexpr int NR = ITEMS * NG;
-    constexpr int DEPTH = 3;
-    auto issue = [&](int ph, int i, uint4 (&ring)[DEPTH + 1]) {
-      const int it = i / NG, g = i - it * NG;
+    constexpr int DEPTH = 2;
+    uint32_t item_addr[ITEMS];  // LDS byte address of entry v of group 0, per item of the phase
+    auto item_base = [&](int ph, int it) {
       const int s = it / P, p = it - s * P;
       const uint32_t v = byte_of(xa[p], ph * KS + s);
-      ring[i % (DEPTH + 1)] = tab[ph & 1][s][g][v];
+      uint32_t addr = (uint32_t)(uintptr_t)&tab[ph & 1][s][0][0] + (v << 4);
+      asm volatile("" : "+v"(addr));  // keep it one register: the group offsets below fit the instruction
+      item_addr[it] = addr;
+    };
+    auto issue = [&](int ph, int i, uint4 (&ring)[DEPTH + 1]) {
+      const int it = i / NG, g = i - it * NG;
+      if (g == 0) item_base(ph, it);
+      const u32x4 e = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(item_addr[it] + g * 4096);
+      ring[i % (DEPTH + 1)] = make_uint4(e.x, e.y, e.z, e.w);
     };
     const uint32_t sel_hi = 0x00010000u;  // selector of the high half
     auto retire = [&](int i, const uint4 (&ring)[DEPTH + 1]) {
@@ -270,19 +299,26 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
     };
 #pragma unroll
     for (int ph = 0; ph < PHASES; ++ph) {
-#pragma unroll
-      for (int u = 0; u < UNITS; ++u) build_issue(u, tv_cur[u >> 1][ph]);
       uint4 ring[DEPTH + 1];
 #pragma unroll
       for (int i = 0; i < DEPTH && i < NR; ++i) issue(ph, i, ring);
 #pragma unroll
       for (int i = 0; i < NR; ++i) {
+        // unit u of this wave is fetched at gather u*NR/UNITS and written out just before
+        // gather (u+1)*NR/UNITS, so that only one unit's rows occupy registers at a time
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u)
+          if (i == u * NR / UNITS) build_issue(u, tv_cur[u >> 1][ph]);
         __builtin_amdgcn_sched_barrier(0);
         if (i + DEPTH < NR) issue(ph, i + DEPTH, ring);
         retire(i, ring);
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u)
+          if (i == (u + 1) * NR / UNITS - 1) {
+            __builtin_amdgcn_sched_barrier(0);
+            build_commit(u, (ph + 1) & 1);
+          }
       }
-      __builtin_amdgcn_sched_barrier(0);
-      build_commit((ph + 1) & 1);
       __syncthreads();
     }
   }
@@ -291,15 +327,13 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
   // corr = acc - z_tab*Sl - z_lane*Sb[j] + K*z_lane*z_tab.  Each of the four terms is below
   // 2^31 in magnitude; for K <= 16384 so is every partial sum, and 32-bit wrap-around
   // arithmetic is exact.  Longer K takes the 64-bit form.
-  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0];  // see kend above
-  // Column constant K*z_lane*z_tab - z_lane*Sb[j] of this workgroup's JT columns.
-  __shared__ long long cterm[JT];
-  if (!SPLIT && tid < JT) {
+  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0];
+  if (whole && tid < JT) {
     int32_t sb = 0;
     for (int q = 0; q < a.nseg; ++q) sb += a.bsum[(size_t)q * a.Jpad + j0 + tid];
     cterm[tid] = a.kzz - (long long)a.z_lane * sb;
   }
-  __syncthreads();
+  __syncthreads();  // cterm visible; every wave is done with the table buffers
   auto dequant = [&](uint32_t accv, uint32_t lterm, int jl) -> float {  // jl = column within the tile
     if constexpr (WIDE) {
       return (float)((long long)(int32_t)(accv - lterm) + cterm[jl]) * a.scale;
@@ -307,54 +341,57 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
       return (float)(int32_t)(accv - lterm + (uint32_t)cterm[jl]) * a.scale;
     }
   };
+  const int slot = 2 * (int)blockIdx.x + (c_beg > 0 ? 0 : 1);
+  int32_t* part = a.part + (size_t)slot * (IT * JT);
+  int32_t* lsum = a.lsum + (size_t)slot * IT;
 
-  if (!CH && a.vec_out) {
-    // Lanes hold whole rows of JT consecutive outputs of one pixel.  Stage 128 pixels at a time
+  if (!whole) {
+    // Partial piece: stored column-major ([column][lane element]) so that consecutive lanes
+    // write consecutive words straight from their registers; tab_fixup_kernel re-orders.
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      const int il = p * THREADS + tid;
+      lsum[il] = (int32_t)sl[p];
+#pragma unroll
+      for (int j = 0; j < JT; ++j) part[j * IT + il] = (int32_t)acc[p][j];
+    }
+  } else if (!CH && a.vec_out) {
+    // Lanes hold whole rows of JT consecutive outputs of one pixel.  Stage PX pixels at a time
     // in LDS (rows padded by 4 dwords: conflict-free 16-byte writes) and read them back so
     // that consecutive lanes store consecutive 16-byte pieces: full-line coalesced stores.
-    constexpr int PX = 128;
     constexpr int ROW = JT + 4;
-    constexpr int NPASS = IT / PX;
+    constexpr int LDSB = 2 * KS * NG * 4096;
+    constexpr int PXMAX = LDSB / (ROW * 4);
+    constexpr int PX = PXMAX >= 512 && THREADS >= 512 ? 512 : PXMAX >= 256 ? 256 : 128;
+    constexpr int QPASS = THREADS / PX;  // passes per lane-element slot
     constexpr int PIECES = PX * (JT / 4);
-    static_assert(PX * ROW * 4 <= 2 * KS * NG * 4096, "stage must fit in the table buffers");
+    static_assert(PX * ROW * 4 <= LDSB && THREADS % PX == 0, "stage must fit in the table buffers");
     uint32_t* stage = reinterpret_cast<uint32_t*>(&tab[0][0][0][0]);
-    int32_t* part = SPLIT ? a.part + (size_t)blockIdx.z * a.out_elems : nullptr;
 #pragma unroll
-    for (int q = 0; q < NPASS; ++q) {
-      const int p_own = (q * PX) / THREADS;
-      const int t0 = q * PX - p_own * THREADS;
-      __syncthreads();
-      if (tid >= t0 && tid < t0 + PX) {
-        uint32_t* row = stage + (tid - t0) * ROW;
+    for (int p = 0; p < P; ++p) {
+#pragma unroll 1
+      for (int qq = 0; qq < QPASS; ++qq) {
+        const int t0 = qq * PX;
+        if (p > 0 || qq > 0) __syncthreads();
+        if (tid >= t0 && tid < t0 + PX) {
+          uint32_t* row = stage + (tid - t0) * ROW;
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
-          if (p == p_own) {
-#pragma unroll
-            for (int j4 = 0; j4 < JT / 4; ++j4)
-              *reinterpret_cast<uint4*>(row + 4 * j4) =
-                  make_uint4(acc[p][4 * j4], acc[p][4 * j4 + 1], acc[p][4 * j4 + 2], acc[p][4 * j4 + 3]);
-            row[JT] = sl[p];
-          }
+          for (int j4 = 0; j4 < JT / 4; ++j4)
+            *reinterpret_cast<uint4*>(row + 4 * j4) =
+                make_uint4(acc[p][4 * j4], acc[p][4 * j4 + 1], acc[p][4 * j4 + 2], acc[p][4 * j4 + 3]);
+          row[JT] = sl[p];
         }
-      }
-      __syncthreads();
-      for (int idx = tid; idx < PIECES; idx += THREADS) {
-        const int r = idx / (JT / 4), c4 = idx - r * (JT / 4);
-        const int i = i0 + q * PX + r, j = j0 + 4 * c4;
-        if (i < a.I && j < a.J) {
-          uint4 v = *reinterpret_cast<const uint4*>(stage + r * ROW + 4 * c4);
-          const uint32_t slv = stage[r * ROW + JT];
-          if constexpr (!SPLIT) {
+        __syncthreads();
+        for (int idx = tid; idx < PIECES; idx += THREADS) {
+          const int r = idx / (JT / 4), c4 = idx - r * (JT / 4);
+          const int i = i0 + p * THREADS + t0 + r, j = j0 + 4 * c4;
+          if (i < a.I && j < a.J) {
+            uint4 v = *reinterpret_cast<const uint4*>(stage + r * ROW + 4 * c4);
+            const uint32_t lterm = (uint32_t)a.z_tab * stage[r * ROW + JT];
             v.x -= padfix; v.y -= padfix; v.z -= padfix; v.w -= padfix;
-          }
-          const size_t o = (size_t)i * a.J + j;
-          if constexpr (SPLIT) {
-            *reinterpret_cast<uint4*>(part + o) = v;
-            if (blockIdx.y == 0 && c4 == 0) a.lsum[(size_t)blockIdx.z * a.I + i] = (int32_t)slv;
-          } else {
+            const size_t o = (size_t)i * a.J + j;
             if (a.acc_out) *reinterpret_cast<uint4*>(a.acc_out + o) = v;
             if (a.y_out) {
-              const uint32_t lterm = (uint32_t)a.z_tab * slv;
               float4 y;
               y.x = dequant(v.x, lterm, 4 * c4);
               y.y = dequant(v.y, lterm, 4 * c4 + 1);
@@ -366,25 +403,10 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
         }
       }
     }
-  } else if constexpr (SPLIT) {
-    int32_t* part = a.part + (size_t)blockIdx.z * a.out_elems;
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-      const int i = li[p];
-      if (i >= a.I) continue;
-      if (blockIdx.y == 0) a.lsum[(size_t)blockIdx.z * a.I + i] = (int32_t)sl[p];
-#pragma unroll
-      for (int j = 0; j < JT; ++j) {
-        if (j0 + j < a.J) {
-          const size_t o = CH ? (size_t)(j0 + j) * a.I + i : (size_t)i * a.J + (j0 + j);
-          part[o] = (int32_t)acc[p][j];
-        }
-      }
-    }
   } else {
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-      const int i = li[p];
+      const int i = i0 + p * THREADS + tid;
       if (i >= a.I) continue;
       const uint32_t lterm = (uint32_t)a.z_tab * sl[p];
 #pragma unroll
@@ -397,73 +419,101 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
       }
     }
   }
+  it_beg += c_end - c_beg;
+  __syncthreads();  // the staging area and cterm are free again
+  }  // segment loop
 }
 
-// Combine the K slices: out = sum of partials, then the correction and dequantization.
-// VEC outputs per thread, contiguous in the output tensor.  VEC = 4 needs 16-byte aligned
-// pointers and a fastest output dimension that is a multiple of 4, so that the four outputs
-// share their row (pixel lanes: same pixel, columns j..j+3; channel lanes: same pixel j, channels
-// i..i+3).  All index arithmetic is 32-bit: tensors have fewer than 2^31 elements.
-template <bool CH, int VEC>
-__global__ __launch_bounds__(256) void tab_reduce_kernel(const TabArgs a, int nsplit) {
-  const uint32_t total = (uint32_t)a.out_elems;
-  const uint32_t o = (blockIdx.x * 256u + threadIdx.x) * VEC;
-  if (o >= total) return;
-  const int klast = ((a.K + kChunk - 1) / kChunk) * kChunk;
+// Combine the pieces of every tile that more than one workgroup worked on.  The pieces lie,
+// column-major, in the slots of consecutive workgroups (see TabArgs::part).  A block takes 64
+// lane elements of one tile and all JT columns: thread (r = t & 63, cg = t >> 6) sums columns
+// cg*JT/4 .. of lane element r over the pieces (coalesced along r).  For pixel lanes the block
+// then turns the 64 x JT patch through LDS so that output rows are written in 16-byte pieces.
+template <int IT, int JT, bool CH>
+__global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) {
+  constexpr int CPT = JT / 4;  // columns per thread
+  const int tile = blockIdx.x / (IT / 64);
+  const int il0 = (blockIdx.x - tile * (IT / 64)) * 64;
+  const long long t_beg = (long long)tile * a.nch, t_last = t_beg + a.nch - 1;
+  auto owner = [&](long long it) {  // the workgroup w with w*total/G <= it < (w+1)*total/G
+    long long w = it * G / a.total_iters;
+    while ((w + 1) * a.total_iters / G <= it) ++w;
+    while (w * a.total_iters / G > it) --w;
+    return (int)w;
+  };
+  const int w_first = owner(t_beg), w_last = owner(t_last);
+  if (w_first == w_last) return;  // finished inside tab_kernel
+  const int ti = tile / a.ntj;
+  const int i0 = ti * IT, j0 = (tile - ti * a.ntj) * JT;
+  if (i0 + il0 >= a.I) return;
+  const int klast = a.nch * kChunk;
   const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0];  // padded taps, see tab_kernel
-  uint32_t acc[VEC];
-#pragma unroll
-  for (int e = 0; e < VEC; ++e) acc[e] = 0u - padfix;
-  for (int s = 0; s < nsplit; ++s) {
-    const int32_t* src = a.part + (size_t)s * total + o;
-    if constexpr (VEC == 4) {
-      const uint4 v = *reinterpret_cast<const uint4*>(src);
-      acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
-    } else {
-      acc[0] += (uint32_t)src[0];
-    }
+  __shared__ long long cterm[JT];
+  __shared__ uint32_t patch[64][JT + 4];
+  __shared__ uint32_t lterm_s[64];
+  const int t = threadIdx.x, r = t & 63, cg = t >> 6;
+  if (t < JT) {
+    int32_t sb = 0;
+    for (int q = 0; q < a.nseg; ++q) sb += a.bsum[(size_t)q * a.Jpad + j0 + t];
+    cterm[t] = a.kzz - (long long)a.z_lane * sb;
   }
-  if (a.acc_out) {
-    if constexpr (VEC == 4)
-      *reinterpret_cast<uint4*>(a.acc_out + o) = make_uint4(acc[0], acc[1], acc[2], acc[3]);
-    else
-      a.acc_out[o] = (int32_t)acc[0];
+  uint32_t v[CPT];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) v[c] = 0u - padfix;
+  uint32_t sl = 0;
+  for (int w = w_first; w <= w_last; ++w) {
+    const int slot = 2 * w + (w == w_first ? 1 : 0);
+    const int32_t* pp = a.part + (size_t)slot * (IT * JT) + il0 + r;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) v[c] += (uint32_t)pp[(cg * CPT + c) * IT];
+    sl += (uint32_t)a.lsum[(size_t)slot * IT + il0 + r];
   }
-  if (a.y_out) {
-    // fastest output dimension F (columns for pixel lanes, lane elements for channel lanes)
-    const uint32_t F = CH ? (uint32_t)a.I : (uint32_t)a.J;
-    const uint32_t row = o / F, col = o - row * F;
-    uint32_t sl[VEC];
-    int32_t sb[VEC];
+  const uint32_t lterm = (uint32_t)a.z_tab * sl;
+  __syncthreads();
+  if (CH) {
+    // output index (j0 + jl) * I + i: consecutive r are consecutive words already
+    const int i = i0 + il0 + r;
+    if (i < a.I) {
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) { sl[e] = 0; sb[e] = 0; }
-    if (CH) {  // row = table column j (pixel), col.. = lane elements i (channels)
-      for (int s = 0; s < nsplit; ++s)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) sl[e] += (uint32_t)a.lsum[(size_t)s * a.I + col + e];
-      int32_t t = 0;
-      for (int q = 0; q < a.nseg; ++q) t += a.bsum[(size_t)q * a.Jpad + row];
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) sb[e] = t;
-    } else {  // row = lane element i (pixel), col.. = table columns j (channels)
-      uint32_t t = 0;
-      for (int s = 0; s < nsplit; ++s) t += (uint32_t)a.lsum[(size_t)s * a.I + row];
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) sl[e] = t;
-      for (int q = 0; q < a.nseg; ++q)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) sb[e] += a.bsum[(size_t)q * a.Jpad + col + e];
+      for (int c = 0; c < CPT; ++c) {
+        const int jl = cg * CPT + c;
+        if (j0 + jl < a.J) {
+          const size_t o = (size_t)(j0 + jl) * a.I + i;
+          if (a.acc_out) a.acc_out[o] = (int32_t)v[c];
+          if (a.y_out) a.y_out[o] = (float)((long long)(int32_t)(v[c] - lterm) + cterm[jl]) * a.scale;
+        }
+      }
     }
-    float y[VEC];
+  } else {
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      const long long corr = (long long)acc[e] - (long long)a.z_tab * sl[e] - (long long)a.z_lane * sb[e] + a.kzz;
-      y[e] = (float)corr * a.scale;
+    for (int c = 0; c < CPT; ++c) patch[r][cg * CPT + c] = v[c];
+    if (cg == 0) lterm_s[r] = lterm;
+    __syncthreads();
+    for (int idx = t; idx < 64 * (JT / 4); idx += 256) {
+      const int rr = idx / (JT / 4), c4 = idx - rr * (JT / 4);
+      const int i = i0 + il0 + rr, j = j0 + 4 * c4;
+      if (i >= a.I || j >= a.J) continue;
+      const uint32_t lt = lterm_s[rr];
+      const size_t o = (size_t)i * a.J + j;
+      if (a.vec_out) {
+        const uint4 q = *reinterpret_cast<const uint4*>(&patch[rr][4 * c4]);
+        if (a.acc_out) *reinterpret_cast<uint4*>(a.acc_out + o) = q;
+        if (a.y_out) {
+          float4 y;
+          y.x = (float)((long long)(int32_t)(q.x - lt) + cterm[4 * c4]) * a.scale;
+          y.y = (float)((long long)(int32_t)(q.y - lt) + cterm[4 * c4 + 1]) * a.scale;
+          y.z = (float)((long long)(int32_t)(q.z - lt) + cterm[4 * c4 + 2]) * a.scale;
+          y.w = (float)((long long)(int32_t)(q.w - lt) + cterm[4 * c4 + 3]) * a.scale;
+          *reinterpret_cast<float4*>(a.y_out + o) = y;
+        }
+      } else {
+        for (int e = 0; e < 4 && j + e < a.J; ++e) {
+          const uint32_t q = patch[rr][4 * c4 + e];
+          if (a.acc_out) a.acc_out[o + e] = (int32_t)q;
+          if (a.y_out) a.y_out[o + e] = (float)((long long)(int32_t)(q - lt) + cterm[4 * c4 + e]) * a.scale;
+        }
+      }
     }
-    if constexpr (VEC == 4)
-      *reinterpret_cast<float4*>(a.y_out + o) = make_float4(y[0], y[1], y[2], y[3]);
-    else
-      a.y_out[o] = y[0];
   }
 }
 
@@ -651,6 +701,36 @@ static double padded_work(long long I, long long J) {
   return (double)cdiv(I, kIT) * kIT * (double)cdiv(J, kJT) * kJT;
 }
 
+static int cu_count() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    n = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+         prop.multiProcessorCount > 0)
+            ? prop.multiProcessorCount
+            : 256;
+  }
+  return n;
+}
+
+// Number of partial tile pieces that a grid of G workgroups produces (see tab_kernel).
+static int count_partials(int ntiles, int nch, int G) {
+  const long long total = (long long)ntiles * nch;
+  int n = 0;
+  for (int w = 0; w < G; ++w) {
+    long long b = (long long)w * total / G;
+    const long long e = (long long)(w + 1) * total / G;
+    while (b < e) {
+      const long long t = b / nch;
+      const long long c0 = b - t * nch, c1 = std::min<long long>(nch, c0 + (e - b));
+      if (!(c0 == 0 && c1 == nch)) ++n;
+      b += c1 - c0;
+    }
+  }
+  return n;
+}
+
 TabPlan tab_plan(const Geom& g, const Options& o) {
   TabPlan p{};
   int v = o.variant;
@@ -659,64 +739,86 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   const long long I = (v == 2) ? g.M : g.Cout;
   const long long J = (v == 2) ? g.Cout : g.M;
   const int kIT = tile_cfg().threads * tile_cfg().P, kJT = tile_cfg().NG * 8;
-  const int tiles = cdiv(I, kIT) * cdiv(J, kJT);
-  const int nchunks = cdiv(g.K, kChunk);
-  int S = o.split_k;
-  if (S <= 0) {
-    // Fill the 256 compute units: pick the slice count with the best machine occupancy,
-    // charging a little for every extra slice (partial sums are written and re-read).
-    const int smax = (int)std::max(1LL, std::min<long long>(64, nchunks / 4));
-    double best = 1e30;
-    S = 1;
-    for (int s = 1; s <= smax; ++s) {
-      const double wgs = (double)tiles * s;
-      const double eff = wgs / (std::ceil(wgs / 256.0) * 256.0);
-      const double cost = 1.0 / eff + 0.03 * (s - 1);
-      if (cost < best - 1e-9) { best = cost; S = s; }
+  const int ntiles = cdiv(I, kIT) * cdiv(J, kJT);
+  const int nch = cdiv(g.K, kChunk);
+  const long long total = (long long)ntiles * nch;
+  const int cus = cu_count();
+
+  // Grid size: either one workgroup per tile (no partial pieces; the hardware runs them in
+  // rounds) or a grid that cuts the iteration space evenly.  A small cost model decides:
+  // a chunk of one tile takes t_chunk on a compute unit; a partial piece is written once and
+  // read once by the fix-up kernel, which also costs a launch.
+  int G = ntiles;
+  if (o.split_k > 0) {
+    G = (int)std::min<long long>(std::min<long long>(total, 4LL * cus), (long long)ntiles * o.split_k);
+  } else {
+    const double t_chunk = 16.0 * kIT * kJT / 60e9;            // seconds, ~60 G lookups/s per compute unit
+    const double t_piece = 2.0 * kIT * kJT * 4.0 / 2.5e12;    // seconds of memory traffic per partial piece
+    auto cost = [&](int Gc) {
+      const double rounds = std::ceil((double)Gc / cus);
+      const double iters = std::ceil((double)total / Gc);
+      const int np = count_partials(ntiles, nch, Gc);
+      return rounds * iters * t_chunk + np * t_piece + (np ? 8e-6 : 0.0);
+    };
+    double best = cost(ntiles);
+    std::vector<int> cand;
+    if (total >= 2) cand.push_back((int)std::min<long long>(cus, total / 2));
+    for (int sdiv = 2; sdiv <= 16; ++sdiv)
+      if ((long long)ntiles * sdiv <= cus && nch / sdiv >= 2) cand.push_back(ntiles * sdiv);
+    for (int Gc : cand) {
+      if (Gc < 1) continue;
+      const double c = cost(Gc);
+      if (c < best * 0.97) { best = c; G = Gc; }
     }
   }
-  S = std::max(1, std::min(S, nchunks));
-  p.k_per_split = cdiv(nchunks, S) * kChunk;
-  p.split_k = cdiv(g.K, p.k_per_split);
+  G = std::max(1, G);
+  p.G = G;
+  p.partials = count_partials(ntiles, nch, G);
 
-  const size_t Kp = (size_t)nchunks * kChunk;
+  const size_t Kp = (size_t)nch * kChunk;
   const size_t Jpad = (size_t)cdiv(J, 64) * 64;
   size_t off = 0;
   p.off_rows = off;   off += up256(131072);
   p.off_bpack = off;  off += up256((Kp + 1) * Jpad);
   p.off_bsum = off;   off += up256(Jpad * 4 * kMaxSeg);
   p.off_apack = off;  off += up256((size_t)I * Kp);  // only used when the lane operand is materialized
-  p.off_lsum = off;   off += up256((size_t)p.split_k * I * 4);
+  p.off_lsum = off;
   p.off_part = off;
-  if (p.split_k > 1) off += up256((size_t)p.split_k * (size_t)g.M * g.Cout * 4);
+  if (p.partials) {
+    off += up256((size_t)2 * G * kIT * 4);
+    p.off_part = off;
+    off += up256((size_t)2 * G * kIT * kJT * 4);
+  }
   p.total = off;
   return p;
 }
 
 template <int THREADS, int P, int NG, int KS, bool CH>
-static void launch_cfg(const TabArgs& a, dim3 grid, bool split, hipStream_t s) {
-  if (split)
-    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, CH, true, false>), grid, dim3(THREADS), 0, s, a);
-  else if (a.K > 16384)
-    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, CH, false, true>), grid, dim3(THREADS), 0, s, a);
+static void launch_cfg(const TabArgs& a, int G, int ntiles, bool fixup, hipStream_t s) {
+  timing_begin(s);
+  if (a.K > 16384)
+    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, CH, true>), dim3(G), dim3(THREADS), 0, s, a);
   else
-    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, CH, false, false>), grid, dim3(THREADS), 0, s, a);
+    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, CH, false>), dim3(G), dim3(THREADS), 0, s, a);
+  timing_end(s);
+  if (fixup)
+    hipLaunchKernelGGL((tab_fixup_kernel<THREADS * P, NG * 8, CH>), dim3(ntiles * (THREADS * P / 64)), dim3(256), 0, s, a, G);
 }
 
 template <bool CH>
-static void launch_main(const TabArgs& a, dim3 grid, bool split, hipStream_t s) {
+static void launch_main(const TabArgs& a, int G, int ntiles, bool fixup, hipStream_t s) {
   const TileCfg& t = tile_cfg();
   const int key = t.threads * 1000 + t.P * 100 + t.NG * 10 + t.KS;
   switch (key) {
-    case 512 * 1000 + 281: launch_cfg<512, 2, 8, 1, CH>(a, grid, split, s); break;
-    case 1024 * 1000 + 181: launch_cfg<1024, 1, 8, 1, CH>(a, grid, split, s); break;
-    case 512 * 1000 + 282: launch_cfg<512, 2, 8, 2, CH>(a, grid, split, s); break;
-    case 1024 * 1000 + 182: launch_cfg<1024, 1, 8, 2, CH>(a, grid, split, s); break;
-    case 512 * 1000 + 441: launch_cfg<512, 4, 4, 1, CH>(a, grid, split, s); break;
-    case 512 * 1000 + 442: launch_cfg<512, 4, 4, 2, CH>(a, grid, split, s); break;
-    case 1024 * 1000 + 242: launch_cfg<1024, 2, 4, 2, CH>(a, grid, split, s); break;
-    case 1024 * 1000 + 244: launch_cfg<1024, 2, 4, 4, CH>(a, grid, split, s); break;
-    case 512 * 1000 + 444: launch_cfg<512, 4, 4, 4, CH>(a, grid, split, s); break;
+    case 512 * 1000 + 281: launch_cfg<512, 2, 8, 1, CH>(a, G, ntiles, fixup, s); break;
+    case 1024 * 1000 + 181: launch_cfg<1024, 1, 8, 1, CH>(a, G, ntiles, fixup, s); break;
+    case 512 * 1000 + 282: launch_cfg<512, 2, 8, 2, CH>(a, G, ntiles, fixup, s); break;
+    case 1024 * 1000 + 182: launch_cfg<1024, 1, 8, 2, CH>(a, G, ntiles, fixup, s); break;
+    case 512 * 1000 + 441: launch_cfg<512, 4, 4, 1, CH>(a, G, ntiles, fixup, s); break;
+    case 512 * 1000 + 442: launch_cfg<512, 4, 4, 2, CH>(a, G, ntiles, fixup, s); break;
+    case 1024 * 1000 + 242: launch_cfg<1024, 2, 4, 2, CH>(a, G, ntiles, fixup, s); break;
+    case 1024 * 1000 + 244: launch_cfg<1024, 2, 4, 4, CH>(a, G, ntiles, fixup, s); break;
+    case 512 * 1000 + 444: launch_cfg<512, 4, 4, 4, CH>(a, G, ntiles, fixup, s); break;
     default: break;
   }
 }
@@ -769,7 +871,10 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   }
   a.pad4 = (uint32_t)qp.pad_code * 0x01010101u;
   a.Bp = Bp; a.Jpad = Jpad; a.J = J; a.bsum = bsum; a.nseg = cdiv(krows, seg_rows); a.rows = rows;
-  a.K = g.K; a.k_per_split = p.k_per_split;
+  a.K = g.K;
+  a.ntj = cdiv(J, kJT);
+  a.nch = nchunks;
+  a.total_iters = (long long)cdiv(I, kIT) * a.ntj * nchunks;
   a.z_lane = ch ? qp.w_zp : qp.x_zp;
   a.z_tab = ch ? qp.x_zp : qp.w_zp;
   a.kzz = (long long)g.K * qp.x_zp * qp.w_zp;
@@ -780,26 +885,8 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.out_elems = (long long)g.M * g.Cout;
   a.vec_out = (!ch && J % 4 == 0 && (((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
 
-  const dim3 grid(cdiv(I, kIT), cdiv(J, kJT), p.split_k);
-  const bool split = p.split_k > 1;
-  timing_begin(s);
-  if (ch) launch_main<true>(a, grid, split, s); else launch_main<false>(a, grid, split, s);
-  timing_end(s);
-  if (split) {
-    const bool vec = (a.out_elems % 4 == 0) && (ch || J % 4 == 0) && ((((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0);
-    const unsigned blocks = (unsigned)cdiv(cdiv(a.out_elems, vec ? 4 : 1), 256);
-    if (ch) {
-      if (vec && I % 4 == 0)
-        hipLaunchKernelGGL((tab_reduce_kernel<true, 4>), dim3(blocks), dim3(256), 0, s, a, p.split_k);
-      else
-        hipLaunchKernelGGL((tab_reduce_kernel<true, 1>), dim3((unsigned)cdiv(a.out_elems, 256)), dim3(256), 0, s, a, p.split_k);
-    } else {
-      if (vec)
-        hipLaunchKernelGGL((tab_reduce_kernel<false, 4>), dim3(blocks), dim3(256), 0, s, a, p.split_k);
-      else
-        hipLaunchKernelGGL((tab_reduce_kernel<false, 1>), dim3((unsigned)cdiv(a.out_elems, 256)), dim3(256), 0, s, a, p.split_k);
-    }
-  }
+  const int ntiles = cdiv(I, kIT) * a.ntj;
+  if (ch) launch_main<true>(a, p.G, ntiles, p.partials > 0, s); else launch_main<false>(a, p.G, ntiles, p.partials > 0, s);
   return hipGetLastError();
 }
 
