@@ -39,7 +39,8 @@ constexpr int kChunk = 16;     // taps per 16-byte lane-operand load
 struct TabArgs {
   // lane-side operand, addressed as an implicit im2col view of an [N,H,W,Cin] tensor
   const uint8_t* A;
-  int I;  // valid lane elements
+  int I;   // valid lane elements
+  int ih;  // lane elements per tile (multiple of 64, at most the kernel's tile height)
   int H, W, Cin, KW, sh, sw, ph, pw, OHW, OW;
   uint32_t pad4;  // pad code in all four bytes
   // table-side operand, packed [Krows][Jpad] with zero fill
@@ -139,14 +140,19 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
   const int c_end = (int)min((long long)a.nch, c_beg + (it_end - it_beg));
   const bool whole = (c_beg == 0) && (c_end == a.nch);
   const int ti = tile / a.ntj;
-  const int i0 = ti * IT;
+  const int i0 = ti * a.ih;  // tiles are a.ih <= IT lane elements high (a multiple of 64)
   const int j0 = (tile - ti * a.ntj) * JT;
   const int kbeg = c_beg * kChunk, kend = c_end * kChunk;
 
   // ---- lane elements -------------------------------------------------------------------
+  // slot il = p*THREADS + tid of the tile is lane element i0 + il; slots at or beyond a.ih (or
+  // beyond the operand) are padding.  act[p]: some lane of this wave's slot p is real.
   int by[P], bx[P], nb[P];
+  bool act[P];
 #pragma unroll
   for (int p = 0; p < P; ++p) {
+    const int w0 = p * THREADS + wave * 64;
+    act[p] = (w0 < a.ih) && (i0 + w0 < a.I);
     const int i = min(i0 + p * THREADS + tid, a.I - 1);
     const int n = i / a.OHW;
     const int r = i - n * a.OHW;
@@ -167,7 +173,7 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
       const bool inside = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
       const uint32_t off = ((uint32_t)(nb[p] + iy) * (uint32_t)a.W + (uint32_t)ix) * (uint32_t)a.Cin + (uint32_t)ci0;
       v[p] = make_uint4(a.pad4, a.pad4, a.pad4, a.pad4);
-      if (inside) v[p] = *reinterpret_cast<const uint4*>(a.A + off);
+      if (inside && act[p]) v[p] = *reinterpret_cast<const uint4*>(a.A + off);
     }
   };
 
@@ -267,57 +273,60 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
       sl[p] = __builtin_amdgcn_sad_u8(xa[p].z, 0u, sl[p]);
       sl[p] = __builtin_amdgcn_sad_u8(xa[p].w, 0u, sl[p]);
     }
-    // A phase issues ITEMS*NG gathers (item = one tap of one lane element).  They run through
-    // a small ring of registers: gather i+DEPTH is issued before the eight adds of gather i,
-    // so that LDS latency hides behind VALU work without a large register footprint.
-    constexpr int ITEMS = KS * P;
-    constexpr int NR = ITEMS * NG;
+    // A phase is cut into SEGS segments, each the gathers of one lane-element slot p over some
+    // taps of the phase.  A segment is skipped by waves whose 64 lanes of slot p lie outside the
+    // tile (wave-uniform), so padded lanes cost no LDS or VALU time.  Inside a segment the
+    // gathers run through a small ring of registers: gather i+DEPTH is issued before the eight
+    // adds of gather i, so that LDS latency hides behind VALU work.  The table rows of the next
+    // phase are fetched and written out between segments, one unit at a time.
+    constexpr int SUB = (UNITS > P) ? UNITS / P : 1;
+    constexpr int SEGS = P * SUB;
+    constexpr int TAPS = KS / SUB;  // taps per segment
+    constexpr int NR = TAPS * NG;   // gathers per segment
     constexpr int DEPTH = 2;
-    uint32_t item_addr[ITEMS];  // LDS byte address of entry v of group 0, per item of the phase
-    auto item_base = [&](int ph, int it) {
-      const int s = it / P, p = it - s * P;
-      const uint32_t v = byte_of(xa[p], ph * KS + s);
-      uint32_t addr = (uint32_t)(uintptr_t)&tab[ph & 1][s][0][0] + (v << 4);
-      asm volatile("" : "+v"(addr));  // keep it one register: the group offsets below fit the instruction
-      item_addr[it] = addr;
-    };
-    auto issue = [&](int ph, int i, uint4 (&ring)[DEPTH + 1]) {
-      const int it = i / NG, g = i - it * NG;
-      if (g == 0) item_base(ph, it);
-      const u32x4 e = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(item_addr[it] + g * 4096);
-      ring[i % (DEPTH + 1)] = make_uint4(e.x, e.y, e.z, e.w);
-    };
+    static_assert(KS % SUB == 0 && SEGS % UNITS == 0, "build units must align with segments");
     const uint32_t sel_hi = 0x00010000u;  // selector of the high half
-    auto retire = [&](int i, const uint4 (&ring)[DEPTH + 1]) {
-      const int it = i / NG, g = i - it * NG;
-      const int p = it % P;
-      const uint4 e = ring[i % (DEPTH + 1)];
-      add_halves(acc[p][g * 8 + 0], acc[p][g * 8 + 1], e.x, sel_hi);
-      add_halves(acc[p][g * 8 + 2], acc[p][g * 8 + 3], e.y, sel_hi);
-      add_halves(acc[p][g * 8 + 4], acc[p][g * 8 + 5], e.z, sel_hi);
-      add_halves(acc[p][g * 8 + 6], acc[p][g * 8 + 7], e.w, sel_hi);
-    };
 #pragma unroll
     for (int ph = 0; ph < PHASES; ++ph) {
-      uint4 ring[DEPTH + 1];
 #pragma unroll
-      for (int i = 0; i < DEPTH && i < NR; ++i) issue(ph, i, ring);
-#pragma unroll
-      for (int i = 0; i < NR; ++i) {
-        // unit u of this wave is fetched at gather u*NR/UNITS and written out just before
-        // gather (u+1)*NR/UNITS, so that only one unit's rows occupy registers at a time
+      for (int q = 0; q < SEGS; ++q) {
+        const int p = q / SUB;
+        const int s0 = (q % SUB) * TAPS;
 #pragma unroll
         for (int u = 0; u < UNITS; ++u)
-          if (i == u * NR / UNITS) build_issue(u, tv_cur[u >> 1][ph]);
+          if (q == u * (SEGS / UNITS)) build_issue(u, tv_cur[u >> 1][ph]);
         __builtin_amdgcn_sched_barrier(0);
-        if (i + DEPTH < NR) issue(ph, i + DEPTH, ring);
-        retire(i, ring);
+        if (act[p]) {
+          uint4 ring[DEPTH + 1];
+          uint32_t tap_addr = 0;  // LDS byte address of entry v of group 0 of the current tap
+          auto issue = [&](int i) {
+            const int t = i / NG, g = i - t * NG;
+            if (g == 0) {
+              const uint32_t v = byte_of(xa[p], ph * KS + s0 + t);
+              tap_addr = (uint32_t)(uintptr_t)&tab[ph & 1][s0 + t][0][0] + (v << 4);
+              asm volatile("" : "+v"(tap_addr));  // one register; the group offsets fit the instruction
+            }
+            const u32x4 e = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(tap_addr + g * 4096);
+            ring[i % (DEPTH + 1)] = make_uint4(e.x, e.y, e.z, e.w);
+          };
+#pragma unroll
+          for (int i = 0; i < DEPTH && i < NR; ++i) issue(i);
+#pragma unroll
+          for (int i = 0; i < NR; ++i) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + DEPTH < NR) issue(i + DEPTH);
+            const int g = i % NG;
+            const uint4 e = ring[i % (DEPTH + 1)];
+            add_halves(acc[p][g * 8 + 0], acc[p][g * 8 + 1], e.x, sel_hi);
+            add_halves(acc[p][g * 8 + 2], acc[p][g * 8 + 3], e.y, sel_hi);
+            add_halves(acc[p][g * 8 + 4], acc[p][g * 8 + 5], e.z, sel_hi);
+            add_halves(acc[p][g * 8 + 6], acc[p][g * 8 + 7], e.w, sel_hi);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < UNITS; ++u)
-          if (i == (u + 1) * NR / UNITS - 1) {
-            __builtin_amdgcn_sched_barrier(0);
-            build_commit(u, (ph + 1) & 1);
-          }
+          if (q == (u + 1) * (SEGS / UNITS) - 1) build_commit(u, (ph + 1) & 1);
       }
       __syncthreads();
     }
@@ -384,8 +393,9 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
         __syncthreads();
         for (int idx = tid; idx < PIECES; idx += THREADS) {
           const int r = idx / (JT / 4), c4 = idx - r * (JT / 4);
-          const int i = i0 + p * THREADS + t0 + r, j = j0 + 4 * c4;
-          if (i < a.I && j < a.J) {
+          const int il = p * THREADS + t0 + r;
+          const int i = i0 + il, j = j0 + 4 * c4;
+          if (il < a.ih && i < a.I && j < a.J) {
             uint4 v = *reinterpret_cast<const uint4*>(stage + r * ROW + 4 * c4);
             const uint32_t lterm = (uint32_t)a.z_tab * stage[r * ROW + JT];
             v.x -= padfix; v.y -= padfix; v.z -= padfix; v.w -= padfix;
@@ -407,7 +417,7 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
 #pragma unroll
     for (int p = 0; p < P; ++p) {
       const int i = i0 + p * THREADS + tid;
-      if (i >= a.I) continue;
+      if (i >= a.I || p * THREADS + tid >= a.ih) continue;
       const uint32_t lterm = (uint32_t)a.z_tab * sl[p];
 #pragma unroll
       for (int j = 0; j < JT; ++j) {
@@ -444,8 +454,8 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
   const int w_first = owner(t_beg), w_last = owner(t_last);
   if (w_first == w_last) return;  // finished inside tab_kernel
   const int ti = tile / a.ntj;
-  const int i0 = ti * IT, j0 = (tile - ti * a.ntj) * JT;
-  if (i0 + il0 >= a.I) return;
+  const int i0 = ti * a.ih, j0 = (tile - ti * a.ntj) * JT;
+  if (il0 >= a.ih || i0 + il0 >= a.I) return;
   const int klast = a.nch * kChunk;
   const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0];  // padded taps, see tab_kernel
   __shared__ long long cterm[JT];
@@ -473,7 +483,7 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
   if (CH) {
     // output index (j0 + jl) * I + i: consecutive r are consecutive words already
     const int i = i0 + il0 + r;
-    if (i < a.I) {
+    if (i < a.I && il0 + r < a.ih) {
 #pragma unroll
       for (int c = 0; c < CPT; ++c) {
         const int jl = cg * CPT + c;
@@ -492,7 +502,7 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
     for (int idx = t; idx < 64 * (JT / 4); idx += 256) {
       const int rr = idx / (JT / 4), c4 = idx - rr * (JT / 4);
       const int i = i0 + il0 + rr, j = j0 + 4 * c4;
-      if (i >= a.I || j >= a.J) continue;
+      if (i >= a.I || il0 + rr >= a.ih || j >= a.J) continue;
       const uint32_t lt = lterm_s[rr];
       const size_t o = (size_t)i * a.J + j;
       if (a.vec_out) {
@@ -684,9 +694,11 @@ static const TileCfg kTiles[] = {
     {1024, 2, 4, 2},  // 6: 2048 x 32 tile, 16 waves
     {1024, 2, 4, 4},  // 7: four taps per barrier (128 KB of tables)
     {512, 4, 4, 4},   // 8
+    {1024, 2, 2, 4},  // 9: 2048 x 16 tile
+    {1024, 2, 2, 8},  // 10: 2048 x 16 tile, eight taps per barrier
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
-constexpr int kDefaultTile = 7;
+constexpr int kDefaultTile = 10;
 static const TileCfg& tile_cfg() { return kTiles[(g_opt.tile >= 1 && g_opt.tile <= kNumTiles) ? g_opt.tile - 1 : kDefaultTile]; }
 int tab_num_tiles() { return kNumTiles; }
 
@@ -819,6 +831,8 @@ static void launch_main(const TabArgs& a, int G, int ntiles, bool fixup, hipStre
     case 1024 * 1000 + 242: launch_cfg<1024, 2, 4, 2, CH>(a, G, ntiles, fixup, s); break;
     case 1024 * 1000 + 244: launch_cfg<1024, 2, 4, 4, CH>(a, G, ntiles, fixup, s); break;
     case 512 * 1000 + 444: launch_cfg<512, 4, 4, 4, CH>(a, G, ntiles, fixup, s); break;
+    case 1024 * 1000 + 224: launch_cfg<1024, 2, 2, 4, CH>(a, G, ntiles, fixup, s); break;
+    case 1024 * 1000 + 228: launch_cfg<1024, 2, 2, 8, CH>(a, G, ntiles, fixup, s); break;
     default: break;
   }
 }
@@ -874,6 +888,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.K = g.K;
   a.ntj = cdiv(J, kJT);
   a.nch = nchunks;
+  a.ih = cdiv(cdiv(I, cdiv(I, kIT)), 64) * 64;  // balanced tile height: padding spread over all tiles
   a.total_iters = (long long)cdiv(I, kIT) * a.ntj * nchunks;
   a.z_lane = ch ? qp.w_zp : qp.x_zp;
   a.z_tab = ch ? qp.x_zp : qp.w_zp;
