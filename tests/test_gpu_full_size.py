@@ -1,0 +1,103 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration that
+bench.py times (automatic variant / tile / work decomposition).
+
+Small layers are compared element by element with the oracle.  For the large ones the oracle
+evaluates sampled outputs one by one, and whole-tensor properties that hold at any size are
+checked on the device: with the exact table a 1x1 layer is an integer matrix product (done in
+float64 on the GPU, exact below 2^53), and with a constant table every accumulator is c*K.
+"""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2002_09481_amd import binding as ax
+from paper_2002_09481_amd import inputs as I
+
+import gpu_common as G
+
+pytestmark = pytest.mark.gpu
+
+SAMPLES = 384
+
+
+def _run(layer, x, w, lut_d, q):
+    xd, wd = G.to_dev(x), G.to_dev(w)
+    if layer.dense:
+        acc, y = ax.ax_dense(xd.view(layer.N, layer.K), wd.view(layer.K, layer.Cout), lut_d, q)
+    else:
+        acc, y = ax.ax_conv2d(xd, wd, lut_d, layer.stride, layer.pad, q)
+    torch.cuda.synchronize()
+    return acc, y
+
+
+def _check_sampled(layer, x, w, lut, q, acc, y, rng, what):
+    n_out = layer.M * layer.Cout
+    # random outputs plus the corners of the tensor (first / last pixel and channel)
+    idx = np.concatenate([rng.integers(0, n_out, size=SAMPLES),
+                          np.array([0, layer.Cout - 1, n_out - layer.Cout, n_out - 1])]).astype(np.int64)
+    a_ref, y_ref = oracle.conv2d_sample(x, w, lut, layer.stride, layer.pad, q, idx)
+    ti = torch.from_numpy(idx).cuda()
+    a_g = acc.reshape(-1)[ti].cpu().numpy()
+    y_g = y.reshape(-1)[ti].cpu().numpy()
+    G.assert_parity(a_g, y_g, a_ref, y_ref, what)
+
+
+def test_config2_full_batch_elementwise():
+    lut = I.lut_random_error(2000)
+    lut_d = ax.lut_to_device(lut)
+    for i, layer in enumerate(I.config_resnet8_cifar(batch=128)):
+        x, w, q = I.make_operands(layer, I.layer_seed(2, i))
+        acc, y = _run(layer, x, w, lut_d, q)
+        acc_ref, y_ref = oracle.conv2d(x, w, lut, layer.stride, layer.pad, q)
+        G.assert_parity(acc.cpu().numpy(), y.cpu().numpy(), acc_ref, y_ref, layer.name)
+
+
+def test_config3_resnet50_batch32_sampled_and_constant_table():
+    lut = I.lut_truncated(6)
+    lut_d = ax.lut_to_device(lut)
+    const_d = ax.lut_to_device(I.lut_const(3))
+    rng = np.random.default_rng(303)
+    layers = I.config_resnet50(32)
+    seen = set()
+    for i, layer in enumerate(layers):
+        key = (layer.H, layer.Cin, layer.KH, layer.Cout, layer.stride, layer.dense)
+        if key in seen:
+            continue
+        seen.add(key)
+        x, w, q = I.make_operands(layer, I.layer_seed(3, i))
+        acc, y = _run(layer, x, w, lut_d, q)
+        _check_sampled(layer, x, w, lut, q, acc, y, rng, layer.name)
+        acc_c, _ = _run(layer, x, w, const_d, q)
+        assert bool((acc_c == 3 * layer.K).all()), "%s: constant table must give c*K everywhere" % layer.name
+    assert len(seen) == 24
+
+
+def test_config4_lut_sweep_layers_batch64():
+    rng = np.random.default_rng(404)
+    for i, layer in enumerate(I.config_lut_sweep(batch=64)):
+        x, w, q = I.make_operands(layer, I.layer_seed(4, i))
+        for lut_seed in (0, 17, 63):
+            lut = I.lut_random_error(lut_seed)
+            acc, y = _run(layer, x, w, ax.lut_to_device(lut), q)
+            _check_sampled(layer, x, w, lut, q, acc, y, rng, "%s lut %d" % (layer.name, lut_seed))
+
+
+def test_config5_gemm_shaped_exact_table_is_integer_gemm():
+    rng = np.random.default_rng(505)
+    exact, trunc = I.lut_exact(), I.lut_truncated(6)
+    for i, layer in enumerate(I.config_gemm_shaped()):
+        x, w, q = I.make_operands(layer, I.layer_seed(5, i))
+        acc, y = _run(layer, x, w, ax.lut_to_device(exact), q)
+        # whole tensor: exact products -> integer GEMM (float64 on the device is exact here)
+        xm = G.to_dev(x).reshape(layer.M, layer.K).double()
+        wm = G.to_dev(w).reshape(layer.K, layer.Cout).double()
+        ref = (xm @ wm).to(torch.int64)
+        assert torch.equal(acc.reshape(layer.M, layer.Cout).to(torch.int64), ref), layer.name
+        _check_sampled(layer, x, w, exact, q, acc, y, rng, layer.name + " exact")
+        acc, y = _run(layer, x, w, ax.lut_to_device(trunc), q)
+        _check_sampled(layer, x, w, trunc, q, acc, y, rng, layer.name + " truncated")
+        # error bound of the truncated multiplier: 0 <= exact - truncated <= K * 321
+        d = ref - acc.reshape(layer.M, layer.Cout).to(torch.int64)
+        assert int(d.min()) >= 0 and int(d.max()) <= layer.K * 321
