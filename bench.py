@@ -28,6 +28,7 @@ def parse():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--cpu-batch", type=int, default=32, help="images per layer for the oracle timing (0 = skip)")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads (configs 2, 4, 5)")
     return ap.parse_args()
 
 
@@ -202,6 +203,60 @@ def main():
                    args.cpu_batch, cmacs / 1e9, dt),
                "images_per_s": args.cpu_batch / dt}
 
+    # ---- secondary workloads (context; the headline stays the ResNet-50 sweep) ----------------
+    extra = None
+    if not args.no_extra:
+        extra = {}
+
+        def time_calls(fns, reps):
+            for f in fns:
+                f()
+            torch.cuda.synchronize()
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for _ in range(reps):
+                for f in fns:
+                    f()
+            a1.record()
+            torch.cuda.synchronize()
+            return a0.elapsed_time(a1) / reps
+
+        def make_call(l, seed, lut_dev):
+            x, w, q = I.make_operands(l, seed)
+            xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
+            if l.dense:
+                xd, wd = xd.view(l.N, l.K), wd.view(l.K, l.Cout)
+                acc = torch.empty((l.N, l.Cout), dtype=torch.int32, device=dev)
+                ws = torch.empty(max(256, ax.ax_dense_workspace_bytes(l.N, l.K, l.Cout)), dtype=torch.uint8, device=dev)
+                y = torch.empty(acc.shape, dtype=torch.float32, device=dev)
+                return lambda lt=lut_dev: ax.ax_dense(xd, wd, lt, q, acc, y, ws)
+            acc = torch.empty((l.N, l.OH, l.OW, l.Cout), dtype=torch.int32, device=dev)
+            ws = torch.empty(max(256, ax.ax_conv2d_workspace_bytes(x.shape, w.shape, l.stride, l.pad)),
+                             dtype=torch.uint8, device=dev)
+            y = torch.empty(acc.shape, dtype=torch.float32, device=dev)
+            return lambda lt=lut_dev: ax.ax_conv2d(xd, wd, lt, l.stride, l.pad, q, acc, y, ws)
+
+        # config 2: CIFAR-shaped stack, batch 128, random-error table
+        l2 = I.config_resnet8_cifar(128)
+        lut2 = ax.lut_to_device(I.lut_random_error(2000))
+        ms = time_calls([make_call(l, I.layer_seed(2, i), lut2) for i, l in enumerate(l2)], 50)
+        m2 = sum(l.macs for l in l2)
+        extra["config2_cifar_stack_b128"] = {"ms": ms, "lut_macs_per_s": m2 / ms * 1e3, "images_per_s": 128 / ms * 1e3}
+        # config 4: two layers against 64 tables back to back (tables resident in HBM; every call
+        # re-lays-out and re-stages its table)
+        l4 = I.config_lut_sweep(64)
+        luts = [ax.lut_to_device(I.lut_random_error(sd)) for sd in range(64)]
+        c4 = [make_call(l, I.layer_seed(4, i), luts[0]) for i, l in enumerate(l4)]
+        fns = [(lambda lt=lt, c=c: c(lt)) for lt in luts for c in c4]
+        ms = time_calls(fns, 3)
+        m4 = sum(l.macs for l in l4) * 64
+        extra["config4_lut_sweep_64_tables"] = {"ms": ms, "lut_macs_per_s": m4 / ms * 1e3, "tables_per_s": 64 / ms * 1e3}
+        # config 5: GEMM-shaped layers, truncated table
+        l5 = I.config_gemm_shaped()
+        ms = time_calls([make_call(l, I.layer_seed(5, i), lut_d) for i, l in enumerate(l5)], 20)
+        m5 = sum(l.macs for l in l5)
+        extra["config5_gemm_shaped"] = {"ms": ms, "lut_macs_per_s": m5 / ms * 1e3}
+
     out = {
         "metric": "LUT-MACs/s (ResNet-50 shapes)",
         "value": value,
@@ -223,6 +278,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "parity_sampled": parity,
+        "other_workloads": extra,
         "wall_s_timed_region": wall,
         "input_generation_s": t_gen,
     }
