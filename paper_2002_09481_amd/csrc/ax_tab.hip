@@ -96,7 +96,8 @@ __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
 }
 
 // THREADS threads, P lane elements per thread, NG table groups (8 columns each) per
-// workgroup, KS taps per barrier phase.
+// workgroup, KS taps per barrier phase, at least WPE waves per SIMD (bounds the registers:
+// 512 threads with WPE = 4 lets two workgroups share a compute unit).
 // CH: lanes are output channels (output index j*I + i) instead of pixels (i*J + j).
 // WIDE: K > 16384, the correction needs 64-bit arithmetic.
 //
@@ -110,8 +111,8 @@ __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
 // global loads of the table rows for the NEXT phase, (b) gathers from the current buffer and
 // accumulates, (c) interleaves the loaded rows into 16-byte entries and stores them into
 // the other buffer, (d) joins the barrier.
-template <int THREADS, int P, int NG, int KS, bool CH, bool WIDE>
-__global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
+template <int THREADS, int P, int NG, int KS, int WPE, bool CH, bool WIDE>
+__global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   constexpr int JT = NG * 8;
   constexpr int IT = P * THREADS;
   constexpr int WAVES = THREADS / 64;
@@ -238,10 +239,22 @@ __global__ __launch_bounds__(THREADS) void tab_kernel(const TabArgs a) {
   uint4 xa[P], xn[P];
   const int nchunks = (kend - kbeg + kChunk - 1) / kChunk;
   load_chunk(kbeg, xn);
+  {
+    // first phase's tables: fetch the rows of all units, then write them out (one global round
+    // trip; the accumulators are not live yet, so the registers are free)
+    uint32_t d0[UNITS][8];
 #pragma unroll
-  for (int u = 0; u < UNITS; ++u) {
-    build_issue(u, load_codes(u >> 1, kbeg));
-    build_commit(u, 0);
+    for (int u = 0; u < UNITS; ++u) {
+      build_issue(u, load_codes(u >> 1, kbeg));
+#pragma unroll
+      for (int c = 0; c < 8; ++c) d0[u][c] = d[c];
+    }
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) d[c] = d0[u][c];
+      build_commit(u, 0);
+    }
   }
   __syncthreads();
   // codes of the phases that follow: tv[u][ph] belongs to taps k0 + (ph+1)*KS ...
@@ -678,28 +691,30 @@ __global__ __launch_bounds__(256) void prep_transpose_kernel(const uint8_t* __re
 
 // ---- host side -------------------------------------------------------------------------
 
-constexpr int kMaxSeg = 8;  // segments of the table-side column sums
+constexpr int kMaxSeg = 64;  // segments of the table-side column sums
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 
 // Tile configurations; the "tile" option selects one by index + 1 (0 = automatic choice).
-struct TileCfg { int threads, P, NG, KS; };
+struct TileCfg { int threads, P, NG, KS, wpe; };
 static const TileCfg kTiles[] = {
-    {512, 2, 8, 1},   // 0: 1024 x 64 tile, 8 waves
-    {1024, 1, 8, 1},  // 1: 1024 x 64 tile, 16 waves
-    {512, 2, 8, 2},   // 2: two taps per barrier
-    {1024, 1, 8, 2},  // 3
-    {512, 4, 4, 1},   // 4: 2048 x 32 tile
-    {512, 4, 4, 2},   // 5
-    {1024, 2, 4, 2},  // 6: 2048 x 32 tile, 16 waves
-    {1024, 2, 4, 4},  // 7: four taps per barrier (128 KB of tables)
-    {512, 4, 4, 4},   // 8
-    {1024, 2, 2, 4},  // 9: 2048 x 16 tile
-    {1024, 2, 2, 8},  // 10: 2048 x 16 tile, eight taps per barrier
+    {512, 2, 8, 1, 2},   // 1: 1024 x 64 tile, 8 waves with up to 256 registers
+    {1024, 1, 8, 2, 4},  // 2: 1024 x 64 tile, 16 waves
+    {1024, 2, 4, 4, 4},  // 3: 2048 x 32 tile, four taps per barrier (128 KB of tables)
+    {1024, 2, 2, 4, 4},  // 4: 2048 x 16 tile
+    {1024, 2, 2, 8, 4},  // 5: 2048 x 16 tile, eight taps per barrier (128 KB of tables)
+    {512, 2, 2, 4, 4},   // 6: 1024 x 16 tile, two workgroups per compute unit
+    {512, 2, 4, 2, 4},   // 7: 1024 x 32 tile, two workgroups per compute unit
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
-constexpr int kDefaultTile = 10;
-static const TileCfg& tile_cfg() { return kTiles[(g_opt.tile >= 1 && g_opt.tile <= kNumTiles) ? g_opt.tile - 1 : kDefaultTile]; }
+constexpr int kDefaultTile = 4;
+// Forced by the "tile" option, else by shape: layers with few taps per output spend relatively
+// more time per tile outside the tap loop (first tables, output stores) and get the tile with
+// twice the columns.
+static const TileCfg& tile_of(const Geom& g) {
+  if (g_opt.tile >= 1 && g_opt.tile <= kNumTiles) return kTiles[g_opt.tile - 1];
+  return kTiles[(g.K <= 256 && g.Cout >= 32) ? 2 : kDefaultTile];
+}
 int tab_num_tiles() { return kNumTiles; }
 
 // The preparation kernels index their pieces with 32-bit integers.
@@ -708,8 +723,8 @@ bool tab_supported(const Geom& g) {
   return (long long)g.M * chunks < (1LL << 31) && (long long)g.Cout * chunks < (1LL << 31);
 }
 
-static double padded_work(long long I, long long J) {
-  const int kIT = tile_cfg().threads * tile_cfg().P, kJT = tile_cfg().NG * 8;
+static double padded_work(const TileCfg& tc, long long I, long long J) {
+  const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
   return (double)cdiv(I, kIT) * kIT * (double)cdiv(J, kJT) * kJT;
 }
 
@@ -745,16 +760,18 @@ static int count_partials(int ntiles, int nch, int G) {
 
 TabPlan tab_plan(const Geom& g, const Options& o) {
   TabPlan p{};
+  const TileCfg& tc = tile_of(g);
   int v = o.variant;
-  if (v != 2 && v != 3) v = padded_work(g.M, g.Cout) <= padded_work(g.Cout, g.M) ? 2 : 3;
+  if (v != 2 && v != 3) v = padded_work(tc, g.M, g.Cout) <= padded_work(tc, g.Cout, g.M) ? 2 : 3;
   p.variant = v;
   const long long I = (v == 2) ? g.M : g.Cout;
   const long long J = (v == 2) ? g.Cout : g.M;
-  const int kIT = tile_cfg().threads * tile_cfg().P, kJT = tile_cfg().NG * 8;
+  const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
   const int ntiles = cdiv(I, kIT) * cdiv(J, kJT);
   const int nch = cdiv(g.K, kChunk);
   const long long total = (long long)ntiles * nch;
-  const int cus = cu_count();
+  // workgroups that fit a compute unit at once (LDS and registers): the balanced grid has that many per unit
+  const int cus = cu_count() * ((tc.threads == 512 && tc.wpe == 4) ? 2 : 1);
 
   // Grid size: either one workgroup per tile (no partial pieces; the hardware runs them in
   // rounds) or a grid that cuts the iteration space evenly.  A small cost model decides:
@@ -764,7 +781,7 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   if (o.split_k > 0) {
     G = (int)std::min<long long>(std::min<long long>(total, 4LL * cus), (long long)ntiles * o.split_k);
   } else {
-    const double t_chunk = 16.0 * kIT * kJT / 60e9;            // seconds, ~60 G lookups/s per compute unit
+    const double t_chunk = 16.0 * kIT * kJT / (60e9 * cu_count() / cus);  // seconds, ~60 G lookups/s per compute unit
     const double t_piece = 2.0 * kIT * kJT * 4.0 / 2.5e12;    // seconds of memory traffic per partial piece
     auto cost = [&](int Gc) {
       const double rounds = std::ceil((double)Gc / cus);
@@ -805,34 +822,29 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   return p;
 }
 
-template <int THREADS, int P, int NG, int KS, bool CH>
+template <int THREADS, int P, int NG, int KS, int WPE, bool CH>
 static void launch_cfg(const TabArgs& a, int G, int ntiles, bool fixup, hipStream_t s) {
   timing_begin(s);
   if (a.K > 16384)
-    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, CH, true>), dim3(G), dim3(THREADS), 0, s, a);
+    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, WPE, CH, true>), dim3(G), dim3(THREADS), 0, s, a);
   else
-    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, CH, false>), dim3(G), dim3(THREADS), 0, s, a);
+    hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, WPE, CH, false>), dim3(G), dim3(THREADS), 0, s, a);
   timing_end(s);
   if (fixup)
     hipLaunchKernelGGL((tab_fixup_kernel<THREADS * P, NG * 8, CH>), dim3(ntiles * (THREADS * P / 64)), dim3(256), 0, s, a, G);
 }
 
 template <bool CH>
-static void launch_main(const TabArgs& a, int G, int ntiles, bool fixup, hipStream_t s) {
-  const TileCfg& t = tile_cfg();
-  const int key = t.threads * 1000 + t.P * 100 + t.NG * 10 + t.KS;
+static void launch_main(const TileCfg& t, const TabArgs& a, int G, int ntiles, bool fixup, hipStream_t s) {
+  const int key = t.threads * 10000 + t.P * 1000 + t.NG * 100 + t.KS * 10 + t.wpe;
   switch (key) {
-    case 512 * 1000 + 281: launch_cfg<512, 2, 8, 1, CH>(a, G, ntiles, fixup, s); break;
-    case 1024 * 1000 + 181: launch_cfg<1024, 1, 8, 1, CH>(a, G, ntiles, fixup, s); break;
-    case 512 * 1000 + 282: launch_cfg<512, 2, 8, 2, CH>(a, G, ntiles, fixup, s); break;
-    case 1024 * 1000 + 182: launch_cfg<1024, 1, 8, 2, CH>(a, G, ntiles, fixup, s); break;
-    case 512 * 1000 + 441: launch_cfg<512, 4, 4, 1, CH>(a, G, ntiles, fixup, s); break;
-    case 512 * 1000 + 442: launch_cfg<512, 4, 4, 2, CH>(a, G, ntiles, fixup, s); break;
-    case 1024 * 1000 + 242: launch_cfg<1024, 2, 4, 2, CH>(a, G, ntiles, fixup, s); break;
-    case 1024 * 1000 + 244: launch_cfg<1024, 2, 4, 4, CH>(a, G, ntiles, fixup, s); break;
-    case 512 * 1000 + 444: launch_cfg<512, 4, 4, 4, CH>(a, G, ntiles, fixup, s); break;
-    case 1024 * 1000 + 224: launch_cfg<1024, 2, 2, 4, CH>(a, G, ntiles, fixup, s); break;
-    case 1024 * 1000 + 228: launch_cfg<1024, 2, 2, 8, CH>(a, G, ntiles, fixup, s); break;
+    case 5120000 + 2812: launch_cfg<512, 2, 8, 1, 2, CH>(a, G, ntiles, fixup, s); break;
+    case 10240000 + 1824: launch_cfg<1024, 1, 8, 2, 4, CH>(a, G, ntiles, fixup, s); break;
+    case 10240000 + 2444: launch_cfg<1024, 2, 4, 4, 4, CH>(a, G, ntiles, fixup, s); break;
+    case 10240000 + 2244: launch_cfg<1024, 2, 2, 4, 4, CH>(a, G, ntiles, fixup, s); break;
+    case 10240000 + 2284: launch_cfg<1024, 2, 2, 8, 4, CH>(a, G, ntiles, fixup, s); break;
+    case 5120000 + 2244: launch_cfg<512, 2, 2, 4, 4, CH>(a, G, ntiles, fixup, s); break;
+    case 5120000 + 2424: launch_cfg<512, 2, 4, 2, 4, CH>(a, G, ntiles, fixup, s); break;
     default: break;
   }
 }
@@ -845,7 +857,8 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   const int J = ch ? g.M : g.Cout;
   const int nchunks = cdiv(g.K, kChunk);
   const int Kp = nchunks * kChunk;
-  const int kIT = tile_cfg().threads * tile_cfg().P, kJT = tile_cfg().NG * 8;
+  const TileCfg& tc = tile_of(g);
+  const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
   const int Jpad = cdiv(J, 64) * 64;
   uint16_t* rows = reinterpret_cast<uint16_t*>(wsb + p.off_rows);
   uint8_t* Bp = wsb + p.off_bpack;
@@ -856,7 +869,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
 
   // Column sums are produced per segment of rows so that more than Jpad/64 blocks share the work.
   const int krows = Kp + 1;
-  const int nseg = std::max(1, std::min(kMaxSeg, cdiv(krows, 256)));
+  const int nseg = std::max(1, std::min(kMaxSeg, cdiv(krows, 64)));
   const int seg_rows = cdiv(cdiv(krows, nseg), 16) * 16;
   const dim3 pgrid(kRowBlocks + nseg * (Jpad / 64));
   if (ch)
@@ -901,7 +914,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.vec_out = (!ch && J % 4 == 0 && (((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
 
   const int ntiles = cdiv(I, kIT) * a.ntj;
-  if (ch) launch_main<true>(a, p.G, ntiles, p.partials > 0, s); else launch_main<false>(a, p.G, ntiles, p.partials > 0, s);
+  if (ch) launch_main<true>(tc, a, p.G, ntiles, p.partials > 0, s); else launch_main<false>(tc, a, p.G, ntiles, p.partials > 0, s);
   return hipGetLastError();
 }
 

@@ -80,7 +80,7 @@ def test_forced_k_slices(variant, split_k):
     G.check_layer(L(40, 1, 1, 1000, 1, 1, 130, dense=True), 6, I.lut_truncated(6))
 
 
-TILES = list(range(1, 12))
+TILES = list(range(1, 8))
 
 
 @pytest.mark.parametrize("variant", [2, 3])
