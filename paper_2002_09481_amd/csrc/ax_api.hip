@@ -174,6 +174,7 @@ extern "C" int ax_set_option(const char* name, int value) {
     g_opt.timing = value;
     return AX_OK;
   }
+
   return AX_ERR_OPTION;
 }
 

@@ -350,7 +350,22 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   // 2^31 in magnitude; for K <= 16384 so is every partial sum, and 32-bit wrap-around
   // arithmetic is exact.  Longer K takes the 64-bit form.
   const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0];
-  if (whole && tid < JT) {
+  const bool finish = whole;  // this workgroup writes the tile's outputs
+  if (!whole) {
+    // Piece of a tile that several workgroups share: stored column-major ([column][lane
+    // element]) so that consecutive lanes write consecutive words straight from their registers.
+    const int slot = 2 * (int)blockIdx.x + (c_beg > 0 ? 0 : 1);
+    int32_t* part = a.part + (size_t)slot * (IT * JT);
+    int32_t* lsum = a.lsum + (size_t)slot * IT;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      const int il = p * THREADS + tid;
+      lsum[il] = (int32_t)sl[p];
+#pragma unroll
+      for (int j = 0; j < JT; ++j) part[j * IT + il] = (int32_t)acc[p][j];
+    }
+  }
+  if (finish && tid < JT) {
     int32_t sb = 0;
     for (int q = 0; q < a.nseg; ++q) sb += a.bsum[(size_t)q * a.Jpad + j0 + tid];
     cterm[tid] = a.kzz - (long long)a.z_lane * sb;
@@ -363,20 +378,9 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
       return (float)(int32_t)(accv - lterm + (uint32_t)cterm[jl]) * a.scale;
     }
   };
-  const int slot = 2 * (int)blockIdx.x + (c_beg > 0 ? 0 : 1);
-  int32_t* part = a.part + (size_t)slot * (IT * JT);
-  int32_t* lsum = a.lsum + (size_t)slot * IT;
 
-  if (!whole) {
-    // Partial piece: stored column-major ([column][lane element]) so that consecutive lanes
-    // write consecutive words straight from their registers; tab_fixup_kernel re-orders.
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-      const int il = p * THREADS + tid;
-      lsum[il] = (int32_t)sl[p];
-#pragma unroll
-      for (int j = 0; j < JT; ++j) part[j * IT + il] = (int32_t)acc[p][j];
-    }
+  if (!finish) {
+    // outputs are written by another workgroup or by tab_fixup_kernel
   } else if (!CH && a.vec_out) {
     // Lanes hold whole rows of JT consecutive outputs of one pixel.  Stage PX pixels at a time
     // in LDS (rows padded by 4 dwords: conflict-free 16-byte writes) and read them back so
@@ -867,6 +871,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
 
   ConvView cv{x, g.H, g.W, g.Cin, g.KW, g.sh, g.sw, g.ph, g.pw, g.OH, g.OW, g.M, g.K, qp.pad_code};
 
+  const int ntiles = cdiv(I, kIT) * cdiv(J, kJT);
   // Column sums are produced per segment of rows so that more than Jpad/64 blocks share the work.
   const int krows = Kp + 1;
   const int nseg = std::max(1, std::min(kMaxSeg, cdiv(krows, 64)));
@@ -913,8 +918,8 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.out_elems = (long long)g.M * g.Cout;
   a.vec_out = (!ch && J % 4 == 0 && (((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
 
-  const int ntiles = cdiv(I, kIT) * a.ntj;
-  if (ch) launch_main<true>(tc, a, p.G, ntiles, p.partials > 0, s); else launch_main<false>(tc, a, p.G, ntiles, p.partials > 0, s);
+  const bool fixup = p.partials > 0;
+  if (ch) launch_main<true>(tc, a, p.G, ntiles, fixup, s); else launch_main<false>(tc, a, p.G, ntiles, fixup, s);
   return hipGetLastError();
 }
 

@@ -74,6 +74,7 @@ def test_edge_shapes(variant, layer):
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("split_k", [2, 3, 7])
 def test_forced_k_slices(variant, split_k):
+    """Output tiles shared by several workgroups (combined by the fix-up kernel)."""
     ax.ax_set_option("variant", variant)
     ax.ax_set_option("split_k", split_k)
     G.check_layer(L(1, 14, 14, 64, 3, 3, 72, 1, 1, x_dist="relu", w_dist="normal"), 5, I.lut_random_error(3))
