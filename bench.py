@@ -29,7 +29,38 @@ def parse():
     ap.add_argument("--cpu-batch", type=int, default=32, help="images per layer for the oracle timing (0 = skip)")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads (configs 2, 4, 5)")
+    ap.add_argument("--probe", action="store_true", help="only run the LDS / copy micro-benchmarks and print a table")
     return ap.parse_args()
+
+
+def probe_table(ax, torch):
+    """LDS gather rates (the denominators of the roofline) and copy bandwidth, as markdown."""
+    a = torch.randn(4096, 4096, device="cuda")
+    t = time.time()
+    while time.time() - t < 1.0:  # let the clocks ramp up
+        (a @ a).sum().item()
+    names = {0: "consecutive (conflict-free)", 1: "uniform random", 2: "random, half of the lanes on entry 0"}
+    print("| read width | pattern | table | T lanes/s | TB/s | lookups per lane |")
+    print("|---|---|---|---|---|---|")
+    for width in (2, 4, 8, 16):
+        for pat in (0, 1, 2):
+            for tb in ((32768,) if pat == 0 else (4096, 131072)):
+                r = ax.ax_probe_lds_gather(width, pat, tb, 1024, 20000 if width < 16 else 10000)
+                lanes = r["wave_reads"] * r["workgroups"] * 64 / r["seconds"]
+                print("| %d B | %s | %d KiB | %.2f | %.1f | %d |" % (width, names[pat], tb // 1024, lanes / 1e12,
+                                                                  lanes * width / 1e12, max(1, width // 2)))
+    nb = 1 << 30
+    x = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    y = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    ax.ax_probe_copy(y, x)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        ax.ax_probe_copy(y, x)
+    e1.record()
+    torch.cuda.synchronize()
+    print("\ncopy kernel, 1 GiB: %.1f GB/s (read + write)" % (2 * nb * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9))
 
 
 def main():
@@ -53,6 +84,10 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+
+    if args.probe:
+        probe_table(ax, torch)
+        return
 
     layers = I.config_resnet50(args.batch)
     lut = I.lut_truncated(6)
