@@ -115,6 +115,14 @@ int ax_version(void);
 int ax_set_option(const char* name, int value);
 int ax_get_option(const char* name, int* value);
 
+/* What a call with this geometry would run under the current options (host arithmetic only):
+ * variant as in the "variant" option (1, 2 or 3), tile configuration (0 for the direct kernel),
+ * grid size of the main kernel and number of partial tile pieces it would produce.  Any output
+ * pointer may be NULL.  A dense layer is the geometry (M, 1, 1, K, 1, 1, N, 1, 1, 0, 0). */
+int ax_conv2d_plan(int N, int H, int W, int Cin, int KH, int KW, int Cout, int stride_h,
+                   int stride_w, int pad_h, int pad_w, int* variant, int* tile, int* workgroups,
+                   int* pieces);
+
 /* Duration in milliseconds of the main kernel of the most recent layer call made while the
  * "timing" option was on (operand preparation and the K-slice reduction are not included).
  * Waits for that kernel to finish.  AX_ERR_OPTION if no timed call has been made. */

@@ -37,7 +37,7 @@ class ax_quant_t(ctypes.Structure):
 
 EXPORTS = [
     "ax_conv2d", "ax_conv2d_workspace_bytes", "ax_dense", "ax_dense_workspace_bytes", "ax_strerror",
-    "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_last_kernel_ms",
+    "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_last_kernel_ms", "ax_conv2d_plan",
 ]
 
 
@@ -73,6 +73,9 @@ def lib():
     L.ax_probe_lds_gather.restype = ci
     L.ax_probe_mac.argtypes = [ci, ci, ci, ci, dp, dp, vp]
     L.ax_probe_mac.restype = ci
+    ip = ctypes.POINTER(ci)
+    L.ax_conv2d_plan.argtypes = [ci] * 11 + [ip, ip, ip, ip]
+    L.ax_conv2d_plan.restype = ci
     L.ax_last_kernel_ms.argtypes = [ctypes.POINTER(ctypes.c_float)]
     L.ax_last_kernel_ms.restype = ci
     L.ax_probe_copy.argtypes = [vp, vp, sz, vp]
@@ -102,6 +105,16 @@ def ax_get_option(name: str) -> int:
     v = ctypes.c_int(0)
     _check(lib().ax_get_option(name.encode(), ctypes.byref(v)))
     return v.value
+
+
+def ax_conv2d_plan(x_shape, w_shape, stride=1, pad=0) -> dict:
+    N, H, W, Cin = [int(v) for v in x_shape]
+    KH, KW, _, Cout = [int(v) for v in w_shape]
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    out = [ctypes.c_int(0) for _ in range(4)]
+    _check(lib().ax_conv2d_plan(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, *[ctypes.byref(o) for o in out]))
+    return {"variant": out[0].value, "tile": out[1].value, "workgroups": out[2].value, "pieces": out[3].value}
 
 
 def ax_last_kernel_ms() -> float:

@@ -193,3 +193,23 @@ extern "C" int ax_last_kernel_ms(float* ms) {
   if (hipEventSynchronize(g_ev1) != hipSuccess) return AX_ERR_HIP;
   return hipEventElapsedTime(ms, g_ev0, g_ev1) == hipSuccess ? AX_OK : AX_ERR_HIP;
 }
+
+extern "C" int ax_conv2d_plan(int N, int H, int W, int Cin, int KH, int KW, int Cout, int stride_h, int stride_w,
+                              int pad_h, int pad_w, int* variant, int* tile, int* workgroups, int* pieces) {
+  Geom g;
+  int rc = make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g);
+  if (rc) return rc;
+  const int v = choose_variant(g);
+  int pv = 1, pt = 0, pg = 0, pp = 0;
+  if (v != 1) {
+    Options o = g_opt;
+    o.variant = v;
+    const TabPlan p = tab_plan(g, o);
+    pv = p.variant; pt = p.tile + 1; pg = p.G; pp = p.partials;
+  }
+  if (variant) *variant = pv;
+  if (tile) *tile = pt;
+  if (workgroups) *workgroups = pg;
+  if (pieces) *pieces = pp;
+  return AX_OK;
+}

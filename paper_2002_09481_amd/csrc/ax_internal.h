@@ -45,6 +45,7 @@ hipError_t launch_direct(const Geom& g, const QParams& qp, const uint8_t* x, con
 // Table-tile kernels (ax_tab.hip).
 struct TabPlan {
   int variant;      // 2 or 3
+  int tile;         // index of the tile configuration
   int G;            // workgroups of the main kernel
   int partials;     // partial tile pieces that grid produces (0: no fix-up pass)
   size_t off_rows;  // workspace offsets (bytes)

@@ -712,24 +712,12 @@ static const TileCfg kTiles[] = {
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int kDefaultTile = 4;
-// Forced by the "tile" option, else by shape: layers with few taps per output spend relatively
-// more time per tile outside the tap loop (first tables, output stores) and get the tile with
-// twice the columns.
-static const TileCfg& tile_of(const Geom& g) {
-  if (g_opt.tile >= 1 && g_opt.tile <= kNumTiles) return kTiles[g_opt.tile - 1];
-  return kTiles[(g.K <= 256 && g.Cout >= 32) ? 2 : kDefaultTile];
-}
 int tab_num_tiles() { return kNumTiles; }
 
 // The preparation kernels index their pieces with 32-bit integers.
 bool tab_supported(const Geom& g) {
   const long long chunks = cdiv(g.K, kChunk);
   return (long long)g.M * chunks < (1LL << 31) && (long long)g.Cout * chunks < (1LL << 31);
-}
-
-static double padded_work(const TileCfg& tc, long long I, long long J) {
-  const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
-  return (double)cdiv(I, kIT) * kIT * (double)cdiv(J, kJT) * kJT;
 }
 
 static int cu_count() {
@@ -762,51 +750,83 @@ static int count_partials(int ntiles, int nch, int G) {
   return n;
 }
 
-TabPlan tab_plan(const Geom& g, const Options& o) {
-  TabPlan p{};
-  const TileCfg& tc = tile_of(g);
-  int v = o.variant;
-  if (v != 2 && v != 3) v = padded_work(tc, g.M, g.Cout) <= padded_work(tc, g.Cout, g.M) ? 2 : 3;
-  p.variant = v;
+// Cost model of one (tile configuration, lane assignment, grid size) choice, in seconds.
+//   - a chunk (16 taps) of a full tile runs at ~75 G lookups/s on a compute unit; tiles are `ih`
+//     high (in steps of 64) and waves without real lane elements skip most of the work;
+//   - every segment a workgroup runs costs a fixed ~5 us (first tables, pipeline fill, stores);
+//   - a partial piece is written once and read once (~2.5 TB/s), and needs the fix-up launch;
+//   - grids larger than the machine run in rounds.
+struct PlanChoice { int tile, variant, G, partials; double cost; };
+
+static PlanChoice plan_choice(const Geom& g, int tile, int v, int forced_split) {
+  const TileCfg& tc = kTiles[tile];
   const long long I = (v == 2) ? g.M : g.Cout;
   const long long J = (v == 2) ? g.Cout : g.M;
   const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
-  const int ntiles = cdiv(I, kIT) * cdiv(J, kJT);
+  const int nti = cdiv(I, kIT);
+  const int ntiles = nti * cdiv(J, kJT);
   const int nch = cdiv(g.K, kChunk);
   const long long total = (long long)ntiles * nch;
-  // workgroups that fit a compute unit at once (LDS and registers): the balanced grid has that many per unit
-  const int cus = cu_count() * ((tc.threads == 512 && tc.wpe == 4) ? 2 : 1);
-
-  // Grid size: either one workgroup per tile (no partial pieces; the hardware runs them in
-  // rounds) or a grid that cuts the iteration space evenly.  A small cost model decides:
-  // a chunk of one tile takes t_chunk on a compute unit; a partial piece is written once and
-  // read once by the fix-up kernel, which also costs a launch.
-  int G = ntiles;
-  if (o.split_k > 0) {
-    G = (int)std::min<long long>(std::min<long long>(total, 4LL * cus), (long long)ntiles * o.split_k);
-  } else {
-    const double t_chunk = 16.0 * kIT * kJT / (60e9 * cu_count() / cus);  // seconds, ~60 G lookups/s per compute unit
-    const double t_piece = 2.0 * kIT * kJT * 4.0 / 2.5e12;    // seconds of memory traffic per partial piece
-    auto cost = [&](int Gc) {
-      const double rounds = std::ceil((double)Gc / cus);
-      const double iters = std::ceil((double)total / Gc);
-      const int np = count_partials(ntiles, nch, Gc);
-      return rounds * iters * t_chunk + np * t_piece + (np ? 8e-6 : 0.0);
-    };
-    double best = cost(ntiles);
-    std::vector<int> cand;
-    if (total >= 2) cand.push_back((int)std::min<long long>(cus, total / 2));
-    for (int sdiv = 2; sdiv <= 16; ++sdiv)
-      if ((long long)ntiles * sdiv <= cus && nch / sdiv >= 2) cand.push_back(ntiles * sdiv);
-    for (int Gc : cand) {
-      if (Gc < 1) continue;
-      const double c = cost(Gc);
-      if (c < best * 0.97) { best = c; G = Gc; }
-    }
+  const int per_cu = (tc.threads == 512 && tc.wpe == 4) ? 2 : 1;  // workgroups resident per compute unit
+  const int slots = cu_count() * per_cu;
+  const int ih = cdiv(cdiv(I, nti), 64) * 64;
+  // waves without real lanes skip the gathers, but tables, barriers and latencies stay: ~30 % of a
+  // chunk's time does not shrink with the tile height
+  const double t_chunk = 16.0 * (0.3 * kIT + 0.7 * ih) * kJT / (75e9 / per_cu);
+  const double t_piece = 2.0 * kIT * kJT * 4.0 / 2.5e12;
+  auto cost = [&](int Gc, int* np_out) {
+    const double rounds = std::ceil((double)Gc / slots);
+    const double iters = std::ceil((double)total / Gc);
+    const double segs = std::ceil(iters / nch) + (Gc == ntiles ? 0.0 : 1.0);
+    const int np = count_partials(ntiles, nch, Gc);
+    *np_out = np;
+    return rounds * (iters * t_chunk + segs * 5e-6) + np * t_piece + (np ? 8e-6 : 0.0);
+  };
+  PlanChoice best{tile, v, ntiles, 0, 0.0};
+  if (forced_split > 0) {
+    best.G = (int)std::max<long long>(1, std::min<long long>(std::min<long long>(total, 4LL * slots), (long long)ntiles * forced_split));
+    best.cost = cost(best.G, &best.partials);
+    return best;
   }
-  G = std::max(1, G);
-  p.G = G;
-  p.partials = count_partials(ntiles, nch, G);
+  best.cost = cost(ntiles, &best.partials);
+  std::vector<int> cand;
+  if (total >= 2) cand.push_back((int)std::min<long long>(slots, total / 2));
+  for (int sdiv = 2; sdiv <= 16; ++sdiv)
+    if ((long long)ntiles * sdiv <= slots && nch / sdiv >= 2) cand.push_back(ntiles * sdiv);
+  for (int Gc : cand) {
+    if (Gc < 1) continue;
+    int np = 0;
+    const double c = cost(Gc, &np);
+    if (c < best.cost * 0.97) { best.cost = c; best.G = Gc; best.partials = np; }
+  }
+  return best;
+}
+
+TabPlan tab_plan(const Geom& g, const Options& o) {
+  TabPlan p{};
+  // Lane assignment: pixels on the lanes unless channels fill the lane tiles clearly better.
+  int v = o.variant;
+  if (v != 2 && v != 3) {
+    auto fill = [](long long n) { return (double)n / ((double)cdiv(n, 2048) * 2048.0); };
+    v = (fill(g.Cout) > fill(g.M) + 0.15) ? 3 : 2;
+  }
+  // Tile and grid: the forced tile, else the cheaper of the two 2048-lane tiles by the cost model.
+  PlanChoice best{0, 0, 0, 0, 1e30};
+  for (int tile = 0; tile < kNumTiles; ++tile) {
+    if (g_opt.tile >= 1 ? tile != g_opt.tile - 1 : (tile != 2 && tile != 4)) continue;
+    const PlanChoice c = plan_choice(g, tile, v, o.split_k);
+    if (c.cost < best.cost) best = c;
+  }
+  p.variant = best.variant;
+  p.tile = best.tile;
+  p.G = best.G;
+  p.partials = best.partials;
+  const TileCfg& tc = kTiles[best.tile];
+  const int G = best.G;
+  const long long I = (v == 2) ? g.M : g.Cout;
+  const long long J = (v == 2) ? g.Cout : g.M;
+  const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
+  const int nch = cdiv(g.K, kChunk);
 
   const size_t Kp = (size_t)nch * kChunk;
   const size_t Jpad = (size_t)cdiv(J, 64) * 64;
@@ -861,7 +881,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   const int J = ch ? g.M : g.Cout;
   const int nchunks = cdiv(g.K, kChunk);
   const int Kp = nchunks * kChunk;
-  const TileCfg& tc = tile_of(g);
+  const TileCfg& tc = kTiles[p.tile];
   const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
   const int Jpad = cdiv(J, 64) * 64;
   uint16_t* rows = reinterpret_cast<uint16_t*>(wsb + p.off_rows);
