@@ -296,7 +296,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     constexpr int SEGS = P * SUB;
     constexpr int TAPS = KS / SUB;  // taps per segment
     constexpr int NR = TAPS * NG;   // gathers per segment
-    constexpr int DEPTH = 2;
+    constexpr int DEPTH = 3;
     static_assert(KS % SUB == 0 && SEGS % UNITS == 0, "build units must align with segments");
     const uint32_t sel_hi = 0x00010000u;  // selector of the high half
 #pragma unroll
@@ -311,15 +311,21 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
         __builtin_amdgcn_sched_barrier(0);
         if (act[p]) {
           uint4 ring[DEPTH + 1];
-          uint32_t tap_addr = 0;  // LDS byte address of entry v of group 0 of the current tap
+          // Address of a gather = table base + group * 4096 + 16 * code.  The constant part goes
+          // into the instruction's 16-bit offset field where it fits (tables in the first 64 KB of
+          // LDS): then 16 * code is one sub-dword shift.  For the others the table base is added
+          // to the register once per tap.
+          uint32_t tap_addr = 0;
           auto issue = [&](int i) {
             const int t = i / NG, g = i - t * NG;
+            const bool low = ((((ph & 1) * KS + s0 + t) * NG + NG) * 4096) <= 65536;
             if (g == 0) {
               const uint32_t v = byte_of(xa[p], ph * KS + s0 + t);
-              tap_addr = (uint32_t)(uintptr_t)&tab[ph & 1][s0 + t][0][0] + (v << 4);
-              asm volatile("" : "+v"(tap_addr));  // one register; the group offsets fit the instruction
+              tap_addr = low ? (v << 4) : (uint32_t)(uintptr_t)&tab[ph & 1][s0 + t][0][0] + (v << 4);
+              asm volatile("" : "+v"(tap_addr));  // keep it one register
             }
-            const u32x4 e = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(tap_addr + g * 4096);
+            const uint32_t cpart = low ? (uint32_t)(uintptr_t)&tab[ph & 1][s0 + t][g][0] : (uint32_t)(g * 4096);
+            const u32x4 e = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(tap_addr + cpart);
             ring[i % (DEPTH + 1)] = make_uint4(e.x, e.y, e.z, e.w);
           };
 #pragma unroll
