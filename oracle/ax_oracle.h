@@ -40,6 +40,28 @@ int ax_oracle_conv2d_sample(const uint8_t* x, int N, int H, int W, int Cin, cons
 int ax_oracle_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint16_t* lut,
                     const ax_oracle_quant* q, int32_t* acc_out, float* y_out);
 
+/* ---- float-in / float-out layer (ax_oracle_quant.c) ------------------------------------ */
+
+/* range_out[0] = min, range_out[1] = max over x[0..n) (after max(.,0) when relu != 0). */
+int ax_oracle_range_f32(const float* x, int64_t n, int relu, float* range_out);
+
+/* (min, max) -> scale alpha and zero point beta of Eq. (1); round_mode 0 = halves to even,
+ * 1 = halves away from zero. */
+int ax_oracle_coeffs(const float* range, int round_mode, float* alpha_out, int32_t* beta_out);
+
+/* codes_out[i] = clamp(round(relu?(x[i]) / alpha) + beta, 0, 255). */
+int ax_oracle_quantize_f32(const float* x, int64_t n, int relu, float alpha, int32_t beta,
+                           int round_mode, uint8_t* codes_out);
+
+/* The whole layer on float tensors: x [N,H,W,Cin], w [KH,KW,Cin,Cout], ranges of two floats
+ * each.  relu applies to x only.  xq_out, wq_out (the codes) and q_out (the coefficients) may
+ * be NULL. */
+int ax_oracle_conv2d_f32(const float* x, int N, int H, int W, int Cin, const float* w, int KH, int KW,
+                         int Cout, const uint16_t* lut, int stride_h, int stride_w, int pad_h,
+                         int pad_w, const float* x_range, const float* w_range, int relu,
+                         int round_mode, uint8_t* xq_out, uint8_t* wq_out, ax_oracle_quant* q_out,
+                         int32_t* acc_out, float* y_out);
+
 /* Number of threads the parallel loops use. */
 int ax_oracle_threads(void);
 

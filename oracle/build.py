@@ -8,12 +8,13 @@ LIB = os.path.join(HERE, "libax_oracle.so")
 
 
 def build(force: bool = True) -> str:
-    src = os.path.join(HERE, "ax_oracle.c")
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(
-        os.path.getmtime(src), os.path.getmtime(os.path.join(HERE, "ax_oracle.h"))
-    ):
+    srcs = [os.path.join(HERE, "ax_oracle.c"), os.path.join(HERE, "ax_oracle_quant.c")]
+    deps = srcs + [os.path.join(HERE, "ax_oracle.h")]
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(d) for d in deps):
         return LIB
-    cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", LIB, src]
+    # -ffp-contract=off: the float32 steps of the quantization must stay single IEEE operations.
+    cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+           "-o", LIB] + srcs + ["-lm"]
     subprocess.run(cmd, check=True, cwd=HERE)
     return LIB
 

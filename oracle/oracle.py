@@ -32,7 +32,15 @@ def lib():
         _lib.ax_oracle_conv2d.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, vp]
         _lib.ax_oracle_conv2d_sample.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, ci, vp, vp]
         _lib.ax_oracle_dense.argtypes = [vp, ci, ci, vp, ci, vp, vp, vp, vp]
-        for f in (_lib.ax_oracle_conv2d, _lib.ax_oracle_conv2d_sample, _lib.ax_oracle_dense, _lib.ax_oracle_threads):
+        i64, cf = ctypes.c_int64, ctypes.c_float
+        _lib.ax_oracle_range_f32.argtypes = [vp, i64, ci, vp]
+        _lib.ax_oracle_coeffs.argtypes = [vp, ci, vp, vp]
+        _lib.ax_oracle_quantize_f32.argtypes = [vp, i64, ci, cf, ctypes.c_int32, ci, vp]
+        _lib.ax_oracle_conv2d_f32.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, ci, ci,
+                                              vp, vp, vp, vp, vp]
+        for f in (_lib.ax_oracle_conv2d, _lib.ax_oracle_conv2d_sample, _lib.ax_oracle_dense, _lib.ax_oracle_threads,
+                  _lib.ax_oracle_range_f32, _lib.ax_oracle_coeffs, _lib.ax_oracle_quantize_f32,
+                  _lib.ax_oracle_conv2d_f32):
             f.restype = ci
     return _lib
 
@@ -113,6 +121,64 @@ def dense(x, w, lut, q):
     if rc:
         raise RuntimeError("ax_oracle_dense failed: %d" % rc)
     return acc, y
+
+
+def range_f32(x, relu=False):
+    """(min, max) of a float32 tensor as a float32 array of two."""
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    out = np.empty(2, np.float32)
+    rc = lib().ax_oracle_range_f32(x.ctypes.data, x.size, int(bool(relu)), out.ctypes.data)
+    if rc:
+        raise RuntimeError("ax_oracle_range_f32 failed: %d" % rc)
+    return out
+
+
+def coeffs(rng, round_mode=0):
+    """(alpha, beta) for a range of two float32 values."""
+    rng = _chk(np.asarray(rng, dtype=np.float32), np.float32, 1)
+    a = ctypes.c_float()
+    b = ctypes.c_int32()
+    rc = lib().ax_oracle_coeffs(rng.ctypes.data, int(round_mode), ctypes.addressof(a), ctypes.addressof(b))
+    if rc:
+        raise RuntimeError("ax_oracle_coeffs failed: %d" % rc)
+    return float(a.value), int(b.value)
+
+
+def quantize_f32(x, alpha, beta, relu=False, round_mode=0):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, np.uint8)
+    rc = lib().ax_oracle_quantize_f32(x.ctypes.data, x.size, int(bool(relu)), float(alpha), int(beta),
+                                      int(round_mode), out.ctypes.data)
+    if rc:
+        raise RuntimeError("ax_oracle_quantize_f32 failed: %d" % rc)
+    return out
+
+
+def conv2d_f32(x, w, lut, stride, pad, x_range, w_range, relu=False, round_mode=0):
+    """Float layer.  Returns dict(acc, y, xq, wq, x_scale, x_zp, w_scale, w_zp)."""
+    x, w, lut = _chk(x, np.float32, 4), _chk(w, np.float32, 4), _lut(lut)
+    xr = _chk(np.asarray(x_range, dtype=np.float32), np.float32, 1)
+    wr = _chk(np.asarray(w_range, dtype=np.float32), np.float32, 1)
+    N, H, W, Cin = x.shape
+    KH, KW, Cin2, Cout = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    OH, OW, sh, sw, ph, pw = out_hw(H, W, KH, KW, stride, pad)
+    if OH <= 0 or OW <= 0:
+        raise ValueError("empty output")
+    acc = np.empty((N, OH, OW, Cout), np.int32)
+    y = np.empty((N, OH, OW, Cout), np.float32)
+    xq = np.empty(x.shape, np.uint8)
+    wq = np.empty(w.shape, np.uint8)
+    qs = _Quant()
+    rc = lib().ax_oracle_conv2d_f32(x.ctypes.data, N, H, W, Cin, w.ctypes.data, KH, KW, Cout, lut.ctypes.data,
+                                    sh, sw, ph, pw, xr.ctypes.data, wr.ctypes.data, int(bool(relu)), int(round_mode),
+                                    xq.ctypes.data, wq.ctypes.data, ctypes.addressof(qs), acc.ctypes.data,
+                                    y.ctypes.data)
+    if rc:
+        raise RuntimeError("ax_oracle_conv2d_f32 failed: %d" % rc)
+    return dict(acc=acc, y=y, xq=xq, wq=wq, x_scale=float(qs.x_scale), x_zp=int(qs.x_zp),
+                w_scale=float(qs.w_scale), w_zp=int(qs.w_zp))
 
 
 def threads() -> int:

@@ -209,6 +209,28 @@ def make_operands(layer: Layer, seed: int) -> Tuple[np.ndarray, np.ndarray, Quan
     return x, w, q
 
 
+def make_float_operands(layer: Layer, seed: int):
+    """Real-valued activations (N,H,W,Cin) and filters (KH,KW,Cin,Cout) as float32, for the
+    float-in / float-out form of the layer.  Activations are standard normal (the layer's own
+    ReLU option, not the generator, clips them); "uniform" layers draw from [-2, 2).  Filters
+    are normal with the layer's sigma, or uniform in [-1, 1)."""
+    rng = np.random.default_rng(seed)
+    xs = (layer.N, layer.H, layer.W, layer.Cin)
+    ws = (layer.KH, layer.KW, layer.Cin, layer.Cout)
+    if layer.x_dist == "uniform":
+        x = (rng.random(size=xs, dtype=np.float32) * np.float32(4.0) - np.float32(2.0)).astype(np.float32)
+    else:
+        x = rng.standard_normal(size=xs, dtype=np.float32)
+        if layer.x_dist == "relu6":
+            np.minimum(x, 6.0, out=x)
+    if layer.w_dist == "uniform":
+        w = (rng.random(size=ws, dtype=np.float32) * np.float32(2.0) - np.float32(1.0)).astype(np.float32)
+    else:
+        sigma = {"normal": 1.0, "normal01": 0.1}[layer.w_dist]
+        w = rng.standard_normal(size=ws, dtype=np.float32) * np.float32(sigma)
+    return x, w
+
+
 # ----------------------------------------------------------------------------------------
 # the five workloads
 # ----------------------------------------------------------------------------------------
