@@ -92,6 +92,67 @@ int ax_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint
 
 size_t ax_dense_workspace_bytes(int M, int K, int N);
 
+/* ---- float-in / float-out form of the layer (Sec. III: the approximate layer reads two
+ * float tensors plus the range of each and returns a float tensor; Algorithm 1: ComputeCoeffs,
+ * quantization, lookup-MAC, dequantization) ------------------------------------------------
+ *
+ * Arithmetic, every step a single IEEE float32 operation in this order:
+ *   lo = min(range[0], 0), hi = max(range[1], 0)     the range is widened to hold r = 0, which
+ *                                                    makes zero exactly representable (Sec. II)
+ *   alpha = (hi - lo) / 255, or 1 if that is not positive
+ *   beta  = clamp(round(-lo / alpha), 0, 255)
+ *   code(r) = clamp(round(r / alpha) + beta, 0, 255)          (Eq. (1) solved for the code)
+ * round_mode 0 rounds halves to even, 1 rounds halves away from zero (the layer's "round mode"
+ * parameter, Sec. III); other values give AX_ERR_OPTION.  relu != 0 replaces r by max(r, 0)
+ * first: the activation between two chained layers, fused into the pass that reads the tensor.
+ * Tensor values must be finite.  Ranges live in DEVICE memory as two floats (min, max), the
+ * way the minimum / maximum operators in front of the layer deliver them (Sec. III).
+ */
+
+/* One (alpha, beta) pair of Eq. (1) as the quantization kernels store it in device memory. */
+typedef struct {
+  float scale;
+  int32_t zero_point;
+} ax_coeffs_t;
+
+/* Minimum and maximum of x[0..n), n >= 1 (AX_ERR_SHAPE otherwise): range_out[0] = min,
+ * range_out[1] = max, of max(x, 0) when relu != 0.  Evaluated once per batch in front of each
+ * layer (Sec. III).  workspace: ax_range_workspace_bytes(n) bytes, 256-byte aligned. */
+int ax_range_f32(const float* x, size_t n, int relu, float* range_out, void* workspace,
+                 size_t workspace_bytes, void* hip_stream);
+size_t ax_range_workspace_bytes(size_t n);
+
+/* codes_out[i] = code(x[i]) with the coefficients derived from `range` (device, two floats).
+ * coeffs_out (device, may be NULL) receives alpha and beta.  n >= 1.  No workspace. */
+int ax_quantize_f32(const float* x, size_t n, const float* range, int relu, int round_mode,
+                    uint8_t* codes_out, ax_coeffs_t* coeffs_out, void* hip_stream);
+
+/*
+ * The whole layer of Algorithm 1 on float tensors:
+ *   x [N,H,W,Cin] float, w [KH,KW,Cin,Cout] float, x_range / w_range device float[2],
+ *   lut as for ax_conv2d; relu applies to x only.
+ *   (alpha1, beta1) from x_range, (alpha2, beta2) from w_range; both tensors are quantized
+ *   (into the workspace); taps outside the image carry the real value 0, i.e. the code beta1;
+ *   acc_out (optional) and y_out are those of ax_conv2d for these codes and coefficients:
+ *   y = float(corr) * (alpha1 * alpha2), the product of the scales taken in float32.
+ * workspace: ax_conv2d_f32_workspace_bytes(...) bytes; it also holds the codes and the
+ * coefficients, which never visit the host.
+ */
+int ax_conv2d_f32(const float* x, int N, int H, int W, int Cin, const float* w, int KH, int KW,
+                  int Cout, const uint16_t* lut, int stride_h, int stride_w, int pad_h, int pad_w,
+                  const float* x_range, const float* w_range, int relu, int round_mode,
+                  int32_t* acc_out, float* y_out, void* workspace, size_t workspace_bytes,
+                  void* hip_stream);
+size_t ax_conv2d_f32_workspace_bytes(int N, int H, int W, int Cin, int KH, int KW, int Cout,
+                                     int stride_h, int stride_w, int pad_h, int pad_w);
+
+/* Dense form: x [M,K] float, w [K,N] float (Eq. (2)-(4) after the same quantization). */
+int ax_dense_f32(const float* x, int M, int K, const float* w, int N, const uint16_t* lut,
+                 const float* x_range, const float* w_range, int relu, int round_mode,
+                 int32_t* acc_out, float* y_out, void* workspace, size_t workspace_bytes,
+                 void* hip_stream);
+size_t ax_dense_f32_workspace_bytes(int M, int K, int N);
+
 const char* ax_strerror(int code);
 
 /* Library version, major * 10000 + minor * 100 + patch. */

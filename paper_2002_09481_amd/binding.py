@@ -38,6 +38,8 @@ class ax_quant_t(ctypes.Structure):
 EXPORTS = [
     "ax_conv2d", "ax_conv2d_workspace_bytes", "ax_dense", "ax_dense_workspace_bytes", "ax_strerror",
     "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_last_kernel_ms", "ax_conv2d_plan",
+    "ax_range_f32", "ax_range_workspace_bytes", "ax_quantize_f32", "ax_conv2d_f32", "ax_conv2d_f32_workspace_bytes",
+    "ax_dense_f32", "ax_dense_f32_workspace_bytes",
 ]
 
 
@@ -80,6 +82,21 @@ def lib():
     L.ax_last_kernel_ms.restype = ci
     L.ax_probe_copy.argtypes = [vp, vp, sz, vp]
     L.ax_probe_copy.restype = ci
+    L.ax_range_f32.argtypes = [vp, sz, ci, vp, vp, sz, vp]
+    L.ax_range_f32.restype = ci
+    L.ax_range_workspace_bytes.argtypes = [sz]
+    L.ax_range_workspace_bytes.restype = sz
+    L.ax_quantize_f32.argtypes = [vp, sz, vp, ci, ci, vp, vp, vp]
+    L.ax_quantize_f32.restype = ci
+    L.ax_conv2d_f32.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, ci, ci, vp, vp, vp,
+                                sz, vp]
+    L.ax_conv2d_f32.restype = ci
+    L.ax_conv2d_f32_workspace_bytes.argtypes = [ci] * 11
+    L.ax_conv2d_f32_workspace_bytes.restype = sz
+    L.ax_dense_f32.argtypes = [vp, ci, ci, vp, ci, vp, vp, vp, ci, ci, vp, vp, vp, sz, vp]
+    L.ax_dense_f32.restype = ci
+    L.ax_dense_f32_workspace_bytes.argtypes = [ci, ci, ci]
+    L.ax_dense_f32_workspace_bytes.restype = sz
     _lib = L
     return L
 
@@ -238,6 +255,141 @@ def ax_dense(x, w, lut, q, acc_out=None, y_out=None, workspace=None, stream=None
     rc = L.ax_dense(_ptr(x), M, K, _ptr(w), N, _ptr(lut), ctypes.byref(qs),
                     _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
                     _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    _check(rc)
+    return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
+def ax_range_workspace_bytes(n: int) -> int:
+    return int(lib().ax_range_workspace_bytes(int(n)))
+
+
+def ax_range_f32(x, relu=False, range_out=None, workspace=None, stream=None):
+    """(min, max) of a float32 CUDA tensor into a float32 CUDA tensor of two."""
+    L = lib()
+    _dev(x, torch.float32, "x")
+    if range_out is None:
+        range_out = torch.empty(2, dtype=torch.float32, device=x.device)
+    _dev(range_out, torch.float32, "range_out")
+    if workspace is None:
+        workspace = torch.empty(int(L.ax_range_workspace_bytes(x.numel())), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    _check(L.ax_range_f32(_ptr(x), x.numel(), int(bool(relu)), _ptr(range_out), _ptr(workspace), workspace.numel(),
+                          ctypes.c_void_p(_stream_ptr(stream))))
+    return range_out
+
+
+def ax_quantize_f32(x, rng, relu=False, round_mode=0, codes_out=None, coeffs_out=None, stream=None):
+    """Codes of a float32 CUDA tensor for the range `rng` (float32 CUDA tensor of two).
+    coeffs_out: int32 CUDA tensor of two receiving the bit pattern of alpha and the value of
+    beta (allocated when None).  Returns (codes_out, coeffs_out)."""
+    L = lib()
+    _dev(x, torch.float32, "x")
+    _dev(rng, torch.float32, "range")
+    if rng.numel() != 2:
+        raise ValueError("range must hold two floats")
+    if codes_out is None:
+        codes_out = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    _dev(codes_out, torch.uint8, "codes_out")
+    if codes_out.numel() != x.numel():
+        raise ValueError("codes_out has the wrong number of elements")
+    if coeffs_out is None:
+        coeffs_out = torch.empty(2, dtype=torch.int32, device=x.device)
+    _dev(coeffs_out, torch.int32, "coeffs_out")
+    _check(L.ax_quantize_f32(_ptr(x), x.numel(), _ptr(rng), int(bool(relu)), int(round_mode), _ptr(codes_out),
+                             _ptr(coeffs_out), ctypes.c_void_p(_stream_ptr(stream))))
+    return codes_out, coeffs_out
+
+
+def ax_conv2d_f32_workspace_bytes(x_shape, w_shape, stride=1, pad=0) -> int:
+    N, H, W, Cin = [int(v) for v in x_shape]
+    KH, KW, _, Cout = [int(v) for v in w_shape]
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    return int(lib().ax_conv2d_f32_workspace_bytes(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw))
+
+
+def ax_dense_f32_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(lib().ax_dense_f32_workspace_bytes(int(M), int(K), int(N)))
+
+
+def _f32_common(x, w, lut, x_range, w_range):
+    _dev(x, torch.float32, "x")
+    _dev(w, torch.float32, "w")
+    _dev(x_range, torch.float32, "x_range")
+    _dev(w_range, torch.float32, "w_range")
+    if x_range.numel() != 2 or w_range.numel() != 2:
+        raise ValueError("ranges must hold two floats")
+    if lut.dtype not in (torch.int16, torch.uint16):
+        raise TypeError("lut must be a 16-bit integer tensor")
+    _dev(lut, lut.dtype, "lut")
+    if lut.numel() != 65536:
+        raise ValueError("lut must have 65536 entries")
+
+
+def _outs(shape, device, acc_out, y_out):
+    if acc_out is None:
+        acc_out = torch.empty(shape, dtype=torch.int32, device=device)
+    if y_out is None:
+        y_out = torch.empty(shape, dtype=torch.float32, device=device)
+    n = 1
+    for v in shape:
+        n *= int(v)
+    if acc_out is not False:
+        _dev(acc_out, torch.int32, "acc_out")
+    if y_out is not False:
+        _dev(y_out, torch.float32, "y_out")
+    for o in (acc_out, y_out):
+        if o is not False and o.numel() != n:
+            raise ValueError("output tensor has the wrong number of elements")
+    return acc_out, y_out
+
+
+def ax_conv2d_f32(x, w, lut, stride, pad, x_range, w_range, relu=False, round_mode=0, acc_out=None, y_out=None,
+                  workspace=None, stream=None):
+    """Float layer.  x: float32 [N,H,W,Cin]; w: float32 [KH,KW,Cin,Cout]; ranges: float32 CUDA
+    tensors of two.  Returns (acc_out, y_out); pass False to skip one of them."""
+    L = lib()
+    _f32_common(x, w, lut, x_range, w_range)
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
+        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout]")
+    N, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    OH = (H + 2 * ph - KH) // sh + 1
+    OW = (W + 2 * pw - KW) // sw + 1
+    if OH <= 0 or OW <= 0:
+        _check(-2)
+    acc_out, y_out = _outs((N, OH, OW, Cout), x.device, acc_out, y_out)
+    if workspace is None:
+        need = int(L.ax_conv2d_f32_workspace_bytes(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw))
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    rc = L.ax_conv2d_f32(_ptr(x), N, H, W, Cin, _ptr(w), KH, KW, Cout, _ptr(lut), sh, sw, ph, pw, _ptr(x_range),
+                         _ptr(w_range), int(bool(relu)), int(round_mode),
+                         _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
+                         _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    _check(rc)
+    return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
+def ax_dense_f32(x, w, lut, x_range, w_range, relu=False, round_mode=0, acc_out=None, y_out=None, workspace=None,
+                 stream=None):
+    """x: float32 [M,K]; w: float32 [K,N]; outputs [M,N]."""
+    L = lib()
+    _f32_common(x, w, lut, x_range, w_range)
+    if x.dim() != 2 or w.dim() != 2 or w.shape[0] != x.shape[1]:
+        raise ValueError("x must be [M,K] and w [K,N]")
+    M, K = x.shape
+    N = w.shape[1]
+    acc_out, y_out = _outs((M, N), x.device, acc_out, y_out)
+    if workspace is None:
+        workspace = torch.empty(int(L.ax_dense_f32_workspace_bytes(M, K, N)), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    rc = L.ax_dense_f32(_ptr(x), M, K, _ptr(w), N, _ptr(lut), _ptr(x_range), _ptr(w_range), int(bool(relu)),
+                        int(round_mode), _ptr(None if acc_out is False else acc_out),
+                        _ptr(None if y_out is False else y_out), _ptr(workspace), workspace.numel(),
+                        ctypes.c_void_p(_stream_ptr(stream)))
     _check(rc)
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
 

@@ -35,11 +35,11 @@ static int make_quant(const ax_quant_t* q, QParams* qp) {
   qp->w_zp = q->w_zp;
   qp->pad_code = q->pad_code < 0 ? q->x_zp : q->pad_code;
   qp->scale = q->x_scale * q->w_scale;
+  qp->dq = nullptr;
   return AX_OK;
 }
 
-static int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw,
-                     Geom* g) {
+int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw, Geom* g) {
   if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || KH <= 0 || KW <= 0 || Cout <= 0) return AX_ERR_SHAPE;
   if (sh < 1 || sw < 1 || ph < 0 || pw < 0) return AX_ERR_SHAPE;
   if (ph > (1 << 20) || pw > (1 << 20)) return AX_ERR_SHAPE;
@@ -65,14 +65,8 @@ static int choose_variant(const Geom& g) {
   return 0;  // let the tab planner pick the lane assignment
 }
 
-static int run(const Geom& g, const ax_quant_t* q, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
-               int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, void* stream) {
-  if (!x || !w || !lut || (!acc_out && !y_out)) return AX_ERR_NULL;
-  if (((uintptr_t)lut & 1) || ((uintptr_t)acc_out & 3) || ((uintptr_t)y_out & 3)) return AX_ERR_ALIGN;
-  QParams qp;
-  int rc = make_quant(q, &qp);
-  if (rc) return rc;
-  hipStream_t s = (hipStream_t)stream;
+int run_layer(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
+              int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, hipStream_t s) {
   const int v = choose_variant(g);
   hipError_t e;
   if (v == 1) {
@@ -87,7 +81,17 @@ static int run(const Geom& g, const ax_quant_t* q, const uint8_t* x, const uint8
   return e == hipSuccess ? AX_OK : AX_ERR_HIP;
 }
 
-static size_t workspace_for(const Geom& g) {
+static int run(const Geom& g, const ax_quant_t* q, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
+               int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, void* stream) {
+  if (!x || !w || !lut || (!acc_out && !y_out)) return AX_ERR_NULL;
+  if (((uintptr_t)lut & 1) || ((uintptr_t)acc_out & 3) || ((uintptr_t)y_out & 3)) return AX_ERR_ALIGN;
+  QParams qp;
+  int rc = make_quant(q, &qp);
+  if (rc) return rc;
+  return run_layer(g, qp, x, w, lut, acc_out, y_out, ws, ws_bytes, (hipStream_t)stream);
+}
+
+size_t layer_workspace(const Geom& g) {
   // Large enough for whichever variant the options may select later.
   if (!tab_supported(g)) return 256;
   size_t need = 256;
@@ -117,7 +121,7 @@ extern "C" size_t ax_conv2d_workspace_bytes(int N, int H, int W, int Cin, int KH
                                             int stride_w, int pad_h, int pad_w) {
   Geom g;
   if (make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g)) return 0;
-  return workspace_for(g);
+  return layer_workspace(g);
 }
 
 extern "C" int ax_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint16_t* lut,
@@ -132,7 +136,7 @@ extern "C" int ax_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N,
 extern "C" size_t ax_dense_workspace_bytes(int M, int K, int N) {
   Geom g;
   if (make_geom(M, 1, 1, K, 1, 1, N, 1, 1, 0, 0, &g)) return 0;
-  return workspace_for(g);
+  return layer_workspace(g);
 }
 
 extern "C" const char* ax_strerror(int code) {

@@ -9,11 +9,18 @@
 
 namespace ax {
 
-__global__ __launch_bounds__(256) void direct_kernel(Geom g, QParams qp, const uint8_t* __restrict__ x,
+__global__ __launch_bounds__(256) void direct_kernel(Geom g, QParams qp_in, const uint8_t* __restrict__ x,
                                                       const uint8_t* __restrict__ w,
                                                       const uint16_t* __restrict__ lut,
                                                       int32_t* __restrict__ acc_out,
                                                       float* __restrict__ y_out) {
+  QParams qp = qp_in;
+  if (qp.dq) {  // coefficients produced on the device
+    qp.x_zp = qp.dq->x_zp;
+    qp.w_zp = qp.dq->w_zp;
+    qp.pad_code = qp.x_zp;
+    qp.scale = qp.dq->x_scale * qp.dq->w_scale;
+  }
   const uint32_t total = (uint32_t)g.M * (uint32_t)g.Cout;
   const uint32_t o = blockIdx.x * 256u + threadIdx.x;
   if (o >= total) return;

@@ -20,11 +20,28 @@ struct Geom {
   int K;  // KH*KW*Cin taps per output
 };
 
-// Quantization parameters as the kernels consume them.
+// Quantization coefficients kept in device memory (written by the quantization kernels of the
+// float-in / float-out layer, where ranges and therefore coefficients exist only on the device).
+struct DevQuant {
+  float x_scale;
+  int32_t x_zp;
+  float w_scale;
+  int32_t w_zp;
+};
+
+// Quantization parameters as the kernels consume them.  With dq != nullptr the four
+// coefficients are read from device memory instead and the pad code is x_zp.
 struct QParams {
   int x_zp, w_zp, pad_code;
   float scale;  // x_scale * w_scale, rounded to float
+  const DevQuant* dq;
 };
+
+// Shared tail of ax_conv2d / ax_conv2d_f32 (ax_api.hip): pick a kernel family and enqueue.
+int run_layer(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
+              int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, hipStream_t s);
+size_t layer_workspace(const Geom& g);
+int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw, Geom* g);
 
 struct Options {
   int variant;  // 0 auto, 1 direct, 2 lanes over pixels, 3 lanes over channels
@@ -54,6 +71,7 @@ struct TabPlan {
   size_t off_apack;
   size_t off_part;
   size_t off_lsum;
+  size_t off_qd;  // QDev block
   size_t total;
 };
 bool tab_supported(const Geom& g);

@@ -1,0 +1,301 @@
+// Float side of the layer: range (min / max) reduction, ComputeCoeffs, float -> 8-bit
+// quantization with a round mode, and the float-in / float-out entry points built on the
+// table-lookup convolution (paper: Sec. III, the layer description and Algorithm 1).
+//
+// Every arithmetic step is one IEEE float32 operation in a fixed order (no contraction into
+// fused multiply-adds), so codes and coefficients are reproducible bit for bit:
+//   lo = min(range_min, 0), hi = max(range_max, 0)
+//   alpha = (hi - lo) / 255        (1 if that is not positive)
+//   beta  = clamp(round(-lo / alpha), 0, 255)
+//   code  = clamp(round(r / alpha) + beta, 0, 255)
+// All kernels here are bound by HBM traffic: 4 bytes read per element for the range, 4 read
+// and 1 written for the quantization.
+#include <algorithm>
+#include <cmath>
+
+#include "ax_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace ax {
+namespace {
+
+constexpr int kRangeBlocks = 2048;  // upper bound of the grids: 8 blocks of 256 threads per compute unit
+constexpr int kThreads = 256;
+
+struct Coeffs {
+  float alpha;
+  int32_t beta;
+};
+
+__device__ __forceinline__ float round_mode_f(float v, int mode) { return mode == 1 ? roundf(v) : rintf(v); }
+
+__device__ __forceinline__ Coeffs compute_coeffs(const float* __restrict__ range, int mode) {
+  const float rmin = range[0], rmax = range[1];
+  const float lo = rmin < 0.0f ? rmin : 0.0f;
+  const float hi = rmax > 0.0f ? rmax : 0.0f;
+  float alpha = (hi - lo) / 255.0f;
+  if (!(alpha > 0.0f)) alpha = 1.0f;
+  float b = round_mode_f(-lo / alpha, mode);
+  b = b < 0.0f ? 0.0f : b;
+  b = b > 255.0f ? 255.0f : b;
+  return Coeffs{alpha, (int32_t)b};
+}
+
+__device__ __forceinline__ uint32_t code_of(float r, int relu, float alpha, float beta, int mode) {
+  if (relu) r = r < 0.0f ? 0.0f : r;
+  float c = round_mode_f(r / alpha, mode) + beta;
+  c = c < 0.0f ? 0.0f : c;
+  c = c > 255.0f ? 255.0f : c;
+  return (uint32_t)c;
+}
+
+__device__ __forceinline__ void block_min_max(float& lo, float& hi, float* red_lo, float* red_hi) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    lo = fminf(lo, __shfl_xor(lo, off, 64));
+    hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+  }
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    red_lo[wave] = lo;
+    red_hi[wave] = hi;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < kThreads / 64; ++w) {
+      lo = fminf(lo, red_lo[w]);
+      hi = fmaxf(hi, red_hi[w]);
+    }
+  }
+}
+
+// Stage 1: every block reduces a grid-strided share of x to one (min, max) pair.  x[0] seeds
+// both so that no identity element is needed.  nvec 16-byte groups start at the first
+// 16-byte aligned element `head`; the elements before it and after the last whole group are
+// read one by one.
+__global__ __launch_bounds__(kThreads) void range_partial_kernel(const float* __restrict__ x, size_t n, size_t head,
+                                                                 size_t nvec, int relu, float2* __restrict__ part) {
+  __shared__ float red_lo[kThreads / 64], red_hi[kThreads / 64];
+  float lo = x[0], hi = lo;
+  const float4* __restrict__ xv = reinterpret_cast<const float4*>(x + head);
+  const size_t stride = (size_t)gridDim.x * kThreads;
+#pragma unroll 4
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
+    const float4 v = xv[i];
+    lo = fminf(fminf(lo, v.x), fminf(v.y, fminf(v.z, v.w)));
+    hi = fmaxf(fmaxf(hi, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
+  }
+  const size_t first = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  for (size_t i = first; i < head; i += stride) {
+    lo = fminf(lo, x[i]);
+    hi = fmaxf(hi, x[i]);
+  }
+  for (size_t i = head + nvec * 4 + first; i < n; i += stride) {
+    lo = fminf(lo, x[i]);
+    hi = fmaxf(hi, x[i]);
+  }
+  block_min_max(lo, hi, red_lo, red_hi);
+  if (threadIdx.x == 0) {
+    if (relu) {  // max(., 0) is monotone: apply it to the two extremes
+      lo = lo < 0.0f ? 0.0f : lo;
+      hi = hi < 0.0f ? 0.0f : hi;
+    }
+    part[blockIdx.x] = make_float2(lo, hi);
+  }
+}
+
+// Stage 2: one block folds the partial pairs.
+__global__ __launch_bounds__(kThreads) void range_final_kernel(const float2* __restrict__ part, int count,
+                                                               float* __restrict__ range_out) {
+  __shared__ float red_lo[kThreads / 64], red_hi[kThreads / 64];
+  float lo = part[0].x, hi = part[0].y;
+  for (int i = threadIdx.x; i < count; i += kThreads) {
+    lo = fminf(lo, part[i].x);
+    hi = fmaxf(hi, part[i].y);
+  }
+  block_min_max(lo, hi, red_lo, red_hi);
+  if (threadIdx.x == 0) {
+    range_out[0] = lo;
+    range_out[1] = hi;
+  }
+}
+
+// Quantization.  Vector body: one thread turns 4 consecutive floats (16-byte load) into one
+// packed dword; x + head is 16-byte aligned and codes_out + head 4-byte aligned (head = 0
+// whenever both pointers are aligned).  Head and tail elements are done one by one.
+// Thread 0 of block 0 also stores the coefficients.
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const float* __restrict__ x, size_t n, size_t head,
+                                                            size_t nvec, const float* __restrict__ range, int relu,
+                                                            int mode, uint8_t* __restrict__ codes_out,
+                                                            ax_coeffs_t* __restrict__ coeffs_out) {
+  const Coeffs c = compute_coeffs(range, mode);
+  const float alpha = c.alpha, beta = (float)c.beta;
+  if (blockIdx.x == 0 && threadIdx.x == 0 && coeffs_out) {
+    coeffs_out->scale = c.alpha;
+    coeffs_out->zero_point = c.beta;
+  }
+  const float4* __restrict__ xv = reinterpret_cast<const float4*>(x + head);
+  uint32_t* __restrict__ ov = reinterpret_cast<uint32_t*>(codes_out + head);
+  const size_t stride = (size_t)gridDim.x * kThreads;
+#pragma unroll 2
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
+    const float4 v = xv[i];
+    ov[i] = code_of(v.x, relu, alpha, beta, mode) | (code_of(v.y, relu, alpha, beta, mode) << 8) |
+            (code_of(v.z, relu, alpha, beta, mode) << 16) | (code_of(v.w, relu, alpha, beta, mode) << 24);
+  }
+  const size_t first = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  for (size_t i = first; i < head; i += stride) codes_out[i] = (uint8_t)code_of(x[i], relu, alpha, beta, mode);
+  for (size_t i = head + nvec * 4 + first; i < n; i += stride)
+    codes_out[i] = (uint8_t)code_of(x[i], relu, alpha, beta, mode);
+}
+
+// Split [0, n) into head (scalar), nvec groups of four (vector) and a tail so that the vector
+// part of x is 16-byte aligned; `out` (may be null) must then be 4-byte aligned at the same
+// element, otherwise everything is done by the scalar loops.
+void split_vec(const float* x, const uint8_t* out, size_t n, size_t* head, size_t* nvec) {
+  size_t h = ((16 - ((uintptr_t)x & 15)) & 15) / 4;
+  if (h > n) h = n;
+  size_t nv = (n - h) / 4;
+  if (out && (((uintptr_t)(out + h)) & 3)) {
+    h = 0;
+    nv = 0;
+  }
+  *head = h;
+  *nvec = nv;
+}
+
+int grid_for(size_t n, size_t nvec) {
+  // 8 iterations per thread (groups of four, or single elements when nothing can be
+  // vectorized) before another block is worth launching.
+  const size_t iters = std::max(nvec, n - nvec * 4);
+  const size_t want = (iters + (size_t)kThreads * 8 - 1) / ((size_t)kThreads * 8);
+  return (int)std::max<size_t>(1, std::min<size_t>(kRangeBlocks, want));
+}
+
+int enqueue_range(const float* x, size_t n, int relu, float* range_out, void* ws, hipStream_t s) {
+  size_t head, nvec;
+  split_vec(x, nullptr, n, &head, &nvec);
+  const int blocks = grid_for(n, nvec);
+  float2* part = static_cast<float2*>(ws);
+  hipLaunchKernelGGL(range_partial_kernel, dim3(blocks), dim3(kThreads), 0, s, x, n, head, nvec, relu, part);
+  hipLaunchKernelGGL(range_final_kernel, dim3(1), dim3(kThreads), 0, s, part, blocks, range_out);
+  return hipGetLastError() == hipSuccess ? AX_OK : AX_ERR_HIP;
+}
+
+int enqueue_quantize(const float* x, size_t n, const float* range, int relu, int mode, uint8_t* codes,
+                     ax_coeffs_t* coeffs, hipStream_t s) {
+  size_t head, nvec;
+  split_vec(x, codes, n, &head, &nvec);
+  hipLaunchKernelGGL(quantize_kernel, dim3(grid_for(n, nvec)), dim3(kThreads), 0, s, x, n, head, nvec, range, relu, mode,
+                     codes, coeffs);
+  return hipGetLastError() == hipSuccess ? AX_OK : AX_ERR_HIP;
+}
+
+constexpr size_t kRangeWs = (size_t)kRangeBlocks * sizeof(float2);
+size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Workspace of the float layer: [coefficients 256 B][x codes][w codes][layer workspace].
+struct F32Plan {
+  size_t off_xq, off_wq, off_layer, total;
+};
+F32Plan f32_plan(const Geom& g) {
+  F32Plan p;
+  size_t off = 256;
+  p.off_xq = off;
+  off += up256((size_t)g.N * g.H * g.W * g.Cin);
+  p.off_wq = off;
+  off += up256((size_t)g.K * g.Cout);
+  p.off_layer = off;
+  p.total = off + layer_workspace(g);
+  return p;
+}
+
+int run_f32(const Geom& g, const float* x, const float* w, const uint16_t* lut, const float* x_range,
+            const float* w_range, int relu, int mode, int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes,
+            void* stream) {
+  if (!x || !w || !lut || !x_range || !w_range || (!acc_out && !y_out)) return AX_ERR_NULL;
+  if (((uintptr_t)x & 3) || ((uintptr_t)w & 3) || ((uintptr_t)x_range & 3) || ((uintptr_t)w_range & 3) ||
+      ((uintptr_t)lut & 1) || ((uintptr_t)acc_out & 3) || ((uintptr_t)y_out & 3))
+    return AX_ERR_ALIGN;
+  if (mode != 0 && mode != 1) return AX_ERR_OPTION;
+  const F32Plan p = f32_plan(g);
+  if (!ws || ws_bytes < p.total || ((uintptr_t)ws & 255)) return AX_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* wsb = static_cast<uint8_t*>(ws);
+  DevQuant* dq = reinterpret_cast<DevQuant*>(wsb);
+  ax_coeffs_t* cx = reinterpret_cast<ax_coeffs_t*>(&dq->x_scale);
+  ax_coeffs_t* cw = reinterpret_cast<ax_coeffs_t*>(&dq->w_scale);
+  uint8_t* xq = wsb + p.off_xq;
+  uint8_t* wq = wsb + p.off_wq;
+  int rc = enqueue_quantize(x, (size_t)g.N * g.H * g.W * g.Cin, x_range, relu ? 1 : 0, mode, xq, cx, s);
+  if (rc) return rc;
+  rc = enqueue_quantize(w, (size_t)g.K * g.Cout, w_range, 0, mode, wq, cw, s);
+  if (rc) return rc;
+  QParams qp{0, 0, 0, 1.0f, dq};
+  return run_layer(g, qp, xq, wq, lut, acc_out, y_out, wsb + p.off_layer, ws_bytes - p.off_layer, s);
+}
+
+}  // namespace
+}  // namespace ax
+
+using namespace ax;
+
+static_assert(sizeof(ax_coeffs_t) == 8 && sizeof(DevQuant) == 16, "coefficient pairs are laid out back to back");
+
+extern "C" size_t ax_range_workspace_bytes(size_t n) {
+  (void)n;
+  return kRangeWs;
+}
+
+extern "C" int ax_range_f32(const float* x, size_t n, int relu, float* range_out, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  if (!x || !range_out) return AX_ERR_NULL;
+  if (n == 0) return AX_ERR_SHAPE;
+  if (((uintptr_t)x & 3) || ((uintptr_t)range_out & 3)) return AX_ERR_ALIGN;
+  if (!workspace || workspace_bytes < kRangeWs || ((uintptr_t)workspace & 255)) return AX_ERR_WORKSPACE;
+  return enqueue_range(x, n, relu ? 1 : 0, range_out, workspace, (hipStream_t)hip_stream);
+}
+
+extern "C" int ax_quantize_f32(const float* x, size_t n, const float* range, int relu, int round_mode,
+                               uint8_t* codes_out, ax_coeffs_t* coeffs_out, void* hip_stream) {
+  if (!x || !range || !codes_out) return AX_ERR_NULL;
+  if (n == 0) return AX_ERR_SHAPE;
+  if (((uintptr_t)x & 3) || ((uintptr_t)range & 3) || ((uintptr_t)coeffs_out & 3)) return AX_ERR_ALIGN;
+  if (round_mode != 0 && round_mode != 1) return AX_ERR_OPTION;
+  return enqueue_quantize(x, n, range, relu ? 1 : 0, round_mode, codes_out, coeffs_out, (hipStream_t)hip_stream);
+}
+
+extern "C" int ax_conv2d_f32(const float* x, int N, int H, int W, int Cin, const float* w, int KH, int KW, int Cout,
+                             const uint16_t* lut, int stride_h, int stride_w, int pad_h, int pad_w,
+                             const float* x_range, const float* w_range, int relu, int round_mode, int32_t* acc_out,
+                             float* y_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Geom g;
+  int rc = make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g);
+  if (rc) return rc;
+  return run_f32(g, x, w, lut, x_range, w_range, relu, round_mode, acc_out, y_out, workspace, workspace_bytes,
+                 hip_stream);
+}
+
+extern "C" size_t ax_conv2d_f32_workspace_bytes(int N, int H, int W, int Cin, int KH, int KW, int Cout, int stride_h,
+                                                int stride_w, int pad_h, int pad_w) {
+  Geom g;
+  if (make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g)) return 0;
+  return f32_plan(g).total;
+}
+
+extern "C" int ax_dense_f32(const float* x, int M, int K, const float* w, int N, const uint16_t* lut,
+                            const float* x_range, const float* w_range, int relu, int round_mode, int32_t* acc_out,
+                            float* y_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Geom g;
+  int rc = make_geom(M, 1, 1, K, 1, 1, N, 1, 1, 0, 0, &g);
+  if (rc) return rc;
+  return run_f32(g, x, w, lut, x_range, w_range, relu, round_mode, acc_out, y_out, workspace, workspace_bytes,
+                 hip_stream);
+}
+
+extern "C" size_t ax_dense_f32_workspace_bytes(int M, int K, int N) {
+  Geom g;
+  if (make_geom(M, 1, 1, K, 1, 1, N, 1, 1, 0, 0, &g)) return 0;
+  return f32_plan(g).total;
+}

@@ -36,13 +36,21 @@ namespace ax {
 
 constexpr int kChunk = 16;     // taps per 16-byte lane-operand load
 
+// Quantization values in the form the table-tile kernels consume, in device memory: prep_kernel
+// derives them from the call's host parameters or from device-resident coefficients.
+struct QDev {
+  int32_t z_lane, z_tab;  // zero points of the lane-side and of the table-side operand
+  long long kzz;          // K * z_lane * z_tab
+  float scale;            // x_scale * w_scale
+  uint32_t pad4;          // pad code in all four bytes
+};
+
 struct TabArgs {
   // lane-side operand, addressed as an implicit im2col view of an [N,H,W,Cin] tensor
   const uint8_t* A;
   int I;   // valid lane elements
   int ih;  // lane elements per tile (multiple of 64, at most the kernel's tile height)
   int H, W, Cin, KW, sh, sw, ph, pw, OHW, OW;
-  uint32_t pad4;  // pad code in all four bytes
   // table-side operand, packed [Krows][Jpad] with zero fill
   const uint8_t* Bp;
   int Jpad, J;
@@ -54,9 +62,7 @@ struct TabArgs {
   // takes iterations [w*total/G, (w+1)*total/G) of the tile-major iteration space
   int ntj, nch;
   long long total_iters;
-  int z_lane, z_tab;
-  long long kzz;  // K * z_lane * z_tab
-  float scale;
+  const struct QDev* qd;  // zero points, scale and pad code as the kernels use them (written by prep_kernel)
   int32_t* acc_out;
   float* y_out;
   int32_t* part;  // [2*G][IT*JT] partial tiles: slot 2w = workgroup w's piece of a tile begun by
@@ -128,6 +134,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t pad4 = a.qd->pad4;
   const int klast = a.nch * kChunk;  // padded K = index of the last (zero) row of Bp
   // Taps K .. klast-1 exist only in materialized operands, where both codes are 0: each adds
   // the table entry (0,0) to every accumulator, which the final epilogue takes off again.
@@ -173,7 +180,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
       const int iy = by[p] + ky, ix = bx[p] + kx;
       const bool inside = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
       const uint32_t off = ((uint32_t)(nb[p] + iy) * (uint32_t)a.W + (uint32_t)ix) * (uint32_t)a.Cin + (uint32_t)ci0;
-      v[p] = make_uint4(a.pad4, a.pad4, a.pad4, a.pad4);
+      v[p] = make_uint4(pad4, pad4, pad4, pad4);
       if (inside && act[p]) v[p] = *reinterpret_cast<const uint4*>(a.A + off);
     }
   };
@@ -374,14 +381,16 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   if (finish && tid < JT) {
     int32_t sb = 0;
     for (int q = 0; q < a.nseg; ++q) sb += a.bsum[(size_t)q * a.Jpad + j0 + tid];
-    cterm[tid] = a.kzz - (long long)a.z_lane * sb;
+    cterm[tid] = a.qd->kzz - (long long)a.qd->z_lane * sb;
   }
   __syncthreads();  // cterm visible; every wave is done with the table buffers
+  const float scale = a.qd->scale;
+  const uint32_t z_tab = (uint32_t)a.qd->z_tab;
   auto dequant = [&](uint32_t accv, uint32_t lterm, int jl) -> float {  // jl = column within the tile
     if constexpr (WIDE) {
-      return (float)((long long)(int32_t)(accv - lterm) + cterm[jl]) * a.scale;
+      return (float)((long long)(int32_t)(accv - lterm) + cterm[jl]) * scale;
     } else {
-      return (float)(int32_t)(accv - lterm + (uint32_t)cterm[jl]) * a.scale;
+      return (float)(int32_t)(accv - lterm + (uint32_t)cterm[jl]) * scale;
     }
   };
 
@@ -420,7 +429,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
           const int i = i0 + il, j = j0 + 4 * c4;
           if (il < a.ih && i < a.I && j < a.J) {
             uint4 v = *reinterpret_cast<const uint4*>(stage + r * ROW + 4 * c4);
-            const uint32_t lterm = (uint32_t)a.z_tab * stage[r * ROW + JT];
+            const uint32_t lterm = z_tab * stage[r * ROW + JT];
             v.x -= padfix; v.y -= padfix; v.z -= padfix; v.w -= padfix;
             const size_t o = (size_t)i * a.J + j;
             if (a.acc_out) *reinterpret_cast<uint4*>(a.acc_out + o) = v;
@@ -441,7 +450,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     for (int p = 0; p < P; ++p) {
       const int i = i0 + p * THREADS + tid;
       if (i >= a.I || p * THREADS + tid >= a.ih) continue;
-      const uint32_t lterm = (uint32_t)a.z_tab * sl[p];
+      const uint32_t lterm = z_tab * sl[p];
 #pragma unroll
       for (int j = 0; j < JT; ++j) {
         if (j0 + j < a.J) {
@@ -488,7 +497,7 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
   if (t < JT) {
     int32_t sb = 0;
     for (int q = 0; q < a.nseg; ++q) sb += a.bsum[(size_t)q * a.Jpad + j0 + t];
-    cterm[t] = a.kzz - (long long)a.z_lane * sb;
+    cterm[t] = a.qd->kzz - (long long)a.qd->z_lane * sb;
   }
   uint32_t v[CPT];
 #pragma unroll
@@ -501,7 +510,8 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
     for (int c = 0; c < CPT; ++c) v[c] += (uint32_t)pp[(cg * CPT + c) * IT];
     sl += (uint32_t)a.lsum[(size_t)slot * IT + il0 + r];
   }
-  const uint32_t lterm = (uint32_t)a.z_tab * sl;
+  const uint32_t lterm = (uint32_t)a.qd->z_tab * sl;
+  const float scale = a.qd->scale;
   __syncthreads();
   if (CH) {
     // output index (j0 + jl) * I + i: consecutive r are consecutive words already
@@ -513,7 +523,7 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
         if (j0 + jl < a.J) {
           const size_t o = (size_t)(j0 + jl) * a.I + i;
           if (a.acc_out) a.acc_out[o] = (int32_t)v[c];
-          if (a.y_out) a.y_out[o] = (float)((long long)(int32_t)(v[c] - lterm) + cterm[jl]) * a.scale;
+          if (a.y_out) a.y_out[o] = (float)((long long)(int32_t)(v[c] - lterm) + cterm[jl]) * scale;
         }
       }
     }
@@ -533,17 +543,17 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
         if (a.acc_out) *reinterpret_cast<uint4*>(a.acc_out + o) = q;
         if (a.y_out) {
           float4 y;
-          y.x = (float)((long long)(int32_t)(q.x - lt) + cterm[4 * c4]) * a.scale;
-          y.y = (float)((long long)(int32_t)(q.y - lt) + cterm[4 * c4 + 1]) * a.scale;
-          y.z = (float)((long long)(int32_t)(q.z - lt) + cterm[4 * c4 + 2]) * a.scale;
-          y.w = (float)((long long)(int32_t)(q.w - lt) + cterm[4 * c4 + 3]) * a.scale;
+          y.x = (float)((long long)(int32_t)(q.x - lt) + cterm[4 * c4]) * scale;
+          y.y = (float)((long long)(int32_t)(q.y - lt) + cterm[4 * c4 + 1]) * scale;
+          y.z = (float)((long long)(int32_t)(q.z - lt) + cterm[4 * c4 + 2]) * scale;
+          y.w = (float)((long long)(int32_t)(q.w - lt) + cterm[4 * c4 + 3]) * scale;
           *reinterpret_cast<float4*>(a.y_out + o) = y;
         }
       } else {
         for (int e = 0; e < 4 && j + e < a.J; ++e) {
           const uint32_t q = patch[rr][4 * c4 + e];
           if (a.acc_out) a.acc_out[o + e] = (int32_t)q;
-          if (a.y_out) a.y_out[o + e] = (float)((long long)(int32_t)(q - lt) + cterm[4 * c4 + e]) * a.scale;
+          if (a.y_out) a.y_out[o + e] = (float)((long long)(int32_t)(q - lt) + cterm[4 * c4 + e]) * scale;
         }
       }
     }
@@ -555,9 +565,14 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
 struct ConvView {  // im2col addressing of x
   const uint8_t* x;
   int H, W, Cin, KW, sh, sw, ph, pw, OH, OW, M, K, pad_code;
+  const DevQuant* dq;  // non-null: the pad code is the activation zero point held on the device
 };
 
-__device__ __forceinline__ uint32_t im2col_code(const ConvView& v, int m, int k) {
+__device__ __forceinline__ uint32_t pad_of(const ConvView& v) {
+  return v.dq ? (uint32_t)v.dq->x_zp : (uint32_t)v.pad_code;
+}
+
+__device__ __forceinline__ uint32_t im2col_code(const ConvView& v, uint32_t pad, int m, int k) {
   const int ohw = v.OH * v.OW;
   const int n = m / ohw;
   const int r = m - n * ohw;
@@ -565,7 +580,7 @@ __device__ __forceinline__ uint32_t im2col_code(const ConvView& v, int m, int k)
   const int tap = k / v.Cin, ci = k - tap * v.Cin;
   const int ky = tap / v.KW, kx = tap - ky * v.KW;
   const int iy = oy * v.sh - v.ph + ky, ix = ox * v.sw - v.pw + kx;
-  if ((unsigned)iy >= (unsigned)v.H || (unsigned)ix >= (unsigned)v.W) return (uint32_t)v.pad_code;
+  if ((unsigned)iy >= (unsigned)v.H || (unsigned)ix >= (unsigned)v.W) return pad;
   return v.x[((size_t)(n * v.H + iy) * v.W + ix) * v.Cin + ci];
 }
 
@@ -584,7 +599,22 @@ template <bool FROM_X>
 __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ lut, uint32_t* __restrict__ rows32,
                                                     const uint8_t* __restrict__ w, ConvView cv, int K, int J, int krows,
                                                     int Jpad, int seg_rows, uint8_t* __restrict__ Bp,
-                                                    int32_t* __restrict__ psum) {
+                                                    int32_t* __restrict__ psum, QParams qp, QDev* __restrict__ qd) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    int xz = qp.x_zp, wz = qp.w_zp, pad = qp.pad_code;
+    float sc = qp.scale;
+    if (qp.dq) {
+      xz = qp.dq->x_zp;
+      wz = qp.dq->w_zp;
+      pad = xz;
+      sc = qp.dq->x_scale * qp.dq->w_scale;
+    }
+    qd->z_lane = FROM_X ? wz : xz;
+    qd->z_tab = FROM_X ? xz : wz;
+    qd->kzz = (long long)K * xz * wz;
+    qd->scale = sc;
+    qd->pad4 = (uint32_t)pad * 0x01010101u;
+  }
   if (blockIdx.x < kRowBlocks) {
     const int dw = blockIdx.x * 256 + threadIdx.x;  // 0 .. 32767
     const int t = dw >> 7, P = dw & 127;
@@ -608,6 +638,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
   const int kbeg = seg * seg_rows, kend = min(krows, kbeg + seg_rows);
   const bool fast = !FROM_X && (J % 4 == 0) && (((uintptr_t)w & 3) == 0) && (j + 3 < J);
   int32_t s[4] = {0, 0, 0, 0};
+  const uint32_t pad = FROM_X ? pad_of(cv) : 0u;
   for (int k = kbeg + r; k < kend; k += 16) {
     uint32_t pk = 0;
     if (k < K) {
@@ -617,7 +648,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           uint32_t bb = 0;
-          if (j + e < J) bb = FROM_X ? im2col_code(cv, j + e, k) : (uint32_t)w[(size_t)k * J + j + e];
+          if (j + e < J) bb = FROM_X ? im2col_code(cv, pad, j + e, k) : (uint32_t)w[(size_t)k * J + j + e];
           pk |= bb << (8 * e);
         }
       }
@@ -654,11 +685,12 @@ __global__ __launch_bounds__(256) void prep_im2col_kernel(ConvView cv, int Kp, u
   int tap = k0 / cv.Cin, ci = k0 - tap * cv.Cin;
   int ky = tap / cv.KW, kx = tap - ky * cv.KW;
   uint32_t pk[4] = {0, 0, 0, 0};
+  const uint32_t pad = pad_of(cv);
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     if (k0 + e < cv.K) {
       const int iy = by + ky, ix = bx + kx;
-      uint32_t v = (uint32_t)cv.pad_code;
+      uint32_t v = pad;
       if ((unsigned)iy < (unsigned)cv.H && (unsigned)ix < (unsigned)cv.W)
         v = cv.x[((size_t)(n * cv.H + iy) * cv.W + ix) * cv.Cin + ci];
       pk[e >> 2] |= v << (8 * (e & 3));
@@ -841,6 +873,7 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   p.off_bpack = off;  off += up256((Kp + 1) * Jpad);
   p.off_bsum = off;   off += up256(Jpad * 4 * kMaxSeg);
   p.off_apack = off;  off += up256((size_t)I * Kp);  // only used when the lane operand is materialized
+  p.off_qd = off;     off += 256;
   p.off_lsum = off;
   p.off_part = off;
   if (p.partials) {
@@ -894,8 +927,9 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   uint8_t* Bp = wsb + p.off_bpack;
   int32_t* bsum = reinterpret_cast<int32_t*>(wsb + p.off_bsum);
   uint8_t* Ap = wsb + p.off_apack;
+  QDev* qd = reinterpret_cast<QDev*>(wsb + p.off_qd);
 
-  ConvView cv{x, g.H, g.W, g.Cin, g.KW, g.sh, g.sw, g.ph, g.pw, g.OH, g.OW, g.M, g.K, qp.pad_code};
+  ConvView cv{x, g.H, g.W, g.Cin, g.KW, g.sh, g.sw, g.ph, g.pw, g.OH, g.OW, g.M, g.K, qp.pad_code, qp.dq};
 
   const int ntiles = cdiv(I, kIT) * cdiv(J, kJT);
   // Column sums are produced per segment of rows so that more than Jpad/64 blocks share the work.
@@ -905,10 +939,10 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   const dim3 pgrid(kRowBlocks + nseg * (Jpad / 64));
   if (ch)
     hipLaunchKernelGGL((prep_kernel<true>), pgrid, dim3(256), 0, s, lut, reinterpret_cast<uint32_t*>(rows), w, cv, g.K, J,
-                       krows, Jpad, seg_rows, Bp, bsum);
+                       krows, Jpad, seg_rows, Bp, bsum, qp, qd);
   else
     hipLaunchKernelGGL((prep_kernel<false>), pgrid, dim3(256), 0, s, lut, reinterpret_cast<uint32_t*>(rows), w, cv, g.K, J,
-                       krows, Jpad, seg_rows, Bp, bsum);
+                       krows, Jpad, seg_rows, Bp, bsum, qp, qd);
 
   TabArgs a{};
   a.I = I;
@@ -927,17 +961,13 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
     a.A = Ap;
     a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
   }
-  a.pad4 = (uint32_t)qp.pad_code * 0x01010101u;
   a.Bp = Bp; a.Jpad = Jpad; a.J = J; a.bsum = bsum; a.nseg = cdiv(krows, seg_rows); a.rows = rows;
   a.K = g.K;
   a.ntj = cdiv(J, kJT);
   a.nch = nchunks;
   a.ih = cdiv(cdiv(I, cdiv(I, kIT)), 64) * 64;  // balanced tile height: padding spread over all tiles
   a.total_iters = (long long)cdiv(I, kIT) * a.ntj * nchunks;
-  a.z_lane = ch ? qp.w_zp : qp.x_zp;
-  a.z_tab = ch ? qp.x_zp : qp.w_zp;
-  a.kzz = (long long)g.K * qp.x_zp * qp.w_zp;
-  a.scale = qp.scale;
+  a.qd = qd;
   a.acc_out = acc_out; a.y_out = y_out;
   a.part = reinterpret_cast<int32_t*>(wsb + p.off_part);
   a.lsum = reinterpret_cast<int32_t*>(wsb + p.off_lsum);
