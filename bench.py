@@ -292,6 +292,82 @@ def main():
         m5 = sum(l.macs for l in l5)
         extra["config5_gemm_shaped"] = {"ms": ms, "lut_macs_per_s": m5 / ms * 1e3}
 
+    # ---- float-in / float-out form of the same sweep (range + quantization glue included) ------
+    float_layer = None
+    if not args.no_extra:
+        fcalls = []
+        n_x = n_w = 0
+        for l, xd, wd, q, acc, y, ws in calls:
+            # real-valued tensors with the sweep's distributions: the dequantized operands
+            xf = ((xd.float() - q.x_zp) * q.x_scale).contiguous()
+            wf = ((wd.float() - q.w_zp) * q.w_scale).contiguous()
+            n_x += xf.numel()
+            n_w += wf.numel()
+            if l.dense:
+                need = ax.ax_dense_f32_workspace_bytes(l.N, l.K, l.Cout)
+            else:
+                need = ax.ax_conv2d_f32_workspace_bytes((l.N, l.H, l.W, l.Cin), (l.KH, l.KW, l.Cin, l.Cout), l.stride, l.pad)
+            wsf = torch.empty(need, dtype=torch.uint8, device=dev)
+            fcalls.append((l, xf, wf, acc, y, wsf))
+
+        def fstep():  # ranges of both tensors are taken inside the layer call, once per call
+            for l, xf, wf, acc, y, wsf in fcalls:
+                if l.dense:
+                    ax.ax_dense_f32(xf, wf, lut_d, None, None, False, 0, acc, y, wsf)
+                else:
+                    ax.ax_conv2d_f32(xf, wf, lut_d, l.stride, l.pad, None, None, False, 0, acc, y, wsf)
+
+        for _ in range(2):
+            fstep()
+        torch.cuda.synchronize()
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        freps = max(1, args.steps // 2)
+        f0.record()
+        for _ in range(freps):
+            fstep()
+        f1.record()
+        torch.cuda.synchronize()
+        fms = f0.elapsed_time(f1) / freps
+        del fcalls
+        # the two glue kernels alone on one large tensor (HBM-bound: 4 B/element read for the
+        # range, 4 B read + 1 B written for the quantization)
+        nbig = 1 << 28
+        big = torch.empty(nbig, dtype=torch.float32, device=dev).normal_()
+        codes = torch.empty(nbig, dtype=torch.uint8, device=dev)
+        rr = torch.empty(2, dtype=torch.float32, device=dev)
+        cc = torch.empty(2, dtype=torch.int32, device=dev)
+        rws = torch.empty(ax.ax_range_workspace_bytes(nbig), dtype=torch.uint8, device=dev)
+
+        def timed(fn, reps=10):
+            fn()
+            torch.cuda.synchronize()
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record()
+            for _ in range(reps):
+                fn()
+            g1.record()
+            torch.cuda.synchronize()
+            return g0.elapsed_time(g1) / reps
+
+        r_ms = timed(lambda: ax.ax_range_f32(big, False, rr, rws))
+        q_ms = timed(lambda: ax.ax_quantize_f32(big, rr, False, 0, codes, cc))
+        del big, codes
+        glue_bytes = 2 * 4 * (n_x + n_w) + (n_x + n_w)  # range pass + quantization pass over both operands
+        float_layer = {
+            "workload": "the same 54 layers with float32 activations and filters: per layer the range and the "
+                        "quantization of both tensors (one launch each), the lookup-MAC convolution and dequantization",
+            "ms_per_step": fms,
+            "lut_macs_per_s": total_macs / (fms * 1e-3),
+            "images_per_s": args.batch / (fms * 1e-3),
+            "glue_ms_per_step": fms - ms_per_step,
+            "glue_algorithmic_bytes_per_step": glue_bytes,
+            "range_kernel": {"bound": "hbm", "achieved": 4 * nbig / (r_ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                             "frac": 4 * nbig / (r_ms * 1e-3) / 8e12, "elements": nbig, "ms": r_ms},
+            "quantize_kernel": {"bound": "hbm", "achieved": 5 * nbig / (q_ms * 1e-3) / 1e9, "peak": 8000.0,
+                                "unit": "GB/s", "frac": 5 * nbig / (q_ms * 1e-3) / 8e12, "elements": nbig, "ms": q_ms},
+            "measured_copy_GBps": copy_gbs,
+        }
+
     out = {
         "metric": "LUT-MACs/s (ResNet-50 shapes)",
         "value": value,
@@ -314,6 +390,7 @@ def main():
         "cpu_baseline": cpu,
         "parity_sampled": parity,
         "other_workloads": extra,
+        "float_layer": float_layer,
         "wall_s_timed_region": wall,
         "input_generation_s": t_gen,
     }

@@ -131,6 +131,9 @@ int ax_quantize_f32(const float* x, size_t n, const float* range, int relu, int 
  * The whole layer of Algorithm 1 on float tensors:
  *   x [N,H,W,Cin] float, w [KH,KW,Cin,Cout] float, x_range / w_range device float[2],
  *   lut as for ax_conv2d; relu applies to x only.
+ *   Either range pointer may be NULL: the layer then takes that tensor's minimum and maximum
+ *   itself (of max(x, 0) for x when relu != 0), once per call, which is what the operators in
+ *   front of the layer would deliver and saves their separate launches.
  *   (alpha1, beta1) from x_range, (alpha2, beta2) from w_range; both tensors are quantized
  *   (into the workspace); taps outside the image carry the real value 0, i.e. the code beta1;
  *   acc_out (optional) and y_out are those of ax_conv2d for these codes and coefficients:

@@ -315,10 +315,12 @@ def ax_dense_f32_workspace_bytes(M: int, K: int, N: int) -> int:
 def _f32_common(x, w, lut, x_range, w_range):
     _dev(x, torch.float32, "x")
     _dev(w, torch.float32, "w")
-    _dev(x_range, torch.float32, "x_range")
-    _dev(w_range, torch.float32, "w_range")
-    if x_range.numel() != 2 or w_range.numel() != 2:
-        raise ValueError("ranges must hold two floats")
+    for r, name in ((x_range, "x_range"), (w_range, "w_range")):
+        if r is None:  # the layer takes the range itself
+            continue
+        _dev(r, torch.float32, name)
+        if r.numel() != 2:
+            raise ValueError("ranges must hold two floats")
     if lut.dtype not in (torch.int16, torch.uint16):
         raise TypeError("lut must be a 16-bit integer tensor")
     _dev(lut, lut.dtype, "lut")
@@ -344,10 +346,10 @@ def _outs(shape, device, acc_out, y_out):
     return acc_out, y_out
 
 
-def ax_conv2d_f32(x, w, lut, stride, pad, x_range, w_range, relu=False, round_mode=0, acc_out=None, y_out=None,
+def ax_conv2d_f32(x, w, lut, stride, pad, x_range=None, w_range=None, relu=False, round_mode=0, acc_out=None, y_out=None,
                   workspace=None, stream=None):
     """Float layer.  x: float32 [N,H,W,Cin]; w: float32 [KH,KW,Cin,Cout]; ranges: float32 CUDA
-    tensors of two.  Returns (acc_out, y_out); pass False to skip one of them."""
+    tensors of two, or None to let the layer take the range of that tensor.  Returns (acc_out, y_out); pass False to skip one of them."""
     L = lib()
     _f32_common(x, w, lut, x_range, w_range)
     if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
@@ -373,7 +375,7 @@ def ax_conv2d_f32(x, w, lut, stride, pad, x_range, w_range, relu=False, round_mo
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
 
 
-def ax_dense_f32(x, w, lut, x_range, w_range, relu=False, round_mode=0, acc_out=None, y_out=None, workspace=None,
+def ax_dense_f32(x, w, lut, x_range=None, w_range=None, relu=False, round_mode=0, acc_out=None, y_out=None, workspace=None,
                  stream=None):
     """x: float32 [M,K]; w: float32 [K,N]; outputs [M,N]."""
     L = lib()

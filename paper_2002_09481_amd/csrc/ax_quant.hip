@@ -70,42 +70,73 @@ __device__ __forceinline__ void block_min_max(float& lo, float& hi, float* red_l
   }
 }
 
-// Stage 1: every block reduces a grid-strided share of x to one (min, max) pair.  x[0] seeds
-// both so that no identity element is needed.  nvec 16-byte groups start at the first
-// 16-byte aligned element `head`; the elements before it and after the last whole group are
-// read one by one.
-__global__ __launch_bounds__(kThreads) void range_partial_kernel(const float* __restrict__ x, size_t n, size_t head,
-                                                                 size_t nvec, int relu, float2* __restrict__ part) {
+// One tensor's share of a range launch: blocks [0, blocks) of the task reduce a grid-strided
+// part of x to one (min, max) pair each.  nvec 16-byte groups start at the first 16-byte
+// aligned element `head`; the elements before it and after the last whole group are read one
+// by one.
+struct RangeTask {
+  const float* x;
+  size_t n, head, nvec;
+  float2* part;  // [blocks]
+  int blocks;
+  int relu;
+};
+
+// Where a quantization finds its range: either two floats, or the per-block pairs of a range
+// launch, which every block folds for itself (a few KB from L2; saves a launch per tensor).
+struct RangeSrc {
+  const float* range;  // non-null: (min, max)
+  const float2* part;
+  int count;
+};
+
+struct QuantTask {
+  const float* x;
+  size_t n, head, nvec;
+  uint8_t* codes;
+  ax_coeffs_t* coeffs;  // may be null
+  RangeSrc src;
+  int blocks;
+  int relu;
+};
+
+// Stage 1 of the range, for up to two tensors in one launch (either task may have 0 blocks).  x[0] seeds
+// both extremes so that no identity element is needed.
+__global__ __launch_bounds__(kThreads) void range_partial_kernel(const RangeTask a, const RangeTask b) {
   __shared__ float red_lo[kThreads / 64], red_hi[kThreads / 64];
+  const bool second = (int)blockIdx.x >= a.blocks;
+  const RangeTask& t = second ? b : a;
+  const int bid = second ? (int)blockIdx.x - a.blocks : (int)blockIdx.x;
+  const float* __restrict__ x = t.x;
   float lo = x[0], hi = lo;
-  const float4* __restrict__ xv = reinterpret_cast<const float4*>(x + head);
-  const size_t stride = (size_t)gridDim.x * kThreads;
+  const float4* __restrict__ xv = reinterpret_cast<const float4*>(x + t.head);
+  const size_t stride = (size_t)t.blocks * kThreads;
+  const size_t first = (size_t)bid * kThreads + threadIdx.x;
 #pragma unroll 4
-  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
+  for (size_t i = first; i < t.nvec; i += stride) {
     const float4 v = xv[i];
     lo = fminf(fminf(lo, v.x), fminf(v.y, fminf(v.z, v.w)));
     hi = fmaxf(fmaxf(hi, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
   }
-  const size_t first = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  for (size_t i = first; i < head; i += stride) {
+  for (size_t i = first; i < t.head; i += stride) {
     lo = fminf(lo, x[i]);
     hi = fmaxf(hi, x[i]);
   }
-  for (size_t i = head + nvec * 4 + first; i < n; i += stride) {
+  for (size_t i = t.head + t.nvec * 4 + first; i < t.n; i += stride) {
     lo = fminf(lo, x[i]);
     hi = fmaxf(hi, x[i]);
   }
   block_min_max(lo, hi, red_lo, red_hi);
   if (threadIdx.x == 0) {
-    if (relu) {  // max(., 0) is monotone: apply it to the two extremes
+    if (t.relu) {  // max(., 0) is monotone: apply it to the two extremes
       lo = lo < 0.0f ? 0.0f : lo;
       hi = hi < 0.0f ? 0.0f : hi;
     }
-    part[blockIdx.x] = make_float2(lo, hi);
+    t.part[bid] = make_float2(lo, hi);
   }
 }
 
-// Stage 2: one block folds the partial pairs.
+// Stage 2 as a kernel of its own (ax_range_f32): one block folds the pairs.
 __global__ __launch_bounds__(kThreads) void range_final_kernel(const float2* __restrict__ part, int count,
                                                                float* __restrict__ range_out) {
   __shared__ float red_lo[kThreads / 64], red_hi[kThreads / 64];
@@ -121,33 +152,54 @@ __global__ __launch_bounds__(kThreads) void range_final_kernel(const float2* __r
   }
 }
 
-// Quantization.  Vector body: one thread turns 4 consecutive floats (16-byte load) into one
-// packed dword; x + head is 16-byte aligned and codes_out + head 4-byte aligned (head = 0
-// whenever both pointers are aligned).  Head and tail elements are done one by one.
-// Thread 0 of block 0 also stores the coefficients.
-__global__ __launch_bounds__(kThreads) void quantize_kernel(const float* __restrict__ x, size_t n, size_t head,
-                                                            size_t nvec, const float* __restrict__ range, int relu,
-                                                            int mode, uint8_t* __restrict__ codes_out,
-                                                            ax_coeffs_t* __restrict__ coeffs_out) {
+// Quantization of up to two tensors in one launch (either task may have 0 blocks).  Vector body: one thread
+// turns 4 consecutive floats (16-byte load) into one packed dword; x + head is 16-byte aligned
+// and codes + head 4-byte aligned (head = 0 whenever both pointers are aligned).  Head and tail
+// elements are done one by one.  Thread 0 of each tensor's first block stores the coefficients.
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantTask a, const QuantTask b, int mode) {
+  __shared__ float red_lo[kThreads / 64], red_hi[kThreads / 64];
+  __shared__ float range_s[2];
+  const bool second = (int)blockIdx.x >= a.blocks;
+  const QuantTask& t = second ? b : a;
+  const int bid = second ? (int)blockIdx.x - a.blocks : (int)blockIdx.x;
+  const float* range = t.src.range;
+  if (!range) {  // fold the per-block pairs (uniform branch: every thread of the block takes it)
+    const float2* __restrict__ part = t.src.part;
+    float lo = part[0].x, hi = part[0].y;
+    for (int i = threadIdx.x; i < t.src.count; i += kThreads) {
+      lo = fminf(lo, part[i].x);
+      hi = fmaxf(hi, part[i].y);
+    }
+    block_min_max(lo, hi, red_lo, red_hi);
+    if (threadIdx.x == 0) {
+      range_s[0] = lo;
+      range_s[1] = hi;
+    }
+    __syncthreads();
+    range = range_s;
+  }
   const Coeffs c = compute_coeffs(range, mode);
   const float alpha = c.alpha, beta = (float)c.beta;
-  if (blockIdx.x == 0 && threadIdx.x == 0 && coeffs_out) {
-    coeffs_out->scale = c.alpha;
-    coeffs_out->zero_point = c.beta;
+  if (bid == 0 && threadIdx.x == 0 && t.coeffs) {
+    t.coeffs->scale = c.alpha;
+    t.coeffs->zero_point = c.beta;
   }
-  const float4* __restrict__ xv = reinterpret_cast<const float4*>(x + head);
-  uint32_t* __restrict__ ov = reinterpret_cast<uint32_t*>(codes_out + head);
-  const size_t stride = (size_t)gridDim.x * kThreads;
+  const float* __restrict__ x = t.x;
+  uint8_t* __restrict__ codes = t.codes;
+  const int relu = t.relu;
+  const float4* __restrict__ xv = reinterpret_cast<const float4*>(x + t.head);
+  uint32_t* __restrict__ ov = reinterpret_cast<uint32_t*>(codes + t.head);
+  const size_t stride = (size_t)t.blocks * kThreads;
+  const size_t first = (size_t)bid * kThreads + threadIdx.x;
 #pragma unroll 2
-  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
+  for (size_t i = first; i < t.nvec; i += stride) {
     const float4 v = xv[i];
     ov[i] = code_of(v.x, relu, alpha, beta, mode) | (code_of(v.y, relu, alpha, beta, mode) << 8) |
             (code_of(v.z, relu, alpha, beta, mode) << 16) | (code_of(v.w, relu, alpha, beta, mode) << 24);
   }
-  const size_t first = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  for (size_t i = first; i < head; i += stride) codes_out[i] = (uint8_t)code_of(x[i], relu, alpha, beta, mode);
-  for (size_t i = head + nvec * 4 + first; i < n; i += stride)
-    codes_out[i] = (uint8_t)code_of(x[i], relu, alpha, beta, mode);
+  for (size_t i = first; i < t.head; i += stride) codes[i] = (uint8_t)code_of(x[i], relu, alpha, beta, mode);
+  for (size_t i = t.head + t.nvec * 4 + first; i < t.n; i += stride)
+    codes[i] = (uint8_t)code_of(x[i], relu, alpha, beta, mode);
 }
 
 // Split [0, n) into head (scalar), nvec groups of four (vector) and a tail so that the vector
@@ -173,35 +225,63 @@ int grid_for(size_t n, size_t nvec) {
   return (int)std::max<size_t>(1, std::min<size_t>(kRangeBlocks, want));
 }
 
+RangeTask range_task(const float* x, size_t n, int relu, float2* part) {
+  RangeTask t{};
+  if (!x) return t;  // blocks = 0: no share of the launch
+  t.x = x;
+  t.n = n;
+  split_vec(x, nullptr, n, &t.head, &t.nvec);
+  t.part = part;
+  t.blocks = grid_for(n, t.nvec);
+  t.relu = relu;
+  return t;
+}
+
+QuantTask quant_task(const float* x, size_t n, int relu, uint8_t* codes, ax_coeffs_t* coeffs, RangeSrc src) {
+  QuantTask t{};
+  if (!x) return t;
+  t.x = x;
+  t.n = n;
+  split_vec(x, codes, n, &t.head, &t.nvec);
+  t.codes = codes;
+  t.coeffs = coeffs;
+  t.src = src;
+  t.blocks = grid_for(n, t.nvec);
+  t.relu = relu;
+  return t;
+}
+
+int launched() { return hipGetLastError() == hipSuccess ? AX_OK : AX_ERR_HIP; }
+
 int enqueue_range(const float* x, size_t n, int relu, float* range_out, void* ws, hipStream_t s) {
-  size_t head, nvec;
-  split_vec(x, nullptr, n, &head, &nvec);
-  const int blocks = grid_for(n, nvec);
-  float2* part = static_cast<float2*>(ws);
-  hipLaunchKernelGGL(range_partial_kernel, dim3(blocks), dim3(kThreads), 0, s, x, n, head, nvec, relu, part);
-  hipLaunchKernelGGL(range_final_kernel, dim3(1), dim3(kThreads), 0, s, part, blocks, range_out);
-  return hipGetLastError() == hipSuccess ? AX_OK : AX_ERR_HIP;
+  const RangeTask a = range_task(x, n, relu, static_cast<float2*>(ws));
+  hipLaunchKernelGGL(range_partial_kernel, dim3(a.blocks), dim3(kThreads), 0, s, a, RangeTask{});
+  hipLaunchKernelGGL(range_final_kernel, dim3(1), dim3(kThreads), 0, s, a.part, a.blocks, range_out);
+  return launched();
 }
 
 int enqueue_quantize(const float* x, size_t n, const float* range, int relu, int mode, uint8_t* codes,
                      ax_coeffs_t* coeffs, hipStream_t s) {
-  size_t head, nvec;
-  split_vec(x, codes, n, &head, &nvec);
-  hipLaunchKernelGGL(quantize_kernel, dim3(grid_for(n, nvec)), dim3(kThreads), 0, s, x, n, head, nvec, range, relu, mode,
-                     codes, coeffs);
-  return hipGetLastError() == hipSuccess ? AX_OK : AX_ERR_HIP;
+  const QuantTask a = quant_task(x, n, relu, codes, coeffs, RangeSrc{range, nullptr, 0});
+  hipLaunchKernelGGL(quantize_kernel, dim3(a.blocks), dim3(kThreads), 0, s, a, QuantTask{}, mode);
+  return launched();
 }
 
 constexpr size_t kRangeWs = (size_t)kRangeBlocks * sizeof(float2);
 size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-// Workspace of the float layer: [coefficients 256 B][x codes][w codes][layer workspace].
+// Workspace of the float layer:
+// [coefficients 256 B][range pairs of x][range pairs of w][x codes][w codes][layer workspace].
 struct F32Plan {
-  size_t off_xq, off_wq, off_layer, total;
+  size_t off_xpart, off_wpart, off_xq, off_wq, off_layer, total;
 };
 F32Plan f32_plan(const Geom& g) {
   F32Plan p;
   size_t off = 256;
+  p.off_xpart = off;
+  off += kRangeWs;
+  p.off_wpart = off;
+  off += kRangeWs;
   p.off_xq = off;
   off += up256((size_t)g.N * g.H * g.W * g.Cin);
   p.off_wq = off;
@@ -211,10 +291,12 @@ F32Plan f32_plan(const Geom& g) {
   return p;
 }
 
+// Two launches in front of the convolution: one range launch covering whichever of the two
+// tensors came without a range, one quantization launch covering both tensors.
 int run_f32(const Geom& g, const float* x, const float* w, const uint16_t* lut, const float* x_range,
             const float* w_range, int relu, int mode, int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes,
             void* stream) {
-  if (!x || !w || !lut || !x_range || !w_range || (!acc_out && !y_out)) return AX_ERR_NULL;
+  if (!x || !w || !lut || (!acc_out && !y_out)) return AX_ERR_NULL;
   if (((uintptr_t)x & 3) || ((uintptr_t)w & 3) || ((uintptr_t)x_range & 3) || ((uintptr_t)w_range & 3) ||
       ((uintptr_t)lut & 1) || ((uintptr_t)acc_out & 3) || ((uintptr_t)y_out & 3))
     return AX_ERR_ALIGN;
@@ -226,14 +308,23 @@ int run_f32(const Geom& g, const float* x, const float* w, const uint16_t* lut, 
   DevQuant* dq = reinterpret_cast<DevQuant*>(wsb);
   ax_coeffs_t* cx = reinterpret_cast<ax_coeffs_t*>(&dq->x_scale);
   ax_coeffs_t* cw = reinterpret_cast<ax_coeffs_t*>(&dq->w_scale);
-  uint8_t* xq = wsb + p.off_xq;
-  uint8_t* wq = wsb + p.off_wq;
-  int rc = enqueue_quantize(x, (size_t)g.N * g.H * g.W * g.Cin, x_range, relu ? 1 : 0, mode, xq, cx, s);
-  if (rc) return rc;
-  rc = enqueue_quantize(w, (size_t)g.K * g.Cout, w_range, 0, mode, wq, cw, s);
-  if (rc) return rc;
+  const size_t nx = (size_t)g.N * g.H * g.W * g.Cin, nw = (size_t)g.K * g.Cout;
+  relu = relu ? 1 : 0;
+
+  RangeTask rx{}, rw{};
+  if (!x_range) rx = range_task(x, nx, relu, reinterpret_cast<float2*>(wsb + p.off_xpart));
+  if (!w_range) rw = range_task(w, nw, 0, reinterpret_cast<float2*>(wsb + p.off_wpart));
+  if (rx.blocks + rw.blocks > 0)  // a task with no blocks takes no part (its tensor came with a range)
+    hipLaunchKernelGGL(range_partial_kernel, dim3(rx.blocks + rw.blocks), dim3(kThreads), 0, s, rx, rw);
+  const RangeSrc sx = x_range ? RangeSrc{x_range, nullptr, 0} : RangeSrc{nullptr, rx.part, rx.blocks};
+  const RangeSrc sw = w_range ? RangeSrc{w_range, nullptr, 0} : RangeSrc{nullptr, rw.part, rw.blocks};
+  const QuantTask qx = quant_task(x, nx, relu, wsb + p.off_xq, cx, sx);
+  const QuantTask qw = quant_task(w, nw, 0, wsb + p.off_wq, cw, sw);
+  hipLaunchKernelGGL(quantize_kernel, dim3(qx.blocks + qw.blocks), dim3(kThreads), 0, s, qx, qw, mode);
+  if (launched() != AX_OK) return AX_ERR_HIP;
   QParams qp{0, 0, 0, 1.0f, dq};
-  return run_layer(g, qp, xq, wq, lut, acc_out, y_out, wsb + p.off_layer, ws_bytes - p.off_layer, s);
+  return run_layer(g, qp, wsb + p.off_xq, wsb + p.off_wq, lut, acc_out, y_out, wsb + p.off_layer,
+                   ws_bytes - p.off_layer, s);
 }
 
 }  // namespace

@@ -101,3 +101,38 @@ def test_config5_gemm_shaped_exact_table_is_integer_gemm():
         # error bound of the truncated multiplier: 0 <= exact - truncated <= K * 321
         d = ref - acc.reshape(layer.M, layer.Cout).to(torch.int64)
         assert int(d.min()) >= 0 and int(d.max()) <= layer.K * 321
+
+
+def test_config3_float_layers_batch32_codes_exact_outputs_sampled():
+    """The float-in / float-out form at full size: a stem, a 3x3, a strided 1x1 and the last
+    1x1 of the ResNet-50-shaped sweep at batch 32.  The oracle quantizes the whole float tensors
+    (codes compared through the accumulators of sampled outputs, which it evaluates one by one
+    from its own codes and coefficients)."""
+    lut = I.lut_truncated(6)
+    lut_d = ax.lut_to_device(lut)
+    rng = np.random.default_rng(333)
+    layers = I.config_resnet50(32)
+    picked = [0, 2, 12, 52]
+    for i in picked:
+        layer = layers[i]
+        assert not layer.dense
+        x, w = I.make_float_operands(layer, I.layer_seed(3, i))
+        relu = i > 0
+        xd, wd = G.to_dev(x), G.to_dev(w)
+        xr, wr = ax.ax_range_f32(xd, relu=relu), ax.ax_range_f32(wd)
+        if i % 4 == 0:
+            acc, y = ax.ax_conv2d_f32(xd, wd, lut_d, layer.stride, layer.pad, xr, wr, relu=relu)
+        else:  # ranges taken inside the layer
+            acc, y = ax.ax_conv2d_f32(xd, wd, lut_d, layer.stride, layer.pad, relu=relu)
+        torch.cuda.synchronize()
+        xr_o, wr_o = oracle.range_f32(x, relu), oracle.range_f32(w)
+        np.testing.assert_array_equal(xr.cpu().numpy(), xr_o)
+        np.testing.assert_array_equal(wr.cpu().numpy(), wr_o)
+        ax_, bx = oracle.coeffs(xr_o)
+        aw_, bw = oracle.coeffs(wr_o)
+        xq = oracle.quantize_f32(x, ax_, bx, relu=relu)
+        wq = oracle.quantize_f32(w, aw_, bw)
+        codes, _ = ax.ax_quantize_f32(xd, xr, relu=relu)
+        assert bool((codes == G.to_dev(xq)).all()), "%s: activation codes differ" % layer.name
+        q = I.Quant(ax_, bx, aw_, bw, -1)
+        _check_sampled(layer, xq, wq, lut, q, acc, y, rng, layer.name + " (float)")

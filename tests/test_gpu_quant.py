@@ -104,12 +104,14 @@ def L(N, H, W, Cin, KH, KW, Cout, s=1, p=0, dense=False, x_dist="normal", w_dist
                    N, H, W, Cin, KH, KW, Cout, s, p, dense=dense, x_dist=x_dist, w_dist=w_dist)
 
 
-def _run_f32(layer, seed, lut, relu, mode, x=None, w=None):
+def _run_f32(layer, seed, lut, relu, mode, x=None, w=None, given="xw"):
+    """given: which ranges are handed to the layer ("xw", "x", "w" or ""); the layer takes the
+    others itself."""
     if x is None:
         x, w = I.make_float_operands(layer, seed)
     xd, wd, ld = G.to_dev(x), G.to_dev(w), ax.lut_to_device(lut)
-    xr = ax.ax_range_f32(xd, relu=relu)
-    wr = ax.ax_range_f32(wd)
+    xr = ax.ax_range_f32(xd, relu=relu) if "x" in given else None
+    wr = ax.ax_range_f32(wd) if "w" in given else None
     if layer.dense:
         acc, y = ax.ax_dense_f32(xd.view(x.shape[0], -1), wd.view(-1, w.shape[-1]), ld, xr, wr, relu=relu,
                                  round_mode=mode)
@@ -121,8 +123,8 @@ def _run_f32(layer, seed, lut, relu, mode, x=None, w=None):
     return acc.cpu().numpy(), y.cpu().numpy(), ref
 
 
-def _check_f32(layer, seed, lut, relu=False, mode=0):
-    acc, y, ref = _run_f32(layer, seed, lut, relu, mode)
+def _check_f32(layer, seed, lut, relu=False, mode=0, given="xw"):
+    acc, y, ref = _run_f32(layer, seed, lut, relu, mode, given=given)
     G.assert_parity(acc, y, ref["acc"], ref["y"], layer.name)
     np.testing.assert_array_equal(y.reshape(-1), ref["y"].reshape(-1))
     return ref
@@ -149,6 +151,13 @@ def test_float_layer_matches_oracle(layer, variant):
     lut = I.lut_random_error(77)
     relu = (layer.Cin % 2 == 0)
     _check_f32(layer, 500 + layer.Cout, lut, relu=relu, mode=variant & 1)
+
+
+@pytest.mark.parametrize("given", ["", "x", "w"])
+@pytest.mark.parametrize("layer", FLOAT_LAYERS, ids=lambda l: l.name)
+def test_float_layer_takes_missing_ranges_itself(layer, given):
+    relu = (layer.Cin % 2 == 1)
+    _check_f32(layer, 700 + layer.Cout, I.lut_random_error(78), relu=relu, mode=len(given), given=given)
 
 
 @pytest.mark.parametrize("split", [2, 3])
@@ -199,7 +208,10 @@ def test_chained_stack_matches_oracle_layer_by_layer():
         _, w = I.make_float_operands(layer, I.layer_seed(2, i))
         relu = i > 0
         wd = G.to_dev(w)
-        xr, wr = ax.ax_range_f32(xg, relu=relu), ax.ax_range_f32(wd)
+        if i % 2:  # alternate between ranges handed in and ranges taken by the layer
+            xr, wr = ax.ax_range_f32(xg, relu=relu), ax.ax_range_f32(wd)
+        else:
+            xr = wr = None
         acc, y = ax.ax_conv2d_f32(xg, wd, ld, layer.stride, layer.pad, xr, wr, relu=relu)
         torch.cuda.synchronize()
         ref = oracle.conv2d_f32(xo, w, lut, layer.stride, layer.pad, oracle.range_f32(xo, relu), oracle.range_f32(w),
