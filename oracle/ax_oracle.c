@@ -189,3 +189,91 @@ int ax_oracle_threads(void) {
 #endif
   return n;
 }
+
+/* ---- operator variants ------------------------------------------------------------------
+ * The paper's layer carries a dilation parameter next to the strides (Sec. III, Algorithm 1
+ * inputs), offers signed multipliers with codes in [-128, 127] next to unsigned ones
+ * (Sec. III), and says every kind of 2-D convolution gets an approximate twin (Sec. III); the
+ * depthwise convolution is the one other kind built here.  Same definition as above with:
+ *   dilation   tap (ky, kx) reads the pixel (oy*sh - ph + ky*dh, ox*sw - pw + kx*dw);
+ *              OH = floor((H + 2*ph - dh*(KH-1) - 1) / sh) + 1.
+ *   signed     codes are int8, table entries int16; the table is addressed by the two codes'
+ *              8-bit two's-complement patterns stitched together (activation pattern * 256 +
+ *              filter pattern); zero points and the pad code lie in [-128, 127].
+ *   depthwise  filters [KH, KW, Cin, mult]; output channel ci*mult + m sums over the KH*KW taps
+ *              of input channel ci only (K = KH*KW).
+ */
+int ax_oracle_conv2d_ex(const void* x, int N, int H, int W, int Cin, const void* w, int KH, int KW,
+                        int Cout, const void* lut, int stride_h, int stride_w, int pad_h, int pad_w,
+                        int dil_h, int dil_w, int depthwise, int is_signed, float x_scale, int x_zp,
+                        float w_scale, int w_zp, int pad_code, int32_t* acc_out, float* y_out) {
+  if (!x || !w || !lut || !acc_out || !y_out) return AX_ORACLE_ERR_ARG;
+  if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || KH <= 0 || KW <= 0 || Cout <= 0) return AX_ORACLE_ERR_ARG;
+  if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1) return AX_ORACLE_ERR_ARG;
+  const int lo = is_signed ? -128 : 0, hi = is_signed ? 127 : 255;
+  if (x_zp < lo || x_zp > hi || w_zp < lo || w_zp > hi || pad_code < lo || pad_code > hi) return AX_ORACLE_ERR_ARG;
+  if (!(x_scale > 0.0f) || !(w_scale > 0.0f)) return AX_ORACLE_ERR_ARG;
+  const int eh = H + 2 * pad_h - dil_h * (KH - 1) - 1, ew = W + 2 * pad_w - dil_w * (KW - 1) - 1;
+  if (eh < 0 || ew < 0) return AX_ORACLE_ERR_ARG;
+  const int OH = eh / stride_h + 1, OW = ew / stride_w + 1;
+  int mult = 0;
+  if (depthwise) {
+    if (Cout % Cin) return AX_ORACLE_ERR_ARG;
+    mult = Cout / Cin;
+  }
+  const uint8_t* xu = (const uint8_t*)x;
+  const uint8_t* wu = (const uint8_t*)w;
+  const int8_t* xs = (const int8_t*)x;
+  const int8_t* ws = (const int8_t*)w;
+  const uint16_t* lu = (const uint16_t*)lut;
+  const int16_t* ls = (const int16_t*)lut;
+  int status = 0;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n) {
+    for (int oy = 0; oy < OH; ++oy) {
+      for (int ox = 0; ox < OW; ++ox) {
+        for (int co = 0; co < Cout; ++co) {
+          const int c_first = depthwise ? co / mult : 0; /* input channels this output sums over */
+          const int c_count = depthwise ? 1 : Cin;
+          int64_t acc = 0, Sp = 0, Sf = 0, K = 0;
+          for (int ky = 0; ky < KH; ++ky) {
+            for (int kx = 0; kx < KW; ++kx) {
+              const int iy = oy * stride_h - pad_h + ky * dil_h;
+              const int ix = ox * stride_w - pad_w + kx * dil_w;
+              const int inside = (iy >= 0 && iy < H && ix >= 0 && ix < W);
+              for (int cc = 0; cc < c_count; ++cc) {
+                const int ci = c_first + cc;
+                const size_t xi = (((size_t)n * H + iy) * W + ix) * Cin + ci;
+                const size_t wi = depthwise ? (((size_t)ky * KW + kx) * Cin + ci) * mult + (co % mult)
+                                            : (((size_t)ky * KW + kx) * Cin + ci) * Cout + co;
+                int a = pad_code, b;
+                if (is_signed) {
+                  if (inside) a = xs[xi];
+                  b = ws[wi];
+                  acc += ls[(a & 0xff) * 256 + (b & 0xff)];
+                } else {
+                  if (inside) a = xu[xi];
+                  b = wu[wi];
+                  acc += lu[a * 256 + b];
+                }
+                Sp += a;
+                Sf += b;
+                K += 1;
+              }
+            }
+          }
+          const size_t o = (((size_t)n * OH + oy) * OW + ox) * Cout + co;
+          if (acc > 2147483647LL || acc < -2147483648LL) {
+#pragma omp atomic write
+            status = AX_ORACLE_ERR_OVERFLOW;
+            continue;
+          }
+          const int64_t corr = acc - (int64_t)w_zp * Sp - (int64_t)x_zp * Sf + K * x_zp * w_zp;
+          acc_out[o] = (int32_t)acc;
+          y_out[o] = (float)((double)x_scale * (double)w_scale * (double)corr);
+        }
+      }
+    }
+  }
+  return status;
+}

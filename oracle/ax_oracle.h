@@ -40,6 +40,14 @@ int ax_oracle_conv2d_sample(const uint8_t* x, int N, int H, int W, int Cin, cons
 int ax_oracle_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint16_t* lut,
                     const ax_oracle_quant* q, int32_t* acc_out, float* y_out);
 
+/* Operator variants (see ax_oracle.c): dilation, signed codes (x, w int8; lut int16, addressed
+ * by the stitched two's-complement patterns), depthwise filters [KH,KW,Cin,Cout/Cin].  pad_code is
+ * given explicitly (no default value). */
+int ax_oracle_conv2d_ex(const void* x, int N, int H, int W, int Cin, const void* w, int KH, int KW,
+                        int Cout, const void* lut, int stride_h, int stride_w, int pad_h, int pad_w,
+                        int dil_h, int dil_w, int depthwise, int is_signed, float x_scale, int x_zp,
+                        float w_scale, int w_zp, int pad_code, int32_t* acc_out, float* y_out);
+
 /* ---- float-in / float-out layer (ax_oracle_quant.c) ------------------------------------ */
 
 /* range_out[0] = min, range_out[1] = max over x[0..n) (after max(.,0) when relu != 0). */

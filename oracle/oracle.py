@@ -38,6 +38,9 @@ def lib():
         _lib.ax_oracle_quantize_f32.argtypes = [vp, i64, ci, cf, ctypes.c_int32, ci, vp]
         _lib.ax_oracle_conv2d_f32.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, ci, ci,
                                               vp, vp, vp, vp, vp]
+        _lib.ax_oracle_conv2d_ex.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci,
+                                             cf, ci, cf, ci, ci, vp, vp]
+        _lib.ax_oracle_conv2d_ex.restype = ci
         for f in (_lib.ax_oracle_conv2d, _lib.ax_oracle_conv2d_sample, _lib.ax_oracle_dense, _lib.ax_oracle_threads,
                   _lib.ax_oracle_range_f32, _lib.ax_oracle_coeffs, _lib.ax_oracle_quantize_f32,
                   _lib.ax_oracle_conv2d_f32):
@@ -120,6 +123,41 @@ def dense(x, w, lut, q):
                                acc.ctypes.data, y.ctypes.data)
     if rc:
         raise RuntimeError("ax_oracle_dense failed: %d" % rc)
+    return acc, y
+
+
+def conv2d_ex(x, w, lut, stride, pad, q, dilation=1, depthwise=False, signed=False):
+    """Operator variants.  signed: x, w int8 and lut int16 (addressed by the two's-complement
+    patterns); depthwise: w is [KH,KW,Cin,mult].  q.pad_code None selects the zero point."""
+    cdt = np.int8 if signed else np.uint8
+    ldt = np.int16 if signed else np.uint16
+    x, w = _chk(x, cdt, 4), _chk(w, cdt, 4)
+    lut = _chk(np.asarray(lut).reshape(-1), ldt, 1)
+    if lut.size != 65536:
+        raise ValueError("table must have 65536 entries")
+    N, H, W, Cin = x.shape
+    KH, KW, Cin2, last = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    Cout = Cin * last if depthwise else last
+    sh, sw = (stride, stride) if np.isscalar(stride) else stride
+    ph, pw = (pad, pad) if np.isscalar(pad) else pad
+    dh, dw = (dilation, dilation) if np.isscalar(dilation) else dilation
+    OH = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+    OW = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+    if OH <= 0 or OW <= 0:
+        raise ValueError("empty output")
+    acc = np.empty((N, OH, OW, Cout), np.int32)
+    y = np.empty((N, OH, OW, Cout), np.float32)
+    pad_code = q.pad_code
+    if pad_code is None or (not signed and pad_code < 0):
+        pad_code = q.x_zp
+    rc = lib().ax_oracle_conv2d_ex(x.ctypes.data, N, H, W, Cin, w.ctypes.data, KH, KW, Cout, lut.ctypes.data,
+                                   sh, sw, ph, pw, dh, dw, int(bool(depthwise)), int(bool(signed)),
+                                   float(q.x_scale), int(q.x_zp), float(q.w_scale), int(q.w_zp), int(pad_code),
+                                   acc.ctypes.data, y.ctypes.data)
+    if rc:
+        raise RuntimeError("ax_oracle_conv2d_ex failed: %d" % rc)
     return acc, y
 
 

@@ -88,6 +88,28 @@ def lut_second_operand() -> np.ndarray:
     return (0 * a + b).astype(np.uint16).reshape(-1)
 
 
+def lut_signed_exact() -> np.ndarray:
+    """Signed 8x8 multiplier as int16 [256,256], addressed by the operands' two's-complement
+    bit patterns: entry [a & 255][b & 255] = a * b for a, b in [-128, 127]."""
+    p = np.arange(256, dtype=np.int64)
+    v = np.where(p < 128, p, p - 256)
+    return (v[:, None] * v[None, :]).astype(np.int16)
+
+
+def lut_signed_random_error(seed: int, amplitude: int = 64) -> np.ndarray:
+    """Signed exact product plus a uniform integer error in [-amplitude, amplitude] on every
+    entry, clipped to int16."""
+    rng = np.random.default_rng(seed)
+    err = rng.integers(-amplitude, amplitude + 1, size=(256, 256), dtype=np.int64)
+    return np.clip(lut_signed_exact().astype(np.int64) + err, -32768, 32767).astype(np.int16)
+
+
+def lut_signed_random(seed: int) -> np.ndarray:
+    """Arbitrary int16 entries over the whole range (stress: sums of either sign)."""
+    rng = np.random.default_rng(seed)
+    return rng.integers(-32768, 32768, size=(256, 256), dtype=np.int64).astype(np.int16)
+
+
 def lut_random(seed: int) -> np.ndarray:
     """Every entry an independent uniform uint16: no multiplier structure at all."""
     rng = np.random.default_rng(seed)
