@@ -92,6 +92,36 @@ int ax_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint
 
 size_t ax_dense_workspace_bytes(int M, int K, int N);
 
+/* ---- operator variants (Sec. III: the layer's dilation parameter next to the strides; signed
+ * multipliers with codes in [-128, 127] next to unsigned ones; an approximate twin for each kind
+ * of 2-D convolution, of which the depthwise one is built) ----------------------------------- */
+
+/* pad_code value that selects the activation zero point in both the unsigned and the signed
+ * form (-1 selects it too, but only for unsigned codes, where -1 is no code). */
+#define AX_PAD_DEFAULT INT32_MIN
+
+typedef struct {
+  int32_t N, H, W, Cin; /* input  [N, H, W, Cin]                                              */
+  int32_t KH, KW, Cout; /* filters [KH, KW, Cin, Cout], or [KH, KW, Cin, Cout/Cin] (depthwise) */
+  int32_t stride_h, stride_w, pad_h, pad_w;
+  int32_t dilation_h, dilation_w; /* >= 1; tap (ky, kx) reads pixel (oy*stride_h - pad_h +
+                                     ky*dilation_h, ox*stride_w - pad_w + kx*dilation_w);
+                                     OH = floor((H + 2*pad_h - dilation_h*(KH-1) - 1)/stride_h) + 1 */
+  int32_t depthwise;    /* 0: ordinary convolution.  1: output channel ci*mult + m (mult =
+                           Cout/Cin, Cout a multiple of Cin) sums over the KH*KW taps of input
+                           channel ci only, so K = KH*KW in the correction                     */
+  int32_t signed_codes; /* 0: x, w uint8, lut uint16.  1: x, w int8, lut int16 with entry index
+                           (uint8_t)x_code * 256 + (uint8_t)w_code (the two's-complement patterns
+                           stitched together); zero points and pad_code in [-128, 127]         */
+} ax_conv_desc_t;
+
+/* ax_conv2d generalized by the descriptor; outputs, workspace rules and errors as for ax_conv2d
+ * (AX_ERR_OPTION for a flag that is neither 0 nor 1).  acc_out is the exact (signed) sum. */
+int ax_conv2d_ex(const ax_conv_desc_t* desc, const void* x, const void* w, const void* lut,
+                 const ax_quant_t* q, int32_t* acc_out, float* y_out, void* workspace,
+                 size_t workspace_bytes, void* hip_stream);
+size_t ax_conv2d_ex_workspace_bytes(const ax_conv_desc_t* desc);
+
 /* ---- float-in / float-out form of the layer (Sec. III: the approximate layer reads two
  * float tensors plus the range of each and returns a float tensor; Algorithm 1: ComputeCoeffs,
  * quantization, lookup-MAC, dequantization) ------------------------------------------------

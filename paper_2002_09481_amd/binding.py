@@ -39,8 +39,17 @@ EXPORTS = [
     "ax_conv2d", "ax_conv2d_workspace_bytes", "ax_dense", "ax_dense_workspace_bytes", "ax_strerror",
     "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_last_kernel_ms", "ax_conv2d_plan",
     "ax_range_f32", "ax_range_workspace_bytes", "ax_quantize_f32", "ax_conv2d_f32", "ax_conv2d_f32_workspace_bytes",
-    "ax_dense_f32", "ax_dense_f32_workspace_bytes",
+    "ax_dense_f32", "ax_dense_f32_workspace_bytes", "ax_conv2d_ex", "ax_conv2d_ex_workspace_bytes",
 ]
+
+
+AX_PAD_DEFAULT = -(1 << 31)
+
+
+class ax_conv_desc_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "N", "H", "W", "Cin", "KH", "KW", "Cout", "stride_h", "stride_w", "pad_h", "pad_w", "dilation_h", "dilation_w",
+        "depthwise", "signed_codes")]
 
 
 def lib():
@@ -82,6 +91,10 @@ def lib():
     L.ax_last_kernel_ms.restype = ci
     L.ax_probe_copy.argtypes = [vp, vp, sz, vp]
     L.ax_probe_copy.restype = ci
+    L.ax_conv2d_ex.argtypes = [ctypes.POINTER(ax_conv_desc_t), vp, vp, vp, ctypes.POINTER(ax_quant_t), vp, vp, vp, sz, vp]
+    L.ax_conv2d_ex.restype = ci
+    L.ax_conv2d_ex_workspace_bytes.argtypes = [ctypes.POINTER(ax_conv_desc_t)]
+    L.ax_conv2d_ex_workspace_bytes.restype = sz
     L.ax_range_f32.argtypes = [vp, sz, ci, vp, vp, sz, vp]
     L.ax_range_f32.restype = ci
     L.ax_range_workspace_bytes.argtypes = [sz]
@@ -259,6 +272,47 @@ def ax_dense(x, w, lut, q, acc_out=None, y_out=None, workspace=None, stream=None
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
 
 
+def ax_conv2d_ex(x, w, lut, stride, pad, q, dilation=1, depthwise=False, acc_out=None, y_out=None, workspace=None,
+                 stream=None):
+    """Operator variants.  Signed form: x, w int8 and lut int16 (chosen by x.dtype).  Depthwise:
+    w is [KH,KW,Cin,mult].  q.pad_code None selects the zero point.  Returns (acc_out, y_out)."""
+    L = lib()
+    signed = x.dtype == torch.int8
+    cdt = torch.int8 if signed else torch.uint8
+    _dev(x, cdt, "x")
+    _dev(w, cdt, "w")
+    if lut.dtype not in (torch.int16, torch.uint16):
+        raise TypeError("lut must be a 16-bit integer tensor")
+    _dev(lut, lut.dtype, "lut")
+    if lut.numel() != 65536:
+        raise ValueError("lut must have 65536 entries")
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
+        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout] (or [KH,KW,Cin,mult])")
+    N, H, W, Cin = x.shape
+    KH, KW, _, last = w.shape
+    Cout = Cin * last if depthwise else last
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    dh, dw = _pair(dilation)
+    desc = ax_conv_desc_t(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, dh, dw, int(bool(depthwise)), int(signed))
+    OH = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+    OW = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+    if OH <= 0 or OW <= 0:
+        _check(-2)
+    acc_out, y_out = _outs((N, OH, OW, Cout), x.device, acc_out, y_out)
+    if workspace is None:
+        need = int(L.ax_conv2d_ex_workspace_bytes(ctypes.byref(desc)))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    pad_code = AX_PAD_DEFAULT if q.pad_code is None else int(q.pad_code)
+    qs = ax_quant_t(float(q.x_scale), int(q.x_zp), float(q.w_scale), int(q.w_zp), pad_code)
+    rc = L.ax_conv2d_ex(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(lut), ctypes.byref(qs),
+                        _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
+                        _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    _check(rc)
+    return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
 def ax_range_workspace_bytes(n: int) -> int:
     return int(lib().ax_range_workspace_bytes(int(n)))
 
@@ -422,8 +476,11 @@ def ax_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
 
 
 def lut_to_device(lut_np, device="cuda") -> torch.Tensor:
-    """uint16 numpy table -> device tensor holding the same bit patterns."""
+    """uint16 (or, for signed multipliers, int16) numpy table -> device tensor holding the same
+    bit patterns."""
     import numpy as np
 
-    a = np.ascontiguousarray(lut_np, dtype=np.uint16).reshape(-1)
-    return torch.from_numpy(a.view(np.int16).copy()).to(device)
+    a = np.ascontiguousarray(lut_np)
+    if a.dtype != np.int16:
+        a = np.ascontiguousarray(a, dtype=np.uint16).view(np.int16)
+    return torch.from_numpy(a.reshape(-1).copy()).to(device)

@@ -25,40 +25,53 @@ void timing_end(hipStream_t s) {
   g_ev_valid = g_ev_valid && hipEventRecord(g_ev1, s) == hipSuccess;
 }
 
-static int make_quant(const ax_quant_t* q, QParams* qp) {
+// Unsigned codes: zero points and pad code in [0, 255], pad_code -1 (or AX_PAD_DEFAULT) = x_zp.
+// Signed codes: all three in [-128, 127], pad_code AX_PAD_DEFAULT = x_zp.
+static int make_quant(const ax_quant_t* q, QParams* qp, int sgn = 0) {
   if (!q) return AX_ERR_NULL;
-  if (q->x_zp < 0 || q->x_zp > 255 || q->w_zp < 0 || q->w_zp > 255) return AX_ERR_QUANT;
-  if (q->pad_code < -1 || q->pad_code > 255) return AX_ERR_QUANT;
+  const int lo = sgn ? -128 : 0, hi = sgn ? 127 : 255;
+  if (q->x_zp < lo || q->x_zp > hi || q->w_zp < lo || q->w_zp > hi) return AX_ERR_QUANT;
+  const bool pad_default = q->pad_code == AX_PAD_DEFAULT || (!sgn && q->pad_code == -1);
+  if (!pad_default && (q->pad_code < lo || q->pad_code > hi)) return AX_ERR_QUANT;
   if (!std::isfinite(q->x_scale) || !std::isfinite(q->w_scale) || !(q->x_scale > 0.f) || !(q->w_scale > 0.f))
     return AX_ERR_QUANT;
   qp->x_zp = q->x_zp;
   qp->w_zp = q->w_zp;
-  qp->pad_code = q->pad_code < 0 ? q->x_zp : q->pad_code;
+  qp->pad_code = pad_default ? q->x_zp : q->pad_code;
   qp->scale = q->x_scale * q->w_scale;
   qp->dq = nullptr;
+  qp->sgn = sgn ? 1 : 0;
   return AX_OK;
 }
 
-int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw, Geom* g) {
+int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw, Geom* g,
+              int dh, int dw, int sgn, int depthwise) {
   if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || KH <= 0 || KW <= 0 || Cout <= 0) return AX_ERR_SHAPE;
-  if (sh < 1 || sw < 1 || ph < 0 || pw < 0) return AX_ERR_SHAPE;
-  if (ph > (1 << 20) || pw > (1 << 20)) return AX_ERR_SHAPE;
-  const long long eh = (long long)H + 2LL * ph - KH, ew = (long long)W + 2LL * pw - KW;
+  if (sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1) return AX_ERR_SHAPE;
+  if (ph > (1 << 20) || pw > (1 << 20) || dh > (1 << 20) || dw > (1 << 20)) return AX_ERR_SHAPE;
+  const long long eh = (long long)H + 2LL * ph - (long long)dh * (KH - 1) - 1;
+  const long long ew = (long long)W + 2LL * pw - (long long)dw * (KW - 1) - 1;
   if (eh < 0 || ew < 0) return AX_ERR_SHAPE;
   const long long OH = eh / sh + 1, OW = ew / sw + 1;
-  const long long K = (long long)KH * KW * Cin;
+  int mult = 0;
+  if (depthwise) {
+    if (Cout % Cin) return AX_ERR_SHAPE;
+    mult = Cout / Cin;
+  }
+  const long long K = (long long)KH * KW * (depthwise ? 1 : Cin);
   if (K > 32768) return AX_ERR_K_OVERFLOW;
   const long long lim = 0x7fffffffLL;
   const long long M = (long long)N * OH * OW;
-  if ((long long)N * H * W * Cin > lim || K * Cout > lim || M > lim || M * Cout > lim) return AX_ERR_SHAPE;
-  *g = Geom{N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, (int)OH, (int)OW, (int)M, (int)K};
+  const long long wsize = (long long)KH * KW * Cin * (depthwise ? mult : Cout);
+  if ((long long)N * H * W * Cin > lim || wsize > lim || M > lim || M * Cout > lim) return AX_ERR_SHAPE;
+  *g = Geom{N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, (int)OH, (int)OW, (int)M, (int)K, dh, dw, sgn ? 1 : 0, mult};
   return AX_OK;
 }
 
 // 1 = direct, 2/3 = table-tile kernels
 static int choose_variant(const Geom& g) {
   if (g_opt.variant == 1) return 1;
-  if (!tab_supported(g)) return 1;
+  if (!tab_supported(g)) return 1;  // incl. depthwise layers: no shared table-side operand
   if (g_opt.variant == 2 || g_opt.variant == 3) return g_opt.variant;
   // Tiny problems do not amortize the table set-up.
   if ((double)g.M * g.K * g.Cout < 4.0e6) return 1;
@@ -86,7 +99,7 @@ static int run(const Geom& g, const ax_quant_t* q, const uint8_t* x, const uint8
   if (!x || !w || !lut || (!acc_out && !y_out)) return AX_ERR_NULL;
   if (((uintptr_t)lut & 1) || ((uintptr_t)acc_out & 3) || ((uintptr_t)y_out & 3)) return AX_ERR_ALIGN;
   QParams qp;
-  int rc = make_quant(q, &qp);
+  int rc = make_quant(q, &qp, g.sgn);
   if (rc) return rc;
   return run_layer(g, qp, x, w, lut, acc_out, y_out, ws, ws_bytes, (hipStream_t)stream);
 }
@@ -121,6 +134,29 @@ extern "C" size_t ax_conv2d_workspace_bytes(int N, int H, int W, int Cin, int KH
                                             int stride_w, int pad_h, int pad_w) {
   Geom g;
   if (make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g)) return 0;
+  return layer_workspace(g);
+}
+
+static int geom_of(const ax_conv_desc_t* d, Geom* g) {
+  if (!d) return AX_ERR_NULL;
+  if ((d->depthwise != 0 && d->depthwise != 1) || (d->signed_codes != 0 && d->signed_codes != 1)) return AX_ERR_OPTION;
+  return make_geom(d->N, d->H, d->W, d->Cin, d->KH, d->KW, d->Cout, d->stride_h, d->stride_w, d->pad_h, d->pad_w, g,
+                   d->dilation_h, d->dilation_w, d->signed_codes, d->depthwise);
+}
+
+extern "C" int ax_conv2d_ex(const ax_conv_desc_t* desc, const void* x, const void* w, const void* lut,
+                            const ax_quant_t* q, int32_t* acc_out, float* y_out, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  Geom g;
+  int rc = geom_of(desc, &g);
+  if (rc) return rc;
+  return run(g, q, static_cast<const uint8_t*>(x), static_cast<const uint8_t*>(w), static_cast<const uint16_t*>(lut),
+             acc_out, y_out, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t ax_conv2d_ex_workspace_bytes(const ax_conv_desc_t* desc) {
+  Geom g;
+  if (geom_of(desc, &g)) return 0;
   return layer_workspace(g);
 }
 

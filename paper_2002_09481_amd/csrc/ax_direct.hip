@@ -31,24 +31,39 @@ __global__ __launch_bounds__(256) void direct_kernel(Geom g, QParams qp_in, cons
   const int oy = m % (uint32_t)g.OH;
   const int n = m / (uint32_t)g.OH;
 
-  uint32_t acc = 0, sp = 0, sf = 0;
+  // Depthwise (g.mult >= 1): output channel co sums over the taps of input channel co / mult
+  // only; filters are [KH, KW, Cin, mult].  Otherwise all Cin channels, filters [KH, KW, Cin, Cout].
+  const int c_first = g.mult ? co / g.mult : 0;
+  const int c_count = g.mult ? 1 : g.Cin;
+  const int wcols = g.mult ? g.mult : g.Cout;   // innermost extent of the filter tensor
+  const int wcol = g.mult ? co % g.mult : co;
+  // Signed codes are sign-extended bytes; the table is addressed by their 8-bit patterns and
+  // its entries are sign-extended too.
+  int32_t acc = 0, sp = 0, sf = 0;
   for (int ky = 0; ky < g.KH; ++ky) {
-    const int iy = oy * g.sh - g.ph + ky;
+    const int iy = oy * g.sh - g.ph + ky * g.dh;
     for (int kx = 0; kx < g.KW; ++kx) {
-      const int ix = ox * g.sw - g.pw + kx;
+      const int ix = ox * g.sw - g.pw + kx * g.dw;
       const bool inside = (iy >= 0) && (iy < g.H) && (ix >= 0) && (ix < g.W);
-      const uint8_t* xp = x + (((size_t)n * g.H + (inside ? iy : 0)) * g.W + (inside ? ix : 0)) * g.Cin;
-      const uint8_t* wp = w + ((size_t)(ky * g.KW + kx) * g.Cin) * g.Cout + co;
-      for (int ci = 0; ci < g.Cin; ++ci) {
-        const uint32_t a = inside ? (uint32_t)xp[ci] : (uint32_t)qp.pad_code;
-        const uint32_t b = wp[(size_t)ci * g.Cout];
-        acc += lut[a * 256u + b];
-        sp += a;
-        sf += b;
+      const uint8_t* xp = x + (((size_t)n * g.H + (inside ? iy : 0)) * g.W + (inside ? ix : 0)) * g.Cin + c_first;
+      const uint8_t* wp = w + ((size_t)(ky * g.KW + kx) * g.Cin + c_first) * wcols + wcol;
+      for (int ci = 0; ci < c_count; ++ci) {
+        const uint32_t ap = inside ? (uint32_t)xp[ci] : ((uint32_t)qp.pad_code & 0xffu);
+        const uint32_t bp = wp[(size_t)ci * wcols];
+        const uint32_t e = lut[ap * 256u + bp];
+        if (g.sgn) {
+          acc += (int32_t)(int16_t)e;
+          sp += (int32_t)(int8_t)ap;
+          sf += (int32_t)(int8_t)bp;
+        } else {
+          acc += (int32_t)e;  // sums stay below 2^31 (K <= 32768)
+          sp += (int32_t)ap;
+          sf += (int32_t)bp;
+        }
       }
     }
   }
-  if (acc_out) acc_out[o] = (int32_t)acc;
+  if (acc_out) acc_out[o] = acc;
   if (y_out) {
     const long long corr = (long long)acc - (long long)qp.w_zp * sp - (long long)qp.x_zp * sf +
                            (long long)g.K * qp.x_zp * qp.w_zp;

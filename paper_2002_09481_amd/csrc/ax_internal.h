@@ -17,7 +17,10 @@ struct Geom {
   int sh, sw, ph, pw;
   int OH, OW;
   int M;  // N*OH*OW output pixels
-  int K;  // KH*KW*Cin taps per output
+  int K;  // taps per output: KH*KW*Cin, or KH*KW for a depthwise layer
+  int dh, dw;  // dilation (>= 1)
+  int sgn;     // 1: codes are int8, table entries int16, addressed by the two's-complement patterns
+  int mult;    // 0: ordinary convolution; >= 1: depthwise with this channel multiplier (Cout = Cin*mult)
 };
 
 // Quantization coefficients kept in device memory (written by the quantization kernels of the
@@ -35,13 +38,15 @@ struct QParams {
   int x_zp, w_zp, pad_code;
   float scale;  // x_scale * w_scale, rounded to float
   const DevQuant* dq;
+  int sgn;  // 1: signed codes (zero points and pad code in [-128, 127]); never set together with dq
 };
 
 // Shared tail of ax_conv2d / ax_conv2d_f32 (ax_api.hip): pick a kernel family and enqueue.
 int run_layer(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
               int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, hipStream_t s);
 size_t layer_workspace(const Geom& g);
-int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw, Geom* g);
+int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw, Geom* g,
+              int dh = 1, int dw = 1, int sgn = 0, int depthwise = 0);
 
 struct Options {
   int variant;  // 0 auto, 1 direct, 2 lanes over pixels, 3 lanes over channels

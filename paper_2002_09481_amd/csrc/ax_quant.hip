@@ -322,7 +322,7 @@ int run_f32(const Geom& g, const float* x, const float* w, const uint16_t* lut, 
   const QuantTask qw = quant_task(w, nw, 0, wsb + p.off_wq, cw, sw);
   hipLaunchKernelGGL(quantize_kernel, dim3(qx.blocks + qw.blocks), dim3(kThreads), 0, s, qx, qw, mode);
   if (launched() != AX_OK) return AX_ERR_HIP;
-  QParams qp{0, 0, 0, 1.0f, dq};
+  QParams qp{0, 0, 0, 1.0f, dq, 0};
   return run_layer(g, qp, wsb + p.off_xq, wsb + p.off_wq, lut, acc_out, y_out, wsb + p.off_layer,
                    ws_bytes - p.off_layer, s);
 }

@@ -63,6 +63,9 @@ struct TabArgs {
   int ntj, nch;
   long long total_iters;
   const struct QDev* qd;  // zero points, scale and pad code as the kernels use them (written by prep_kernel)
+  int dh, dw;        // dilation of the implicit im2col view
+  uint32_t xor4;     // 0x80808080 when A holds signed codes (turned into offset binary as they are read), else 0
+  uint32_t bias_k;   // 32768 * K for signed tables (their entries are stored with that offset), else 0
   int32_t* acc_out;
   float* y_out;
   int32_t* part;  // [2*G][IT*JT] partial tiles: slot 2w = workgroup w's piece of a tile begun by
@@ -177,11 +180,14 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     const int kx = tap - ky * a.KW;
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-      const int iy = by[p] + ky, ix = bx[p] + kx;
+      const int iy = by[p] + ky * a.dh, ix = bx[p] + kx * a.dw;
       const bool inside = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
       const uint32_t off = ((uint32_t)(nb[p] + iy) * (uint32_t)a.W + (uint32_t)ix) * (uint32_t)a.Cin + (uint32_t)ci0;
       v[p] = make_uint4(pad4, pad4, pad4, pad4);
-      if (inside && act[p]) v[p] = *reinterpret_cast<const uint4*>(a.A + off);
+      if (inside && act[p]) {
+        v[p] = *reinterpret_cast<const uint4*>(a.A + off);
+        v[p].x ^= a.xor4; v[p].y ^= a.xor4; v[p].z ^= a.xor4; v[p].w ^= a.xor4;
+      }
     }
   };
 
@@ -362,7 +368,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   // corr = acc - z_tab*Sl - z_lane*Sb[j] + K*z_lane*z_tab.  Each of the four terms is below
   // 2^31 in magnitude; for K <= 16384 so is every partial sum, and 32-bit wrap-around
   // arithmetic is exact.  Longer K takes the 64-bit form.
-  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0];
+  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0] + a.bias_k;
   const bool finish = whole;  // this workgroup writes the tile's outputs
   if (!whole) {
     // Piece of a tile that several workgroups share: stored column-major ([column][lane
@@ -489,7 +495,7 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
   const int i0 = ti * a.ih, j0 = (tile - ti * a.ntj) * JT;
   if (il0 >= a.ih || i0 + il0 >= a.I) return;
   const int klast = a.nch * kChunk;
-  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0];  // padded taps, see tab_kernel
+  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0] + a.bias_k;  // see tab_kernel
   __shared__ long long cterm[JT];
   __shared__ uint32_t patch[64][JT + 4];
   __shared__ uint32_t lterm_s[64];
@@ -566,10 +572,12 @@ struct ConvView {  // im2col addressing of x
   const uint8_t* x;
   int H, W, Cin, KW, sh, sw, ph, pw, OH, OW, M, K, pad_code;
   const DevQuant* dq;  // non-null: the pad code is the activation zero point held on the device
+  int dh, dw;
+  uint32_t sx;  // 0x80 for signed codes: every code read or padded is turned into offset binary
 };
 
 __device__ __forceinline__ uint32_t pad_of(const ConvView& v) {
-  return v.dq ? (uint32_t)v.dq->x_zp : (uint32_t)v.pad_code;
+  return v.dq ? (uint32_t)v.dq->x_zp : (((uint32_t)v.pad_code & 0xffu) ^ v.sx);
 }
 
 __device__ __forceinline__ uint32_t im2col_code(const ConvView& v, uint32_t pad, int m, int k) {
@@ -579,9 +587,9 @@ __device__ __forceinline__ uint32_t im2col_code(const ConvView& v, uint32_t pad,
   const int oy = r / v.OW, ox = r - (r / v.OW) * v.OW;
   const int tap = k / v.Cin, ci = k - tap * v.Cin;
   const int ky = tap / v.KW, kx = tap - ky * v.KW;
-  const int iy = oy * v.sh - v.ph + ky, ix = ox * v.sw - v.pw + kx;
+  const int iy = oy * v.sh - v.ph + ky * v.dh, ix = ox * v.sw - v.pw + kx * v.dw;
   if ((unsigned)iy >= (unsigned)v.H || (unsigned)ix >= (unsigned)v.W) return pad;
-  return v.x[((size_t)(n * v.H + iy) * v.W + ix) * v.Cin + ci];
+  return (uint32_t)v.x[((size_t)(n * v.H + iy) * v.W + ix) * v.Cin + ci] ^ v.sx;
 }
 
 // rows[t][2P] = R[t][P], rows[t][2P+1] = R[t][P+128]  (P < 128), where R[t][v] is the
@@ -609,24 +617,29 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
       pad = xz;
       sc = qp.dq->x_scale * qp.dq->w_scale;
     }
+    // Signed codes c are handled as offset binary c' = c + 128 (their byte with the top bit
+    // flipped).  The sums the kernels form are then sums of c', 128 * K too large each, which the
+    // constant term takes back: corr = acc - wz*Sp - xz*Sf + K*xz*wz with Sp = Sp' - 128 K etc.
     qd->z_lane = FROM_X ? wz : xz;
     qd->z_tab = FROM_X ? xz : wz;
-    qd->kzz = (long long)K * xz * wz;
+    qd->kzz = (long long)K * xz * wz + (qp.sgn ? 128LL * K * (xz + wz) : 0LL);
     qd->scale = sc;
-    qd->pad4 = (uint32_t)pad * 0x01010101u;
+    qd->pad4 = (((uint32_t)pad & 0xffu) ^ (qp.sgn ? 0x80u : 0u)) * 0x01010101u;
   }
+  const uint32_t sx = qp.sgn ? 0x80u : 0u;  // pattern <-> offset-binary code; also moves int16 entries to offset form
   if (blockIdx.x < kRowBlocks) {
     const int dw = blockIdx.x * 256 + threadIdx.x;  // 0 .. 32767
     const int t = dw >> 7, P = dw & 127;
     uint32_t lo, hi;
+    const uint32_t tp = (uint32_t)t ^ sx, p0 = (uint32_t)P ^ sx, p1 = (uint32_t)(P + 128) ^ sx;
     if (FROM_X) {  // table side = activation code t, lane side = filter code v
-      lo = lut[t * 256 + P];
-      hi = lut[t * 256 + P + 128];
+      lo = lut[tp * 256 + p0];
+      hi = lut[tp * 256 + p1];
     } else {  // table side = filter code t, lane side = activation code v
-      lo = lut[P * 256 + t];
-      hi = lut[(P + 128) * 256 + t];
+      lo = lut[p0 * 256 + tp];
+      hi = lut[p1 * 256 + tp];
     }
-    rows32[dw] = lo | (hi << 16);
+    rows32[dw] = (lo | (hi << 16)) ^ (sx * 0x01000100u);  // signed entries + 32768
     return;
   }
   __shared__ int32_t red[16][65];
@@ -643,12 +656,12 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
     uint32_t pk = 0;
     if (k < K) {
       if (fast) {
-        pk = *reinterpret_cast<const uint32_t*>(w + (size_t)k * J + j);
+        pk = *reinterpret_cast<const uint32_t*>(w + (size_t)k * J + j) ^ (sx * 0x01010101u);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           uint32_t bb = 0;
-          if (j + e < J) bb = FROM_X ? im2col_code(cv, pad, j + e, k) : (uint32_t)w[(size_t)k * J + j + e];
+          if (j + e < J) bb = FROM_X ? im2col_code(cv, pad, j + e, k) : ((uint32_t)w[(size_t)k * J + j + e] ^ sx);
           pk |= bb << (8 * e);
         }
       }
@@ -689,10 +702,10 @@ __global__ __launch_bounds__(256) void prep_im2col_kernel(ConvView cv, int Kp, u
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     if (k0 + e < cv.K) {
-      const int iy = by + ky, ix = bx + kx;
+      const int iy = by + ky * cv.dh, ix = bx + kx * cv.dw;
       uint32_t v = pad;
       if ((unsigned)iy < (unsigned)cv.H && (unsigned)ix < (unsigned)cv.W)
-        v = cv.x[((size_t)(n * cv.H + iy) * cv.W + ix) * cv.Cin + ci];
+        v = (uint32_t)cv.x[((size_t)(n * cv.H + iy) * cv.W + ix) * cv.Cin + ci] ^ cv.sx;
       pk[e >> 2] |= v << (8 * (e & 3));
       if (++ci == cv.Cin) {
         ci = 0;
@@ -705,7 +718,7 @@ __global__ __launch_bounds__(256) void prep_im2col_kernel(ConvView cv, int Kp, u
 
 // Ap[j][k] = w[k][j] (zero fill for k >= K), 64x64 tiles through LDS.
 __global__ __launch_bounds__(256) void prep_transpose_kernel(const uint8_t* __restrict__ w, int K, int J, int Kp,
-                                                              uint8_t* __restrict__ Ap) {
+                                                              uint8_t* __restrict__ Ap, uint32_t sx) {
   __shared__ uint8_t tile[64][68];
   const int k0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
   const int t = threadIdx.x;
@@ -715,7 +728,7 @@ __global__ __launch_bounds__(256) void prep_transpose_kernel(const uint8_t* __re
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       const int j = j0 + seg + e;
-      tile[r][seg + e] = (k < K && j < J) ? w[(size_t)k * J + j] : (uint8_t)0;
+      tile[r][seg + e] = (k < K && j < J) ? (uint8_t)(w[(size_t)k * J + j] ^ sx) : (uint8_t)0;
     }
   }
   __syncthreads();
@@ -754,6 +767,7 @@ int tab_num_tiles() { return kNumTiles; }
 
 // The preparation kernels index their pieces with 32-bit integers.
 bool tab_supported(const Geom& g) {
+  if (g.mult) return false;  // depthwise: every output channel has its own lane-side operand
   const long long chunks = cdiv(g.K, kChunk);
   return (long long)g.M * chunks < (1LL << 31) && (long long)g.Cout * chunks < (1LL << 31);
 }
@@ -929,7 +943,8 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   uint8_t* Ap = wsb + p.off_apack;
   QDev* qd = reinterpret_cast<QDev*>(wsb + p.off_qd);
 
-  ConvView cv{x, g.H, g.W, g.Cin, g.KW, g.sh, g.sw, g.ph, g.pw, g.OH, g.OW, g.M, g.K, qp.pad_code, qp.dq};
+  ConvView cv{x, g.H, g.W, g.Cin, g.KW, g.sh, g.sw, g.ph, g.pw, g.OH, g.OW, g.M, g.K, qp.pad_code, qp.dq,
+              g.dh, g.dw, g.sgn ? 0x80u : 0u};
 
   const int ntiles = cdiv(I, kIT) * cdiv(J, kJT);
   // Column sums are produced per segment of rows so that more than Jpad/64 blocks share the work.
@@ -948,18 +963,22 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.I = I;
   if (ch) {
     hipLaunchKernelGGL(prep_transpose_kernel, dim3(cdiv(Kp, 64), cdiv(g.Cout, 64)), dim3(256), 0, s, w, g.K,
-                       g.Cout, Kp, Ap);
+                       g.Cout, Kp, Ap, cv.sx);
     a.A = Ap;
     a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
+    a.dh = 1; a.dw = 1;
   } else if (g.Cin % 16 == 0 && ((uintptr_t)x & 15) == 0) {
     a.A = x;
     a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.KW = g.KW; a.sh = g.sh; a.sw = g.sw; a.ph = g.ph; a.pw = g.pw;
     a.OHW = g.OH * g.OW; a.OW = g.OW;
+    a.dh = g.dh; a.dw = g.dw;
+    a.xor4 = cv.sx * 0x01010101u;
   } else {
     const long long pieces = (long long)g.M * (Kp / 16);
     hipLaunchKernelGGL(prep_im2col_kernel, dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, s, cv, Kp, Ap);
     a.A = Ap;
     a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
+    a.dh = 1; a.dw = 1;
   }
   a.Bp = Bp; a.Jpad = Jpad; a.J = J; a.bsum = bsum; a.nseg = cdiv(krows, seg_rows); a.rows = rows;
   a.K = g.K;
@@ -968,6 +987,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.ih = cdiv(cdiv(I, cdiv(I, kIT)), 64) * 64;  // balanced tile height: padding spread over all tiles
   a.total_iters = (long long)cdiv(I, kIT) * a.ntj * nchunks;
   a.qd = qd;
+  a.bias_k = g.sgn ? 32768u * (uint32_t)g.K : 0u;
   a.acc_out = acc_out; a.y_out = y_out;
   a.part = reinterpret_cast<int32_t*>(wsb + p.off_part);
   a.lsum = reinterpret_cast<int32_t*>(wsb + p.off_lsum);

@@ -1,0 +1,151 @@
+"""GPU parity of the operator variants (dilation, signed codes and tables, depthwise) through
+ax_conv2d_ex against the CPU oracle: int32 accumulators bit exact, float outputs within
+1e-5 relative + 1e-6 absolute."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2002_09481_amd import binding as ax
+from paper_2002_09481_amd import inputs as I
+
+import gpu_common as G
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset_options():
+    yield
+    ax.ax_set_option("variant", 0)
+    ax.ax_set_option("split_k", 0)
+    ax.ax_set_option("tile", 0)
+
+
+def _operands(shape, seed, signed, depthwise=False, mult=1):
+    N, H, W, Cin, KH, KW, Cout = shape
+    rng = np.random.default_rng(seed)
+    lo, hi, dt = (-128, 128, np.int8) if signed else (0, 256, np.uint8)
+    x = rng.integers(lo, hi, (N, H, W, Cin)).astype(dt)
+    # half of the activations at one value, like post-ReLU tensors
+    x[rng.random(x.shape) < 0.5] = dt(lo + 5)
+    wshape = (KH, KW, Cin, mult) if depthwise else (KH, KW, Cin, Cout)
+    w = rng.integers(lo, hi, wshape).astype(dt)
+    q = I.Quant(0.021, int(rng.integers(lo, hi)), 0.0043, int(rng.integers(lo, hi)),
+                None if seed % 2 else int(rng.integers(lo, hi)))
+    return x, w, q
+
+
+def _check(x, w, lut, s, p, d, q, depthwise=False, what=""):
+    signed = x.dtype == np.int8
+    acc, y = ax.ax_conv2d_ex(G.to_dev(x), G.to_dev(w), ax.lut_to_device(lut), s, p, q, dilation=d, depthwise=depthwise)
+    torch.cuda.synchronize()
+    acc_ref, y_ref = oracle.conv2d_ex(x, w, lut, s, p, q, dilation=d, depthwise=depthwise, signed=signed)
+    G.assert_parity(acc.cpu().numpy(), y.cpu().numpy(), acc_ref, y_ref, what)
+
+
+SHAPES = [
+    # N, H, W, Cin, KH, KW, Cout, stride, pad, dilation
+    ((1, 1, 1, 1, 1, 1, 1), 1, 0, 1),
+    ((2, 9, 7, 5, 3, 3, 6), 2, 1, 1),
+    ((1, 12, 12, 4, 3, 3, 5), 1, 2, 2),
+    ((2, 11, 9, 3, 3, 2, 4), 2, 3, 3),
+    ((2, 20, 20, 16, 3, 3, 24), 1, (2, 4), (2, 4)),        # implicit patch reads, dilation differs per axis
+    ((1, 40, 40, 32, 3, 3, 72), 1, 2, 2),                  # several channel tiles
+    ((2, 30, 30, 20, 5, 5, 9), 2, 4, 2),                   # materialized patches (Cin % 16 != 0)
+    ((1, 7, 7, 256, 3, 3, 512), 1, 3, 3),                  # few pixels, many channels
+    ((4, 14, 14, 64, 1, 1, 200), 1, 0, 1),
+]
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("signed", [False, True])
+@pytest.mark.parametrize("case", SHAPES, ids=lambda c: "x".join(map(str, c[0])) + "_d%s" % (c[3],))
+def test_dilated_and_signed_layers(case, signed, variant):
+    shape, s, p, d = case
+    ax.ax_set_option("variant", variant)
+    x, w, q = _operands(shape, 100 + shape[3] + variant, signed)
+    lut = I.lut_signed_random_error(5) if signed else I.lut_random_error(5)
+    _check(x, w, lut, s, p, d, q, what=str(case))
+
+
+@pytest.mark.parametrize("table", ["exact", "random", "minimum"])
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_signed_tables_of_either_sign(table, variant):
+    """Arbitrary int16 entries (sums of either sign), and the table of all -32768: the most
+    negative accumulator, -32768 * K."""
+    ax.ax_set_option("variant", variant)
+    shape = (2, 10, 10, 32, 3, 3, 40)
+    x, w, q = _operands(shape, 7, True)
+    lut = {"exact": I.lut_signed_exact(), "random": I.lut_signed_random(11),
+           "minimum": np.full((256, 256), -32768, np.int16)}[table]
+    _check(x, w, lut, 1, 1, 1, q, what=table)
+    if table == "minimum":
+        acc, _ = ax.ax_conv2d_ex(G.to_dev(x), G.to_dev(w), ax.lut_to_device(lut), 1, 1, q)
+        assert bool((acc == -32768 * 288).all())
+
+
+@pytest.mark.parametrize("split", [2, 3])
+@pytest.mark.parametrize("signed", [False, True])
+def test_variants_with_forced_k_split(split, signed):
+    ax.ax_set_option("split_k", split)
+    shape = (1, 20, 20, 64, 3, 3, 64)
+    x, w, q = _operands(shape, 31, signed)
+    lut = I.lut_signed_random(3) if signed else I.lut_random(3)
+    _check(x, w, lut, 1, 2, 2, q, what="split %d" % split)
+
+
+def test_signed_long_k_wide_epilogue():
+    """K above 16384 takes the 64-bit correction path."""
+    shape = (1, 3, 3, 2048, 3, 3, 24)
+    x, w, q = _operands(shape, 5, True)
+    for variant in (2, 3):
+        ax.ax_set_option("variant", variant)
+        _check(x, w, I.lut_signed_random(9), 1, 1, 1, q, what="K=18432 variant %d" % variant)
+
+
+DEPTHWISE = [
+    # N, H, W, Cin, KH, KW, mult, stride, pad, dilation
+    (1, 1, 1, 2, 1, 1, 2, 1, 0, 1),
+    (2, 8, 7, 4, 3, 3, 1, 2, 1, 1),
+    (2, 8, 7, 4, 3, 3, 3, 1, 1, 2),
+    (4, 28, 28, 96, 3, 3, 1, 1, 1, 1),        # a MobileNet-like depthwise layer
+    (2, 14, 14, 33, 5, 5, 2, 2, 2, 1),
+]
+
+
+@pytest.mark.parametrize("signed", [False, True])
+@pytest.mark.parametrize("case", DEPTHWISE, ids=lambda c: "x".join(map(str, c)))
+def test_depthwise_layers(case, signed):
+    N, H, W, Cin, KH, KW, mult, s, p, d = case
+    x, w, q = _operands((N, H, W, Cin, KH, KW, Cin * mult), 200 + Cin, signed, depthwise=True, mult=mult)
+    lut = I.lut_signed_random(13) if signed else I.lut_random(13)
+    _check(x, w, lut, s, p, d, q, depthwise=True, what=str(case))
+
+
+def test_descriptor_with_defaults_is_the_plain_layer():
+    layer = I.Layer("plain", 2, 16, 16, 32, 3, 3, 48, 1, 1, x_dist="relu", w_dist="normal")
+    x, w, q = I.make_operands(layer, 3)
+    lut = I.lut_truncated(5)
+    a0, y0 = ax.ax_conv2d(G.to_dev(x), G.to_dev(w), ax.lut_to_device(lut), 1, 1, q)
+    a1, y1 = ax.ax_conv2d_ex(G.to_dev(x), G.to_dev(w), ax.lut_to_device(lut), 1, 1, q)
+    assert torch.equal(a0, a1) and torch.equal(y0, y1)
+
+
+def test_descriptor_errors():
+    L_ = ax.lib()
+    x = torch.zeros((1, 4, 4, 2), dtype=torch.uint8, device="cuda")
+    w = torch.zeros((3, 3, 2, 2), dtype=torch.uint8, device="cuda")
+    lut = ax.lut_to_device(I.lut_exact())
+    with pytest.raises(ax.AxError):  # dilated kernel larger than the padded image
+        ax.ax_conv2d_ex(x, w, lut, 1, 0, I.Quant(), dilation=2)
+    with pytest.raises(ax.AxError):  # signed zero point out of range
+        ax.ax_conv2d_ex(x.to(torch.int8), w.to(torch.int8), lut, 1, 1, I.Quant(1.0, 200, 1.0, 0, None))
+    # for signed layers -1 is a code, not "default": accepted
+    ax.ax_conv2d_ex(x.to(torch.int8), w.to(torch.int8), lut, 1, 1, I.Quant(1.0, 0, 1.0, 0, -1))
+    d = ax.ax_conv_desc_t(1, 4, 4, 2, 3, 3, 3, 1, 1, 1, 1, 1, 1, 1, 0)  # depthwise with Cout % Cin != 0
+    assert L_.ax_conv2d_ex_workspace_bytes(d) == 0
+    d = ax.ax_conv_desc_t(1, 4, 4, 2, 3, 3, 2, 1, 1, 1, 1, 1, 1, 2, 0)  # flag that is neither 0 nor 1
+    assert L_.ax_conv2d_ex_workspace_bytes(d) == 0
+    torch.cuda.synchronize()
