@@ -64,7 +64,6 @@ struct TabArgs {
   long long total_iters;
   const struct QDev* qd;  // zero points, scale and pad code as the kernels use them (written by prep_kernel)
   int dh, dw;        // dilation of the implicit im2col view
-  uint32_t xor4;     // 0x80808080 when A holds signed codes (turned into offset binary as they are read), else 0
   uint32_t bias_k;   // 32768 * K for signed tables (their entries are stored with that offset), else 0
   int32_t* acc_out;
   float* y_out;
@@ -184,10 +183,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
       const bool inside = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
       const uint32_t off = ((uint32_t)(nb[p] + iy) * (uint32_t)a.W + (uint32_t)ix) * (uint32_t)a.Cin + (uint32_t)ci0;
       v[p] = make_uint4(pad4, pad4, pad4, pad4);
-      if (inside && act[p]) {
-        v[p] = *reinterpret_cast<const uint4*>(a.A + off);
-        v[p].x ^= a.xor4; v[p].y ^= a.xor4; v[p].z ^= a.xor4; v[p].w ^= a.xor4;
-      }
+      if (inside && act[p]) v[p] = *reinterpret_cast<const uint4*>(a.A + off);
     }
   };
 
@@ -716,6 +712,16 @@ __global__ __launch_bounds__(256) void prep_im2col_kernel(ConvView cv, int Kp, u
   *reinterpret_cast<uint4*>(Ap + (size_t)m * Kp + k0) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
 }
 
+// Signed activations read through the implicit patch view: one pass turns the tensor into
+// offset binary (top bit of every byte flipped), 16 bytes per thread; n16 = elements / 16.
+__global__ __launch_bounds__(256) void prep_flip_kernel(const uint4* __restrict__ x, uint4* __restrict__ out, uint32_t n16) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= n16) return;
+  uint4 v = x[i];
+  v.x ^= 0x80808080u; v.y ^= 0x80808080u; v.z ^= 0x80808080u; v.w ^= 0x80808080u;
+  out[i] = v;
+}
+
 // Ap[j][k] = w[k][j] (zero fill for k >= K), 64x64 tiles through LDS.
 __global__ __launch_bounds__(256) void prep_transpose_kernel(const uint8_t* __restrict__ w, int K, int J, int Kp,
                                                               uint8_t* __restrict__ Ap, uint32_t sx) {
@@ -886,7 +892,8 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   p.off_rows = off;   off += up256(131072);
   p.off_bpack = off;  off += up256((Kp + 1) * Jpad);
   p.off_bsum = off;   off += up256(Jpad * 4 * kMaxSeg);
-  p.off_apack = off;  off += up256((size_t)I * Kp);  // only used when the lane operand is materialized
+  // materialized lane operand, or (signed codes, implicit patch view) the offset-binary copy of x
+  p.off_apack = off;  off += up256(std::max((size_t)I * Kp, (size_t)g.N * g.H * g.W * g.Cin));
   p.off_qd = off;     off += 256;
   p.off_lsum = off;
   p.off_part = off;
@@ -969,10 +976,15 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
     a.dh = 1; a.dw = 1;
   } else if (g.Cin % 16 == 0 && ((uintptr_t)x & 15) == 0) {
     a.A = x;
+    if (g.sgn) {  // N*H*W*Cin is a multiple of 16 here
+      const uint32_t n16 = (uint32_t)(((size_t)g.N * g.H * g.W * g.Cin) / 16);
+      hipLaunchKernelGGL(prep_flip_kernel, dim3(cdiv(n16, 256)), dim3(256), 0, s, reinterpret_cast<const uint4*>(x),
+                         reinterpret_cast<uint4*>(Ap), n16);
+      a.A = Ap;
+    }
     a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.KW = g.KW; a.sh = g.sh; a.sw = g.sw; a.ph = g.ph; a.pw = g.pw;
     a.OHW = g.OH * g.OW; a.OW = g.OW;
     a.dh = g.dh; a.dw = g.dw;
-    a.xor4 = cv.sx * 0x01010101u;
   } else {
     const long long pieces = (long long)g.M * (Kp / 16);
     hipLaunchKernelGGL(prep_im2col_kernel, dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, s, cv, Kp, Ap);
