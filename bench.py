@@ -292,6 +292,44 @@ def main():
         m5 = sum(l.macs for l in l5)
         extra["config5_gemm_shaped"] = {"ms": ms, "lut_macs_per_s": m5 / ms * 1e3}
 
+        # operator variants: one ResNet-50 3x3 layer in unsigned, signed and dilated form, and two
+        # depthwise layers of MobileNet size (whole table in LDS, HBM-bound on the outputs)
+        def time_ex(x, w, lut_np, stride, pad, q, dilation=1, depthwise=False, reps=20):
+            xd, wd, ld = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev), ax.lut_to_device(lut_np)
+            acc, y = ax.ax_conv2d_ex(xd, wd, ld, stride, pad, q, dilation=dilation, depthwise=depthwise)
+            wsz = ax.lib().ax_conv2d_ex_workspace_bytes(ax.ax_conv_desc_t(
+                x.shape[0], x.shape[1], x.shape[2], x.shape[3], w.shape[0], w.shape[1],
+                x.shape[3] * w.shape[3] if depthwise else w.shape[3], stride, stride, pad, pad, dilation, dilation,
+                int(depthwise), int(x.dtype == np.int8)))
+            ws = torch.empty(max(256, int(wsz)), dtype=torch.uint8, device=dev)
+            return time_calls([lambda: ax.ax_conv2d_ex(xd, wd, ld, stride, pad, q, dilation=dilation,
+                                                       depthwise=depthwise, acc_out=acc, y_out=y, workspace=ws)], reps)
+
+        vr = np.random.default_rng(77)
+        var = {}
+        shp = (args.batch, 56, 56, 64)
+        xu = vr.integers(0, 256, shp).astype(np.uint8)
+        wu = vr.integers(0, 256, (3, 3, 64, 64)).astype(np.uint8)
+        xs_ = (xu.astype(np.int16) - 128).astype(np.int8)
+        ws_ = (wu.astype(np.int16) - 128).astype(np.int8)
+        macs = args.batch * 56 * 56 * 64 * 64 * 9
+        for name, ms in (("conv3x3_56x56x64_unsigned", time_ex(xu, wu, I.lut_random_error(1), 1, 1, I.Quant(0.02, 3, 0.01, 128, None))),
+                         ("conv3x3_56x56x64_signed", time_ex(xs_, ws_, I.lut_signed_random_error(1), 1, 1, I.Quant(0.02, -125, 0.01, 0, None))),
+                         ("conv3x3_56x56x64_dilation2", time_ex(xu, wu, I.lut_random_error(1), 1, 2, I.Quant(0.02, 3, 0.01, 128, None), dilation=2))):
+            var[name] = {"ms": ms, "lut_macs_per_s": macs / ms * 1e3}
+        for hw, c in ((112, 32), (56, 128)):
+            xdw = vr.integers(0, 256, (args.batch, hw, hw, c)).astype(np.uint8)
+            wdw = vr.integers(0, 256, (3, 3, c, 1)).astype(np.uint8)
+            ms = time_ex(xdw, wdw, I.lut_random_error(1), 1, 1, I.Quant(0.02, 3, 0.01, 128, None), depthwise=True)
+            n_out = args.batch * hw * hw * c
+            byts = xdw.size + wdw.size + 131072 + 8 * n_out
+            var["depthwise3x3_%dx%dx%d" % (hw, hw, c)] = {
+                "ms": ms, "lut_macs_per_s": n_out * 9 / ms * 1e3,
+                "roofline": {"bound": "hbm", "achieved": byts / ms / 1e6, "peak": 8000.0, "unit": "GB/s",
+                             "frac": byts / ms / 1e6 / 8000.0, "algorithmic_bytes": byts,
+                             "lds_random_gather_Glookup_s": lds_rand / 1e9}}
+        extra["variants_batch%d" % args.batch] = var
+
     # ---- float-in / float-out form of the same sweep (range + quantization glue included) ------
     float_layer = None
     if not args.no_extra:

@@ -82,7 +82,9 @@ int run_layer(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t*
               int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, hipStream_t s) {
   const int v = choose_variant(g);
   hipError_t e;
-  if (v == 1) {
+  if (v == 1 && g.mult && g_opt.variant != 1 && dw_supported(g, x, w, lut)) {
+    e = launch_dw(g, qp, x, w, lut, acc_out, y_out, s);
+  } else if (v == 1) {
     e = launch_direct(g, qp, x, w, lut, acc_out, y_out, s);
   } else {
     Options o = g_opt;

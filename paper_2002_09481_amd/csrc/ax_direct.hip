@@ -5,6 +5,8 @@
 // output channels of one pixel, so the activation code is wave-uniform, the filter codes
 // are a coalesced 64-byte read and the lookups fall into one 512-byte table row.  It is
 // used for tiny problems and for shapes the table-tile kernels do not take.
+#include <algorithm>
+
 #include "ax_internal.h"
 
 namespace ax {
@@ -69,6 +71,154 @@ __global__ __launch_bounds__(256) void direct_kernel(Geom g, QParams qp_in, cons
                            (long long)g.K * qp.x_zp * qp.w_zp;
     y_out[o] = (float)corr * qp.scale;
   }
+}
+
+// Depthwise layers (channel multiplier 1, Cin % 4 == 0).  No table-side operand is shared
+// between output channels, so the table-tile scheme does not apply; instead every workgroup
+// keeps the whole 128 KB table in LDS (one workgroup of 1024 threads per compute unit) and
+// gathers 2-byte entries at random addresses.  One thread takes 4 consecutive channels of one
+// output pixel: activations and filters arrive as one dword per tap, the four results leave as
+// one 16-byte store per output tensor.  Signed tables are stored with 32768 added to every
+// entry and activation sums are taken over the byte patterns with the top bit flipped (code +
+// 128); both offsets come off again in the epilogue.
+constexpr int kDwMaxC = 4096;  // channels whose filter sums fit next to the table in LDS
+
+// KS: kernel height = width known at compile time (taps fully unrolled, so that the loads of all
+// taps of an item are in flight together), or 0 for any kernel size.
+template <int KS>
+__global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const uint8_t* __restrict__ x,
+                                                   const uint8_t* __restrict__ w, const uint16_t* __restrict__ lut,
+                                                   int32_t* __restrict__ acc_out, float* __restrict__ y_out,
+                                                   int vec_out) {
+  __shared__ uint16_t tab[65536];
+  __shared__ int32_t sfs[kDwMaxC];  // per channel: sum over the taps of the filter codes (+128 each if signed)
+  QParams qp = qp_in;
+  if (qp.dq) {
+    qp.x_zp = qp.dq->x_zp;
+    qp.w_zp = qp.dq->w_zp;
+    qp.pad_code = qp.x_zp;
+    qp.scale = qp.dq->x_scale * qp.dq->w_scale;
+  }
+  const uint32_t flip16 = g.sgn ? 0x80008000u : 0u;
+  const uint32_t flip8 = g.sgn ? 0x80808080u : 0u;
+  const int KH = KS ? KS : g.KH, KW = KS ? KS : g.KW;
+  const int K = KH * KW;
+  {
+    const uint4* __restrict__ src = reinterpret_cast<const uint4*>(lut);
+    uint4* dst = reinterpret_cast<uint4*>(tab);
+    for (int i = threadIdx.x; i < 8192; i += 1024) {
+      uint4 v = src[i];
+      v.x ^= flip16; v.y ^= flip16; v.z ^= flip16; v.w ^= flip16;
+      dst[i] = v;
+    }
+    for (int c = threadIdx.x; c < g.Cin; c += 1024) {
+      int32_t t = 0;
+      for (int k = 0; k < K; ++k) t += (int32_t)((uint32_t)w[(size_t)k * g.Cin + c] ^ (flip8 & 0xffu));
+      sfs[c] = t;
+    }
+  }
+  __syncthreads();
+  const uint32_t C4 = (uint32_t)g.Cin / 4u;
+  const uint32_t items = (uint32_t)g.M * C4;  // M * Cin < 2^31
+  const uint32_t pad4 = ((uint32_t)qp.pad_code & 0xffu) * 0x01010101u;
+  const uint32_t bias = g.sgn ? 32768u * (uint32_t)K : 0u;
+  const int off128 = g.sgn ? 128 * K : 0;
+  const long long kzz = (long long)K * qp.x_zp * qp.w_zp;
+  for (uint32_t it = blockIdx.x * 1024u + threadIdx.x; it < items; it += gridDim.x * 1024u) {
+    const uint32_t c4 = it % C4;
+    const uint32_t pix = it / C4;
+    uint32_t m = pix;
+    const int ox = m % (uint32_t)g.OW;
+    m /= (uint32_t)g.OW;
+    const int oy = m % (uint32_t)g.OH;
+    const int n = m / (uint32_t)g.OH;
+    const int by = oy * g.sh - g.ph, bx = ox * g.sw - g.pw;
+    const uint8_t* __restrict__ xn = x + (size_t)n * g.H * g.W * g.Cin + 4u * c4;
+    const uint8_t* __restrict__ wc = w + 4u * c4;
+    uint32_t acc[4] = {0, 0, 0, 0};
+    uint32_t sp[4] = {0, 0, 0, 0};
+    auto tap = [&](uint32_t xd, uint32_t wd) {
+      const uint32_t xs = xd ^ flip8;  // code + 128 for signed codes
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t a = (xd >> (8 * j)) & 0xffu, b = (wd >> (8 * j)) & 0xffu;
+        acc[j] += tab[a * 256u + b];
+        sp[j] += (xs >> (8 * j)) & 0xffu;
+      }
+    };
+    if constexpr (KS > 0) {
+      uint32_t xd[KS * KS], wd[KS * KS];
+#pragma unroll
+      for (int ky = 0; ky < KS; ++ky) {
+#pragma unroll
+        for (int kx = 0; kx < KS; ++kx) {
+          const int iy = by + ky * g.dh, ix = bx + kx * g.dw;
+          const bool inside = (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
+          xd[ky * KS + kx] = pad4;
+          if (inside) xd[ky * KS + kx] = *reinterpret_cast<const uint32_t*>(xn + ((size_t)iy * g.W + ix) * g.Cin);
+          wd[ky * KS + kx] = *reinterpret_cast<const uint32_t*>(wc + (size_t)(ky * KS + kx) * g.Cin);
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < KS * KS; ++t) tap(xd[t], wd[t]);
+    } else {
+      for (int ky = 0; ky < KH; ++ky) {
+        const int iy = by + ky * g.dh;
+        for (int kx = 0; kx < KW; ++kx) {
+          const int ix = bx + kx * g.dw;
+          const bool inside = (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
+          uint32_t xd = pad4;
+          if (inside) xd = *reinterpret_cast<const uint32_t*>(xn + ((size_t)iy * g.W + ix) * g.Cin);
+          tap(xd, *reinterpret_cast<const uint32_t*>(wc + (size_t)(ky * KW + kx) * g.Cin));
+        }
+      }
+    }
+    const int4 sf4 = *reinterpret_cast<const int4*>(&sfs[4u * c4]);
+    const int32_t sf[4] = {sf4.x, sf4.y, sf4.z, sf4.w};
+    int32_t av[4];
+    float yv[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      av[j] = (int32_t)(acc[j] - bias);
+      const long long corr = (long long)av[j] - (long long)qp.w_zp * ((int32_t)sp[j] - off128) -
+                             (long long)qp.x_zp * (sf[j] - off128) + kzz;
+      yv[j] = (float)corr * qp.scale;
+    }
+    const size_t o = (size_t)pix * g.Cout + 4u * c4;  // Cout == Cin
+    if (vec_out) {
+      if (acc_out) *reinterpret_cast<int4*>(acc_out + o) = make_int4(av[0], av[1], av[2], av[3]);
+      if (y_out) *reinterpret_cast<float4*>(y_out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (acc_out) acc_out[o + j] = av[j];
+        if (y_out) y_out[o + j] = yv[j];
+      }
+    }
+  }
+}
+
+bool dw_supported(const Geom& g, const uint8_t* x, const uint8_t* w, const uint16_t* lut) {
+  if (g.mult != 1 || g.Cin % 4 != 0 || g.Cin > kDwMaxC) return false;
+  if (((uintptr_t)x & 3) || ((uintptr_t)w & 3) || ((uintptr_t)lut & 15)) return false;
+  // staging the table costs every workgroup 128 KB of reads: not worth it for small layers
+  return (double)g.M * g.Cin * g.K >= 4.0e6;
+}
+
+hipError_t launch_dw(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
+                     int32_t* acc_out, float* y_out, hipStream_t s) {
+  const uint64_t items = (uint64_t)g.M * (g.Cin / 4);
+  const uint32_t blocks = (uint32_t)std::min<uint64_t>((uint64_t)cu_count(), (items + 1023) / 1024);
+  const int vec_out = ((((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
+  timing_begin(s);
+  if (g.KH == 3 && g.KW == 3)
+    hipLaunchKernelGGL(dw_kernel<3>, dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+  else if (g.KH == 5 && g.KW == 5)
+    hipLaunchKernelGGL(dw_kernel<5>, dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+  else
+    hipLaunchKernelGGL(dw_kernel<0>, dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+  timing_end(s);
+  return hipGetLastError();
 }
 
 hipError_t launch_direct(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w,

@@ -64,6 +64,13 @@ void timing_end(hipStream_t s);
 hipError_t launch_direct(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w,
                          const uint16_t* lut, int32_t* acc_out, float* y_out, hipStream_t s);
 
+// Depthwise kernel with the whole table in LDS (ax_direct.hip); dw_supported tells whether the
+// layer and its pointers fit it (channel multiplier 1, Cin a multiple of 4, aligned tensors,
+// enough work to pay for staging the table per workgroup).
+bool dw_supported(const Geom& g, const uint8_t* x, const uint8_t* w, const uint16_t* lut);
+hipError_t launch_dw(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
+                     int32_t* acc_out, float* y_out, hipStream_t s);
+
 // Table-tile kernels (ax_tab.hip).
 struct TabPlan {
   int variant;      // 2 or 3
@@ -79,6 +86,7 @@ struct TabPlan {
   size_t off_qd;  // QDev block
   size_t total;
 };
+int cu_count();  // compute units of the current device
 bool tab_supported(const Geom& g);
 int tab_num_tiles();
 TabPlan tab_plan(const Geom& g, const Options& o);

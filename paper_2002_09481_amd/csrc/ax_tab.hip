@@ -778,7 +778,7 @@ bool tab_supported(const Geom& g) {
   return (long long)g.M * chunks < (1LL << 31) && (long long)g.Cout * chunks < (1LL << 31);
 }
 
-static int cu_count() {
+int cu_count() {
   static int n = 0;
   if (n == 0) {
     int dev = 0;

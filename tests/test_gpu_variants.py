@@ -124,6 +124,42 @@ def test_depthwise_layers(case, signed):
     _check(x, w, lut, s, p, d, q, depthwise=True, what=str(case))
 
 
+DEPTHWISE_LDS = [
+    # large enough for the kernel that keeps the whole table in LDS (multiplier 1, Cin % 4 == 0)
+    (8, 56, 56, 64, 3, 3, 1, 1, 1, 1),
+    (4, 57, 55, 36, 3, 3, 1, 2, 1, 1),        # ragged everything, stride 2
+    (2, 64, 64, 32, 5, 5, 1, 1, 4, 2),        # 5x5, dilation 2
+    (16, 28, 28, 128, 3, 3, 1, 1, 0, 1),      # no padding
+]
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("signed", [False, True])
+@pytest.mark.parametrize("case", DEPTHWISE_LDS, ids=lambda c: "x".join(map(str, c)))
+def test_depthwise_layers_table_in_lds(case, signed, variant):
+    """variant 0 takes the LDS-table depthwise kernel for these sizes, variant 1 forces the
+    one-thread-per-output kernel; both must match the oracle."""
+    ax.ax_set_option("variant", variant)
+    N, H, W, Cin, KH, KW, mult, s, p, d = case
+    x, w, q = _operands((N, H, W, Cin, KH, KW, Cin * mult), 300 + Cin, signed, depthwise=True, mult=mult)
+    lut = I.lut_signed_random(17) if signed else I.lut_random(17)
+    _check(x, w, lut, s, p, d, q, depthwise=True, what=str(case))
+
+
+def test_depthwise_outputs_not_16_byte_aligned():
+    N, H, W, Cin = 8, 56, 56, 64
+    x, w, q = _operands((N, H, W, Cin, 3, 3, Cin), 9, False, depthwise=True)
+    lut = I.lut_random(19)
+    n_out = N * H * W * Cin
+    acc_buf = torch.zeros(n_out + 1, dtype=torch.int32, device="cuda")
+    y_buf = torch.zeros(n_out + 1, dtype=torch.float32, device="cuda")
+    acc, y = ax.ax_conv2d_ex(G.to_dev(x), G.to_dev(w), ax.lut_to_device(lut), 1, 1, q, depthwise=True,
+                             acc_out=acc_buf[1:], y_out=y_buf[1:])
+    torch.cuda.synchronize()
+    acc_ref, y_ref = oracle.conv2d_ex(x, w, lut, 1, 1, q, depthwise=True)
+    G.assert_parity(acc.cpu().numpy(), y.cpu().numpy(), acc_ref, y_ref, "unaligned outputs")
+
+
 def test_descriptor_with_defaults_is_the_plain_layer():
     layer = I.Layer("plain", 2, 16, 16, 32, 3, 3, 48, 1, 1, x_dist="relu", w_dist="normal")
     x, w, q = I.make_operands(layer, 3)
