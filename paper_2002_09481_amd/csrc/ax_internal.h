@@ -77,6 +77,8 @@ struct TabPlan {
   int tile;         // index of the tile configuration
   int G;            // workgroups of the main kernel
   int partials;     // partial tile pieces that grid produces (0: no fix-up pass)
+  int nti;          // tiles along the lane dimension
+  int ih;           // their height in lane elements (multiple of 64, nti * ih >= I)
   size_t off_rows;  // workspace offsets (bytes)
   size_t off_bpack;
   size_t off_bsum;

@@ -814,20 +814,49 @@ static int count_partials(int ntiles, int nch, int G) {
 //   - every segment a workgroup runs costs a fixed ~5 us (first tables, pipeline fill, stores);
 //   - a partial piece is written once and read once (~2.5 TB/s), and needs the fix-up launch;
 //   - grids larger than the machine run in rounds.
-struct PlanChoice { int tile, variant, G, partials; double cost; };
+//   - the lane dimension may be cut into more (lower) tiles than it needs, when that makes the
+//     tile count fill whole rounds of the machine.
+struct PlanChoice { int tile, variant, G, partials, nti, ih; double cost; };
+
+static PlanChoice plan_choice_nti(const Geom& g, int tile, int v, int forced_split, int nti);
 
 static PlanChoice plan_choice(const Geom& g, int tile, int v, int forced_split) {
   const TileCfg& tc = kTiles[tile];
   const long long I = (v == 2) ? g.M : g.Cout;
   const long long J = (v == 2) ? g.Cout : g.M;
   const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
-  const int nti = cdiv(I, kIT);
+  const int base = cdiv(I, kIT), ntj = cdiv(J, kJT);
+  PlanChoice best = plan_choice_nti(g, tile, v, forced_split, base);
+  if (forced_split > 0) return best;
+  const int per_cu = (tc.threads == 512 && tc.wpe == 4) ? 2 : 1;
+  const int slots = cu_count() * per_cu;
+  // the largest row-tile count whose tiles still fit r rounds, for the first r where that is more
+  // than the minimum (and the tiles stay at least 64 lane elements high)
+  for (int r = 1; r <= 64; ++r) {
+    const long long n = (long long)r * slots / ntj;
+    if (n <= base) continue;
+    if (n > cdiv(I, 64) || n > 2LL * base + 1) break;
+    const PlanChoice c = plan_choice_nti(g, tile, v, 0, (int)n);
+    if (c.cost < best.cost * 0.97) best = c;
+    break;
+  }
+  return best;
+}
+
+static PlanChoice plan_choice_nti(const Geom& g, int tile, int v, int forced_split, int nti_wanted) {
+  const TileCfg& tc = kTiles[tile];
+  const long long I = (v == 2) ? g.M : g.Cout;
+  const long long J = (v == 2) ? g.Cout : g.M;
+  const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
+  // balanced tile height (padding spread over all tiles, in steps of one wave), then as many
+  // tiles as that height needs (rounding the height up can free the last one)
+  const int ih = cdiv(cdiv(I, nti_wanted), 64) * 64;
+  const int nti = cdiv(I, ih);
   const int ntiles = nti * cdiv(J, kJT);
   const int nch = cdiv(g.K, kChunk);
   const long long total = (long long)ntiles * nch;
   const int per_cu = (tc.threads == 512 && tc.wpe == 4) ? 2 : 1;  // workgroups resident per compute unit
   const int slots = cu_count() * per_cu;
-  const int ih = cdiv(cdiv(I, nti), 64) * 64;
   // waves without real lanes skip the gathers, but tables, barriers and latencies stay: ~30 % of a
   // chunk's time does not shrink with the tile height
   const double t_chunk = 16.0 * (0.3 * kIT + 0.7 * ih) * kJT / (75e9 / per_cu);
@@ -840,7 +869,7 @@ static PlanChoice plan_choice(const Geom& g, int tile, int v, int forced_split) 
     *np_out = np;
     return rounds * (iters * t_chunk + segs * 5e-6) + np * t_piece + (np ? 8e-6 : 0.0);
   };
-  PlanChoice best{tile, v, ntiles, 0, 0.0};
+  PlanChoice best{tile, v, ntiles, 0, nti, ih, 0.0};
   if (forced_split > 0) {
     best.G = (int)std::max<long long>(1, std::min<long long>(std::min<long long>(total, 4LL * slots), (long long)ntiles * forced_split));
     best.cost = cost(best.G, &best.partials);
@@ -869,7 +898,7 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
     v = (fill(g.Cout) > fill(g.M) + 0.15) ? 3 : 2;
   }
   // Tile and grid: the forced tile, else the cheaper of the two 2048-lane tiles by the cost model.
-  PlanChoice best{0, 0, 0, 0, 1e30};
+  PlanChoice best{0, 0, 0, 0, 0, 0, 1e30};
   for (int tile = 0; tile < kNumTiles; ++tile) {
     if (g_opt.tile >= 1 ? tile != g_opt.tile - 1 : (tile != 2 && tile != 4)) continue;
     const PlanChoice c = plan_choice(g, tile, v, o.split_k);
@@ -879,6 +908,8 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   p.tile = best.tile;
   p.G = best.G;
   p.partials = best.partials;
+  p.nti = best.nti;
+  p.ih = best.ih;
   const TileCfg& tc = kTiles[best.tile];
   const int G = best.G;
   const long long I = (v == 2) ? g.M : g.Cout;
@@ -953,7 +984,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   ConvView cv{x, g.H, g.W, g.Cin, g.KW, g.sh, g.sw, g.ph, g.pw, g.OH, g.OW, g.M, g.K, qp.pad_code, qp.dq,
               g.dh, g.dw, g.sgn ? 0x80u : 0u};
 
-  const int ntiles = cdiv(I, kIT) * cdiv(J, kJT);
+  const int ntiles = p.nti * cdiv(J, kJT);
   // Column sums are produced per segment of rows so that more than Jpad/64 blocks share the work.
   const int krows = Kp + 1;
   const int nseg = std::max(1, std::min(kMaxSeg, cdiv(krows, 64)));
@@ -996,8 +1027,8 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.K = g.K;
   a.ntj = cdiv(J, kJT);
   a.nch = nchunks;
-  a.ih = cdiv(cdiv(I, cdiv(I, kIT)), 64) * 64;  // balanced tile height: padding spread over all tiles
-  a.total_iters = (long long)cdiv(I, kIT) * a.ntj * nchunks;
+  a.ih = p.ih;
+  a.total_iters = (long long)p.nti * a.ntj * nchunks;
   a.qd = qd;
   a.bias_k = g.sgn ? 32768u * (uint32_t)g.K : 0u;
   a.acc_out = acc_out; a.y_out = y_out;
