@@ -202,6 +202,8 @@ int ax_version(void);
  *   "tile"     0 = choose the table-tile configuration automatically (default), n >= 1 =
  *              force configuration n (threads, lane elements per thread, table groups,
  *              taps per barrier)
+ *   "row_tiles" 0 = choose automatically how many tiles the lane dimension is cut into (default),
+ *              1 = as few as fit, n >= 2 = n tiles (clamped to what the layer allows)
  *   "timing"   1 = record a HIP event pair around the main kernel of every layer call on
  *              the call's stream (see ax_last_kernel_ms); 0 = off (default)
  * Returns AX_OK or AX_ERR_OPTION.  Not thread safe with respect to concurrent calls.

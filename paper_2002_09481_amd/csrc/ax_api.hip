@@ -6,7 +6,7 @@
 
 namespace ax {
 
-Options g_opt = {0, 0, 0, 0};
+Options g_opt = {0, 0, 0, 0, 0};
 
 static hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
 static bool g_ev_valid = false;
@@ -111,7 +111,7 @@ size_t layer_workspace(const Geom& g) {
   if (!tab_supported(g)) return 256;
   size_t need = 256;
   for (int v = 2; v <= 3; ++v) {
-    Options o = {v, g_opt.split_k, g_opt.tile, 0};
+    Options o = {v, g_opt.split_k, g_opt.tile, 0, g_opt.row_tiles};
     const size_t t = tab_plan(g, o).total;
     if (t > need) need = t;
   }
@@ -211,6 +211,11 @@ extern "C" int ax_set_option(const char* name, int value) {
     g_opt.tile = value;
     return AX_OK;
   }
+  if (!std::strcmp(name, "row_tiles")) {
+    if (value < 0 || value > (1 << 20)) return AX_ERR_OPTION;
+    g_opt.row_tiles = value;
+    return AX_OK;
+  }
   if (!std::strcmp(name, "timing")) {
     if (value < 0 || value > 1) return AX_ERR_OPTION;
     g_opt.timing = value;
@@ -226,6 +231,7 @@ extern "C" int ax_get_option(const char* name, int* value) {
   if (!std::strcmp(name, "split_k")) { *value = g_opt.split_k; return AX_OK; }
   if (!std::strcmp(name, "tile")) { *value = g_opt.tile; return AX_OK; }
   if (!std::strcmp(name, "timing")) { *value = g_opt.timing; return AX_OK; }
+  if (!std::strcmp(name, "row_tiles")) { *value = g_opt.row_tiles; return AX_OK; }
   return AX_ERR_OPTION;
 }
 

@@ -53,6 +53,7 @@ struct Options {
   int split_k;  // 0 auto
   int tile;     // index of the table-tile configuration (0 = default)
   int timing;   // 1: bracket the main kernel of every call with HIP events
+  int row_tiles;  // 0 auto, 1 as few tiles along the lane dimension as fit, n that many (clamped)
 };
 extern Options g_opt;
 

@@ -820,12 +820,14 @@ struct PlanChoice { int tile, variant, G, partials, nti, ih; double cost; };
 
 static PlanChoice plan_choice_nti(const Geom& g, int tile, int v, int forced_split, int nti);
 
-static PlanChoice plan_choice(const Geom& g, int tile, int v, int forced_split) {
+static PlanChoice plan_choice(const Geom& g, int tile, int v, int forced_split, int forced_rows) {
   const TileCfg& tc = kTiles[tile];
   const long long I = (v == 2) ? g.M : g.Cout;
   const long long J = (v == 2) ? g.Cout : g.M;
   const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
   const int base = cdiv(I, kIT), ntj = cdiv(J, kJT);
+  if (forced_rows > 0)
+    return plan_choice_nti(g, tile, v, forced_split, std::max(base, std::min(forced_rows, cdiv(I, 64))));
   PlanChoice best = plan_choice_nti(g, tile, v, forced_split, base);
   if (forced_split > 0) return best;
   const int per_cu = (tc.threads == 512 && tc.wpe == 4) ? 2 : 1;
@@ -901,7 +903,7 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   PlanChoice best{0, 0, 0, 0, 0, 0, 1e30};
   for (int tile = 0; tile < kNumTiles; ++tile) {
     if (g_opt.tile >= 1 ? tile != g_opt.tile - 1 : (tile != 2 && tile != 4)) continue;
-    const PlanChoice c = plan_choice(g, tile, v, o.split_k);
+    const PlanChoice c = plan_choice(g, tile, v, o.split_k, o.row_tiles);
     if (c.cost < best.cost) best = c;
   }
   p.variant = best.variant;

@@ -22,6 +22,7 @@ def _reset_options():
     ax.ax_set_option("variant", 0)
     ax.ax_set_option("split_k", 0)
     ax.ax_set_option("tile", 0)
+    ax.ax_set_option("row_tiles", 0)
 
 
 def L(N, H, W, Cin, KH, KW, Cout, s=1, p=0, dense=False, x_dist="uniform", w_dist="uniform", name=None):
@@ -79,6 +80,20 @@ def test_forced_k_slices(variant, split_k):
     ax.ax_set_option("split_k", split_k)
     G.check_layer(L(1, 14, 14, 64, 3, 3, 72, 1, 1, x_dist="relu", w_dist="normal"), 5, I.lut_random_error(3))
     G.check_layer(L(40, 1, 1, 1000, 1, 1, 130, dense=True), 6, I.lut_truncated(6))
+
+
+@pytest.mark.parametrize("variant", [2, 3])
+@pytest.mark.parametrize("rows", [1, 2, 3, 5, 40, 100000])
+def test_forced_row_tile_counts(variant, rows):
+    """The lane dimension cut into more (lower) tiles than it needs, incl. counts that leave the
+    last tile nearly empty and counts beyond what the layer allows (clamped)."""
+    ax.ax_set_option("variant", variant)
+    ax.ax_set_option("row_tiles", rows)
+    lut = I.lut_random(23)
+    G.check_layer(L(2, 50, 47, 32, 3, 3, 72, 1, 1), 41, lut)           # 4700 pixels: 3 tiles at least
+    G.check_layer(L(1, 20, 20, 48, 1, 1, 30, 2, 0), 42, lut)
+    ax.ax_set_option("split_k", 2)
+    G.check_layer(L(1, 64, 64, 64, 3, 3, 40, 1, 1), 43, lut)
 
 
 TILES = list(range(1, 8))

@@ -23,6 +23,7 @@ def _reset_options():
     ax.ax_set_option("variant", 0)
     ax.ax_set_option("split_k", 0)
     ax.ax_set_option("tile", 0)
+    ax.ax_set_option("row_tiles", 0)
 
 
 def _data(n, seed, kind="normal"):

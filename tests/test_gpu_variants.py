@@ -21,6 +21,7 @@ def _reset_options():
     ax.ax_set_option("variant", 0)
     ax.ax_set_option("split_k", 0)
     ax.ax_set_option("tile", 0)
+    ax.ax_set_option("row_tiles", 0)
 
 
 def _operands(shape, seed, signed, depthwise=False, mult=1):
