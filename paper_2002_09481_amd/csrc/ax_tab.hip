@@ -266,12 +266,22 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     }
   }
   __syncthreads();
-  // codes of the phases that follow: tv[u][ph] belongs to taps k0 + (ph+1)*KS ...
-  uint2 tv_cur[CODES][PHASES], tv_nxt[CODES][PHASES];
-#pragma unroll
-  for (int u = 0; u < CODES; ++u)
-#pragma unroll
-    for (int ph = 0; ph < PHASES; ++ph) tv_nxt[u][ph] = load_codes(u, kbeg + (ph + 1) * KS);
+  // Codes of the phases that follow: tv_cur[u][ph] belongs to taps k0 + (ph+1)*KS ...  They are
+  // fetched a whole chunk ahead by a vector load in which lane li = u * PHASES + ph reads the
+  // eight codes of (unit pair u, phase ph), and handed to the scalar side with readlane at the
+  // start of the chunk that uses them: by then the load has long returned, so nothing waits for
+  // memory (a uniform load followed at once by readfirstlane would stall every chunk).
+  uint2 tv_cur[CODES][PHASES];
+  const int li = min(lane, CODES * PHASES - 1);
+  const int l_ph = li % PHASES;
+  const int l_q = wave * UNITS + 2 * (li / PHASES);
+  const int l_qq = l_q < HALVES ? l_q : 0;
+  const size_t l_col = (size_t)j0 + 8 * ((l_qq >> 1) % NG);
+  const int l_s = l_qq / (2 * NG);
+  auto fetch_codes = [&](int kfirst) {  // phases starting at taps kfirst, kfirst + KS, ...
+    return *reinterpret_cast<const uint2*>(a.Bp + (size_t)min(kfirst + l_ph * KS + l_s, klast) * a.Jpad + l_col);
+  };
+  uint2 tvv = fetch_codes(kbeg + KS);
 
   for (int c = 0; c < nchunks; ++c) {
     const int k0 = kbeg + c * kChunk;
@@ -280,13 +290,12 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
 #pragma unroll
     for (int u = 0; u < CODES; ++u)
 #pragma unroll
-      for (int ph = 0; ph < PHASES; ++ph) tv_cur[u][ph] = tv_nxt[u][ph];
+      for (int ph = 0; ph < PHASES; ++ph)
+        tv_cur[u][ph] = make_uint2((uint32_t)__builtin_amdgcn_readlane((int)tvv.x, u * PHASES + ph),
+                                   (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, u * PHASES + ph));
     if (c + 1 < nchunks) {
       load_chunk(k0 + kChunk, xn);
-#pragma unroll
-      for (int u = 0; u < CODES; ++u)
-#pragma unroll
-        for (int ph = 0; ph < PHASES; ++ph) tv_nxt[u][ph] = load_codes(u, k0 + kChunk + (ph + 1) * KS);
+      tvv = fetch_codes(k0 + kChunk + KS);
     }
 #pragma unroll
     for (int p = 0; p < P; ++p) {
