@@ -293,10 +293,6 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
       for (int ph = 0; ph < PHASES; ++ph)
         tv_cur[u][ph] = make_uint2((uint32_t)__builtin_amdgcn_readlane((int)tvv.x, u * PHASES + ph),
                                    (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, u * PHASES + ph));
-    if (c + 1 < nchunks) {
-      load_chunk(k0 + kChunk, xn);
-      tvv = fetch_codes(k0 + kChunk + KS);
-    }
 #pragma unroll
     for (int p = 0; p < P; ++p) {
       sl[p] = __builtin_amdgcn_sad_u8(xa[p].x, 0u, sl[p]);
@@ -326,6 +322,15 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
 #pragma unroll
         for (int u = 0; u < UNITS; ++u)
           if (q == u * (SEGS / UNITS)) build_issue(u, tv_cur[u >> 1][ph]);
+        if (ph == 0 && q == 0) {
+          // operand and codes of the next chunk: fetched behind the first row fetches of this
+          // chunk, so that the wait for those rows does not also wait for these
+          __builtin_amdgcn_sched_barrier(0);
+          if (c + 1 < nchunks) {
+            load_chunk(k0 + kChunk, xn);
+            tvv = fetch_codes(k0 + kChunk + KS);
+          }
+        }
         __builtin_amdgcn_sched_barrier(0);
         if (act[p]) {
           uint4 ring[DEPTH + 1];
