@@ -226,8 +226,8 @@ def ax_conv2d(x, w, lut, stride, pad, q, acc_out=None, y_out=None, workspace=Non
     for o in (acc_out, y_out):
         if o is not False and o.numel() != N * OH * OW * Cout:
             raise ValueError("output tensor has the wrong number of elements")
-    need = int(L.ax_conv2d_workspace_bytes(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw))
-    if workspace is None:
+    if workspace is None:  # (a workspace handed in is checked by the C call itself)
+        need = int(L.ax_conv2d_workspace_bytes(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw))
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     _dev(workspace, torch.uint8, "workspace")
     qs = _quant(q)
@@ -260,8 +260,8 @@ def ax_dense(x, w, lut, q, acc_out=None, y_out=None, workspace=None, stream=None
         _dev(acc_out, torch.int32, "acc_out")
     if y_out is not False:
         _dev(y_out, torch.float32, "y_out")
-    need = int(L.ax_dense_workspace_bytes(M, K, N))
     if workspace is None:
+        need = int(L.ax_dense_workspace_bytes(M, K, N))
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     _dev(workspace, torch.uint8, "workspace")
     qs = _quant(q)

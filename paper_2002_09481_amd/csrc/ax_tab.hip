@@ -24,6 +24,9 @@
 // combined by a small fix-up kernel (integer addition is associative: same bits).
 #include <algorithm>
 #include <cmath>
+#include <cstring>
+#include <map>
+#include <mutex>
 #include <vector>
 
 #include "ax_internal.h"
@@ -905,7 +908,30 @@ static PlanChoice plan_choice_nti(const Geom& g, int tile, int v, int forced_spl
   return best;
 }
 
+static TabPlan tab_plan_uncached(const Geom& g, const Options& o);
+
+// Planning walks over candidate grids and counts their partial pieces, which takes tens of
+// microseconds: as much as a small layer's kernels.  Plans are therefore remembered per
+// (geometry, options); the table is small and cleared when it grows past a bound.
 TabPlan tab_plan(const Geom& g, const Options& o) {
+  struct Key {
+    int v[20];
+    bool operator<(const Key& other) const { return std::memcmp(v, other.v, sizeof(v)) < 0; }
+  };
+  static std::mutex mu;
+  static std::map<Key, TabPlan> cache;
+  const Key k{{g.N, g.H, g.W, g.Cin, g.KH, g.KW, g.Cout, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.sgn, g.mult, o.variant,
+               o.split_k, o.tile, o.row_tiles, cu_count()}};
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = cache.find(k);
+  if (it != cache.end()) return it->second;
+  if (cache.size() > 4096) cache.clear();
+  const TabPlan p = tab_plan_uncached(g, o);
+  cache.emplace(k, p);
+  return p;
+}
+
+static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   TabPlan p{};
   // Lane assignment: pixels on the lanes unless channels fill the lane tiles clearly better.
   int v = o.variant;
@@ -916,7 +942,7 @@ TabPlan tab_plan(const Geom& g, const Options& o) {
   // Tile and grid: the forced tile, else the cheaper of the two 2048-lane tiles by the cost model.
   PlanChoice best{0, 0, 0, 0, 0, 0, 1e30};
   for (int tile = 0; tile < kNumTiles; ++tile) {
-    if (g_opt.tile >= 1 ? tile != g_opt.tile - 1 : (tile != 2 && tile != 4)) continue;
+    if (o.tile >= 1 ? tile != o.tile - 1 : (tile != 2 && tile != 4)) continue;
     const PlanChoice c = plan_choice(g, tile, v, o.split_k, o.row_tiles);
     if (c.cost < best.cost) best = c;
   }
