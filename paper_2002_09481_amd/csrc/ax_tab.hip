@@ -391,6 +391,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     int32_t* lsum = a.lsum + (size_t)slot * IT;
 #pragma unroll
     for (int p = 0; p < P; ++p) {
+      if (!act[p]) continue;  // rows of tile padding: the fix-up never reads them
       const int il = p * THREADS + tid;
       lsum[il] = (int32_t)sl[p];
 #pragma unroll
