@@ -879,8 +879,9 @@ static PlanChoice plan_choice_nti(const Geom& g, int tile, int v, int forced_spl
   const int slots = cu_count() * per_cu;
   // waves without real lanes skip the gathers, but tables, barriers and latencies stay: ~30 % of a
   // chunk's time does not shrink with the tile height
-  const double t_chunk = 16.0 * (0.3 * kIT + 0.7 * ih) * kJT / (75e9 / per_cu);
-  const double t_piece = 2.0 * kIT * kJT * 4.0 / 2.5e12;
+  const double rate = (tc.NG >= 4 ? 80e9 : 75e9) / per_cu;  // wider tiles spend less on gather addresses
+  const double t_chunk = 16.0 * (0.3 * kIT + 0.7 * ih) * kJT / rate;
+  const double t_piece = 2.0 * kIT * kJT * 4.0 / 6.0e12;
   auto cost = [&](int Gc, int* np_out) {
     const double rounds = std::ceil((double)Gc / slots);
     const double iters = std::ceil((double)total / Gc);
