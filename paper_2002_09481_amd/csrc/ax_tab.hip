@@ -313,7 +313,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     constexpr int SEGS = P * SUB;
     constexpr int TAPS = KS / SUB;  // taps per segment
     constexpr int NR = TAPS * NG;   // gathers per segment
-    constexpr int DEPTH = 3;
+    constexpr int DEPTH = (P * JT > 32) ? 2 : 3;  // fewer ring slots where the accumulators crowd the registers
     static_assert(KS % SUB == 0 && SEGS % UNITS == 0, "build units must align with segments");
     const uint32_t sel_hi = 0x00010000u;  // selector of the high half
 #pragma unroll
