@@ -286,6 +286,23 @@ def main():
         ms = time_calls(fns, 3)
         m4 = sum(l.macs for l in l4) * 64
         extra["config4_lut_sweep_64_tables"] = {"ms": ms, "lut_macs_per_s": m4 / ms * 1e3, "tables_per_s": 64 / ms * 1e3}
+        # the same sweep through ax_conv2d_multi_lut: one call per layer for all 64 tables (operands
+        # prepared once, the tiles of all tables share one grid)
+        luts_all = torch.stack(luts)
+        mcalls = []
+        for i, l in enumerate(l4):
+            x, w, q = I.make_operands(l, I.layer_seed(4, i))
+            xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
+            acc = torch.empty((64, l.N, l.OH, l.OW, l.Cout), dtype=torch.int32, device=dev)
+            y = torch.empty(acc.shape, dtype=torch.float32, device=dev)
+            ws = torch.empty(ax.ax_conv2d_multi_lut_workspace_bytes(x.shape, w.shape, 64, l.stride, l.pad),
+                             dtype=torch.uint8, device=dev)
+            mcalls.append(lambda xd=xd, wd=wd, q=q, acc=acc, y=y, ws=ws, l=l: ax.ax_conv2d_multi_lut(
+                xd, wd, luts_all, l.stride, l.pad, q, acc, y, ws))
+        ms = time_calls(mcalls, 3)
+        extra["config4_lut_sweep_64_tables_one_call_per_layer"] = {"ms": ms, "lut_macs_per_s": m4 / ms * 1e3,
+                                                                   "tables_per_s": 64 / ms * 1e3}
+        del mcalls
         # config 5: GEMM-shaped layers, truncated table
         l5 = I.config_gemm_shaped()
         ms = time_calls([make_call(l, I.layer_seed(5, i), lut_d) for i, l in enumerate(l5)], 20)

@@ -122,6 +122,23 @@ int ax_conv2d_ex(const ax_conv_desc_t* desc, const void* x, const void* w, const
                  size_t workspace_bytes, void* hip_stream);
 size_t ax_conv2d_ex_workspace_bytes(const ax_conv_desc_t* desc);
 
+/*
+ * One layer against several multiplier tables in one call: the use the paper builds the
+ * emulator for is evaluating many candidate approximate multipliers on the same network
+ * (Sec. I, Sec. IV).  luts holds num_luts (1 .. 65536) tables of 65536 entries back to back;
+ * acc_out / y_out hold num_luts result tensors back to back ([num_luts][N, OH, OW, Cout]),
+ * each exactly what ax_conv2d gives for that table.  The operands are prepared once, and the
+ * tiles of all tables form one pool of work, so that the machine is filled without cutting
+ * output tiles along K.
+ */
+int ax_conv2d_multi_lut(const uint8_t* x, int N, int H, int W, int Cin, const uint8_t* w, int KH,
+                        int KW, int Cout, const uint16_t* luts, int num_luts, int stride_h,
+                        int stride_w, int pad_h, int pad_w, const ax_quant_t* q, int32_t* acc_out,
+                        float* y_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t ax_conv2d_multi_lut_workspace_bytes(int N, int H, int W, int Cin, int KH, int KW, int Cout,
+                                           int num_luts, int stride_h, int stride_w, int pad_h,
+                                           int pad_w);
+
 /* ---- float-in / float-out form of the layer (Sec. III: the approximate layer reads two
  * float tensors plus the range of each and returns a float tensor; Algorithm 1: ComputeCoeffs,
  * quantization, lookup-MAC, dequantization) ------------------------------------------------

@@ -40,6 +40,7 @@ EXPORTS = [
     "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_last_kernel_ms", "ax_conv2d_plan",
     "ax_range_f32", "ax_range_workspace_bytes", "ax_quantize_f32", "ax_conv2d_f32", "ax_conv2d_f32_workspace_bytes",
     "ax_dense_f32", "ax_dense_f32_workspace_bytes", "ax_conv2d_ex", "ax_conv2d_ex_workspace_bytes",
+    "ax_conv2d_multi_lut", "ax_conv2d_multi_lut_workspace_bytes",
 ]
 
 
@@ -91,6 +92,11 @@ def lib():
     L.ax_last_kernel_ms.restype = ci
     L.ax_probe_copy.argtypes = [vp, vp, sz, vp]
     L.ax_probe_copy.restype = ci
+    L.ax_conv2d_multi_lut.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci,
+                                      ctypes.POINTER(ax_quant_t), vp, vp, vp, sz, vp]
+    L.ax_conv2d_multi_lut.restype = ci
+    L.ax_conv2d_multi_lut_workspace_bytes.argtypes = [ci] * 12
+    L.ax_conv2d_multi_lut_workspace_bytes.restype = sz
     L.ax_conv2d_ex.argtypes = [ctypes.POINTER(ax_conv_desc_t), vp, vp, vp, ctypes.POINTER(ax_quant_t), vp, vp, vp, sz, vp]
     L.ax_conv2d_ex.restype = ci
     L.ax_conv2d_ex_workspace_bytes.argtypes = [ctypes.POINTER(ax_conv_desc_t)]
@@ -268,6 +274,50 @@ def ax_dense(x, w, lut, q, acc_out=None, y_out=None, workspace=None, stream=None
     rc = L.ax_dense(_ptr(x), M, K, _ptr(w), N, _ptr(lut), ctypes.byref(qs),
                     _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
                     _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    _check(rc)
+    return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
+def ax_conv2d_multi_lut_workspace_bytes(x_shape, w_shape, num_luts, stride=1, pad=0) -> int:
+    N, H, W, Cin = [int(v) for v in x_shape]
+    KH, KW, _, Cout = [int(v) for v in w_shape]
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    return int(lib().ax_conv2d_multi_lut_workspace_bytes(N, H, W, Cin, KH, KW, Cout, int(num_luts), sh, sw, ph, pw))
+
+
+def ax_conv2d_multi_lut(x, w, luts, stride, pad, q, acc_out=None, y_out=None, workspace=None, stream=None):
+    """One layer against T tables.  luts: 16-bit integer CUDA tensor [T, 65536]; outputs
+    [T, N, OH, OW, Cout].  Returns (acc_out, y_out); pass False to skip one of them."""
+    L = lib()
+    _dev(x, torch.uint8, "x")
+    _dev(w, torch.uint8, "w")
+    if luts.dtype not in (torch.int16, torch.uint16):
+        raise TypeError("luts must be a 16-bit integer tensor")
+    _dev(luts, luts.dtype, "luts")
+    if luts.dim() != 2 or luts.shape[1] != 65536:
+        raise ValueError("luts must be [T, 65536]")
+    T = int(luts.shape[0])
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
+        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout]")
+    N, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    OH = (H + 2 * ph - KH) // sh + 1
+    OW = (W + 2 * pw - KW) // sw + 1
+    if OH <= 0 or OW <= 0:
+        _check(-2)
+    acc_out, y_out = _outs((T, N, OH, OW, Cout), x.device, acc_out, y_out)
+    if workspace is None:
+        need = int(L.ax_conv2d_multi_lut_workspace_bytes(N, H, W, Cin, KH, KW, Cout, T, sh, sw, ph, pw))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    qs = _quant(q)
+    rc = L.ax_conv2d_multi_lut(_ptr(x), N, H, W, Cin, _ptr(w), KH, KW, Cout, _ptr(luts), T, sh, sw, ph, pw,
+                               ctypes.byref(qs), _ptr(None if acc_out is False else acc_out),
+                               _ptr(None if y_out is False else y_out), _ptr(workspace), workspace.numel(),
+                               ctypes.c_void_p(_stream_ptr(stream)))
     _check(rc)
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
 

@@ -64,7 +64,7 @@ int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, in
   const long long M = (long long)N * OH * OW;
   const long long wsize = (long long)KH * KW * Cin * (depthwise ? mult : Cout);
   if ((long long)N * H * W * Cin > lim || wsize > lim || M > lim || M * Cout > lim) return AX_ERR_SHAPE;
-  *g = Geom{N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, (int)OH, (int)OW, (int)M, (int)K, dh, dw, sgn ? 1 : 0, mult};
+  *g = Geom{N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, (int)OH, (int)OW, (int)M, (int)K, dh, dw, sgn ? 1 : 0, mult, 1};
   return AX_OK;
 }
 
@@ -82,10 +82,16 @@ int run_layer(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t*
               int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, hipStream_t s) {
   const int v = choose_variant(g);
   hipError_t e;
-  if (v == 1 && g.mult && g_opt.variant != 1 && dw_supported(g, x, w, lut)) {
-    e = launch_dw(g, qp, x, w, lut, acc_out, y_out, s);
-  } else if (v == 1) {
-    e = launch_direct(g, qp, x, w, lut, acc_out, y_out, s);
+  if (v == 1) {  // kernels that take one table at a time
+    e = hipSuccess;
+    const bool dw = g.mult && g_opt.variant != 1 && dw_supported(g, x, w, lut);
+    const size_t per_table = (size_t)g.M * g.Cout;
+    for (int t = 0; t < g.T && e == hipSuccess; ++t) {
+      const uint16_t* lt = lut + (size_t)t * 65536;
+      int32_t* at = acc_out ? acc_out + t * per_table : nullptr;
+      float* yt = y_out ? y_out + t * per_table : nullptr;
+      e = dw ? launch_dw(g, qp, x, w, lt, at, yt, s) : launch_direct(g, qp, x, w, lt, at, yt, s);
+    }
   } else {
     Options o = g_opt;
     o.variant = v;
@@ -159,6 +165,28 @@ extern "C" int ax_conv2d_ex(const ax_conv_desc_t* desc, const void* x, const voi
 extern "C" size_t ax_conv2d_ex_workspace_bytes(const ax_conv_desc_t* desc) {
   Geom g;
   if (geom_of(desc, &g)) return 0;
+  return layer_workspace(g);
+}
+
+extern "C" int ax_conv2d_multi_lut(const uint8_t* x, int N, int H, int W, int Cin, const uint8_t* w, int KH, int KW,
+                                   int Cout, const uint16_t* luts, int num_luts, int stride_h, int stride_w,
+                                   int pad_h, int pad_w, const ax_quant_t* q, int32_t* acc_out, float* y_out,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Geom g;
+  int rc = make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g);
+  if (rc) return rc;
+  if (num_luts < 1 || num_luts > 65536) return AX_ERR_SHAPE;
+  g.T = num_luts;
+  return run(g, q, x, w, luts, acc_out, y_out, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t ax_conv2d_multi_lut_workspace_bytes(int N, int H, int W, int Cin, int KH, int KW, int Cout,
+                                                      int num_luts, int stride_h, int stride_w, int pad_h,
+                                                      int pad_w) {
+  Geom g;
+  if (make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g)) return 0;
+  if (num_luts < 1 || num_luts > 65536) return 0;
+  g.T = num_luts;
   return layer_workspace(g);
 }
 

@@ -21,6 +21,7 @@ struct Geom {
   int dh, dw;  // dilation (>= 1)
   int sgn;     // 1: codes are int8, table entries int16, addressed by the two's-complement patterns
   int mult;    // 0: ordinary convolution; >= 1: depthwise with this channel multiplier (Cout = Cin*mult)
+  int T;       // multiplier tables evaluated by the call (1 except for ax_conv2d_multi_lut)
 };
 
 // Quantization coefficients kept in device memory (written by the quantization kernels of the

@@ -73,7 +73,8 @@ struct TabArgs {
   int32_t* part;  // [2*G][IT*JT] partial tiles: slot 2w = workgroup w's piece of a tile begun by
                   // another workgroup, slot 2w+1 = its piece of a tile it begins but does not end
   int32_t* lsum;  // [2*G][IT] lane-operand sums of the same pieces
-  long long out_elems;
+  long long out_elems;   // outputs per table (M * Cout)
+  int ntiles1;           // tiles of one table; tile index space = table * ntiles1 + tile (several tables: ax_conv2d_multi_lut)
   int vec_out;  // outputs may be written in aligned 16-byte pieces along j
 };
 
@@ -148,8 +149,13 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   __shared__ long long cterm[JT];  // column constants of the current tile, see the epilogue
 
   while (it_beg < it_end) {
-  const int tile = (int)(it_beg / a.nch);
-  const int c_beg = (int)(it_beg - (long long)tile * a.nch);
+  const int gtile = (int)(it_beg / a.nch);
+  const int c_beg = (int)(it_beg - (long long)gtile * a.nch);
+  const int tbl = gtile / a.ntiles1;  // which multiplier table
+  const int tile = gtile - tbl * a.ntiles1;
+  const uint16_t* __restrict__ rows = a.rows + (size_t)tbl * 65536;
+  int32_t* __restrict__ acc_base = a.acc_out ? a.acc_out + (size_t)tbl * a.out_elems : nullptr;
+  float* __restrict__ y_base = a.y_out ? a.y_out + (size_t)tbl * a.out_elems : nullptr;
   const int c_end = (int)min((long long)a.nch, c_beg + (it_end - it_beg));
   const bool whole = (c_beg == 0) && (c_end == a.nch);
   const int ti = tile / a.ntj;
@@ -196,7 +202,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   // loads whose scalar offset selects the row (code * 512 bytes) and whose per-lane offset
   // selects dword `lane` (+64 for the second half): 256 contiguous bytes per wave.
   const __amdgpu_buffer_rsrc_t rows_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.rows), 0, 131072, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(rows), 0, 131072, 0x00020000);
   int us[UNITS], ug[UNITS], uh[UNITS];
   bool uvalid[UNITS];
 #pragma unroll
@@ -381,7 +387,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   // corr = acc - z_tab*Sl - z_lane*Sb[j] + K*z_lane*z_tab.  Each of the four terms is below
   // 2^31 in magnitude; for K <= 16384 so is every partial sum, and 32-bit wrap-around
   // arithmetic is exact.  Longer K takes the 64-bit form.
-  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0] + a.bias_k;
+  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)rows[0] + a.bias_k;
   const bool finish = whole;  // this workgroup writes the tile's outputs
   if (!whole) {
     // Piece of a tile that several workgroups share: stored column-major ([column][lane
@@ -452,14 +458,14 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
             const uint32_t lterm = z_tab * stage[r * ROW + JT];
             v.x -= padfix; v.y -= padfix; v.z -= padfix; v.w -= padfix;
             const size_t o = (size_t)i * a.J + j;
-            if (a.acc_out) *reinterpret_cast<uint4*>(a.acc_out + o) = v;
-            if (a.y_out) {
+            if (acc_base) *reinterpret_cast<uint4*>(acc_base + o) = v;
+            if (y_base) {
               float4 y;
               y.x = dequant(v.x, lterm, 4 * c4);
               y.y = dequant(v.y, lterm, 4 * c4 + 1);
               y.z = dequant(v.z, lterm, 4 * c4 + 2);
               y.w = dequant(v.w, lterm, 4 * c4 + 3);
-              *reinterpret_cast<float4*>(a.y_out + o) = y;
+              *reinterpret_cast<float4*>(y_base + o) = y;
             }
           }
         }
@@ -475,8 +481,8 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
       for (int j = 0; j < JT; ++j) {
         if (j0 + j < a.J) {
           const size_t o = CH ? (size_t)(j0 + j) * a.I + i : (size_t)i * a.J + (j0 + j);
-          if (a.acc_out) a.acc_out[o] = (int32_t)(acc[p][j] - padfix);
-          if (a.y_out) a.y_out[o] = dequant(acc[p][j] - padfix, lterm, j);
+          if (acc_base) acc_base[o] = (int32_t)(acc[p][j] - padfix);
+          if (y_base) y_base[o] = dequant(acc[p][j] - padfix, lterm, j);
         }
       }
     }
@@ -494,9 +500,9 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
 template <int IT, int JT, bool CH>
 __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) {
   constexpr int CPT = JT / 4;  // columns per thread
-  const int tile = blockIdx.x / (IT / 64);
-  const int il0 = (blockIdx.x - tile * (IT / 64)) * 64;
-  const long long t_beg = (long long)tile * a.nch, t_last = t_beg + a.nch - 1;
+  const int gtile = blockIdx.x / (IT / 64);
+  const int il0 = (blockIdx.x - gtile * (IT / 64)) * 64;
+  const long long t_beg = (long long)gtile * a.nch, t_last = t_beg + a.nch - 1;
   auto owner = [&](long long it) {  // the workgroup w with w*total/G <= it < (w+1)*total/G
     long long w = it * G / a.total_iters;
     while ((w + 1) * a.total_iters / G <= it) ++w;
@@ -505,11 +511,16 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
   };
   const int w_first = owner(t_beg), w_last = owner(t_last);
   if (w_first == w_last) return;  // finished inside tab_kernel
+  const int tbl = gtile / a.ntiles1;
+  const int tile = gtile - tbl * a.ntiles1;
+  const uint16_t* __restrict__ rows = a.rows + (size_t)tbl * 65536;
+  int32_t* __restrict__ acc_base = a.acc_out ? a.acc_out + (size_t)tbl * a.out_elems : nullptr;
+  float* __restrict__ y_base = a.y_out ? a.y_out + (size_t)tbl * a.out_elems : nullptr;
   const int ti = tile / a.ntj;
   const int i0 = ti * a.ih, j0 = (tile - ti * a.ntj) * JT;
   if (il0 >= a.ih || i0 + il0 >= a.I) return;
   const int klast = a.nch * kChunk;
-  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)a.rows[0] + a.bias_k;  // see tab_kernel
+  const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)rows[0] + a.bias_k;  // see tab_kernel
   __shared__ long long cterm[JT];
   __shared__ uint32_t patch[64][JT + 4];
   __shared__ uint32_t lterm_s[64];
@@ -542,8 +553,8 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
         const int jl = cg * CPT + c;
         if (j0 + jl < a.J) {
           const size_t o = (size_t)(j0 + jl) * a.I + i;
-          if (a.acc_out) a.acc_out[o] = (int32_t)v[c];
-          if (a.y_out) a.y_out[o] = (float)((long long)(int32_t)(v[c] - lterm) + cterm[jl]) * scale;
+          if (acc_base) acc_base[o] = (int32_t)v[c];
+          if (y_base) y_base[o] = (float)((long long)(int32_t)(v[c] - lterm) + cterm[jl]) * scale;
         }
       }
     }
@@ -560,20 +571,20 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
       const size_t o = (size_t)i * a.J + j;
       if (a.vec_out) {
         const uint4 q = *reinterpret_cast<const uint4*>(&patch[rr][4 * c4]);
-        if (a.acc_out) *reinterpret_cast<uint4*>(a.acc_out + o) = q;
-        if (a.y_out) {
+        if (acc_base) *reinterpret_cast<uint4*>(acc_base + o) = q;
+        if (y_base) {
           float4 y;
           y.x = (float)((long long)(int32_t)(q.x - lt) + cterm[4 * c4]) * scale;
           y.y = (float)((long long)(int32_t)(q.y - lt) + cterm[4 * c4 + 1]) * scale;
           y.z = (float)((long long)(int32_t)(q.z - lt) + cterm[4 * c4 + 2]) * scale;
           y.w = (float)((long long)(int32_t)(q.w - lt) + cterm[4 * c4 + 3]) * scale;
-          *reinterpret_cast<float4*>(a.y_out + o) = y;
+          *reinterpret_cast<float4*>(y_base + o) = y;
         }
       } else {
         for (int e = 0; e < 4 && j + e < a.J; ++e) {
           const uint32_t q = patch[rr][4 * c4 + e];
-          if (a.acc_out) a.acc_out[o + e] = (int32_t)q;
-          if (a.y_out) a.y_out[o + e] = (float)((long long)(int32_t)(q - lt) + cterm[4 * c4 + e]) * scale;
+          if (acc_base) acc_base[o + e] = (int32_t)q;
+          if (y_base) y_base[o + e] = (float)((long long)(int32_t)(q - lt) + cterm[4 * c4 + e]) * scale;
         }
       }
     }
@@ -621,7 +632,8 @@ template <bool FROM_X>
 __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ lut, uint32_t* __restrict__ rows32,
                                                     const uint8_t* __restrict__ w, ConvView cv, int K, int J, int krows,
                                                     int Jpad, int seg_rows, uint8_t* __restrict__ Bp,
-                                                    int32_t* __restrict__ psum, QParams qp, QDev* __restrict__ qd) {
+                                                    int32_t* __restrict__ psum, QParams qp, QDev* __restrict__ qd,
+                                                    int tables) {
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     int xz = qp.x_zp, wz = qp.w_zp, pad = qp.pad_code;
     float sc = qp.scale;
@@ -641,8 +653,11 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
     qd->pad4 = (((uint32_t)pad & 0xffu) ^ (qp.sgn ? 0x80u : 0u)) * 0x01010101u;
   }
   const uint32_t sx = qp.sgn ? 0x80u : 0u;  // pattern <-> offset-binary code; also moves int16 entries to offset form
-  if (blockIdx.x < kRowBlocks) {
-    const int dw = blockIdx.x * 256 + threadIdx.x;  // 0 .. 32767
+  if (blockIdx.x < kRowBlocks * tables) {  // kRowBlocks blocks per multiplier table
+    const int tbl = blockIdx.x / kRowBlocks;
+    lut += (size_t)tbl * 65536;
+    rows32 += (size_t)tbl * 32768;
+    const int dw = (blockIdx.x - tbl * kRowBlocks) * 256 + threadIdx.x;  // 0 .. 32767
     const int t = dw >> 7, P = dw & 127;
     uint32_t lo, hi;
     const uint32_t tp = (uint32_t)t ^ sx, p0 = (uint32_t)P ^ sx, p1 = (uint32_t)(P + 128) ^ sx;
@@ -657,7 +672,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
     return;
   }
   __shared__ int32_t red[16][65];
-  const int b = blockIdx.x - kRowBlocks;
+  const int b = blockIdx.x - kRowBlocks * tables;
   const int jblocks = Jpad / 64;
   const int seg = b / jblocks, jb = b - seg * jblocks;
   const int c4 = threadIdx.x & 15, r = threadIdx.x >> 4;
@@ -793,6 +808,8 @@ int tab_num_tiles() { return kNumTiles; }
 bool tab_supported(const Geom& g) {
   if (g.mult) return false;  // depthwise: every output channel has its own lane-side operand
   const long long chunks = cdiv(g.K, kChunk);
+  // tile indices over all tables and the fix-up grid are 32-bit: tiles hold at least 64 x 16 outputs
+  if ((double)g.M * g.Cout * g.T >= 5.0e10) return false;
   return (long long)g.M * chunks < (1LL << 31) && (long long)g.Cout * chunks < (1LL << 31);
 }
 
@@ -843,7 +860,7 @@ static PlanChoice plan_choice(const Geom& g, int tile, int v, int forced_split, 
   const long long I = (v == 2) ? g.M : g.Cout;
   const long long J = (v == 2) ? g.Cout : g.M;
   const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
-  const int base = cdiv(I, kIT), ntj = cdiv(J, kJT);
+  const int base = cdiv(I, kIT), ntj = cdiv(J, kJT) * g.T;  // column tiles of all tables
   if (forced_rows > 0)
     return plan_choice_nti(g, tile, v, forced_split, std::max(base, std::min(forced_rows, cdiv(I, 64))));
   PlanChoice best = plan_choice_nti(g, tile, v, forced_split, base);
@@ -872,7 +889,7 @@ static PlanChoice plan_choice_nti(const Geom& g, int tile, int v, int forced_spl
   // tiles as that height needs (rounding the height up can free the last one)
   const int ih = cdiv(cdiv(I, nti_wanted), 64) * 64;
   const int nti = cdiv(I, ih);
-  const int ntiles = nti * cdiv(J, kJT);
+  const int ntiles = nti * cdiv(J, kJT) * g.T;
   const int nch = cdiv(g.K, kChunk);
   const long long total = (long long)ntiles * nch;
   const int per_cu = (tc.threads == 512 && tc.wpe == 4) ? 2 : 1;  // workgroups resident per compute unit
@@ -917,13 +934,13 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o);
 // (geometry, options); the table is small and cleared when it grows past a bound.
 TabPlan tab_plan(const Geom& g, const Options& o) {
   struct Key {
-    int v[20];
+    int v[21];
     bool operator<(const Key& other) const { return std::memcmp(v, other.v, sizeof(v)) < 0; }
   };
   static std::mutex mu;
   static std::map<Key, TabPlan> cache;
   const Key k{{g.N, g.H, g.W, g.Cin, g.KH, g.KW, g.Cout, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.sgn, g.mult, o.variant,
-               o.split_k, o.tile, o.row_tiles, cu_count()}};
+               o.split_k, o.tile, o.row_tiles, cu_count(), g.T}};
   std::lock_guard<std::mutex> lock(mu);
   auto it = cache.find(k);
   if (it != cache.end()) return it->second;
@@ -964,7 +981,7 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   const size_t Kp = (size_t)nch * kChunk;
   const size_t Jpad = (size_t)cdiv(J, 64) * 64;
   size_t off = 0;
-  p.off_rows = off;   off += up256(131072);
+  p.off_rows = off;   off += up256((size_t)131072 * g.T);
   p.off_bpack = off;  off += up256((Kp + 1) * Jpad);
   p.off_bsum = off;   off += up256(Jpad * 4 * kMaxSeg);
   // materialized lane operand, or (signed codes, implicit patch view) the offset-binary copy of x
@@ -1028,18 +1045,19 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   ConvView cv{x, g.H, g.W, g.Cin, g.KW, g.sh, g.sw, g.ph, g.pw, g.OH, g.OW, g.M, g.K, qp.pad_code, qp.dq,
               g.dh, g.dw, g.sgn ? 0x80u : 0u};
 
-  const int ntiles = p.nti * cdiv(J, kJT);
+  const int ntiles1 = p.nti * cdiv(J, kJT);  // per table
+  const int ntiles = ntiles1 * g.T;
   // Column sums are produced per segment of rows so that more than Jpad/64 blocks share the work.
   const int krows = Kp + 1;
   const int nseg = std::max(1, std::min(kMaxSeg, cdiv(krows, 64)));
   const int seg_rows = cdiv(cdiv(krows, nseg), 16) * 16;
-  const dim3 pgrid(kRowBlocks + nseg * (Jpad / 64));
+  const dim3 pgrid(kRowBlocks * g.T + nseg * (Jpad / 64));
   if (ch)
     hipLaunchKernelGGL((prep_kernel<true>), pgrid, dim3(256), 0, s, lut, reinterpret_cast<uint32_t*>(rows), w, cv, g.K, J,
-                       krows, Jpad, seg_rows, Bp, bsum, qp, qd);
+                       krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T);
   else
     hipLaunchKernelGGL((prep_kernel<false>), pgrid, dim3(256), 0, s, lut, reinterpret_cast<uint32_t*>(rows), w, cv, g.K, J,
-                       krows, Jpad, seg_rows, Bp, bsum, qp, qd);
+                       krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T);
 
   TabArgs a{};
   a.I = I;
@@ -1072,7 +1090,8 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.ntj = cdiv(J, kJT);
   a.nch = nchunks;
   a.ih = p.ih;
-  a.total_iters = (long long)p.nti * a.ntj * nchunks;
+  a.ntiles1 = ntiles1;
+  a.total_iters = (long long)ntiles * nchunks;
   a.qd = qd;
   a.bias_k = g.sgn ? 32768u * (uint32_t)g.K : 0u;
   a.acc_out = acc_out; a.y_out = y_out;
