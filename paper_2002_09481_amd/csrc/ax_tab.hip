@@ -31,10 +31,6 @@
 
 #include "ax_internal.h"
 
-#ifndef AX_ADD_SDWA
-#define AX_ADD_SDWA 0
-#endif
-
 namespace ax {
 
 constexpr int kChunk = 16;     // taps per 16-byte lane-operand load
@@ -84,20 +80,11 @@ struct TabArgs {
 // (1,0) / (0,1) selector is an add of one half; it issues a little faster than the
 // sub-dword-select form of v_add_u32.
 __device__ __forceinline__ void add_halves(uint32_t& acc_lo, uint32_t& acc_hi, uint32_t e, uint32_t sel_hi) {
-#if AX_ADD_SDWA
-  (void)sel_hi;
-  asm volatile(
-      "v_add_u32_sdwa %0, %0, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
-      "v_add_u32_sdwa %1, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1"
-      : "+v"(acc_lo), "+v"(acc_hi)
-      : "v"(e));
-#else
   asm volatile(
       "v_dot2_u32_u16 %0, %2, 1, %0\n\t"
       "v_dot2_u32_u16 %1, %2, %3, %1"
       : "+v"(acc_lo), "+v"(acc_hi)
       : "v"(e), "s"(sel_hi));
-#endif
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -198,9 +185,9 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
 
   // ---- table building ------------------------------------------------------------------
   // Unit q of a phase = (tap s of the phase, table g, half h).  The eight table-side codes of
-  // a unit are wave-uniform and come through scalar loads; the rows are read with buffer
-  // loads whose scalar offset selects the row (code * 512 bytes) and whose per-lane offset
-  // selects dword `lane` (+64 for the second half): 256 contiguous bytes per wave.
+  // a unit are wave-uniform (scalar registers); the rows are read with buffer loads whose
+  // scalar offset selects the row (code * 512 bytes) and whose per-lane offset selects dword
+  // `lane` (+64 for the second half): 256 contiguous bytes per wave.
   const __amdgpu_buffer_rsrc_t rows_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(rows), 0, 131072, 0x00020000);
   int us[UNITS], ug[UNITS], uh[UNITS];
@@ -801,7 +788,6 @@ static const TileCfg kTiles[] = {
     {512, 2, 4, 2, 4},   // 7: 1024 x 32 tile, two workgroups per compute unit
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
-constexpr int kDefaultTile = 4;
 int tab_num_tiles() { return kNumTiles; }
 
 // The preparation kernels index their pieces with 32-bit integers.
@@ -1034,7 +1020,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   const int nchunks = cdiv(g.K, kChunk);
   const int Kp = nchunks * kChunk;
   const TileCfg& tc = kTiles[p.tile];
-  const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
+  const int kJT = tc.NG * 8;
   const int Jpad = cdiv(J, 64) * 64;
   uint16_t* rows = reinterpret_cast<uint16_t*>(wsb + p.off_rows);
   uint8_t* Bp = wsb + p.off_bpack;
