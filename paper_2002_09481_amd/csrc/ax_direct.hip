@@ -85,7 +85,11 @@ constexpr int kDwMaxC = 4096;  // channels whose filter sums fit next to the tab
 
 // KS: kernel height = width known at compile time (taps fully unrolled, so that the loads of all
 // taps of an item are in flight together), or 0 for any kernel size.
-template <int KS>
+// HOIST (3x3 only): the grid stride is a multiple of the channel groups, so a thread keeps its four
+// channels for every item: the filter codes are loaded once and kept, pre-shifted, in registers.
+// A lookup then costs four vector instructions (extract the activation code, form the address,
+// add the entry, add the code to the patch sum) next to its LDS read.
+template <int KS, bool HOIST>
 __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const uint8_t* __restrict__ x,
                                                    const uint8_t* __restrict__ w, const uint16_t* __restrict__ lut,
                                                    int32_t* __restrict__ acc_out, float* __restrict__ y_out,
@@ -106,8 +110,11 @@ __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const u
   {
     const uint4* __restrict__ src = reinterpret_cast<const uint4*>(lut);
     uint4* dst = reinterpret_cast<uint4*>(tab);
+    // signed activations index the table by code + 128 (the byte with its top bit flipped), the
+    // same value the patch sums are taken over: rows are staged in that order (a row = 32 chunks)
+    const int rowflip = g.sgn ? (0x80 << 5) : 0;
     for (int i = threadIdx.x; i < 8192; i += 1024) {
-      uint4 v = src[i];
+      uint4 v = src[i ^ rowflip];
       v.x ^= flip16; v.y ^= flip16; v.z ^= flip16; v.w ^= flip16;
       dst[i] = v;
     }
@@ -124,6 +131,17 @@ __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const u
   const uint32_t bias = g.sgn ? 32768u * (uint32_t)K : 0u;
   const int off128 = g.sgn ? 128 * K : 0;
   const long long kzz = (long long)K * qp.x_zp * qp.w_zp;
+  const char* tabb = reinterpret_cast<const char*>(tab);
+  uint32_t wb2[HOIST ? KS * KS : 1][4];  // 2 * filter code = byte offset within a table row
+  if constexpr (HOIST) {
+    const uint32_t c4 = (blockIdx.x * 1024u + threadIdx.x) % C4;
+#pragma unroll
+    for (int t = 0; t < KS * KS; ++t) {
+      const uint32_t wd = *reinterpret_cast<const uint32_t*>(w + (size_t)t * g.Cin + 4u * c4);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) wb2[t][j] = ((wd >> (8 * j)) & 0xffu) << 1;
+    }
+  }
   for (uint32_t it = blockIdx.x * 1024u + threadIdx.x; it < items; it += gridDim.x * 1024u) {
     const uint32_t c4 = it % C4;
     const uint32_t pix = it / C4;
@@ -141,9 +159,18 @@ __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const u
       const uint32_t xs = xd ^ flip8;  // code + 128 for signed codes
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const uint32_t a = (xd >> (8 * j)) & 0xffu, b = (wd >> (8 * j)) & 0xffu;
-        acc[j] += tab[a * 256u + b];
-        sp[j] += (xs >> (8 * j)) & 0xffu;
+        const uint32_t a = (xs >> (8 * j)) & 0xffu, b = (wd >> (8 * j)) & 0xffu;
+        acc[j] += *reinterpret_cast<const uint16_t*>(tabb + ((a << 9) | (b << 1)));
+        sp[j] += a;
+      }
+    };
+    auto tap_hoisted = [&](uint32_t xd, int t) {
+      const uint32_t xs = xd ^ flip8;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t a = (xs >> (8 * j)) & 0xffu;
+        acc[j] += *reinterpret_cast<const uint16_t*>(tabb + ((a << 9) | wb2[HOIST ? t : 0][j]));
+        sp[j] += a;
       }
     };
     if constexpr (KS > 0) {
@@ -156,11 +183,13 @@ __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const u
           const bool inside = (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
           xd[ky * KS + kx] = pad4;
           if (inside) xd[ky * KS + kx] = *reinterpret_cast<const uint32_t*>(xn + ((size_t)iy * g.W + ix) * g.Cin);
-          wd[ky * KS + kx] = *reinterpret_cast<const uint32_t*>(wc + (size_t)(ky * KS + kx) * g.Cin);
+          if constexpr (!HOIST) wd[ky * KS + kx] = *reinterpret_cast<const uint32_t*>(wc + (size_t)(ky * KS + kx) * g.Cin);
         }
       }
 #pragma unroll
-      for (int t = 0; t < KS * KS; ++t) tap(xd[t], wd[t]);
+      for (int t = 0; t < KS * KS; ++t) {
+        if constexpr (HOIST) tap_hoisted(xd[t], t); else tap(xd[t], wd[t]);
+      }
     } else {
       for (int ky = 0; ky < KH; ++ky) {
         const int iy = by + ky * g.dh;
@@ -211,12 +240,15 @@ hipError_t launch_dw(const Geom& g, const QParams& qp, const uint8_t* x, const u
   const uint32_t blocks = (uint32_t)std::min<uint64_t>((uint64_t)cu_count(), (items + 1023) / 1024);
   const int vec_out = ((((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
   timing_begin(s);
-  if (g.KH == 3 && g.KW == 3)
-    hipLaunchKernelGGL(dw_kernel<3>, dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+  const bool keeps_channels = 1024 % (g.Cin / 4) == 0;  // the grid stride is then a multiple of the channel groups
+  if (g.KH == 3 && g.KW == 3 && keeps_channels)
+    hipLaunchKernelGGL((dw_kernel<3, true>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+  else if (g.KH == 3 && g.KW == 3)
+    hipLaunchKernelGGL((dw_kernel<3, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
   else if (g.KH == 5 && g.KW == 5)
-    hipLaunchKernelGGL(dw_kernel<5>, dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+    hipLaunchKernelGGL((dw_kernel<5, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
   else
-    hipLaunchKernelGGL(dw_kernel<0>, dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+    hipLaunchKernelGGL((dw_kernel<0, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
   timing_end(s);
   return hipGetLastError();
 }
