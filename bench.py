@@ -155,8 +155,11 @@ def main():
     # measured denominators: LDS lookup rates and copy bandwidth on this device
     r_cf = ax.ax_probe_lds_gather(2, 0, 131072, 1024, 20000)
     r_rand = ax.ax_probe_lds_gather(2, 1, 131072, 1024, 8000)
+    r_cf16 = ax.ax_probe_lds_gather(16, 0, 32768, 1024, 20000)
+    r_rand16 = ax.ax_probe_lds_gather(16, 1, 4096, 1024, 8000)
     lookups = lambda r: r["wave_reads"] * r["workgroups"] * 64 / r["seconds"]
     lds_peak, lds_rand = lookups(r_cf), lookups(r_rand)
+    lds_wide, lds_wide_rand = 8 * lookups(r_cf16), 8 * lookups(r_rand16)  # a 16-byte entry holds 8 products
     nb = 1 << 30
     a = torch.empty(nb, dtype=torch.uint8, device=dev)
     b = torch.empty(nb, dtype=torch.uint8, device=dev)
@@ -192,6 +195,11 @@ def main():
         "algorithmic_lookups_per_launch": total_macs / n_launch,
         "traffic": traffic,
         "frac_of_random_gather_rate": kern_rate / lds_rand,
+        "note": "frac can exceed 1: the denominator is the rate of one-product (2-byte) LDS lookups, the kernel "
+                "fetches eight products per 16-byte lookup; lds_wide prices it against 16-byte gathers",
+        "lds_wide": {"achieved": kern_rate / 1e9, "peak": lds_wide / 1e9, "unit": "Glookup/s",
+                     "frac": kern_rate / lds_wide, "peak_source": "measured: conflict-free 16-byte LDS gathers x 8 "
+                     "products per entry", "frac_of_random_16_byte_gathers": kern_rate / lds_wide_rand},
         "alu": {"achieved": kern_rate / 1e12, "peak": 39.32, "unit": "Tint32-add/s", "frac": kern_rate / 39.32e12},
         "hbm": {"achieved": alg_bytes / (main_ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
                 "frac": alg_bytes / (main_ms * 1e-3) / 8e12, "measured_copy_GBps": copy_gbs,
