@@ -70,6 +70,15 @@ int ax_oracle_conv2d_f32(const float* x, int N, int H, int W, int Cin, const flo
                          int round_mode, uint8_t* xq_out, uint8_t* wq_out, ax_oracle_quant* q_out,
                          int32_t* acc_out, float* y_out);
 
+/* The same with dilation, signed codes (codes and zero points lowered by 128, lut int16 addressed
+ * by the two's-complement patterns) and depthwise filters [KH,KW,Cin,Cout/Cin]. */
+int ax_oracle_conv2d_f32_ex(const float* x, int N, int H, int W, int Cin, const float* w, int KH, int KW,
+                            int Cout, const void* lut, int stride_h, int stride_w, int pad_h,
+                            int pad_w, int dil_h, int dil_w, int depthwise, int is_signed,
+                            const float* x_range, const float* w_range, int relu, int round_mode,
+                            uint8_t* xq_out, uint8_t* wq_out, ax_oracle_quant* q_out,
+                            int32_t* acc_out, float* y_out);
+
 /* Number of threads the parallel loops use. */
 int ax_oracle_threads(void);
 

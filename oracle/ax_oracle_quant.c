@@ -85,18 +85,30 @@ int ax_oracle_quantize_f32(const float* x, int64_t n, int relu, float alpha, int
   return 0;
 }
 
-int ax_oracle_conv2d_f32(const float* x, int N, int H, int W, int Cin, const float* w, int KH, int KW,
-                         int Cout, const uint16_t* lut, int stride_h, int stride_w, int pad_h,
-                         int pad_w, const float* x_range, const float* w_range, int relu,
-                         int round_mode, uint8_t* xq_out, uint8_t* wq_out, ax_oracle_quant* q_out,
-                         int32_t* acc_out, float* y_out) {
+/* The float layer with the layer's full parameter set (Sec. III, Algorithm 1: strides, dilations,
+ * padding; signed or unsigned multiplier; round mode) and the depthwise kind.  Signed form: the
+ * same alpha; codes and zero point are the unsigned ones lowered by 128, so that they span
+ * [-128, 127] and real zero stays exactly representable; the table (int16 entries) is addressed
+ * by the two codes' two's-complement patterns.  xq_out / wq_out receive the code bytes. */
+int ax_oracle_conv2d_f32_ex(const float* x, int N, int H, int W, int Cin, const float* w, int KH, int KW,
+                            int Cout, const void* lut, int stride_h, int stride_w, int pad_h,
+                            int pad_w, int dil_h, int dil_w, int depthwise, int is_signed,
+                            const float* x_range, const float* w_range, int relu, int round_mode,
+                            uint8_t* xq_out, uint8_t* wq_out, ax_oracle_quant* q_out,
+                            int32_t* acc_out, float* y_out) {
   if (!x || !w || !lut || !x_range || !w_range || !acc_out || !y_out) return AX_ORACLE_ERR_ARG;
   if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || KH <= 0 || KW <= 0 || Cout <= 0) return AX_ORACLE_ERR_ARG;
-  if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0) return AX_ORACLE_ERR_ARG;
-  if (H + 2 * pad_h < KH || W + 2 * pad_w < KW) return AX_ORACLE_ERR_ARG;
-  const int OH = (H + 2 * pad_h - KH) / stride_h + 1;
-  const int OW = (W + 2 * pad_w - KW) / stride_w + 1;
-  const int64_t nx = (int64_t)N * H * W * Cin, nw = (int64_t)KH * KW * Cin * Cout;
+  if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1) return AX_ORACLE_ERR_ARG;
+  const int eh = H + 2 * pad_h - dil_h * (KH - 1) - 1, ew = W + 2 * pad_w - dil_w * (KW - 1) - 1;
+  if (eh < 0 || ew < 0) return AX_ORACLE_ERR_ARG;
+  const int OH = eh / stride_h + 1, OW = ew / stride_w + 1;
+  int mult = 0;
+  if (depthwise) {
+    if (Cout % Cin) return AX_ORACLE_ERR_ARG;
+    mult = Cout / Cin;
+  }
+  const int wlast = depthwise ? mult : Cout; /* innermost extent of the filter tensor */
+  const int64_t nx = (int64_t)N * H * W * Cin, nw = (int64_t)KH * KW * Cin * wlast;
 
   /* steps 2 and 3 */
   ax_oracle_quant q;
@@ -114,6 +126,14 @@ int ax_oracle_conv2d_f32(const float* x, int N, int H, int W, int Cin, const flo
   }
   ax_oracle_quantize_f32(x, nx, relu, q.x_scale, q.x_zp, round_mode, xq);
   ax_oracle_quantize_f32(w, nw, 0, q.w_scale, q.w_zp, round_mode, wq);
+  if (is_signed) { /* lower codes and zero points by 128; bytes now hold int8 patterns */
+    for (int64_t i = 0; i < nx; ++i) xq[i] = (uint8_t)((int)xq[i] - 128);
+    for (int64_t i = 0; i < nw; ++i) wq[i] = (uint8_t)((int)wq[i] - 128);
+    q.x_zp -= 128;
+    q.w_zp -= 128;
+  }
+  const uint16_t* lu = (const uint16_t*)lut;
+  const int16_t* ls = (const int16_t*)lut;
 
   /* step 4: per output element, the lookup sum, the integer correction of the expanded
    * Eq. (3) and the float32 dequantization */
@@ -124,28 +144,34 @@ int ax_oracle_conv2d_f32(const float* x, int N, int H, int W, int Cin, const flo
     for (int oy = 0; oy < OH; ++oy) {
       for (int ox = 0; ox < OW; ++ox) {
         for (int co = 0; co < Cout; ++co) {
-          int64_t acc = 0, Sp = 0, Sf = 0;
+          const int c_first = depthwise ? co / mult : 0;
+          const int c_count = depthwise ? 1 : Cin;
+          const int wcol = depthwise ? co % mult : co;
+          int64_t acc = 0, Sp = 0, Sf = 0, K = 0;
           for (int ky = 0; ky < KH; ++ky) {
             for (int kx = 0; kx < KW; ++kx) {
-              const int iy = oy * stride_h - pad_h + ky;
-              const int ix = ox * stride_w - pad_w + kx;
+              const int iy = oy * stride_h - pad_h + ky * dil_h;
+              const int ix = ox * stride_w - pad_w + kx * dil_w;
               const int inside = (iy >= 0 && iy < H && ix >= 0 && ix < W);
-              for (int ci = 0; ci < Cin; ++ci) {
-                const int a = inside ? xq[(((size_t)n * H + iy) * W + ix) * Cin + ci] : q.x_zp;
-                const int b = wq[(((size_t)ky * KW + kx) * Cin + ci) * Cout + co];
-                acc += lut[a * 256 + b];
+              for (int cc = 0; cc < c_count; ++cc) {
+                const int ci = c_first + cc;
+                const uint8_t ab = inside ? xq[(((size_t)n * H + iy) * W + ix) * Cin + ci] : (uint8_t)q.x_zp;
+                const uint8_t bb = wq[(((size_t)ky * KW + kx) * Cin + ci) * wlast + wcol];
+                const int a = is_signed ? (int)(int8_t)ab : (int)ab;
+                const int b = is_signed ? (int)(int8_t)bb : (int)bb;
+                acc += is_signed ? (int64_t)ls[(int)ab * 256 + (int)bb] : (int64_t)lu[(int)ab * 256 + (int)bb];
                 Sp += a;
                 Sf += b;
+                K += 1;
               }
             }
           }
           const size_t o = (((size_t)n * OH + oy) * OW + ox) * Cout + co;
-          if (acc > 2147483647LL) {
+          if (acc > 2147483647LL || acc < -2147483648LL) {
 #pragma omp atomic write
             status = AX_ORACLE_ERR_OVERFLOW;
             continue;
           }
-          const int64_t K = (int64_t)KH * KW * Cin;
           const int64_t corr = acc - (int64_t)q.w_zp * Sp - (int64_t)q.x_zp * Sf + K * q.x_zp * q.w_zp;
           acc_out[o] = (int32_t)acc;
           y_out[o] = (float)corr * scale;
@@ -161,4 +187,14 @@ int ax_oracle_conv2d_f32(const float* x, int N, int H, int W, int Cin, const flo
   free(xq);
   free(wq);
   return status;
+}
+
+/* The plain form: stride and padding only, unsigned codes, ordinary convolution. */
+int ax_oracle_conv2d_f32(const float* x, int N, int H, int W, int Cin, const float* w, int KH, int KW,
+                         int Cout, const uint16_t* lut, int stride_h, int stride_w, int pad_h,
+                         int pad_w, const float* x_range, const float* w_range, int relu,
+                         int round_mode, uint8_t* xq_out, uint8_t* wq_out, ax_oracle_quant* q_out,
+                         int32_t* acc_out, float* y_out) {
+  return ax_oracle_conv2d_f32_ex(x, N, H, W, Cin, w, KH, KW, Cout, lut, stride_h, stride_w, pad_h, pad_w, 1, 1, 0, 0,
+                                 x_range, w_range, relu, round_mode, xq_out, wq_out, q_out, acc_out, y_out);
 }

@@ -41,6 +41,9 @@ def lib():
         _lib.ax_oracle_conv2d_ex.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci,
                                              cf, ci, cf, ci, ci, vp, vp]
         _lib.ax_oracle_conv2d_ex.restype = ci
+        _lib.ax_oracle_conv2d_f32_ex.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci,
+                                                 vp, vp, ci, ci, vp, vp, vp, vp, vp]
+        _lib.ax_oracle_conv2d_f32_ex.restype = ci
         for f in (_lib.ax_oracle_conv2d, _lib.ax_oracle_conv2d_sample, _lib.ax_oracle_dense, _lib.ax_oracle_threads,
                   _lib.ax_oracle_range_f32, _lib.ax_oracle_coeffs, _lib.ax_oracle_quantize_f32,
                   _lib.ax_oracle_conv2d_f32):
@@ -215,6 +218,46 @@ def conv2d_f32(x, w, lut, stride, pad, x_range, w_range, relu=False, round_mode=
                                     y.ctypes.data)
     if rc:
         raise RuntimeError("ax_oracle_conv2d_f32 failed: %d" % rc)
+    return dict(acc=acc, y=y, xq=xq, wq=wq, x_scale=float(qs.x_scale), x_zp=int(qs.x_zp),
+                w_scale=float(qs.w_scale), w_zp=int(qs.w_zp))
+
+
+def conv2d_f32_ex(x, w, lut, stride, pad, x_range, w_range, relu=False, round_mode=0, dilation=1, depthwise=False,
+                  signed=False):
+    """Float layer with dilation / signed codes / depthwise filters ([KH,KW,Cin,mult]).
+    Returns dict(acc, y, xq, wq, x_scale, x_zp, w_scale, w_zp); codes are int8 when signed."""
+    x, w = _chk(x, np.float32, 4), _chk(w, np.float32, 4)
+    lut = _chk(np.asarray(lut).reshape(-1), np.int16 if signed else np.uint16, 1)
+    if lut.size != 65536:
+        raise ValueError("table must have 65536 entries")
+    xr = _chk(np.asarray(x_range, dtype=np.float32), np.float32, 1)
+    wr = _chk(np.asarray(w_range, dtype=np.float32), np.float32, 1)
+    N, H, W, Cin = x.shape
+    KH, KW, Cin2, last = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    Cout = Cin * last if depthwise else last
+    sh, sw = (stride, stride) if np.isscalar(stride) else stride
+    ph, pw = (pad, pad) if np.isscalar(pad) else pad
+    dh, dw = (dilation, dilation) if np.isscalar(dilation) else dilation
+    OH = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+    OW = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+    if OH <= 0 or OW <= 0:
+        raise ValueError("empty output")
+    acc = np.empty((N, OH, OW, Cout), np.int32)
+    y = np.empty((N, OH, OW, Cout), np.float32)
+    xq = np.empty(x.shape, np.uint8)
+    wq = np.empty(w.shape, np.uint8)
+    qs = _Quant()
+    rc = lib().ax_oracle_conv2d_f32_ex(x.ctypes.data, N, H, W, Cin, w.ctypes.data, KH, KW, Cout, lut.ctypes.data,
+                                       sh, sw, ph, pw, dh, dw, int(bool(depthwise)), int(bool(signed)),
+                                       xr.ctypes.data, wr.ctypes.data, int(bool(relu)), int(round_mode),
+                                       xq.ctypes.data, wq.ctypes.data, ctypes.addressof(qs), acc.ctypes.data,
+                                       y.ctypes.data)
+    if rc:
+        raise RuntimeError("ax_oracle_conv2d_f32_ex failed: %d" % rc)
+    if signed:
+        xq, wq = xq.view(np.int8), wq.view(np.int8)
     return dict(acc=acc, y=y, xq=xq, wq=wq, x_scale=float(qs.x_scale), x_zp=int(qs.x_zp),
                 w_scale=float(qs.w_scale), w_zp=int(qs.w_zp))
 

@@ -217,3 +217,77 @@ def test_float_layer_close_to_unquantized_convolution(shape):
         + conv(torch.full_like(xd, ax / 2), torch.full_like(wd, aw / 2))
     assert np.all(np.abs(r["y"] - ref) <= bound * (1 + 1e-4) + 1e-5)
     assert np.abs(r["y"] - ref).max() > 0  # it is a quantized result, not the float one
+
+
+# ---- the float layer with the full parameter set (dilation, signed codes, depthwise) --------------
+
+EX_CASES = [
+    # N, H, W, Cin, KH, KW, last, stride, pad, dilation, depthwise   (last = Cout, or the multiplier)
+    (2, 9, 8, 5, 3, 3, 6, 1, 2, 2, False),
+    (1, 10, 10, 4, 3, 2, 3, 2, 3, (3, 2), False),
+    (2, 8, 8, 6, 3, 3, 2, 1, 1, 1, True),
+    (1, 9, 9, 3, 3, 3, 1, 2, 2, 2, True),
+]
+
+
+def _ex_operands(case, seed):
+    N, H, W, Cin, KH, KW, last, s, p, d, dwise = case
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((N, H, W, Cin)).astype(np.float32)
+    w = (rng.standard_normal((KH, KW, Cin, last)) * 0.2).astype(np.float32)
+    return x, w, s, p, d, dwise
+
+
+@pytest.mark.parametrize("signed", [False, True])
+@pytest.mark.parametrize("case", EX_CASES)
+def test_extended_float_layer_composes_pinned_parts(case, signed):
+    """Its integer part must be the (separately pinned) variant oracle applied to its own codes and
+    coefficients, its codes the pinned quantization (lowered by 128 when signed)."""
+    x, w, s, p, d, dwise = _ex_operands(case, 41)
+    relu = not signed
+    xr, wr = oracle.range_f32(x, relu), oracle.range_f32(w)
+    lut = I.lut_signed_random_error(9) if signed else I.lut_random_error(9)
+    r = oracle.conv2d_f32_ex(x, w, lut, s, p, xr, wr, relu=relu, dilation=d, depthwise=dwise, signed=signed)
+    au, bu = oracle.coeffs(xr)
+    codes_u = oracle.quantize_f32(x, au, bu, relu=relu).astype(np.int64)
+    np.testing.assert_array_equal(r["xq"].astype(np.int64), codes_u - (128 if signed else 0))
+    assert r["x_zp"] == bu - (128 if signed else 0) and r["x_scale"] == au
+    q = I.Quant(r["x_scale"], r["x_zp"], r["w_scale"], r["w_zp"], None)
+    acc, y = oracle.conv2d_ex(r["xq"], r["wq"], lut, s, p, q, dilation=d, depthwise=dwise, signed=signed)
+    np.testing.assert_array_equal(r["acc"], acc)
+    assert Hh.float_ok(r["y"], y, rtol=2e-7, atol=1e-30)
+
+
+@pytest.mark.parametrize("case", EX_CASES)
+def test_signed_and_unsigned_float_layers_agree_with_exact_multipliers(case):
+    """(a - beta1)(b - beta2) does not change when codes and zero points are lowered by 128: with
+    the exact signed and the exact unsigned multiplier the two forms give the same outputs."""
+    x, w, s, p, d, dwise = _ex_operands(case, 42)
+    xr, wr = oracle.range_f32(x), oracle.range_f32(w)
+    ru = oracle.conv2d_f32_ex(x, w, I.lut_exact(), s, p, xr, wr, dilation=d, depthwise=dwise)
+    rs = oracle.conv2d_f32_ex(x, w, I.lut_signed_exact(), s, p, xr, wr, dilation=d, depthwise=dwise, signed=True)
+    np.testing.assert_array_equal(ru["y"], rs["y"])
+    assert (ru["acc"] != rs["acc"]).any()  # the raw sums differ, only the corrected result is the same
+
+
+@pytest.mark.parametrize("case", EX_CASES)
+def test_extended_float_layer_exact_table_equals_library_convolution(case):
+    N, H, W, Cin, KH, KW, last, s, p, d, dwise = case
+    x, w, s, p, d, dwise = _ex_operands(case, 43)
+    r = oracle.conv2d_f32_ex(x, w, I.lut_signed_exact(), s, p, oracle.range_f32(x), oracle.range_f32(w), dilation=d,
+                             depthwise=dwise, signed=True)
+    xf = r["x_scale"] * (torch.from_numpy(r["xq"].astype(np.float64)) - r["x_zp"])
+    wf = r["w_scale"] * (torch.from_numpy(r["wq"].astype(np.float64)) - r["w_zp"])
+    pair = lambda v: (v, v) if np.isscalar(v) else tuple(v)
+    if dwise:
+        wt = wf.permute(2, 3, 0, 1).reshape(Cin * last, 1, KH, KW)
+        ref = torch.nn.functional.conv2d(xf.permute(0, 3, 1, 2), wt, stride=pair(s), padding=pair(p), dilation=pair(d),
+                                         groups=Cin)
+    else:
+        ref = torch.nn.functional.conv2d(xf.permute(0, 3, 1, 2), wf.permute(3, 2, 0, 1), stride=pair(s),
+                                         padding=pair(p), dilation=pair(d))
+    assert Hh.float_ok(r["y"], ref.permute(0, 2, 3, 1).numpy(), rtol=1e-5, atol=1e-5)
+    # and it is a quantization of the unquantized convolution: zero real input stays exactly zero
+    z = oracle.conv2d_f32_ex(np.zeros_like(x), w, I.lut_signed_exact(), s, p, oracle.range_f32(x), oracle.range_f32(w),
+                             dilation=d, depthwise=dwise, signed=True)
+    assert not z["y"].any()
