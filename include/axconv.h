@@ -196,6 +196,17 @@ int ax_conv2d_f32(const float* x, int N, int H, int W, int Cin, const float* w, 
 size_t ax_conv2d_f32_workspace_bytes(int N, int H, int W, int Cin, int KH, int KW, int Cout,
                                      int stride_h, int stride_w, int pad_h, int pad_w);
 
+/* The float layer with the layer's full parameter set (Sec. III, Algorithm 1: strides,
+ * dilations, padding, signed or unsigned multiplier, round mode) and the depthwise kind, given by
+ * the descriptor of ax_conv2d_ex.  signed_codes = 1: the same alpha; codes and zero points are
+ * the unsigned ones lowered by 128 (they span [-128, 127], real zero stays representable), lut is
+ * int16 addressed by the codes' two's-complement patterns.  Everything else as ax_conv2d_f32. */
+int ax_conv2d_f32_ex(const ax_conv_desc_t* desc, const float* x, const float* w, const void* lut,
+                     const float* x_range, const float* w_range, int relu, int round_mode,
+                     int32_t* acc_out, float* y_out, void* workspace, size_t workspace_bytes,
+                     void* hip_stream);
+size_t ax_conv2d_f32_ex_workspace_bytes(const ax_conv_desc_t* desc);
+
 /* Dense form: x [M,K] float, w [K,N] float (Eq. (2)-(4) after the same quantization). */
 int ax_dense_f32(const float* x, int M, int K, const float* w, int N, const uint16_t* lut,
                  const float* x_range, const float* w_range, int relu, int round_mode,

@@ -40,7 +40,7 @@ EXPORTS = [
     "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_last_kernel_ms", "ax_conv2d_plan",
     "ax_range_f32", "ax_range_workspace_bytes", "ax_quantize_f32", "ax_conv2d_f32", "ax_conv2d_f32_workspace_bytes",
     "ax_dense_f32", "ax_dense_f32_workspace_bytes", "ax_conv2d_ex", "ax_conv2d_ex_workspace_bytes",
-    "ax_conv2d_multi_lut", "ax_conv2d_multi_lut_workspace_bytes",
+    "ax_conv2d_multi_lut", "ax_conv2d_multi_lut_workspace_bytes", "ax_conv2d_f32_ex", "ax_conv2d_f32_ex_workspace_bytes",
 ]
 
 
@@ -97,6 +97,10 @@ def lib():
     L.ax_conv2d_multi_lut.restype = ci
     L.ax_conv2d_multi_lut_workspace_bytes.argtypes = [ci] * 12
     L.ax_conv2d_multi_lut_workspace_bytes.restype = sz
+    L.ax_conv2d_f32_ex.argtypes = [ctypes.POINTER(ax_conv_desc_t), vp, vp, vp, vp, vp, ci, ci, vp, vp, vp, sz, vp]
+    L.ax_conv2d_f32_ex.restype = ci
+    L.ax_conv2d_f32_ex_workspace_bytes.argtypes = [ctypes.POINTER(ax_conv_desc_t)]
+    L.ax_conv2d_f32_ex_workspace_bytes.restype = sz
     L.ax_conv2d_ex.argtypes = [ctypes.POINTER(ax_conv_desc_t), vp, vp, vp, ctypes.POINTER(ax_quant_t), vp, vp, vp, sz, vp]
     L.ax_conv2d_ex.restype = ci
     L.ax_conv2d_ex_workspace_bytes.argtypes = [ctypes.POINTER(ax_conv_desc_t)]
@@ -475,6 +479,38 @@ def ax_conv2d_f32(x, w, lut, stride, pad, x_range=None, w_range=None, relu=False
                          _ptr(w_range), int(bool(relu)), int(round_mode),
                          _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
                          _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    _check(rc)
+    return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
+def ax_conv2d_f32_ex(x, w, lut, stride, pad, x_range=None, w_range=None, relu=False, round_mode=0, dilation=1,
+                     depthwise=False, signed=False, acc_out=None, y_out=None, workspace=None, stream=None):
+    """Float layer with dilation / signed codes / depthwise filters (w [KH,KW,Cin,mult]).
+    Returns (acc_out, y_out); pass False to skip one of them."""
+    L = lib()
+    _f32_common(x, w, lut, x_range, w_range)
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
+        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout] (or [KH,KW,Cin,mult])")
+    N, H, W, Cin = x.shape
+    KH, KW, _, last = w.shape
+    Cout = Cin * last if depthwise else last
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    dh, dw = _pair(dilation)
+    desc = ax_conv_desc_t(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, dh, dw, int(bool(depthwise)), int(bool(signed)))
+    OH = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+    OW = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+    if OH <= 0 or OW <= 0:
+        _check(-2)
+    acc_out, y_out = _outs((N, OH, OW, Cout), x.device, acc_out, y_out)
+    if workspace is None:
+        need = int(L.ax_conv2d_f32_ex_workspace_bytes(ctypes.byref(desc)))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    rc = L.ax_conv2d_f32_ex(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(lut), _ptr(x_range), _ptr(w_range),
+                            int(bool(relu)), int(round_mode), _ptr(None if acc_out is False else acc_out),
+                            _ptr(None if y_out is False else y_out), _ptr(workspace), workspace.numel(),
+                            ctypes.c_void_p(_stream_ptr(stream)))
     _check(rc)
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
 

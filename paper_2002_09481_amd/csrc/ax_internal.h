@@ -39,7 +39,7 @@ struct QParams {
   int x_zp, w_zp, pad_code;
   float scale;  // x_scale * w_scale, rounded to float
   const DevQuant* dq;
-  int sgn;  // 1: signed codes (zero points and pad code in [-128, 127]); never set together with dq
+  int sgn;  // 1: signed codes (zero points and pad code in [-128, 127], also those read through dq)
 };
 
 // Shared tail of ax_conv2d / ax_conv2d_f32 (ax_api.hip): pick a kernel family and enqueue.

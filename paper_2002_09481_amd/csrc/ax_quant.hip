@@ -98,6 +98,7 @@ struct QuantTask {
   RangeSrc src;
   int blocks;
   int relu;
+  uint32_t sflip;  // 0x80: signed form, codes and zero point lowered by 128 (the byte's top bit flipped)
 };
 
 // Stage 1 of the range, for up to two tensors in one launch (either task may have 0 blocks).  x[0] seeds
@@ -182,8 +183,9 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantTask a, c
   const float alpha = c.alpha, beta = (float)c.beta;
   if (bid == 0 && threadIdx.x == 0 && t.coeffs) {
     t.coeffs->scale = c.alpha;
-    t.coeffs->zero_point = c.beta;
+    t.coeffs->zero_point = c.beta - (t.sflip ? 128 : 0);
   }
+  const uint32_t sflip = t.sflip, sflip4 = t.sflip * 0x01010101u;
   const float* __restrict__ x = t.x;
   uint8_t* __restrict__ codes = t.codes;
   const int relu = t.relu;
@@ -194,12 +196,12 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantTask a, c
 #pragma unroll 2
   for (size_t i = first; i < t.nvec; i += stride) {
     const float4 v = xv[i];
-    ov[i] = code_of(v.x, relu, alpha, beta, mode) | (code_of(v.y, relu, alpha, beta, mode) << 8) |
-            (code_of(v.z, relu, alpha, beta, mode) << 16) | (code_of(v.w, relu, alpha, beta, mode) << 24);
+    ov[i] = (code_of(v.x, relu, alpha, beta, mode) | (code_of(v.y, relu, alpha, beta, mode) << 8) |
+             (code_of(v.z, relu, alpha, beta, mode) << 16) | (code_of(v.w, relu, alpha, beta, mode) << 24)) ^ sflip4;
   }
-  for (size_t i = first; i < t.head; i += stride) codes[i] = (uint8_t)code_of(x[i], relu, alpha, beta, mode);
+  for (size_t i = first; i < t.head; i += stride) codes[i] = (uint8_t)(code_of(x[i], relu, alpha, beta, mode) ^ sflip);
   for (size_t i = t.head + t.nvec * 4 + first; i < t.n; i += stride)
-    codes[i] = (uint8_t)code_of(x[i], relu, alpha, beta, mode);
+    codes[i] = (uint8_t)(code_of(x[i], relu, alpha, beta, mode) ^ sflip);
 }
 
 // Split [0, n) into head (scalar), nvec groups of four (vector) and a tail so that the vector
@@ -237,7 +239,8 @@ RangeTask range_task(const float* x, size_t n, int relu, float2* part) {
   return t;
 }
 
-QuantTask quant_task(const float* x, size_t n, int relu, uint8_t* codes, ax_coeffs_t* coeffs, RangeSrc src) {
+QuantTask quant_task(const float* x, size_t n, int relu, uint8_t* codes, ax_coeffs_t* coeffs, RangeSrc src,
+                     int sgn = 0) {
   QuantTask t{};
   if (!x) return t;
   t.x = x;
@@ -248,6 +251,7 @@ QuantTask quant_task(const float* x, size_t n, int relu, uint8_t* codes, ax_coef
   t.src = src;
   t.blocks = grid_for(n, t.nvec);
   t.relu = relu;
+  t.sflip = sgn ? 0x80u : 0u;
   return t;
 }
 
@@ -318,11 +322,11 @@ int run_f32(const Geom& g, const float* x, const float* w, const uint16_t* lut, 
     hipLaunchKernelGGL(range_partial_kernel, dim3(rx.blocks + rw.blocks), dim3(kThreads), 0, s, rx, rw);
   const RangeSrc sx = x_range ? RangeSrc{x_range, nullptr, 0} : RangeSrc{nullptr, rx.part, rx.blocks};
   const RangeSrc sw = w_range ? RangeSrc{w_range, nullptr, 0} : RangeSrc{nullptr, rw.part, rw.blocks};
-  const QuantTask qx = quant_task(x, nx, relu, wsb + p.off_xq, cx, sx);
-  const QuantTask qw = quant_task(w, nw, 0, wsb + p.off_wq, cw, sw);
+  const QuantTask qx = quant_task(x, nx, relu, wsb + p.off_xq, cx, sx, g.sgn);
+  const QuantTask qw = quant_task(w, nw, 0, wsb + p.off_wq, cw, sw, g.sgn);
   hipLaunchKernelGGL(quantize_kernel, dim3(qx.blocks + qw.blocks), dim3(kThreads), 0, s, qx, qw, mode);
   if (launched() != AX_OK) return AX_ERR_HIP;
-  QParams qp{0, 0, 0, 1.0f, dq, 0};
+  QParams qp{0, 0, 0, 1.0f, dq, g.sgn};
   return run_layer(g, qp, wsb + p.off_xq, wsb + p.off_wq, lut, acc_out, y_out, wsb + p.off_layer,
                    ws_bytes - p.off_layer, s);
 }
@@ -372,6 +376,30 @@ extern "C" size_t ax_conv2d_f32_workspace_bytes(int N, int H, int W, int Cin, in
                                                 int stride_w, int pad_h, int pad_w) {
   Geom g;
   if (make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g)) return 0;
+  return f32_plan(g).total;
+}
+
+static int geom_of_desc(const ax_conv_desc_t* d, Geom* g) {
+  if (!d) return AX_ERR_NULL;
+  if ((d->depthwise != 0 && d->depthwise != 1) || (d->signed_codes != 0 && d->signed_codes != 1)) return AX_ERR_OPTION;
+  return make_geom(d->N, d->H, d->W, d->Cin, d->KH, d->KW, d->Cout, d->stride_h, d->stride_w, d->pad_h, d->pad_w, g,
+                   d->dilation_h, d->dilation_w, d->signed_codes, d->depthwise);
+}
+
+extern "C" int ax_conv2d_f32_ex(const ax_conv_desc_t* desc, const float* x, const float* w, const void* lut,
+                                const float* x_range, const float* w_range, int relu, int round_mode,
+                                int32_t* acc_out, float* y_out, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  Geom g;
+  int rc = geom_of_desc(desc, &g);
+  if (rc) return rc;
+  return run_f32(g, x, w, static_cast<const uint16_t*>(lut), x_range, w_range, relu, round_mode, acc_out, y_out,
+                 workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t ax_conv2d_f32_ex_workspace_bytes(const ax_conv_desc_t* desc) {
+  Geom g;
+  if (geom_of_desc(desc, &g)) return 0;
   return f32_plan(g).total;
 }
 

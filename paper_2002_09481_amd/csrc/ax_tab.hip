@@ -589,7 +589,7 @@ struct ConvView {  // im2col addressing of x
 };
 
 __device__ __forceinline__ uint32_t pad_of(const ConvView& v) {
-  return v.dq ? (uint32_t)v.dq->x_zp : (((uint32_t)v.pad_code & 0xffu) ^ v.sx);
+  return (((uint32_t)(v.dq ? v.dq->x_zp : v.pad_code)) & 0xffu) ^ v.sx;
 }
 
 __device__ __forceinline__ uint32_t im2col_code(const ConvView& v, uint32_t pad, int m, int k) {

@@ -245,3 +245,38 @@ def test_float_entry_points_reject_bad_arguments():
                          ax.lut_to_device(I.lut_exact()), 1, 1, rng, rng,
                          workspace=torch.zeros(256, dtype=torch.uint8, device="cuda"))
     torch.cuda.synchronize()
+
+
+EX_LAYERS = [
+    # N, H, W, Cin, KH, KW, last, stride, pad, dilation, depthwise   (last = Cout, or the multiplier)
+    (2, 9, 8, 5, 3, 3, 6, 1, 2, 2, False),
+    (1, 40, 40, 16, 3, 3, 72, 1, 2, 2, False),              # table-tile path, implicit patch view
+    (2, 30, 30, 20, 5, 5, 9, 2, 4, (2, 1), False),          # materialized patches
+    (1, 7, 7, 256, 3, 3, 512, 1, 1, 1, False),              # lanes over channels when chosen
+    (2, 8, 8, 6, 3, 3, 2, 1, 1, 1, True),
+    (8, 56, 56, 64, 3, 3, 1, 1, 1, 1, True),                # depthwise kernel with the table in LDS
+]
+
+
+@pytest.mark.parametrize("variant", [0, 1, 3])
+@pytest.mark.parametrize("signed", [False, True])
+@pytest.mark.parametrize("case", EX_LAYERS, ids=lambda c: "x".join(str(v) for v in c[:7]) + ("_dw" if c[10] else ""))
+def test_float_layer_with_the_full_parameter_set(case, signed, variant):
+    N, H, W, Cin, KH, KW, last, s, p, d, dwise = case
+    ax.ax_set_option("variant", variant)
+    rng = np.random.default_rng(600 + Cin + last)
+    x = rng.standard_normal((N, H, W, Cin)).astype(np.float32)
+    w = (rng.standard_normal((KH, KW, Cin, last)) * 0.2).astype(np.float32)
+    relu = not signed
+    lut = I.lut_signed_random_error(21) if signed else I.lut_random_error(21)
+    given = variant == 1  # ranges handed in for one of the variants, taken by the layer otherwise
+    xd, wd = G.to_dev(x), G.to_dev(w)
+    xr = ax.ax_range_f32(xd, relu=relu) if given else None
+    wr = ax.ax_range_f32(wd) if given else None
+    acc, y = ax.ax_conv2d_f32_ex(xd, wd, ax.lut_to_device(lut), s, p, xr, wr, relu=relu, round_mode=int(signed),
+                                 dilation=d, depthwise=dwise, signed=signed)
+    torch.cuda.synchronize()
+    ref = oracle.conv2d_f32_ex(x, w, lut, s, p, oracle.range_f32(x, relu), oracle.range_f32(w), relu=relu,
+                               round_mode=int(signed), dilation=d, depthwise=dwise, signed=signed)
+    G.assert_parity(acc.cpu().numpy(), y.cpu().numpy(), ref["acc"], ref["y"], str(case))
+    np.testing.assert_array_equal(y.cpu().numpy(), ref["y"])
