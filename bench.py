@@ -242,6 +242,8 @@ def main():
         dt = time.perf_counter() - t
         cmacs = sum(l.macs for l in cl)
         cpu = {"value": cmacs / dt, "unit": "LUT-MAC/s", "cores": oracle.threads(), "kind": "oracle",
+               "per_core": cmacs / dt / max(1, oracle.threads()),
+               "gpu_over_oracle": (total_macs / (ms_per_step * 1e-3)) / (cmacs / dt),
                "sample": "all 54 layers of the same workload at batch %d (%.2f G lookups, %.1f s)" % (
                    args.cpu_batch, cmacs / 1e9, dt),
                "images_per_s": args.cpu_batch / dt}
@@ -294,6 +296,20 @@ def main():
         ms = time_calls(fns, 3)
         m4 = sum(l.macs for l in l4) * 64
         extra["config4_lut_sweep_64_tables"] = {"ms": ms, "lut_macs_per_s": m4 / ms * 1e3, "tables_per_s": 64 / ms * 1e3}
+        # the same, with every table's 128 KB host-to-device copy (from pinned host memory) inside the
+        # timed region, enqueued on the same stream in front of the table's two layer calls
+        host_luts = [torch.from_numpy(np.ascontiguousarray(I.lut_random_error(sd)).reshape(-1).view(np.int16).copy())
+                     .pin_memory() for sd in range(64)]
+        stage = torch.empty(65536, dtype=torch.int16, device=dev)
+
+        def with_upload(h):
+            stage.copy_(h, non_blocking=True)
+            for c in c4:
+                c(stage)
+
+        ms = time_calls([(lambda h=h: with_upload(h)) for h in host_luts], 3)
+        extra["config4_lut_sweep_64_tables_upload_in_timing"] = {"ms": ms, "lut_macs_per_s": m4 / ms * 1e3,
+                                                                 "tables_per_s": 64 / ms * 1e3}
         # the same sweep through ax_conv2d_multi_lut: one call per layer for all 64 tables (operands
         # prepared once, the tiles of all tables share one grid)
         luts_all = torch.stack(luts)
@@ -316,6 +332,18 @@ def main():
         ms = time_calls([make_call(l, I.layer_seed(5, i), lut_d) for i, l in enumerate(l5)], 20)
         m5 = sum(l.macs for l in l5)
         extra["config5_gemm_shaped"] = {"ms": ms, "lut_macs_per_s": m5 / ms * 1e3}
+        # run time must not depend on the table's content, but it does depend on the operands'
+        # distribution (LDS bank conflicts): the same two layers with the exact table, and one 3x3
+        # layer with uniform codes against ReLU-distributed codes (about half of them equal)
+        lut_exact_d = ax.lut_to_device(I.lut_exact())
+        ms_exact = time_calls([make_call(l, I.layer_seed(5, i), lut_exact_d) for i, l in enumerate(l5)], 20)
+        extra["config5_gemm_shaped"]["ms_exact_table"] = ms_exact
+        dep = {}
+        for dist in ("uniform", "relu"):
+            ld = I.Layer("dep." + dist, args.batch, 28, 28, 128, 3, 3, 128, 1, 1, x_dist=dist,
+                         w_dist="uniform" if dist == "uniform" else "normal")
+            dep[dist] = time_calls([make_call(ld, 99, lut_d)], 20)
+        extra["operand_distribution_3x3_28x28x128"] = {"ms_uniform_codes": dep["uniform"], "ms_relu_codes": dep["relu"]}
 
         # operator variants: one ResNet-50 3x3 layer in unsigned, signed and dilated form, and two
         # depthwise layers of MobileNet size (whole table in LDS, HBM-bound on the outputs)
@@ -452,6 +480,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "parity_sampled": parity,
+        "paper_context": "the paper reports about 200x for its GPU version (GTX 1080) over its optimized CPU version "
+                         "(Xeon E5-2620) on CIFAR-10 ResNets; other hardware and workload, not a target",
         "other_workloads": extra,
         "float_layer": float_layer,
         "wall_s_timed_region": wall,

@@ -84,6 +84,26 @@ def test_config4_lut_sweep_layers_batch64():
             _check_sampled(layer, x, w, lut, q, acc, y, rng, "%s lut %d" % (layer.name, lut_seed))
 
 
+def test_config4_all_64_tables_sampled_one_call_per_layer():
+    """Both layers of the table sweep at batch 64 against all 64 tables (one multi-table call per
+    layer), a handful of outputs of every table checked one by one by the oracle."""
+    rng = np.random.default_rng(464)
+    tabs = [np.ascontiguousarray(I.lut_random_error(sd)).reshape(-1) for sd in range(64)]
+    luts_d = torch.stack([ax.lut_to_device(t) for t in tabs])
+    for i, layer in enumerate(I.config_lut_sweep(batch=64)):
+        x, w, q = I.make_operands(layer, I.layer_seed(4, i))
+        acc, y = ax.ax_conv2d_multi_lut(G.to_dev(x), G.to_dev(w), luts_d, layer.stride, layer.pad, q)
+        torch.cuda.synchronize()
+        n_out = layer.M * layer.Cout
+        for t in range(64):
+            idx = np.concatenate([rng.integers(0, n_out, size=24), np.array([0, n_out - 1])]).astype(np.int64)
+            a_ref, y_ref = oracle.conv2d_sample(x, w, tabs[t], layer.stride, layer.pad, q, idx)
+            ti = torch.from_numpy(idx).cuda()
+            G.assert_parity(acc[t].reshape(-1)[ti].cpu().numpy(), y[t].reshape(-1)[ti].cpu().numpy(), a_ref, y_ref,
+                            "%s table %d" % (layer.name, t))
+        del acc, y
+
+
 def test_config5_gemm_shaped_exact_table_is_integer_gemm():
     rng = np.random.default_rng(505)
     exact, trunc = I.lut_exact(), I.lut_truncated(6)
