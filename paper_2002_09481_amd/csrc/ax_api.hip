@@ -220,7 +220,7 @@ extern "C" const char* ax_strerror(int code) {
   }
 }
 
-extern "C" int ax_version(void) { return 100; }
+extern "C" int ax_version(void) { return 200; }
 
 extern "C" int ax_set_option(const char* name, int value) {
   if (!name) return AX_ERR_OPTION;
