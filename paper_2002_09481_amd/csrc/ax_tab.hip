@@ -942,7 +942,7 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   int v = o.variant;
   if (v != 2 && v != 3) {
     auto fill = [](long long n) { return (double)n / ((double)cdiv(n, 2048) * 2048.0); };
-    v = (fill(g.Cout) > fill(g.M) + 0.15) ? 3 : 2;
+    v = (fill(g.Cout) > fill(g.M) + 0.30) ? 3 : 2;
   }
   // Tile and grid: the forced tile, else the cheaper of the two 2048-lane tiles by the cost model.
   PlanChoice best{0, 0, 0, 0, 0, 0, 1e30};
