@@ -287,6 +287,26 @@ def main():
         ms = time_calls([make_call(l, I.layer_seed(2, i), lut2) for i, l in enumerate(l2)], 50)
         m2 = sum(l.macs for l in l2)
         extra["config2_cifar_stack_b128"] = {"ms": ms, "lut_macs_per_s": m2 / ms * 1e3, "images_per_s": 128 / ms * 1e3}
+        # the same seven calls captured once into a HIP graph and replayed (the calls only enqueue
+        # kernels, so nothing but launch overhead changes)
+        try:
+            c2 = [make_call(l, I.layer_seed(2, i), lut2) for i, l in enumerate(l2)]
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for f in c2:
+                    f()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2):
+                for f in c2:
+                    f()
+            ms_g = time_calls([g2.replay], 50)
+            extra["config2_cifar_stack_b128"]["ms_hip_graph_replay"] = ms_g
+            del g2, c2
+        except Exception as e:  # capture support is not needed for any other number
+            extra["config2_cifar_stack_b128"]["ms_hip_graph_replay"] = "capture failed: %s" % e
         # config 4: two layers against 64 tables back to back (tables resident in HBM; every call
         # re-lays-out and re-stages its table)
         l4 = I.config_lut_sweep(64)
