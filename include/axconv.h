@@ -232,8 +232,10 @@ int ax_version(void);
  *              taps per barrier)
  *   "row_tiles" 0 = choose automatically how many tiles the lane dimension is cut into (default),
  *              1 = as few as fit, n >= 2 = n tiles (clamped to what the layer allows)
- *   "timing"   1 = record a HIP event pair around the main kernel of every layer call on
- *              the call's stream (see ax_last_kernel_ms); 0 = off (default)
+ *   "timing"   n in 1..16 = record a HIP event pair around n back-to-back launches of the main
+ *              kernel of every layer call on the call's stream (see ax_last_kernel_ms; the
+ *              repeats rewrite the same results and only dilute the events' own cost);
+ *              0 = off (default)
  * Returns AX_OK or AX_ERR_OPTION.  Not thread safe with respect to concurrent calls.
  */
 int ax_set_option(const char* name, int value);
@@ -247,8 +249,8 @@ int ax_conv2d_plan(int N, int H, int W, int Cin, int KH, int KW, int Cout, int s
                    int stride_w, int pad_h, int pad_w, int* variant, int* tile, int* workgroups,
                    int* pieces);
 
-/* Duration in milliseconds of the main kernel of the most recent layer call made while the
- * "timing" option was on (operand preparation and the K-slice reduction are not included).
+/* Duration in milliseconds of one launch of the main kernel of the most recent layer call made
+ * while the "timing" option was on (operand preparation and the K-slice reduction are not included).
  * Waits for that kernel to finish.  AX_ERR_OPTION if no timed call has been made. */
 int ax_last_kernel_ms(float* ms);
 

@@ -10,6 +10,7 @@ Options g_opt = {0, 0, 0, 0, 0};
 
 static hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
 static bool g_ev_valid = false;
+static int g_ev_reps = 1;  // launches of the main kernel between the two events
 
 void timing_begin(hipStream_t s) {
   if (!g_opt.timing) return;
@@ -20,9 +21,10 @@ void timing_begin(hipStream_t s) {
   g_ev_valid = hipEventRecord(g_ev0, s) == hipSuccess;
 }
 
-void timing_end(hipStream_t s) {
+void timing_end(hipStream_t s, int reps) {
   if (!g_opt.timing || !g_ev0) return;
   g_ev_valid = g_ev_valid && hipEventRecord(g_ev1, s) == hipSuccess;
+  g_ev_reps = reps > 0 ? reps : 1;
 }
 
 // Unsigned codes: zero points and pad code in [0, 255], pad_code -1 (or AX_PAD_DEFAULT) = x_zp.
@@ -245,7 +247,7 @@ extern "C" int ax_set_option(const char* name, int value) {
     return AX_OK;
   }
   if (!std::strcmp(name, "timing")) {
-    if (value < 0 || value > 1) return AX_ERR_OPTION;
+    if (value < 0 || value > 16) return AX_ERR_OPTION;
     g_opt.timing = value;
     return AX_OK;
   }
@@ -267,7 +269,9 @@ extern "C" int ax_last_kernel_ms(float* ms) {
   if (!ms) return AX_ERR_NULL;
   if (!g_ev_valid || !g_ev0) return AX_ERR_OPTION;
   if (hipEventSynchronize(g_ev1) != hipSuccess) return AX_ERR_HIP;
-  return hipEventElapsedTime(ms, g_ev0, g_ev1) == hipSuccess ? AX_OK : AX_ERR_HIP;
+  if (hipEventElapsedTime(ms, g_ev0, g_ev1) != hipSuccess) return AX_ERR_HIP;
+  *ms /= (float)g_ev_reps;
+  return AX_OK;
 }
 
 extern "C" int ax_conv2d_plan(int N, int H, int W, int Cin, int KH, int KW, int Cout, int stride_h, int stride_w,

@@ -53,14 +53,14 @@ struct Options {
   int variant;  // 0 auto, 1 direct, 2 lanes over pixels, 3 lanes over channels
   int split_k;  // 0 auto
   int tile;     // index of the table-tile configuration (0 = default)
-  int timing;   // 1: bracket the main kernel of every call with HIP events
+  int timing;   // n >= 1: bracket n back-to-back launches of the main kernel of every call with HIP events
   int row_tiles;  // 0 auto, 1 as few tiles along the lane dimension as fit, n that many (clamped)
 };
 extern Options g_opt;
 
 // Event pair around the most recent main-kernel launch (only when g_opt.timing is set).
 void timing_begin(hipStream_t s);
-void timing_end(hipStream_t s);
+void timing_end(hipStream_t s, int reps = 1);
 
 // Direct kernel (ax_direct.hip): needs no workspace.
 hipError_t launch_direct(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w,
