@@ -89,6 +89,13 @@ __device__ __forceinline__ void add_halves(uint32_t& acc_lo, uint32_t& acc_hi, u
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Position of workgroup b of a grid of G when the workgroups are listed XCD by XCD (workgroup b
+// runs on XCD b % 8): a bijection of 0 .. G-1.
+__device__ __forceinline__ int xcd_major(int b, int G) {
+  const int x = b & 7, q = G >> 3, r = G & 7;
+  return x * q + min(x, r) + (b >> 3);
+}
+
 __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
   const uint32_t w = (kk < 4) ? v.x : (kk < 8) ? v.y : (kk < 12) ? v.z : v.w;
   return (w >> (8 * (kk & 3))) & 0xffu;
@@ -131,8 +138,12 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   const int klast = a.nch * kChunk;  // padded K = index of the last (zero) row of Bp
   // Taps K .. klast-1 exist only in materialized operands, where both codes are 0: each adds
   // the table entry (0,0) to every accumulator, which the final epilogue takes off again.
-  long long it_beg = (long long)blockIdx.x * a.total_iters / gridDim.x;
-  const long long it_end = (long long)(blockIdx.x + 1) * a.total_iters / gridDim.x;
+  // Workgroups go to the eight XCDs (each with its own L2) in turn.  The share of work is taken by
+  // a renumbered index under which every XCD holds a contiguous run of shares: neighbouring tiles
+  // read the same lane-side rows, which then come from one L2 instead of being fetched into eight.
+  const int wg = xcd_major((int)blockIdx.x, (int)gridDim.x);
+  long long it_beg = (long long)wg * a.total_iters / gridDim.x;
+  const long long it_end = (long long)(wg + 1) * a.total_iters / gridDim.x;
   __shared__ long long cterm[JT];  // column constants of the current tile, see the epilogue
 
   while (it_beg < it_end) {
@@ -379,7 +390,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   if (!whole) {
     // Piece of a tile that several workgroups share: stored column-major ([column][lane
     // element]) so that consecutive lanes write consecutive words straight from their registers.
-    const int slot = 2 * (int)blockIdx.x + (c_beg > 0 ? 0 : 1);
+    const int slot = 2 * wg + (c_beg > 0 ? 0 : 1);
     int32_t* part = a.part + (size_t)slot * (IT * JT);
     int32_t* lsum = a.lsum + (size_t)slot * IT;
 #pragma unroll
