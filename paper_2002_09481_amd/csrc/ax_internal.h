@@ -81,6 +81,7 @@ struct TabPlan {
   int partials;     // partial tile pieces that grid produces (0: no fix-up pass)
   int nti;          // tiles along the lane dimension
   int ih;           // their height in lane elements (multiple of 64, nti * ih >= I)
+  int xcd;          // 1: shares of work numbered XCD by XCD, 0: in launch order
   size_t off_rows;  // workspace offsets (bytes)
   size_t off_bpack;
   size_t off_bsum;

@@ -72,6 +72,7 @@ struct TabArgs {
   long long out_elems;   // outputs per table (M * Cout)
   int ntiles1;           // tiles of one table; tile index space = table * ntiles1 + tile (several tables: ax_conv2d_multi_lut)
   int vec_out;  // outputs may be written in aligned 16-byte pieces along j
+  int xcd;      // 1: shares of work are numbered XCD by XCD (see xcd_major), 0: in launch order
 };
 
 // acc_lo += low half of e, acc_hi += high half of e.  Written as instructions because the
@@ -138,10 +139,12 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   const int klast = a.nch * kChunk;  // padded K = index of the last (zero) row of Bp
   // Taps K .. klast-1 exist only in materialized operands, where both codes are 0: each adds
   // the table entry (0,0) to every accumulator, which the final epilogue takes off again.
-  // Workgroups go to the eight XCDs (each with its own L2) in turn.  The share of work is taken by
-  // a renumbered index under which every XCD holds a contiguous run of shares: neighbouring tiles
-  // read the same lane-side rows, which then come from one L2 instead of being fetched into eight.
-  const int wg = xcd_major((int)blockIdx.x, (int)gridDim.x);
+  // Workgroups go to the eight XCDs (each with its own L2) in turn.  With a.xcd the share of work
+  // is taken by a renumbered index under which every XCD holds a contiguous run of shares:
+  // neighbouring tiles read the same lane-side rows, which then come from one L2 instead of being
+  // fetched into eight.  (Where tiles are cut into a multiple of eight shares the launch order
+  // already gives every XCD one slice of K of all tiles; the planner picks per layer.)
+  const int wg = a.xcd ? xcd_major((int)blockIdx.x, (int)gridDim.x) : (int)blockIdx.x;
   long long it_beg = (long long)wg * a.total_iters / gridDim.x;
   const long long it_end = (long long)(wg + 1) * a.total_iters / gridDim.x;
   __shared__ long long cterm[JT];  // column constants of the current tile, see the epilogue
@@ -926,6 +929,40 @@ static PlanChoice plan_choice_nti(const Geom& g, int tile, int v, int forced_spl
 
 static TabPlan tab_plan_uncached(const Geom& g, const Options& o);
 
+// Operand bytes that the eight L2s fetch in total when share w of G (iterations w*total/G ..) runs
+// on XCD w % 8 (xcd = 0) or when the shares are dealt out XCD by XCD (xcd = 1): per XCD the
+// distinct (lane tile, chunk) and (column tile, chunk) pairs its shares touch.  The tables of a
+// multi-table call share both operands.
+static double xcd_fetch_bytes(int xcd, int G, int nti, int ntj, int nch, int T, int ih, int jt) {
+  const long long total = (long long)nti * ntj * nch * T;
+  std::vector<uint8_t> seen_a((size_t)nti * nch), seen_b((size_t)ntj * nch);
+  const int q = G >> 3, r = G & 7;
+  double bytes = 0.0;
+  for (int x = 0; x < 8; ++x) {
+    std::fill(seen_a.begin(), seen_a.end(), 0);
+    std::fill(seen_b.begin(), seen_b.end(), 0);
+    long long na = 0, nb = 0;
+    const int w0 = xcd ? x * q + std::min(x, r) : x;
+    const int nw = q + (x < r ? 1 : 0);
+    for (int k = 0; k < nw; ++k) {
+      const int w = xcd ? w0 + k : x + 8 * k;
+      const long long b = (long long)w * total / G, e = (long long)(w + 1) * total / G;
+      for (long long it = b; it < e; ++it) {
+        const long long gt = it / nch;
+        const int ch = (int)(it - gt * nch);
+        const int tile = (int)(gt % ((long long)nti * ntj));
+        const int ti = tile / ntj, tj = tile - ti * ntj;
+        uint8_t& sa = seen_a[(size_t)ti * nch + ch];
+        uint8_t& sb = seen_b[(size_t)tj * nch + ch];
+        na += !sa; sa = 1;
+        nb += !sb; sb = 1;
+      }
+    }
+    bytes += 16.0 * ((double)na * ih + (double)nb * jt);
+  }
+  return bytes;
+}
+
 // Planning walks over candidate grids and counts their partial pieces, which takes tens of
 // microseconds: as much as a small layer's kernels.  Plans are therefore remembered per
 // (geometry, options); the table is small and cleared when it grows past a bound.
@@ -969,6 +1006,17 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   p.nti = best.nti;
   p.ih = best.ih;
   const TileCfg& tc = kTiles[best.tile];
+  {
+    // numbering of the shares: whichever lets the XCDs' L2s fetch less (ties and very large
+    // iteration spaces, not worth walking: XCD by XCD)
+    const int ntj = cdiv((v == 2) ? g.Cout : g.M, tc.NG * 8), nchk = cdiv(g.K, kChunk);
+    p.xcd = 1;
+    if ((long long)p.nti * ntj * nchk * g.T <= (1LL << 22) && best.G >= 16) {
+      const double f1 = xcd_fetch_bytes(1, best.G, p.nti, ntj, nchk, g.T, p.ih, tc.NG * 8);
+      const double f0 = xcd_fetch_bytes(0, best.G, p.nti, ntj, nchk, g.T, p.ih, tc.NG * 8);
+      if (f0 < 0.9 * f1) p.xcd = 0;
+    }
+  }
   const int G = best.G;
   const long long I = (v == 2) ? g.M : g.Cout;
   const long long J = (v == 2) ? g.Cout : g.M;
@@ -1100,6 +1148,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.part = reinterpret_cast<int32_t*>(wsb + p.off_part);
   a.lsum = reinterpret_cast<int32_t*>(wsb + p.off_lsum);
   a.out_elems = (long long)g.M * g.Cout;
+  a.xcd = p.xcd;
   a.vec_out = (!ch && J % 4 == 0 && (((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
 
   const bool fixup = p.partials > 0;
