@@ -295,6 +295,30 @@ def main():
             "ms": ms_k, "lut_macs_per_s": m2k / ms_k * 1e3, "images_per_s": 1000 / ms_k * 1e3,
             "context": "the paper's ResNet-8 (7 conv layers, 21 M MACs per image) took 1.5 s for 10^4 CIFAR-10 images "
                        "on a GTX 1080, about 0.14 T lookup-MAC/s; another network, machine and decade: context only"}
+        # the stack chained from float tensors: every layer takes the ranges of its input (after
+        # ReLU) and of its filters, quantizes both, runs the lookup-MAC convolution and hands its
+        # float output to the next layer; nothing returns to the host in between
+        try:
+            xf0, _ = I.make_float_operands(l2k[0], I.layer_seed(2, 0))
+            xf = torch.from_numpy(xf0).to(dev)
+            wf = [torch.from_numpy(I.make_float_operands(l, I.layer_seed(2, i))[1]).to(dev) for i, l in enumerate(l2k)]
+            yf = [torch.empty((l.N, l.OH, l.OW, l.Cout), dtype=torch.float32, device=dev) for l in l2k]
+            wsf = [torch.empty(ax.ax_conv2d_f32_workspace_bytes((l.N, l.H, l.W, l.Cin), (l.KH, l.KW, l.Cin, l.Cout),
+                                                                l.stride, l.pad), dtype=torch.uint8, device=dev)
+                   for l in l2k]
+
+            def chained():
+                cur = xf
+                for i, l in enumerate(l2k):
+                    ax.ax_conv2d_f32(cur, wf[i], lut2, l.stride, l.pad, None, None, relu=i > 0, acc_out=False,
+                                     y_out=yf[i], workspace=wsf[i])
+                    cur = yf[i]
+            ms_c = time_calls([chained], 10)
+            extra["config2_cifar_stack_b1000_chained_float"] = {
+                "ms": ms_c, "lut_macs_per_s": m2k / ms_c * 1e3, "images_per_s": 1000 / ms_c * 1e3,
+                "note": "float32 in, seven chained layers with ReLU, ranges and quantization on the device"}
+        except Exception as e:  # never lose the main line
+            extra["config2_cifar_stack_b1000_chained_float"] = {"error": repr(e)}
         # the same seven calls captured once into a HIP graph and replayed (the calls only enqueue
         # kernels, so nothing but launch overhead changes)
         try:
