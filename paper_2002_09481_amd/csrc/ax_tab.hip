@@ -75,21 +75,31 @@ struct TabArgs {
   int xcd;      // 1: shares of work are numbered XCD by XCD (see xcd_major), 0: in launch order
 };
 
-// Accumulate the two 16-bit products l (low half) and h (high half) of e.  Every instruction
-// that adds one half of a register (sub-dword select, 16-bit dot product, multiply-add) issues at
-// half the rate of a plain 32-bit add, so the pair is accumulated in a different basis instead:
-//   acc_b += e            = l + 65536 h   (plain add, full rate)
-//   acc_a += l + h                        (sum of absolute differences against 0, half rate)
+// Accumulate the eight 16-bit products of one gathered entry (four registers, each with a
+// product l in its low and a product h in its high half) into eight accumulators.  Every
+// instruction that adds one half of a register (sub-dword select, 16-bit dot product,
+// multiply-add) issues at half the rate of a plain 32-bit add, so each pair is accumulated in a
+// different basis instead:
+//   b += e        = l + 65536 h   (plain add, full rate)
+//   a += l + h                    (sum of absolute differences against 0, half rate)
 // both modulo 2^32.  Since 65535 is odd the two sums determine both column sums exactly
-// (split_sums below); measured 37 T lookups/s against 33 T for two half-selecting adds.  Written
-// as instructions because the optimizer otherwise regroups each accumulator's chain of adds
-// across a whole unrolled chunk into a tree, which keeps every gathered value alive at once.
-__device__ __forceinline__ void add_halves(uint32_t& acc_b, uint32_t& acc_a, uint32_t e) {
+// (split_sums below).  The four adds go first and the four sums after them: alternating between
+// the two kinds costs issue cycles (measured 39 T lookups/s grouped, 33 T alternating, 32 T for
+// eight 16-bit dot products).  Written as instructions because the optimizer otherwise regroups
+// each accumulator's chain of adds across a whole unrolled chunk into a tree, which keeps every
+// gathered value alive at once.
+__device__ __forceinline__ void add_entry(uint32_t (&a)[8], const uint4& e) {
   asm volatile(
-      "v_add_u32 %0, %2, %0\n\t"
-      "v_sad_u16 %1, %2, 0, %1"
-      : "+v"(acc_b), "+v"(acc_a)
-      : "v"(e));
+      "v_add_u32 %0, %8, %0\n\t"
+      "v_add_u32 %2, %9, %2\n\t"
+      "v_add_u32 %4, %10, %4\n\t"
+      "v_add_u32 %6, %11, %6\n\t"
+      "v_sad_u16 %1, %8, 0, %1\n\t"
+      "v_sad_u16 %3, %9, 0, %3\n\t"
+      "v_sad_u16 %5, %10, 0, %5\n\t"
+      "v_sad_u16 %7, %11, 0, %7"
+      : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+      : "v"(e.x), "v"(e.y), "v"(e.z), "v"(e.w));
 }
 // From B = L + 65536 H and A = L + H (mod 2^32) to L and H, the sums of the low and of the high
 // halves (each below 2^31): A - B = -65535 H and -65535 * -65537 = 1 (mod 2^32).
@@ -258,13 +268,13 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   };
 
   // ---- main loop -----------------------------------------------------------------------
-  uint32_t acc[P][JT];
+  uint32_t accg[P][NG][8];  // per lane element and column group; acc[p][j] below names column j
   uint32_t sl[P];
 #pragma unroll
   for (int p = 0; p < P; ++p) {
     sl[p] = 0;
 #pragma unroll
-    for (int j = 0; j < JT; ++j) acc[p][j] = 0;
+    for (int j = 0; j < JT; ++j) accg[p][j >> 3][j & 7] = 0;
   }
 
   uint4 xa[P], xn[P];
@@ -380,10 +390,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
             if (i + DEPTH < NR) issue(i + DEPTH);
             const int g = i % NG;
             const uint4 e = ring[i % (DEPTH + 1)];
-            add_halves(acc[p][g * 8 + 0], acc[p][g * 8 + 1], e.x);
-            add_halves(acc[p][g * 8 + 2], acc[p][g * 8 + 3], e.y);
-            add_halves(acc[p][g * 8 + 4], acc[p][g * 8 + 5], e.z);
-            add_halves(acc[p][g * 8 + 6], acc[p][g * 8 + 7], e.w);
+            add_entry(accg[p][g], e);
           }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -395,11 +402,16 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     }
   }
 
-  // the accumulator pairs held (B, A) so far: back to the column sums
+  // the accumulator pairs held (l + 65536 h, l + h) so far: back to the column sums
+  uint32_t acc[P][JT];
 #pragma unroll
   for (int p = 0; p < P; ++p)
 #pragma unroll
-    for (int j = 0; j < JT; j += 2) split_sums(acc[p][j], acc[p][j + 1]);
+    for (int j = 0; j < JT; j += 2) {
+      acc[p][j + 1] = accg[p][j >> 3][(j & 7) + 1];
+      acc[p][j] = accg[p][j >> 3][j & 7];
+      split_sums(acc[p][j], acc[p][j + 1]);
+    }
 
   // ---- epilogue ------------------------------------------------------------------------
   // corr = acc - z_tab*Sl - z_lane*Sb[j] + K*z_lane*z_tab.  Each of the four terms is below
