@@ -232,6 +232,9 @@ int ax_version(void);
  *              taps per barrier)
  *   "row_tiles" 0 = choose automatically how many tiles the lane dimension is cut into (default),
  *              1 = as few as fit, n >= 2 = n tiles (clamped to what the layer allows)
+ *   "share_order" 0 = choose automatically how workgroups take their shares of the work (default),
+ *              1 = in launch order, 2 = XCD by XCD (every XCD, with its own L2, gets a contiguous
+ *              run of tiles); results do not depend on it
  *   "timing"   n in 1..16 = record a HIP event pair around n back-to-back launches of the main
  *              kernel of every layer call on the call's stream (see ax_last_kernel_ms; the
  *              repeats rewrite the same results and only dilute the events' own cost);

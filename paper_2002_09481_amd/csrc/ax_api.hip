@@ -6,7 +6,7 @@
 
 namespace ax {
 
-Options g_opt = {0, 0, 0, 0, 0};
+Options g_opt = {0, 0, 0, 0, 0, 0};
 
 static hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
 static bool g_ev_valid = false;
@@ -119,7 +119,7 @@ size_t layer_workspace(const Geom& g) {
   if (!tab_supported(g)) return 256;
   size_t need = 256;
   for (int v = 2; v <= 3; ++v) {
-    Options o = {v, g_opt.split_k, g_opt.tile, 0, g_opt.row_tiles};
+    Options o = {v, g_opt.split_k, g_opt.tile, 0, g_opt.row_tiles, g_opt.share_order};
     const size_t t = tab_plan(g, o).total;
     if (t > need) need = t;
   }
@@ -246,6 +246,11 @@ extern "C" int ax_set_option(const char* name, int value) {
     g_opt.row_tiles = value;
     return AX_OK;
   }
+  if (!std::strcmp(name, "share_order")) {
+    if (value < 0 || value > 2) return AX_ERR_OPTION;
+    g_opt.share_order = value;
+    return AX_OK;
+  }
   if (!std::strcmp(name, "timing")) {
     if (value < 0 || value > 16) return AX_ERR_OPTION;
     g_opt.timing = value;
@@ -262,6 +267,7 @@ extern "C" int ax_get_option(const char* name, int* value) {
   if (!std::strcmp(name, "tile")) { *value = g_opt.tile; return AX_OK; }
   if (!std::strcmp(name, "timing")) { *value = g_opt.timing; return AX_OK; }
   if (!std::strcmp(name, "row_tiles")) { *value = g_opt.row_tiles; return AX_OK; }
+  if (!std::strcmp(name, "share_order")) { *value = g_opt.share_order; return AX_OK; }
   return AX_ERR_OPTION;
 }
 

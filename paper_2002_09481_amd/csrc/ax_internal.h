@@ -55,6 +55,7 @@ struct Options {
   int tile;     // index of the table-tile configuration (0 = default)
   int timing;   // n >= 1: bracket n back-to-back launches of the main kernel of every call with HIP events
   int row_tiles;  // 0 auto, 1 as few tiles along the lane dimension as fit, n that many (clamped)
+  int share_order;  // numbering of the work shares: 0 auto, 1 launch order, 2 XCD by XCD
 };
 extern Options g_opt;
 

@@ -997,13 +997,13 @@ static double xcd_fetch_bytes(int xcd, int G, int nti, int ntj, int nch, int T, 
 // (geometry, options); the table is small and cleared when it grows past a bound.
 TabPlan tab_plan(const Geom& g, const Options& o) {
   struct Key {
-    int v[21];
+    int v[22];
     bool operator<(const Key& other) const { return std::memcmp(v, other.v, sizeof(v)) < 0; }
   };
   static std::mutex mu;
   static std::map<Key, TabPlan> cache;
   const Key k{{g.N, g.H, g.W, g.Cin, g.KH, g.KW, g.Cout, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.sgn, g.mult, o.variant,
-               o.split_k, o.tile, o.row_tiles, cu_count(), g.T}};
+               o.split_k, o.tile, o.row_tiles, cu_count(), g.T, o.share_order}};
   std::lock_guard<std::mutex> lock(mu);
   auto it = cache.find(k);
   if (it != cache.end()) return it->second;
@@ -1040,7 +1040,9 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
     // iteration spaces, not worth walking: XCD by XCD)
     const int ntj = cdiv((v == 2) ? g.Cout : g.M, tc.NG * 8), nchk = cdiv(g.K, kChunk);
     p.xcd = 1;
-    if ((long long)p.nti * ntj * nchk * g.T <= (1LL << 22) && best.G >= 16) {
+    if (o.share_order) {
+      p.xcd = o.share_order - 1;
+    } else if ((long long)p.nti * ntj * nchk * g.T <= (1LL << 22) && best.G >= 16) {
       const double f1 = xcd_fetch_bytes(1, best.G, p.nti, ntj, nchk, g.T, p.ih, tc.NG * 8);
       const double f0 = xcd_fetch_bytes(0, best.G, p.nti, ntj, nchk, g.T, p.ih, tc.NG * 8);
       if (f0 < 0.9 * f1) p.xcd = 0;

@@ -41,6 +41,12 @@ def test_host_side_calls_without_gpu():
         binding.ax_set_option("variant", 99)
     with pytest.raises(binding.AxError):
         binding.ax_set_option("no_such_option", 1)
+    for name, top in (("share_order", 2), ("timing", 16), ("row_tiles", 1 << 20)):
+        binding.ax_set_option(name, top)
+        assert binding.ax_get_option(name) == top
+        with pytest.raises(binding.AxError):
+            binding.ax_set_option(name, top + 1)
+        binding.ax_set_option(name, 0)
     # workspace queries are pure host arithmetic
     assert binding.ax_conv2d_workspace_bytes((1, 16, 16, 8), (3, 3, 8, 8), 1, 1) >= 256
     assert binding.ax_dense_workspace_bytes(32, 2048, 1000) >= 256

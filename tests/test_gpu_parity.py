@@ -23,6 +23,7 @@ def _reset_options():
     ax.ax_set_option("split_k", 0)
     ax.ax_set_option("tile", 0)
     ax.ax_set_option("row_tiles", 0)
+    ax.ax_set_option("share_order", 0)
 
 
 def L(N, H, W, Cin, KH, KW, Cout, s=1, p=0, dense=False, x_dist="uniform", w_dist="uniform", name=None):
@@ -94,6 +95,22 @@ def test_forced_row_tile_counts(variant, rows):
     G.check_layer(L(1, 20, 20, 48, 1, 1, 30, 2, 0), 42, lut)
     ax.ax_set_option("split_k", 2)
     G.check_layer(L(1, 64, 64, 64, 3, 3, 40, 1, 1), 43, lut)
+
+
+@pytest.mark.parametrize("variant", [2, 3])
+@pytest.mark.parametrize("order", [1, 2])
+@pytest.mark.parametrize("split_k", [0, 1, 3, 8])
+def test_share_numberings(variant, order, split_k):
+    """Workgroups take their shares of the (tile, chunk) space in launch order or XCD by XCD;
+    grids that are and are not multiples of eight, with and without shared tiles."""
+    ax.ax_set_option("variant", variant)
+    ax.ax_set_option("share_order", order)
+    ax.ax_set_option("split_k", split_k)
+    lut = I.lut_random(29)
+    G.check_layer(L(3, 40, 41, 32, 3, 3, 72, 1, 1), 51, lut)           # 4920 pixels x 72 channels
+    G.check_layer(L(1, 20, 20, 48, 1, 1, 30, 2, 0), 52, lut)           # a single tile
+    G.check_layer(L(37, 1, 1, 600, 1, 1, 333, dense=True), 53, lut)
+    G.check_layer(L(2, 33, 33, 16, 5, 5, 24, 2, 2, x_dist="relu", w_dist="normal"), 54, I.lut_truncated(6))
 
 
 TILES = list(range(1, 8))
