@@ -742,6 +742,93 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
 
 // Materialized im2col, Ap[m][Kp] (zero fill for k >= K): used when the implicit view cannot be
 // read in aligned 16-byte pieces (Cin not a multiple of 16, or a misaligned base pointer).
+// Staged form of the same materialization for the usual case (few input channels, e.g. the
+// first layer of a network): a block takes kStripe consecutive output pixels of one output row
+// and copies the input rows they touch into LDS once (every input byte is used by about
+// KH*KW/(sh*sw) patches).  The position of a patch byte in that stage is the same for every pixel
+// up to a constant step, so the four offsets of each output dword are decoded once per block
+// (one table entry per dword of a patch); the block's part of Ap is contiguous and is then
+// written dword by dword, consecutive threads to consecutive addresses, with no division or
+// multiplication per element.  Used when both LDS areas are small enough (im2col_staged_fits).
+constexpr int kStripe = 32;
+static inline size_t im2col_row_bytes(const ConvView& cv) {
+  return (size_t)((kStripe - 1) * cv.sw + (cv.KW - 1) * cv.dw + 1) * cv.Cin;
+}
+static inline size_t im2col_stage_bytes(const ConvView& cv, int KH) { return (im2col_row_bytes(cv) * KH + 15) & ~(size_t)15; }
+static inline bool im2col_staged_fits(const ConvView& cv, int KH, int Kp) {
+  return im2col_stage_bytes(cv, KH) <= 16384 && Kp <= 4096;
+}
+__global__ __launch_bounds__(256) void prep_im2col_lds_kernel(ConvView cv, int KH, int Kp, int row_bytes, int stage_bytes,
+                                                              uint8_t* __restrict__ Ap) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  uint8_t* stage = smem;                                     // [KH][row_bytes] input bytes
+  int4* offtab = reinterpret_cast<int4*>(smem + stage_bytes);  // [Kp / 4] stage offsets of a dword's bytes, -1: zero
+  const uint32_t pad = pad_of(cv);
+  const int ox0 = blockIdx.x * kStripe, oy = blockIdx.y, n = blockIdx.z;
+  const int ix0 = ox0 * cv.sw - cv.pw;
+  // Byte b of a staged row is byte ix0 * Cin + b of the input row: in the image for
+  // lo_b <= b < hi_b, padding outside.
+  const int lo_b = max(0, -ix0) * cv.Cin;
+  const int hi_b = min(row_bytes, (cv.W - ix0) * cv.Cin);
+  // Eight filter rows at a time, every load unconditional and from an address clamped into the
+  // image (what lies outside is replaced afterwards): the loads of a thread are then issued back
+  // to back instead of one memory round trip per row.
+  const bool any_col = hi_b > lo_b;
+  for (int ky0 = 0; ky0 < KH && any_col; ky0 += 8) {
+    for (int b = threadIdx.x; b < row_bytes; b += 256) {
+      const bool col_in = b >= lo_b && b < hi_b;
+      const int bc = min(max(b, lo_b), hi_b - 1);
+      uint32_t v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int iy = oy * cv.sh - cv.ph + min(ky0 + j, KH - 1) * cv.dh;
+        const int iyc = min(max(iy, 0), cv.H - 1);
+        v[j] = cv.x[((long long)(n * cv.H + iyc) * cv.W + ix0) * cv.Cin + bc];
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int iy = oy * cv.sh - cv.ph + (ky0 + j) * cv.dh;
+        const bool in = col_in && (unsigned)iy < (unsigned)cv.H;
+        if (ky0 + j < KH) stage[(ky0 + j) * row_bytes + b] = (uint8_t)(in ? v[j] ^ cv.sx : pad);
+      }
+    }
+  }
+  if (!any_col)  // the whole stripe reads padding columns only
+    for (int idx = threadIdx.x; idx < KH * row_bytes; idx += 256) stage[idx] = (uint8_t)pad;
+  const int ndw = Kp / 4;
+  for (int j = threadIdx.x; j < ndw; j += 256) {
+    int o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int k = 4 * j + e;
+      const int tap = k / cv.Cin, ci = k - tap * cv.Cin;
+      const int ky = tap / cv.KW, kx = tap - ky * cv.KW;
+      o[e] = k < cv.K ? ky * row_bytes + kx * cv.dw * cv.Cin + ci : -1;
+    }
+    offtab[j] = make_int4(o[0], o[1], o[2], o[3]);
+  }
+  __syncthreads();
+  const int npix = min(kStripe, cv.OW - ox0);
+  const int pix_step = cv.sw * cv.Cin;  // stage bytes between neighbouring output pixels
+  uint32_t* dst = reinterpret_cast<uint32_t*>(Ap + (((size_t)n * cv.OH + oy) * cv.OW + ox0) * Kp);
+  // element idx = pixel * ndw + j, walked in steps of 256 without dividing again
+  int oxl = threadIdx.x / ndw, j = threadIdx.x - oxl * ndw;
+  const int d_ox = 256 / ndw, d_j = 256 - d_ox * ndw;
+  for (int idx = threadIdx.x; idx < npix * ndw; idx += 256) {
+    const int4 o = offtab[j];
+    const int base = oxl * pix_step;
+    uint32_t v = 0;
+    if (o.x >= 0) v = stage[o.x + base];
+    if (o.y >= 0) v |= (uint32_t)stage[o.y + base] << 8;
+    if (o.z >= 0) v |= (uint32_t)stage[o.z + base] << 16;
+    if (o.w >= 0) v |= (uint32_t)stage[o.w + base] << 24;
+    dst[idx] = v;
+    oxl += d_ox;
+    j += d_j;
+    if (j >= ndw) { j -= ndw; ++oxl; }
+  }
+}
+
 // One thread per 16-byte piece: the pixel is decoded once and the tap index advanced
 // incrementally; consecutive threads write consecutive pieces.
 __global__ __launch_bounds__(256) void prep_im2col_kernel(ConvView cv, int Kp, uint8_t* __restrict__ Ap) {
@@ -1160,8 +1247,15 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
     a.OHW = g.OH * g.OW; a.OW = g.OW;
     a.dh = g.dh; a.dw = g.dw;
   } else {
-    const long long pieces = (long long)g.M * (Kp / 16);
-    hipLaunchKernelGGL(prep_im2col_kernel, dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, s, cv, Kp, Ap);
+    if (im2col_staged_fits(cv, g.KH, Kp) && g.OH <= 65535 && g.N <= 65535) {
+      const size_t stage_bytes = im2col_stage_bytes(cv, g.KH);
+      hipLaunchKernelGGL(prep_im2col_lds_kernel, dim3(cdiv(g.OW, kStripe), g.OH, g.N), dim3(256),
+                         (unsigned)(stage_bytes + (size_t)Kp * 4), s, cv, g.KH, Kp, (int)im2col_row_bytes(cv),
+                         (int)stage_bytes, Ap);
+    } else {
+      const long long pieces = (long long)g.M * (Kp / 16);
+      hipLaunchKernelGGL(prep_im2col_kernel, dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, s, cv, Kp, Ap);
+    }
     a.A = Ap;
     a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
     a.dh = 1; a.dw = 1;

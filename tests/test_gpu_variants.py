@@ -71,6 +71,29 @@ def test_dilated_and_signed_layers(case, signed, variant):
     _check(x, w, lut, s, p, d, q, what=str(case))
 
 
+MATERIALIZED = [
+    # patches copied out by the staged kernel (input rows in LDS) ...
+    ((3, 37, 70, 3, 7, 7, 16), 2, 3, 1),                   # stem-like, three stripes per row, the last ragged
+    ((2, 19, 33, 5, 3, 5, 8), (1, 2), (2, 0), (2, 3)),     # dilation, stride and padding differ per axis
+    ((1, 9, 150, 1, 1, 3, 8), 1, (0, 40), 1),              # stripes that read padding columns only
+    ((2, 16, 16, 24, 3, 3, 16), 1, 1, 1),                  # Cin % 16 == 8
+    ((1, 12, 12, 100, 7, 7, 8), 1, 3, 1),                  # ... and by the one-thread-per-piece kernel: long patch
+    ((1, 10, 10, 20, 3, 3, 8), 1, 40, 36),                 # widely dilated, still staged
+    ((1, 10, 10, 20, 3, 3, 8), 1, 150, 150),               # dilated beyond what the stage holds
+]
+
+
+@pytest.mark.parametrize("signed", [False, True])
+@pytest.mark.parametrize("case", MATERIALIZED, ids=lambda c: "x".join(map(str, c[0])) + "_d%s" % (c[3],))
+def test_materialized_patches(case, signed):
+    """Cin not a multiple of 16: the lane-side operand is written out by one of two kernels."""
+    shape, s, p, d = case
+    ax.ax_set_option("variant", 2)
+    x, w, q = _operands(shape, 300 + shape[3], signed)
+    lut = I.lut_signed_random(9) if signed else I.lut_random(9)
+    _check(x, w, lut, s, p, d, q, what=str(case))
+
+
 @pytest.mark.parametrize("table", ["exact", "random", "minimum"])
 @pytest.mark.parametrize("variant", [1, 2, 3])
 def test_signed_tables_of_either_sign(table, variant):
