@@ -527,7 +527,9 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
 // lane elements of one tile and all JT columns: thread (r = t & 63, cg = t >> 6) sums columns
 // cg*JT/4 .. of lane element r over the pieces (coalesced along r).  For pixel lanes the block
 // then turns the 64 x JT patch through LDS so that output rows are written in 16-byte pieces.
-template <int IT, int JT, bool CH>
+// MANY: the form for tiles cut into many pieces (see the piece loop); it needs more registers, so
+// it is a kernel of its own and the usual form keeps its occupancy.
+template <int IT, int JT, bool CH, bool MANY>
 __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) {
   constexpr int CPT = JT / 4;  // columns per thread
   const int gtile = blockIdx.x / (IT / 64);
@@ -564,7 +566,30 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
 #pragma unroll
   for (int c = 0; c < CPT; ++c) v[c] = 0u - padfix;
   uint32_t sl = 0;
-  for (int w = w_first; w <= w_last; ++w) {
+  int w = w_first;
+  // Many pieces (a short, wide layer cut into many K slices): four at a time, all their loads
+  // issued before the first add, so that the block does not pay one memory round trip per piece.
+  // With few pieces the plain loop below is faster.
+  if constexpr (MANY) {
+    for (; w + 3 <= w_last; w += 4) {
+      uint32_t tv[4][CPT], ts[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int slot = 2 * (w + k) + (w + k == w_first ? 1 : 0);
+        const int32_t* pp = a.part + (size_t)slot * (IT * JT) + il0 + r;
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) tv[k][c] = (uint32_t)pp[(cg * CPT + c) * IT];
+        ts[k] = (uint32_t)a.lsum[(size_t)slot * IT + il0 + r];
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) v[c] += tv[k][c];
+        sl += ts[k];
+      }
+    }
+  }
+  for (; w <= w_last; ++w) {
     const int slot = 2 * w + (w == w_first ? 1 : 0);
     const int32_t* pp = a.part + (size_t)slot * (IT * JT) + il0 + r;
 #pragma unroll
@@ -1174,8 +1199,10 @@ static void launch_cfg(const TabArgs& a, int G, int ntiles, bool fixup, hipStrea
       hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, WPE, CH, false>), dim3(G), dim3(THREADS), 0, s, a);
   }
   timing_end(s, reps);
-  if (fixup)
-    hipLaunchKernelGGL((tab_fixup_kernel<THREADS * P, NG * 8, CH>), dim3(ntiles * (THREADS * P / 64)), dim3(256), 0, s, a, G);
+  if (fixup && G >= 16 * ntiles)
+    hipLaunchKernelGGL((tab_fixup_kernel<THREADS * P, NG * 8, CH, true>), dim3(ntiles * (THREADS * P / 64)), dim3(256), 0, s, a, G);
+  else if (fixup)
+    hipLaunchKernelGGL((tab_fixup_kernel<THREADS * P, NG * 8, CH, false>), dim3(ntiles * (THREADS * P / 64)), dim3(256), 0, s, a, G);
 }
 
 template <bool CH>
