@@ -136,7 +136,7 @@ def main():
     value = total_macs / (ms_per_step * 1e-3)
 
     # ---- dominant kernel: HIP events around the main kernel of every layer call ------------
-    ax.ax_set_option("timing", 4)  # four launches between the events: their own cost is diluted
+    ax.ax_set_option("timing", 8)  # eight launches between the events: their own cost is diluted
     kern_ms = []
     for rep in range(3):
         per = []
