@@ -20,6 +20,10 @@
  *     returned by the matching *_workspace_bytes function; a smaller buffer is an error.
  *   - Return value: AX_OK (0) or a negative AX_ERR_* code; ax_strerror() gives text.
  *     Nothing is printed, thrown or aborted.
+ *   - The library keeps no mutable process-wide state: tuning overrides travel with the call
+ *     (ax_tune_t) or with a layer handle, so calls from several host threads do not interact.
+ *
+ * Micro-benchmarks and kernel timing helpers are declared in axconv_probe.h, not here.
  */
 #ifndef AXCONV_H
 #define AXCONV_H
@@ -42,7 +46,8 @@ extern "C" {
 #define AX_ERR_WORKSPACE (-5)  /* workspace NULL, too small or not 256-byte aligned            */
 #define AX_ERR_HIP (-6)        /* a HIP runtime call failed (launch, attribute, event)         */
 #define AX_ERR_ALIGN (-7)      /* a tensor pointer is not aligned to its element size          */
-#define AX_ERR_OPTION (-8)     /* unknown option name or value out of range                    */
+#define AX_ERR_OPTION (-8)     /* a flag, round mode or tuning value out of range              */
+#define AX_ERR_STATE (-9)      /* layer handle used before ax_layer_prepare                    */
 
 /* Affine quantization parameters, real = scale * (code - zero_point)  (Eq. (1)).
  * x_* are alpha_1 / beta_1 of the activations, w_* are alpha_2 / beta_2 of the filters
@@ -92,9 +97,9 @@ int ax_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint
 
 size_t ax_dense_workspace_bytes(int M, int K, int N);
 
-/* ---- operator variants (Sec. III: the layer's dilation parameter next to the strides; signed
- * multipliers with codes in [-128, 127] next to unsigned ones; an approximate twin for each kind
- * of 2-D convolution, of which the depthwise one is built) ----------------------------------- */
+/* ---- operator variants (Sec. III, Algorithm 1: the layer's dilation parameter next to the
+ * strides; Sec. II: signed multipliers with codes in [-128, 127] next to unsigned ones, and an
+ * approximate twin for each kind of 2-D convolution, of which the depthwise one is built) ----- */
 
 /* pad_code value that selects the activation zero point in both the unsigned and the signed
  * form (-1 selects it too, but only for unsigned codes, where -1 is no code). */
@@ -115,17 +120,39 @@ typedef struct {
                            stitched together); zero points and pad_code in [-128, 127]         */
 } ax_conv_desc_t;
 
+/*
+ * Tuning overrides for one call or one layer handle.  Every field 0 (or a NULL pointer where a
+ * tune is accepted) selects the automatic choice; results never depend on them (integer addition
+ * is associative), only run time does.  The tests force them to reach every kernel path.
+ *   variant      1 = direct kernel: one thread per output, table read from global memory
+ *                2 = table-tile kernel, lanes over output pixels
+ *                3 = table-tile kernel, lanes over output channels
+ *   split_k      n >= 1 (at most 64): n equal workgroup shares per output tile (n slices of the
+ *                sum over the taps)
+ *   tile         n >= 1: table-tile configuration n (threads, lane elements per thread, table
+ *                groups, taps per barrier)
+ *   row_tiles    1 = as few tiles along the lane dimension as fit, n >= 2 = n tiles (clamped to
+ *                what the layer allows; at most 2^20)
+ *   share_order  1 = workgroups take their shares of the work in launch order, 2 = XCD by XCD
+ *                (every XCD, with its own L2, gets a contiguous run of tiles)
+ * A value out of range gives AX_ERR_OPTION.
+ */
+typedef struct {
+  int32_t variant, split_k, tile, row_tiles, share_order;
+} ax_tune_t;
+
 /* ax_conv2d generalized by the descriptor; outputs, workspace rules and errors as for ax_conv2d
- * (AX_ERR_OPTION for a flag that is neither 0 nor 1).  acc_out is the exact (signed) sum. */
-int ax_conv2d_ex(const ax_conv_desc_t* desc, const void* x, const void* w, const void* lut,
-                 const ax_quant_t* q, int32_t* acc_out, float* y_out, void* workspace,
-                 size_t workspace_bytes, void* hip_stream);
-size_t ax_conv2d_ex_workspace_bytes(const ax_conv_desc_t* desc);
+ * (AX_ERR_OPTION for a flag that is neither 0 nor 1).  acc_out is the exact (signed) sum.
+ * tune may be NULL. */
+int ax_conv2d_ex(const ax_conv_desc_t* desc, const ax_tune_t* tune, const void* x, const void* w,
+                 const void* lut, const ax_quant_t* q, int32_t* acc_out, float* y_out,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t ax_conv2d_ex_workspace_bytes(const ax_conv_desc_t* desc, const ax_tune_t* tune);
 
 /*
  * One layer against several multiplier tables in one call: the use the paper builds the
  * emulator for is evaluating many candidate approximate multipliers on the same network
- * (Sec. I, Sec. IV).  luts holds num_luts (1 .. 65536) tables of 65536 entries back to back;
+ * (Sec. I, Sec. V).  luts holds num_luts (1 .. 65536) tables of 65536 entries back to back;
  * acc_out / y_out hold num_luts result tensors back to back ([num_luts][N, OH, OW, Cout]),
  * each exactly what ax_conv2d gives for that table.  The operands are prepared once, and the
  * tiles of all tables form one pool of work, so that the machine is filled without cutting
@@ -139,9 +166,51 @@ size_t ax_conv2d_multi_lut_workspace_bytes(int N, int H, int W, int Cin, int KH,
                                            int num_luts, int stride_h, int stride_w, int pad_h,
                                            int pad_w);
 
-/* ---- float-in / float-out form of the layer (Sec. III: the approximate layer reads two
- * float tensors plus the range of each and returns a float tensor; Algorithm 1: ComputeCoeffs,
- * quantization, lookup-MAC, dequantization) ------------------------------------------------
+/* ---- layer handles: filters and table prepared once, then many calls ---------------------
+ *
+ * Filters, multiplier table and quantization coefficients of a layer do not change from batch
+ * to batch (Sec. III, Algorithm 1 derives everything that depends on them once per layer; Sec. I:
+ * the emulator runs whole data sets through one network and one candidate multiplier).  A handle
+ * fixes the layer's geometry, coefficients, number of tables and tuning; ax_layer_prepare turns
+ * filters and tables into the form the kernels consume (re-laid-out table, packed filters, filter
+ * sums) in a caller-owned device block; ax_layer_run then only needs the activations.  Results
+ * are those of ax_conv2d_ex / ax_conv2d_multi_lut, bit for bit.
+ *
+ * The handle is a small host object (malloc / free); device memory stays with the caller:
+ *   prepared   ax_layer_prepared_bytes() bytes, 256-byte aligned, written by ax_layer_prepare and
+ *              read by every ax_layer_run until the next ax_layer_prepare (which may be given
+ *              another block: e.g. two blocks to prepare the next table while the current one
+ *              is still in use on another stream).  May be 0 bytes (NULL is then accepted).
+ *   workspace  ax_layer_workspace_bytes() bytes of per-call scratch, as for ax_conv2d.
+ * w and luts given to ax_layer_prepare must stay valid and unchanged while the handle is used:
+ * layers that take the direct or the depthwise kernel read them in every call.
+ * A handle may be used from one host thread at a time; runs of one handle on different streams
+ * need separate workspaces.
+ */
+typedef struct ax_layer ax_layer_t;
+
+/* num_luts >= 1 tables as in ax_conv2d_multi_lut (1 for a plain layer); q and tune are copied
+ * (tune may be NULL).  Errors as for ax_conv2d_ex; *layer_out is NULL on error. */
+int ax_layer_create(const ax_conv_desc_t* desc, int num_luts, const ax_quant_t* q,
+                    const ax_tune_t* tune, ax_layer_t** layer_out);
+void ax_layer_destroy(ax_layer_t* layer); /* NULL is ignored */
+size_t ax_layer_prepared_bytes(const ax_layer_t* layer);
+size_t ax_layer_workspace_bytes(const ax_layer_t* layer);
+/* w: filters, luts: num_luts tables back to back (device pointers, types as the descriptor says). */
+int ax_layer_prepare(ax_layer_t* layer, const void* w, const void* luts, void* prepared,
+                     size_t prepared_bytes, void* hip_stream);
+/* x: activations; acc_out / y_out: [num_luts][N, OH, OW, Cout], either may be NULL (not both).
+ * AX_ERR_STATE before the first ax_layer_prepare. */
+int ax_layer_run(const ax_layer_t* layer, const void* x, int32_t* acc_out, float* y_out,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+/* What the handle's calls run (host arithmetic only): variant as in ax_tune_t (1, 2 or 3), tile
+ * configuration (0 for the direct and depthwise kernels), grid size of the main kernel and
+ * number of partial tile pieces it produces.  Any output pointer may be NULL. */
+int ax_layer_plan(const ax_layer_t* layer, int* variant, int* tile, int* workgroups, int* pieces);
+
+/* ---- float-in / float-out form of the layer (Sec. II: the approximate layer reads two float
+ * tensors plus the range of each and returns a float tensor; Sec. III, Algorithm 1:
+ * ComputeCoeffs, quantization, lookup-MAC, dequantization) ---------------------------------
  *
  * Arithmetic, every step a single IEEE float32 operation in this order:
  *   lo = min(range[0], 0), hi = max(range[1], 0)     the range is widened to hold r = 0, which
@@ -150,10 +219,10 @@ size_t ax_conv2d_multi_lut_workspace_bytes(int N, int H, int W, int Cin, int KH,
  *   beta  = clamp(round(-lo / alpha), 0, 255)
  *   code(r) = clamp(round(r / alpha) + beta, 0, 255)          (Eq. (1) solved for the code)
  * round_mode 0 rounds halves to even, 1 rounds halves away from zero (the layer's "round mode"
- * parameter, Sec. III); other values give AX_ERR_OPTION.  relu != 0 replaces r by max(r, 0)
+ * parameter, Sec. II); other values give AX_ERR_OPTION.  relu != 0 replaces r by max(r, 0)
  * first: the activation between two chained layers, fused into the pass that reads the tensor.
  * Tensor values must be finite.  Ranges live in DEVICE memory as two floats (min, max), the
- * way the minimum / maximum operators in front of the layer deliver them (Sec. III).
+ * way the minimum / maximum operators in front of the layer deliver them (Sec. II, design flow).
  */
 
 /* One (alpha, beta) pair of Eq. (1) as the quantization kernels store it in device memory. */
@@ -164,7 +233,7 @@ typedef struct {
 
 /* Minimum and maximum of x[0..n), n >= 1 (AX_ERR_SHAPE otherwise): range_out[0] = min,
  * range_out[1] = max, of max(x, 0) when relu != 0.  Evaluated once per batch in front of each
- * layer (Sec. III).  workspace: ax_range_workspace_bytes(n) bytes, 256-byte aligned. */
+ * layer (Sec. II, design flow).  workspace: ax_range_workspace_bytes(n) bytes, 256-byte aligned. */
 int ax_range_f32(const float* x, size_t n, int relu, float* range_out, void* workspace,
                  size_t workspace_bytes, void* hip_stream);
 size_t ax_range_workspace_bytes(size_t n);
@@ -197,15 +266,15 @@ size_t ax_conv2d_f32_workspace_bytes(int N, int H, int W, int Cin, int KH, int K
                                      int stride_h, int stride_w, int pad_h, int pad_w);
 
 /* The float layer with the layer's full parameter set (Sec. III, Algorithm 1: strides,
- * dilations, padding, signed or unsigned multiplier, round mode) and the depthwise kind, given by
- * the descriptor of ax_conv2d_ex.  signed_codes = 1: the same alpha; codes and zero points are
+ * dilations, padding; Sec. II: signed or unsigned multiplier, round mode) and the depthwise kind,
+ * given by the descriptor of ax_conv2d_ex; tune may be NULL.  signed_codes = 1: the same alpha; codes and zero points are
  * the unsigned ones lowered by 128 (they span [-128, 127], real zero stays representable), lut is
  * int16 addressed by the codes' two's-complement patterns.  Everything else as ax_conv2d_f32. */
-int ax_conv2d_f32_ex(const ax_conv_desc_t* desc, const float* x, const float* w, const void* lut,
-                     const float* x_range, const float* w_range, int relu, int round_mode,
-                     int32_t* acc_out, float* y_out, void* workspace, size_t workspace_bytes,
-                     void* hip_stream);
-size_t ax_conv2d_f32_ex_workspace_bytes(const ax_conv_desc_t* desc);
+int ax_conv2d_f32_ex(const ax_conv_desc_t* desc, const ax_tune_t* tune, const float* x,
+                     const float* w, const void* lut, const float* x_range, const float* w_range,
+                     int relu, int round_mode, int32_t* acc_out, float* y_out, void* workspace,
+                     size_t workspace_bytes, void* hip_stream);
+size_t ax_conv2d_f32_ex_workspace_bytes(const ax_conv_desc_t* desc, const ax_tune_t* tune);
 
 /* Dense form: x [M,K] float, w [K,N] float (Eq. (2)-(4) after the same quantization). */
 int ax_dense_f32(const float* x, int M, int K, const float* w, int N, const uint16_t* lut,
@@ -218,75 +287,6 @@ const char* ax_strerror(int code);
 
 /* Library version, major * 10000 + minor * 100 + patch. */
 int ax_version(void);
-
-/*
- * Process-wide tuning / test knobs.  Names:
- *   "variant"  0 = choose automatically (default)
- *              1 = direct kernel: one thread per output, table read from global memory
- *              2 = table-tile kernel, lanes over output pixels
- *              3 = table-tile kernel, lanes over output channels
- *   "split_k"  0 = choose the work decomposition automatically, n >= 1 = force n equal
- *              workgroup shares per output tile (n slices of the K loop)
- *   "tile"     0 = choose the table-tile configuration automatically (default), n >= 1 =
- *              force configuration n (threads, lane elements per thread, table groups,
- *              taps per barrier)
- *   "row_tiles" 0 = choose automatically how many tiles the lane dimension is cut into (default),
- *              1 = as few as fit, n >= 2 = n tiles (clamped to what the layer allows)
- *   "share_order" 0 = choose automatically how workgroups take their shares of the work (default),
- *              1 = in launch order, 2 = XCD by XCD (every XCD, with its own L2, gets a contiguous
- *              run of tiles); results do not depend on it
- *   "timing"   n in 1..16 = record a HIP event pair around n back-to-back launches of the main
- *              kernel of every layer call on the call's stream (see ax_last_kernel_ms; the
- *              repeats rewrite the same results and only dilute the events' own cost);
- *              0 = off (default)
- * Returns AX_OK or AX_ERR_OPTION.  Not thread safe with respect to concurrent calls.
- */
-int ax_set_option(const char* name, int value);
-int ax_get_option(const char* name, int* value);
-
-/* What a call with this geometry would run under the current options (host arithmetic only):
- * variant as in the "variant" option (1, 2 or 3), tile configuration (0 for the direct kernel),
- * grid size of the main kernel and number of partial tile pieces it would produce.  Any output
- * pointer may be NULL.  A dense layer is the geometry (M, 1, 1, K, 1, 1, N, 1, 1, 0, 0). */
-int ax_conv2d_plan(int N, int H, int W, int Cin, int KH, int KW, int Cout, int stride_h,
-                   int stride_w, int pad_h, int pad_w, int* variant, int* tile, int* workgroups,
-                   int* pieces);
-
-/* Duration in milliseconds of one launch of the main kernel of the most recent layer call made
- * while the "timing" option was on (operand preparation and the K-slice reduction are not included).
- * Waits for that kernel to finish.  AX_ERR_OPTION if no timed call has been made. */
-int ax_last_kernel_ms(float* ms);
-
-/* ---- measurement helpers (not part of the layer path) -------------------------------- */
-
-/*
- * LDS gather micro-benchmark: one workgroup per compute unit keeps a table of
- * `table_bytes` in LDS and every lane repeatedly reads `width_bytes` (2, 4, 8 or 16)
- * from it.  pattern 0: lane l reads consecutive elements (no bank conflict);
- * pattern 1: every lane reads independent uniformly random aligned elements;
- * pattern 2: like 1, but half of the lanes (chosen at random) read element 0.
- * Unlike the layer calls, this one allocates temporary device memory and synchronizes.
- * Outputs (host pointers): wave_reads = wave-level read
- * instructions executed per workgroup, cycles = mean shader-clock cycles per workgroup,
- * seconds = elapsed time of the kernel, workgroups = grid size.
- */
-int ax_probe_lds_gather(int width_bytes, int pattern, int table_bytes, int threads, int iters,
-                        double* wave_reads, double* cycles, double* seconds, int* workgroups,
-                        void* hip_stream);
-
-/*
- * Instruction-mix micro-benchmark.  mode 0: independent integer adds only (ops = lane adds);
- * modes 1..4: the inner loop of the table-tile kernels without table building or barriers,
- * for (threads, lane elements per thread, table groups) = (512,2,8), (1024,1,8), (512,4,4),
- * (1024,2,4) (ops = lookup-MACs).  pattern 1: uniform random codes, 2: half of the codes zero.
- * Allocates temporary device memory and synchronizes.  Outputs are host pointers.
- */
-int ax_probe_mac(int mode, int pattern, int iters, int wgs_per_cu, double* ops, double* seconds,
-                 void* hip_stream);
-
-/* Plain device-to-device copy kernel of `bytes` (multiple of 16), for the HBM roofline and
- * for calibrating memory-traffic counters.  Asynchronous. */
-int ax_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

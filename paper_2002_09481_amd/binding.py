@@ -1,8 +1,14 @@
-"""ctypes binding of libaxconv.so: the same entry points as include/axconv.h.
+"""ctypes binding of libaxconv.so: the same entry points as include/axconv.h and
+include/axconv_probe.h.
 
 Only argument marshalling happens here.  Tensors are torch CUDA tensors (torch provides
 device memory and the stream); every step of the layer runs in the HIP kernels.  There is
 no fallback: a missing library raises at first use.
+
+The library itself keeps no options: tuning overrides travel with each call as an ax_tune_t.
+ax_set_option / ax_get_option below only keep this module's default for that argument (the
+tests use them to force every kernel path); calls made while a default is set go through the
+entry points that accept a tune (ax_conv2d_ex, ax_conv2d_f32_ex, the layer handles).
 """
 
 from __future__ import annotations
@@ -35,16 +41,24 @@ class ax_quant_t(ctypes.Structure):
     ]
 
 
-EXPORTS = [
+EXPORTS = [  # include/axconv.h
     "ax_conv2d", "ax_conv2d_workspace_bytes", "ax_dense", "ax_dense_workspace_bytes", "ax_strerror",
-    "ax_version", "ax_set_option", "ax_get_option", "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_last_kernel_ms", "ax_conv2d_plan",
-    "ax_range_f32", "ax_range_workspace_bytes", "ax_quantize_f32", "ax_conv2d_f32", "ax_conv2d_f32_workspace_bytes",
-    "ax_dense_f32", "ax_dense_f32_workspace_bytes", "ax_conv2d_ex", "ax_conv2d_ex_workspace_bytes",
-    "ax_conv2d_multi_lut", "ax_conv2d_multi_lut_workspace_bytes", "ax_conv2d_f32_ex", "ax_conv2d_f32_ex_workspace_bytes",
+    "ax_version", "ax_range_f32", "ax_range_workspace_bytes", "ax_quantize_f32", "ax_conv2d_f32",
+    "ax_conv2d_f32_workspace_bytes", "ax_dense_f32", "ax_dense_f32_workspace_bytes", "ax_conv2d_ex",
+    "ax_conv2d_ex_workspace_bytes", "ax_conv2d_multi_lut", "ax_conv2d_multi_lut_workspace_bytes", "ax_conv2d_f32_ex",
+    "ax_conv2d_f32_ex_workspace_bytes", "ax_layer_create", "ax_layer_destroy", "ax_layer_prepared_bytes",
+    "ax_layer_workspace_bytes", "ax_layer_prepare", "ax_layer_run", "ax_layer_plan",
+]
+PROBE_EXPORTS = [  # include/axconv_probe.h
+    "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_probe_layer_kernel_ms",
 ]
 
 
 AX_PAD_DEFAULT = -(1 << 31)
+
+
+class ax_tune_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("variant", "split_k", "tile", "row_tiles", "share_order")]
 
 
 class ax_conv_desc_t(ctypes.Structure):
@@ -76,20 +90,30 @@ def lib():
     L.ax_strerror.restype = ctypes.c_char_p
     L.ax_version.argtypes = []
     L.ax_version.restype = ci
-    L.ax_set_option.argtypes = [ctypes.c_char_p, ci]
-    L.ax_set_option.restype = ci
-    L.ax_get_option.argtypes = [ctypes.c_char_p, ctypes.POINTER(ci)]
-    L.ax_get_option.restype = ci
     dp = ctypes.POINTER(ctypes.c_double)
     L.ax_probe_lds_gather.argtypes = [ci, ci, ci, ci, ci, dp, dp, dp, ctypes.POINTER(ci), vp]
     L.ax_probe_lds_gather.restype = ci
     L.ax_probe_mac.argtypes = [ci, ci, ci, ci, dp, dp, vp]
     L.ax_probe_mac.restype = ci
     ip = ctypes.POINTER(ci)
-    L.ax_conv2d_plan.argtypes = [ci] * 11 + [ip, ip, ip, ip]
-    L.ax_conv2d_plan.restype = ci
-    L.ax_last_kernel_ms.argtypes = [ctypes.POINTER(ctypes.c_float)]
-    L.ax_last_kernel_ms.restype = ci
+    tp = ctypes.POINTER(ax_tune_t)
+    descp = ctypes.POINTER(ax_conv_desc_t)
+    L.ax_layer_create.argtypes = [descp, ci, ctypes.POINTER(ax_quant_t), tp, ctypes.POINTER(vp)]
+    L.ax_layer_create.restype = ci
+    L.ax_layer_destroy.argtypes = [vp]
+    L.ax_layer_destroy.restype = None
+    L.ax_layer_prepared_bytes.argtypes = [vp]
+    L.ax_layer_prepared_bytes.restype = sz
+    L.ax_layer_workspace_bytes.argtypes = [vp]
+    L.ax_layer_workspace_bytes.restype = sz
+    L.ax_layer_prepare.argtypes = [vp, vp, vp, vp, sz, vp]
+    L.ax_layer_prepare.restype = ci
+    L.ax_layer_run.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+    L.ax_layer_run.restype = ci
+    L.ax_layer_plan.argtypes = [vp, ip, ip, ip, ip]
+    L.ax_layer_plan.restype = ci
+    L.ax_probe_layer_kernel_ms.argtypes = [vp, vp, vp, vp, vp, sz, ci, ctypes.POINTER(ctypes.c_float), vp]
+    L.ax_probe_layer_kernel_ms.restype = ci
     L.ax_probe_copy.argtypes = [vp, vp, sz, vp]
     L.ax_probe_copy.restype = ci
     L.ax_conv2d_multi_lut.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci,
@@ -97,13 +121,13 @@ def lib():
     L.ax_conv2d_multi_lut.restype = ci
     L.ax_conv2d_multi_lut_workspace_bytes.argtypes = [ci] * 12
     L.ax_conv2d_multi_lut_workspace_bytes.restype = sz
-    L.ax_conv2d_f32_ex.argtypes = [ctypes.POINTER(ax_conv_desc_t), vp, vp, vp, vp, vp, ci, ci, vp, vp, vp, sz, vp]
+    L.ax_conv2d_f32_ex.argtypes = [descp, tp, vp, vp, vp, vp, vp, ci, ci, vp, vp, vp, sz, vp]
     L.ax_conv2d_f32_ex.restype = ci
-    L.ax_conv2d_f32_ex_workspace_bytes.argtypes = [ctypes.POINTER(ax_conv_desc_t)]
+    L.ax_conv2d_f32_ex_workspace_bytes.argtypes = [descp, tp]
     L.ax_conv2d_f32_ex_workspace_bytes.restype = sz
-    L.ax_conv2d_ex.argtypes = [ctypes.POINTER(ax_conv_desc_t), vp, vp, vp, ctypes.POINTER(ax_quant_t), vp, vp, vp, sz, vp]
+    L.ax_conv2d_ex.argtypes = [descp, tp, vp, vp, vp, ctypes.POINTER(ax_quant_t), vp, vp, vp, sz, vp]
     L.ax_conv2d_ex.restype = ci
-    L.ax_conv2d_ex_workspace_bytes.argtypes = [ctypes.POINTER(ax_conv_desc_t)]
+    L.ax_conv2d_ex_workspace_bytes.argtypes = [descp, tp]
     L.ax_conv2d_ex_workspace_bytes.restype = sz
     L.ax_range_f32.argtypes = [vp, sz, ci, vp, vp, sz, vp]
     L.ax_range_f32.restype = ci
@@ -137,34 +161,54 @@ def ax_version() -> int:
     return int(lib().ax_version())
 
 
+_TUNE_FIELDS = ("variant", "split_k", "tile", "row_tiles", "share_order")
+_tune = {n: 0 for n in _TUNE_FIELDS}  # this module's default ax_tune_t (all zero = automatic)
+
+
+def _tune_arg(tune=None):
+    """ctypes argument for a `const ax_tune_t*` parameter: NULL when everything is automatic."""
+    t = _tune if tune is None else tune
+    if not any(t[n] for n in _TUNE_FIELDS):
+        return None
+    return ctypes.byref(ax_tune_t(*[int(t[n]) for n in _TUNE_FIELDS]))
+
+
 def ax_set_option(name: str, value: int) -> None:
-    _check(lib().ax_set_option(name.encode(), int(value)))
+    """Set one field of the module's default tune; the library checks the value's range."""
+    if name not in _tune:
+        raise AxError(-8, lib().ax_strerror(-8).decode())
+    trial = dict(_tune)
+    trial[name] = int(value)
+    if not -(1 << 31) <= trial[name] < (1 << 31):
+        raise AxError(-8, lib().ax_strerror(-8).decode())
+    desc = ax_conv_desc_t(1, 1, 1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 1, 0, 0)
+    q = ax_quant_t(1.0, 0, 1.0, 0, -1)
+    h = ctypes.c_void_p()
+    _check(lib().ax_layer_create(ctypes.byref(desc), 1, ctypes.byref(q), _tune_arg(trial), ctypes.byref(h)))
+    lib().ax_layer_destroy(h)
+    _tune[name] = trial[name]
 
 
 def ax_get_option(name: str) -> int:
-    v = ctypes.c_int(0)
-    _check(lib().ax_get_option(name.encode(), ctypes.byref(v)))
-    return v.value
+    if name not in _tune:
+        raise AxError(-8, lib().ax_strerror(-8).decode())
+    return _tune[name]
 
 
-def ax_conv2d_plan(x_shape, w_shape, stride=1, pad=0) -> dict:
+def ax_conv2d_plan(x_shape, w_shape, stride=1, pad=0, num_luts=1) -> dict:
+    """What a layer of this geometry runs under the module's default tune (host arithmetic)."""
     N, H, W, Cin = [int(v) for v in x_shape]
     KH, KW, _, Cout = [int(v) for v in w_shape]
     sh, sw = _pair(stride)
     ph, pw = _pair(pad)
-    out = [ctypes.c_int(0) for _ in range(4)]
-    _check(lib().ax_conv2d_plan(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, *[ctypes.byref(o) for o in out]))
-    return {"variant": out[0].value, "tile": out[1].value, "workgroups": out[2].value, "pieces": out[3].value}
-
-
-def ax_last_kernel_ms() -> float:
-    v = ctypes.c_float(0.0)
-    _check(lib().ax_last_kernel_ms(ctypes.byref(v)))
-    return float(v.value)
+    desc = ax_conv_desc_t(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, 1, 1, 0, 0)
+    with AxLayer(desc, ax_quant_t(1.0, 0, 1.0, 0, -1), num_luts) as layer:
+        return layer.plan()
 
 
 def _quant(q) -> ax_quant_t:
-    return ax_quant_t(float(q.x_scale), int(q.x_zp), float(q.w_scale), int(q.w_zp), int(q.pad_code))
+    pad_code = AX_PAD_DEFAULT if q.pad_code is None else int(q.pad_code)
+    return ax_quant_t(float(q.x_scale), int(q.x_zp), float(q.w_scale), int(q.w_zp), pad_code)
 
 
 def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
@@ -190,16 +234,58 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-def ax_conv2d_workspace_bytes(x_shape, w_shape, stride=1, pad=0) -> int:
+def _workspace(need: int, device, stream) -> torch.Tensor:
+    """Temporary scratch for one call.  torch's allocator hands memory back to the current
+    stream's pool when the tensor dies: for a call on another stream the allocation is tied to
+    that stream as well, so that it is not reused while the kernels still run."""
+    ws = torch.empty(max(int(need), 256), dtype=torch.uint8, device=device)
+    if stream is not None:
+        ws.record_stream(stream)
+    return ws
+
+
+def _conv_desc(x_shape, w_shape, stride, pad, dilation=1, depthwise=False, signed=False) -> ax_conv_desc_t:
     N, H, W, Cin = [int(v) for v in x_shape]
-    KH, KW, _, Cout = [int(v) for v in w_shape]
+    KH, KW, _, last = [int(v) for v in w_shape]
+    Cout = Cin * last if depthwise else last
     sh, sw = _pair(stride)
     ph, pw = _pair(pad)
-    return int(lib().ax_conv2d_workspace_bytes(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw))
+    dh, dw = _pair(dilation)
+    return ax_conv_desc_t(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, dh, dw, int(bool(depthwise)), int(bool(signed)))
+
+
+def _dense_desc(M: int, K: int, N: int) -> ax_conv_desc_t:
+    return ax_conv_desc_t(int(M), 1, 1, int(K), 1, 1, int(N), 1, 1, 0, 0, 1, 1, 0, 0)
+
+
+def _out_hw(d: ax_conv_desc_t) -> Tuple[int, int]:
+    OH = (d.H + 2 * d.pad_h - d.dilation_h * (d.KH - 1) - 1) // d.stride_h + 1
+    OW = (d.W + 2 * d.pad_w - d.dilation_w * (d.KW - 1) - 1) // d.stride_w + 1
+    return OH, OW
+
+
+def ax_conv2d_workspace_bytes(x_shape, w_shape, stride=1, pad=0) -> int:
+    d = _conv_desc(x_shape, w_shape, stride, pad)
+    t = _tune_arg()
+    if t is not None:
+        return int(lib().ax_conv2d_ex_workspace_bytes(ctypes.byref(d), t))
+    return int(lib().ax_conv2d_workspace_bytes(d.N, d.H, d.W, d.Cin, d.KH, d.KW, d.Cout, d.stride_h, d.stride_w,
+                                               d.pad_h, d.pad_w))
 
 
 def ax_dense_workspace_bytes(M: int, K: int, N: int) -> int:
+    t = _tune_arg()
+    if t is not None:
+        return int(lib().ax_conv2d_ex_workspace_bytes(ctypes.byref(_dense_desc(M, K, N)), t))
     return int(lib().ax_dense_workspace_bytes(int(M), int(K), int(N)))
+
+
+def _check_lut(lut, n_entries=65536):
+    if lut.dtype not in (torch.int16, torch.uint16):
+        raise TypeError("lut must be a 16-bit integer tensor")
+    _dev(lut, lut.dtype, "lut")
+    if lut.numel() != n_entries:
+        raise ValueError("lut must have %d entries" % n_entries)
 
 
 def ax_conv2d(x, w, lut, stride, pad, q, acc_out=None, y_out=None, workspace=None, stream=None):
@@ -210,40 +296,26 @@ def ax_conv2d(x, w, lut, stride, pad, q, acc_out=None, y_out=None, workspace=Non
     L = lib()
     _dev(x, torch.uint8, "x")
     _dev(w, torch.uint8, "w")
-    if lut.dtype not in (torch.int16, torch.uint16):
-        raise TypeError("lut must be a 16-bit integer tensor")
-    _dev(lut, lut.dtype, "lut")
-    if lut.numel() != 65536:
-        raise ValueError("lut must have 65536 entries")
+    _check_lut(lut)
     if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
         raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout]")
-    N, H, W, Cin = x.shape
-    KH, KW, _, Cout = w.shape
-    sh, sw = _pair(stride)
-    ph, pw = _pair(pad)
-    OH = (H + 2 * ph - KH) // sh + 1
-    OW = (W + 2 * pw - KW) // sw + 1
+    d = _conv_desc(x.shape, w.shape, stride, pad)
+    OH, OW = _out_hw(d)
     if OH <= 0 or OW <= 0:
         _check(-2)
-    if acc_out is None:
-        acc_out = torch.empty((N, OH, OW, Cout), dtype=torch.int32, device=x.device)
-    if y_out is None:
-        y_out = torch.empty((N, OH, OW, Cout), dtype=torch.float32, device=x.device)
-    if acc_out is not False:
-        _dev(acc_out, torch.int32, "acc_out")
-    if y_out is not False:
-        _dev(y_out, torch.float32, "y_out")
-    for o in (acc_out, y_out):
-        if o is not False and o.numel() != N * OH * OW * Cout:
-            raise ValueError("output tensor has the wrong number of elements")
+    acc_out, y_out = _outs((d.N, OH, OW, d.Cout), x.device, acc_out, y_out)
     if workspace is None:  # (a workspace handed in is checked by the C call itself)
-        need = int(L.ax_conv2d_workspace_bytes(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw))
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        workspace = _workspace(ax_conv2d_workspace_bytes(x.shape, w.shape, stride, pad), x.device, stream)
     _dev(workspace, torch.uint8, "workspace")
     qs = _quant(q)
-    rc = L.ax_conv2d(_ptr(x), N, H, W, Cin, _ptr(w), KH, KW, Cout, _ptr(lut), sh, sw, ph, pw, ctypes.byref(qs),
-                     _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
-                     _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    t = _tune_arg()
+    tail = (ctypes.byref(qs), _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
+            _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    if t is None:
+        rc = L.ax_conv2d(_ptr(x), d.N, d.H, d.W, d.Cin, _ptr(w), d.KH, d.KW, d.Cout, _ptr(lut), d.stride_h, d.stride_w,
+                         d.pad_h, d.pad_w, *tail)
+    else:
+        rc = L.ax_conv2d_ex(ctypes.byref(d), t, _ptr(x), _ptr(w), _ptr(lut), *tail)
     _check(rc)
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
 
@@ -253,75 +325,64 @@ def ax_dense(x, w, lut, q, acc_out=None, y_out=None, workspace=None, stream=None
     L = lib()
     _dev(x, torch.uint8, "x")
     _dev(w, torch.uint8, "w")
-    if lut.dtype not in (torch.int16, torch.uint16):
-        raise TypeError("lut must be a 16-bit integer tensor")
-    _dev(lut, lut.dtype, "lut")
-    if lut.numel() != 65536:
-        raise ValueError("lut must have 65536 entries")
+    _check_lut(lut)
     if x.dim() != 2 or w.dim() != 2 or w.shape[0] != x.shape[1]:
         raise ValueError("x must be [M,K] and w [K,N]")
     M, K = x.shape
     N = w.shape[1]
-    if acc_out is None:
-        acc_out = torch.empty((M, N), dtype=torch.int32, device=x.device)
-    if y_out is None:
-        y_out = torch.empty((M, N), dtype=torch.float32, device=x.device)
-    if acc_out is not False:
-        _dev(acc_out, torch.int32, "acc_out")
-    if y_out is not False:
-        _dev(y_out, torch.float32, "y_out")
+    acc_out, y_out = _outs((M, N), x.device, acc_out, y_out)
     if workspace is None:
-        need = int(L.ax_dense_workspace_bytes(M, K, N))
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        workspace = _workspace(ax_dense_workspace_bytes(M, K, N), x.device, stream)
     _dev(workspace, torch.uint8, "workspace")
     qs = _quant(q)
-    rc = L.ax_dense(_ptr(x), M, K, _ptr(w), N, _ptr(lut), ctypes.byref(qs),
-                    _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
-                    _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    t = _tune_arg()
+    tail = (ctypes.byref(qs), _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
+            _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    if t is None:
+        rc = L.ax_dense(_ptr(x), M, K, _ptr(w), N, _ptr(lut), *tail)
+    else:
+        rc = L.ax_conv2d_ex(ctypes.byref(_dense_desc(M, K, N)), t, _ptr(x), _ptr(w), _ptr(lut), *tail)
     _check(rc)
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
 
 
 def ax_conv2d_multi_lut_workspace_bytes(x_shape, w_shape, num_luts, stride=1, pad=0) -> int:
-    N, H, W, Cin = [int(v) for v in x_shape]
-    KH, KW, _, Cout = [int(v) for v in w_shape]
-    sh, sw = _pair(stride)
-    ph, pw = _pair(pad)
-    return int(lib().ax_conv2d_multi_lut_workspace_bytes(N, H, W, Cin, KH, KW, Cout, int(num_luts), sh, sw, ph, pw))
+    d = _conv_desc(x_shape, w_shape, stride, pad)
+    return int(lib().ax_conv2d_multi_lut_workspace_bytes(d.N, d.H, d.W, d.Cin, d.KH, d.KW, d.Cout, int(num_luts),
+                                                         d.stride_h, d.stride_w, d.pad_h, d.pad_w))
 
 
 def ax_conv2d_multi_lut(x, w, luts, stride, pad, q, acc_out=None, y_out=None, workspace=None, stream=None):
     """One layer against T tables.  luts: 16-bit integer CUDA tensor [T, 65536]; outputs
-    [T, N, OH, OW, Cout].  Returns (acc_out, y_out); pass False to skip one of them."""
+    [T, N, OH, OW, Cout].  Returns (acc_out, y_out); pass False to skip one of them.  With a
+    default tune set the call goes through a layer handle (the one-call entry takes no tune)."""
     L = lib()
     _dev(x, torch.uint8, "x")
     _dev(w, torch.uint8, "w")
-    if luts.dtype not in (torch.int16, torch.uint16):
-        raise TypeError("luts must be a 16-bit integer tensor")
-    _dev(luts, luts.dtype, "luts")
     if luts.dim() != 2 or luts.shape[1] != 65536:
         raise ValueError("luts must be [T, 65536]")
     T = int(luts.shape[0])
+    _check_lut(luts, T * 65536)
     if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
         raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout]")
-    N, H, W, Cin = x.shape
-    KH, KW, _, Cout = w.shape
-    sh, sw = _pair(stride)
-    ph, pw = _pair(pad)
-    OH = (H + 2 * ph - KH) // sh + 1
-    OW = (W + 2 * pw - KW) // sw + 1
+    d = _conv_desc(x.shape, w.shape, stride, pad)
+    OH, OW = _out_hw(d)
     if OH <= 0 or OW <= 0:
         _check(-2)
-    acc_out, y_out = _outs((T, N, OH, OW, Cout), x.device, acc_out, y_out)
-    if workspace is None:
-        need = int(L.ax_conv2d_multi_lut_workspace_bytes(N, H, W, Cin, KH, KW, Cout, T, sh, sw, ph, pw))
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
-    _dev(workspace, torch.uint8, "workspace")
+    acc_out, y_out = _outs((T, d.N, OH, OW, d.Cout), x.device, acc_out, y_out)
     qs = _quant(q)
-    rc = L.ax_conv2d_multi_lut(_ptr(x), N, H, W, Cin, _ptr(w), KH, KW, Cout, _ptr(luts), T, sh, sw, ph, pw,
-                               ctypes.byref(qs), _ptr(None if acc_out is False else acc_out),
-                               _ptr(None if y_out is False else y_out), _ptr(workspace), workspace.numel(),
-                               ctypes.c_void_p(_stream_ptr(stream)))
+    if _tune_arg() is not None:
+        with AxLayer(d, qs, T) as layer:
+            layer.prepare(w, luts, stream=stream)
+            layer.run(x, acc_out, y_out, workspace=workspace, stream=stream)
+        return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+    if workspace is None:
+        workspace = _workspace(ax_conv2d_multi_lut_workspace_bytes(x.shape, w.shape, T, stride, pad), x.device, stream)
+    _dev(workspace, torch.uint8, "workspace")
+    rc = L.ax_conv2d_multi_lut(_ptr(x), d.N, d.H, d.W, d.Cin, _ptr(w), d.KH, d.KW, d.Cout, _ptr(luts), T, d.stride_h,
+                               d.stride_w, d.pad_h, d.pad_w, ctypes.byref(qs),
+                               _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
+                               _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
     _check(rc)
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
 
@@ -335,36 +396,122 @@ def ax_conv2d_ex(x, w, lut, stride, pad, q, dilation=1, depthwise=False, acc_out
     cdt = torch.int8 if signed else torch.uint8
     _dev(x, cdt, "x")
     _dev(w, cdt, "w")
-    if lut.dtype not in (torch.int16, torch.uint16):
-        raise TypeError("lut must be a 16-bit integer tensor")
-    _dev(lut, lut.dtype, "lut")
-    if lut.numel() != 65536:
-        raise ValueError("lut must have 65536 entries")
+    _check_lut(lut)
     if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
         raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout] (or [KH,KW,Cin,mult])")
-    N, H, W, Cin = x.shape
-    KH, KW, _, last = w.shape
-    Cout = Cin * last if depthwise else last
-    sh, sw = _pair(stride)
-    ph, pw = _pair(pad)
-    dh, dw = _pair(dilation)
-    desc = ax_conv_desc_t(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, dh, dw, int(bool(depthwise)), int(signed))
-    OH = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
-    OW = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+    desc = _conv_desc(x.shape, w.shape, stride, pad, dilation, depthwise, signed)
+    OH, OW = _out_hw(desc)
     if OH <= 0 or OW <= 0:
         _check(-2)
-    acc_out, y_out = _outs((N, OH, OW, Cout), x.device, acc_out, y_out)
+    acc_out, y_out = _outs((desc.N, OH, OW, desc.Cout), x.device, acc_out, y_out)
+    t = _tune_arg()
     if workspace is None:
-        need = int(L.ax_conv2d_ex_workspace_bytes(ctypes.byref(desc)))
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        workspace = _workspace(int(L.ax_conv2d_ex_workspace_bytes(ctypes.byref(desc), t)), x.device, stream)
     _dev(workspace, torch.uint8, "workspace")
-    pad_code = AX_PAD_DEFAULT if q.pad_code is None else int(q.pad_code)
-    qs = ax_quant_t(float(q.x_scale), int(q.x_zp), float(q.w_scale), int(q.w_zp), pad_code)
-    rc = L.ax_conv2d_ex(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(lut), ctypes.byref(qs),
+    qs = _quant(q)
+    rc = L.ax_conv2d_ex(ctypes.byref(desc), t, _ptr(x), _ptr(w), _ptr(lut), ctypes.byref(qs),
                         _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
                         _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
     _check(rc)
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
+class AxLayer:
+    """A layer handle (ax_layer_*): filters and tables prepared once, then many calls.
+
+    desc: ax_conv_desc_t; q: ax_quant_t or an object with x_scale, x_zp, w_scale, w_zp,
+    pad_code (None = zero point); tune: dict with the fields of ax_tune_t (None = the module's
+    default).  Device memory (prepared block, workspace) is torch tensors owned by this object
+    unless the caller hands tensors in."""
+
+    def __init__(self, desc: ax_conv_desc_t, q, num_luts: int = 1, tune=None):
+        self._h = ctypes.c_void_p()
+        self.desc = desc
+        self.num_luts = int(num_luts)
+        qs = q if isinstance(q, ax_quant_t) else _quant(q)
+        _check(lib().ax_layer_create(ctypes.byref(desc), self.num_luts, ctypes.byref(qs), _tune_arg(tune),
+                                     ctypes.byref(self._h)))
+        self._keep = None  # tensors the handle's device pointers refer to
+        self._ws = None
+
+    def close(self):
+        if self._h and _lib is not None:
+            _lib.ax_layer_destroy(self._h)
+        self._h = ctypes.c_void_p()
+        self._keep = None
+        self._ws = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:  # interpreter shutdown: the module's globals may be gone
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    @property
+    def prepared_bytes(self) -> int:
+        return int(lib().ax_layer_prepared_bytes(self._h))
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(lib().ax_layer_workspace_bytes(self._h))
+
+    def out_shape(self):
+        OH, OW = _out_hw(self.desc)
+        shape = (self.desc.N, OH, OW, self.desc.Cout)
+        return shape if self.num_luts == 1 else (self.num_luts,) + shape
+
+    def plan(self) -> dict:
+        out = [ctypes.c_int(0) for _ in range(4)]
+        _check(lib().ax_layer_plan(self._h, *[ctypes.byref(o) for o in out]))
+        return {"variant": out[0].value, "tile": out[1].value, "workgroups": out[2].value, "pieces": out[3].value}
+
+    def prepare(self, w, luts, prepared=None, stream=None):
+        cdt = torch.int8 if self.desc.signed_codes else torch.uint8
+        _dev(w, cdt, "w")
+        _check_lut(luts, self.num_luts * 65536)
+        if prepared is None:
+            prepared = torch.empty(max(self.prepared_bytes, 256), dtype=torch.uint8, device=w.device)
+        _dev(prepared, torch.uint8, "prepared")
+        _check(lib().ax_layer_prepare(self._h, _ptr(w), _ptr(luts), _ptr(prepared), prepared.numel(),
+                                      ctypes.c_void_p(_stream_ptr(stream))))
+        self._keep = (w, luts, prepared)
+        return prepared
+
+    def _args(self, x, acc_out, y_out, workspace, stream):
+        cdt = torch.int8 if self.desc.signed_codes else torch.uint8
+        _dev(x, cdt, "x")
+        acc_out, y_out = _outs(self.out_shape(), x.device, acc_out, y_out)
+        if workspace is None:
+            if self._ws is None or self._ws.device != x.device:
+                self._ws = torch.empty(max(self.workspace_bytes, 256), dtype=torch.uint8, device=x.device)
+            workspace = self._ws
+            if stream is not None:
+                workspace.record_stream(stream)
+        _dev(workspace, torch.uint8, "workspace")
+        return acc_out, y_out, workspace
+
+    def run(self, x, acc_out=None, y_out=None, workspace=None, stream=None):
+        acc_out, y_out, workspace = self._args(x, acc_out, y_out, workspace, stream)
+        _check(lib().ax_layer_run(self._h, _ptr(x), _ptr(None if acc_out is False else acc_out),
+                                  _ptr(None if y_out is False else y_out), _ptr(workspace), workspace.numel(),
+                                  ctypes.c_void_p(_stream_ptr(stream))))
+        return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+    def kernel_ms(self, x, acc_out=None, y_out=None, workspace=None, reps: int = 8, stream=None) -> float:
+        """ax_probe_layer_kernel_ms: duration of one launch of the layer's main kernel."""
+        acc_out, y_out, workspace = self._args(x, acc_out, y_out, workspace, stream)
+        ms = ctypes.c_float(0.0)
+        _check(lib().ax_probe_layer_kernel_ms(self._h, _ptr(x), _ptr(None if acc_out is False else acc_out),
+                                              _ptr(None if y_out is False else y_out), _ptr(workspace),
+                                              workspace.numel(), int(reps), ctypes.byref(ms),
+                                              ctypes.c_void_p(_stream_ptr(stream))))
+        return float(ms.value)
 
 
 def ax_range_workspace_bytes(n: int) -> int:
@@ -409,14 +556,18 @@ def ax_quantize_f32(x, rng, relu=False, round_mode=0, codes_out=None, coeffs_out
 
 
 def ax_conv2d_f32_workspace_bytes(x_shape, w_shape, stride=1, pad=0) -> int:
-    N, H, W, Cin = [int(v) for v in x_shape]
-    KH, KW, _, Cout = [int(v) for v in w_shape]
-    sh, sw = _pair(stride)
-    ph, pw = _pair(pad)
-    return int(lib().ax_conv2d_f32_workspace_bytes(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw))
+    d = _conv_desc(x_shape, w_shape, stride, pad)
+    t = _tune_arg()
+    if t is not None:
+        return int(lib().ax_conv2d_f32_ex_workspace_bytes(ctypes.byref(d), t))
+    return int(lib().ax_conv2d_f32_workspace_bytes(d.N, d.H, d.W, d.Cin, d.KH, d.KW, d.Cout, d.stride_h, d.stride_w,
+                                                   d.pad_h, d.pad_w))
 
 
 def ax_dense_f32_workspace_bytes(M: int, K: int, N: int) -> int:
+    t = _tune_arg()
+    if t is not None:
+        return int(lib().ax_conv2d_f32_ex_workspace_bytes(ctypes.byref(_dense_desc(M, K, N)), t))
     return int(lib().ax_dense_f32_workspace_bytes(int(M), int(K), int(N)))
 
 
@@ -429,11 +580,7 @@ def _f32_common(x, w, lut, x_range, w_range):
         _dev(r, torch.float32, name)
         if r.numel() != 2:
             raise ValueError("ranges must hold two floats")
-    if lut.dtype not in (torch.int16, torch.uint16):
-        raise TypeError("lut must be a 16-bit integer tensor")
-    _dev(lut, lut.dtype, "lut")
-    if lut.numel() != 65536:
-        raise ValueError("lut must have 65536 entries")
+    _check_lut(lut)
 
 
 def _outs(shape, device, acc_out, y_out):
@@ -454,6 +601,21 @@ def _outs(shape, device, acc_out, y_out):
     return acc_out, y_out
 
 
+def _f32_ex(desc, x, w, lut, x_range, w_range, relu, round_mode, acc_out, y_out, workspace, stream, out_shape):
+    L = lib()
+    acc_out, y_out = _outs(out_shape, x.device, acc_out, y_out)
+    t = _tune_arg()
+    if workspace is None:
+        workspace = _workspace(int(L.ax_conv2d_f32_ex_workspace_bytes(ctypes.byref(desc), t)), x.device, stream)
+    _dev(workspace, torch.uint8, "workspace")
+    rc = L.ax_conv2d_f32_ex(ctypes.byref(desc), t, _ptr(x), _ptr(w), _ptr(lut), _ptr(x_range), _ptr(w_range),
+                            int(bool(relu)), int(round_mode), _ptr(None if acc_out is False else acc_out),
+                            _ptr(None if y_out is False else y_out), _ptr(workspace), workspace.numel(),
+                            ctypes.c_void_p(_stream_ptr(stream)))
+    _check(rc)
+    return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
 def ax_conv2d_f32(x, w, lut, stride, pad, x_range=None, w_range=None, relu=False, round_mode=0, acc_out=None, y_out=None,
                   workspace=None, stream=None):
     """Float layer.  x: float32 [N,H,W,Cin]; w: float32 [KH,KW,Cin,Cout]; ranges: float32 CUDA
@@ -462,21 +624,19 @@ def ax_conv2d_f32(x, w, lut, stride, pad, x_range=None, w_range=None, relu=False
     _f32_common(x, w, lut, x_range, w_range)
     if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
         raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout]")
-    N, H, W, Cin = x.shape
-    KH, KW, _, Cout = w.shape
-    sh, sw = _pair(stride)
-    ph, pw = _pair(pad)
-    OH = (H + 2 * ph - KH) // sh + 1
-    OW = (W + 2 * pw - KW) // sw + 1
+    d = _conv_desc(x.shape, w.shape, stride, pad)
+    OH, OW = _out_hw(d)
     if OH <= 0 or OW <= 0:
         _check(-2)
-    acc_out, y_out = _outs((N, OH, OW, Cout), x.device, acc_out, y_out)
+    if _tune_arg() is not None:
+        return _f32_ex(d, x, w, lut, x_range, w_range, relu, round_mode, acc_out, y_out, workspace, stream,
+                       (d.N, OH, OW, d.Cout))
+    acc_out, y_out = _outs((d.N, OH, OW, d.Cout), x.device, acc_out, y_out)
     if workspace is None:
-        need = int(L.ax_conv2d_f32_workspace_bytes(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw))
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        workspace = _workspace(ax_conv2d_f32_workspace_bytes(x.shape, w.shape, stride, pad), x.device, stream)
     _dev(workspace, torch.uint8, "workspace")
-    rc = L.ax_conv2d_f32(_ptr(x), N, H, W, Cin, _ptr(w), KH, KW, Cout, _ptr(lut), sh, sw, ph, pw, _ptr(x_range),
-                         _ptr(w_range), int(bool(relu)), int(round_mode),
+    rc = L.ax_conv2d_f32(_ptr(x), d.N, d.H, d.W, d.Cin, _ptr(w), d.KH, d.KW, d.Cout, _ptr(lut), d.stride_h, d.stride_w,
+                         d.pad_h, d.pad_w, _ptr(x_range), _ptr(w_range), int(bool(relu)), int(round_mode),
                          _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
                          _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
     _check(rc)
@@ -487,32 +647,15 @@ def ax_conv2d_f32_ex(x, w, lut, stride, pad, x_range=None, w_range=None, relu=Fa
                      depthwise=False, signed=False, acc_out=None, y_out=None, workspace=None, stream=None):
     """Float layer with dilation / signed codes / depthwise filters (w [KH,KW,Cin,mult]).
     Returns (acc_out, y_out); pass False to skip one of them."""
-    L = lib()
     _f32_common(x, w, lut, x_range, w_range)
     if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
         raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout] (or [KH,KW,Cin,mult])")
-    N, H, W, Cin = x.shape
-    KH, KW, _, last = w.shape
-    Cout = Cin * last if depthwise else last
-    sh, sw = _pair(stride)
-    ph, pw = _pair(pad)
-    dh, dw = _pair(dilation)
-    desc = ax_conv_desc_t(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, dh, dw, int(bool(depthwise)), int(bool(signed)))
-    OH = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
-    OW = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+    desc = _conv_desc(x.shape, w.shape, stride, pad, dilation, depthwise, signed)
+    OH, OW = _out_hw(desc)
     if OH <= 0 or OW <= 0:
         _check(-2)
-    acc_out, y_out = _outs((N, OH, OW, Cout), x.device, acc_out, y_out)
-    if workspace is None:
-        need = int(L.ax_conv2d_f32_ex_workspace_bytes(ctypes.byref(desc)))
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
-    _dev(workspace, torch.uint8, "workspace")
-    rc = L.ax_conv2d_f32_ex(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(lut), _ptr(x_range), _ptr(w_range),
-                            int(bool(relu)), int(round_mode), _ptr(None if acc_out is False else acc_out),
-                            _ptr(None if y_out is False else y_out), _ptr(workspace), workspace.numel(),
-                            ctypes.c_void_p(_stream_ptr(stream)))
-    _check(rc)
-    return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+    return _f32_ex(desc, x, w, lut, x_range, w_range, relu, round_mode, acc_out, y_out, workspace, stream,
+                   (desc.N, OH, OW, desc.Cout))
 
 
 def ax_dense_f32(x, w, lut, x_range=None, w_range=None, relu=False, round_mode=0, acc_out=None, y_out=None, workspace=None,
@@ -524,9 +667,12 @@ def ax_dense_f32(x, w, lut, x_range=None, w_range=None, relu=False, round_mode=0
         raise ValueError("x must be [M,K] and w [K,N]")
     M, K = x.shape
     N = w.shape[1]
+    if _tune_arg() is not None:
+        return _f32_ex(_dense_desc(M, K, N), x, w, lut, x_range, w_range, relu, round_mode, acc_out, y_out, workspace,
+                       stream, (M, N))
     acc_out, y_out = _outs((M, N), x.device, acc_out, y_out)
     if workspace is None:
-        workspace = torch.empty(int(L.ax_dense_f32_workspace_bytes(M, K, N)), dtype=torch.uint8, device=x.device)
+        workspace = _workspace(ax_dense_f32_workspace_bytes(M, K, N), x.device, stream)
     _dev(workspace, torch.uint8, "workspace")
     rc = L.ax_dense_f32(_ptr(x), M, K, _ptr(w), N, _ptr(lut), _ptr(x_range), _ptr(w_range), int(bool(relu)),
                         int(round_mode), _ptr(None if acc_out is False else acc_out),

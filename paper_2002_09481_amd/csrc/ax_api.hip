@@ -1,31 +1,13 @@
-// C ABI of libaxconv: argument validation, dispatch, error text.  No device code here.
+// C ABI of libaxconv: argument validation, dispatch, layer handles, error text.  No device code
+// and no mutable global state here.
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
+#include <new>
 
 #include "ax_internal.h"
 
 namespace ax {
-
-Options g_opt = {0, 0, 0, 0, 0, 0};
-
-static hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
-static bool g_ev_valid = false;
-static int g_ev_reps = 1;  // launches of the main kernel between the two events
-
-void timing_begin(hipStream_t s) {
-  if (!g_opt.timing) return;
-  if (!g_ev0 && (hipEventCreate(&g_ev0) != hipSuccess || hipEventCreate(&g_ev1) != hipSuccess)) {
-    g_ev0 = g_ev1 = nullptr;
-    return;
-  }
-  g_ev_valid = hipEventRecord(g_ev0, s) == hipSuccess;
-}
-
-void timing_end(hipStream_t s, int reps) {
-  if (!g_opt.timing || !g_ev0) return;
-  g_ev_valid = g_ev_valid && hipEventRecord(g_ev1, s) == hipSuccess;
-  g_ev_reps = reps > 0 ? reps : 1;
-}
 
 // Unsigned codes: zero points and pad code in [0, 255], pad_code -1 (or AX_PAD_DEFAULT) = x_zp.
 // Signed codes: all three in [-128, 127], pad_code AX_PAD_DEFAULT = x_zp.
@@ -43,6 +25,18 @@ static int make_quant(const ax_quant_t* q, QParams* qp, int sgn = 0) {
   qp->scale = q->x_scale * q->w_scale;
   qp->dq = nullptr;
   qp->sgn = sgn ? 1 : 0;
+  return AX_OK;
+}
+
+int make_options(const ax_tune_t* t, Options* o) {
+  *o = Options{0, 0, 0, 0, 0};
+  if (!t) return AX_OK;
+  if (t->variant < 0 || t->variant > 3) return AX_ERR_OPTION;
+  if (t->split_k < 0 || t->split_k > 64) return AX_ERR_OPTION;
+  if (t->tile < 0 || t->tile > tab_num_tiles()) return AX_ERR_OPTION;
+  if (t->row_tiles < 0 || t->row_tiles > (1 << 20)) return AX_ERR_OPTION;
+  if (t->share_order < 0 || t->share_order > 2) return AX_ERR_OPTION;
+  *o = Options{t->variant, t->split_k, t->tile, t->row_tiles, t->share_order};
   return AX_OK;
 }
 
@@ -70,60 +64,84 @@ int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, in
   return AX_OK;
 }
 
-// 1 = direct, 2/3 = table-tile kernels
-static int choose_variant(const Geom& g) {
-  if (g_opt.variant == 1) return 1;
-  if (!tab_supported(g)) return 1;  // incl. depthwise layers: no shared table-side operand
-  if (g_opt.variant == 2 || g_opt.variant == 3) return g_opt.variant;
-  // Tiny problems do not amortize the table set-up.
-  if ((double)g.M * g.K * g.Cout < 4.0e6) return 1;
-  return 0;  // let the tab planner pick the lane assignment
+int geom_of_desc(const ax_conv_desc_t* d, Geom* g) {
+  if (!d) return AX_ERR_NULL;
+  if ((d->depthwise != 0 && d->depthwise != 1) || (d->signed_codes != 0 && d->signed_codes != 1)) return AX_ERR_OPTION;
+  return make_geom(d->N, d->H, d->W, d->Cin, d->KH, d->KW, d->Cout, d->stride_h, d->stride_w, d->pad_h, d->pad_w, g,
+                   d->dilation_h, d->dilation_w, d->signed_codes, d->depthwise);
 }
 
-int run_layer(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
-              int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, hipStream_t s) {
-  const int v = choose_variant(g);
-  hipError_t e;
-  if (v == 1) {  // kernels that take one table at a time
-    e = hipSuccess;
-    const bool dw = g.mult && g_opt.variant != 1 && dw_supported(g, x, w, lut);
-    const size_t per_table = (size_t)g.M * g.Cout;
-    for (int t = 0; t < g.T && e == hipSuccess; ++t) {
-      const uint16_t* lt = lut + (size_t)t * 65536;
-      int32_t* at = acc_out ? acc_out + t * per_table : nullptr;
-      float* yt = y_out ? y_out + t * per_table : nullptr;
-      e = dw ? launch_dw(g, qp, x, w, lt, at, yt, s) : launch_direct(g, qp, x, w, lt, at, yt, s);
-    }
-  } else {
-    Options o = g_opt;
-    o.variant = v;
-    const TabPlan p = tab_plan(g, o);
-    if (!ws || ws_bytes < p.total || ((uintptr_t)ws & 255)) return AX_ERR_WORKSPACE;
-    e = launch_tab(g, qp, p, x, w, lut, acc_out, y_out, ws, s);
+// 1 = direct (or depthwise) kernels, 0 = table-tile kernels with the planner's lane assignment,
+// 2 / 3 = table-tile kernels with that lane assignment
+static int choose_variant(const Geom& g, const Options& o) {
+  if (o.variant == 1) return 1;
+  if (!tab_supported(g)) return 1;  // incl. depthwise layers: no shared table-side operand
+  if (o.variant == 2 || o.variant == 3) return o.variant;
+  // Tiny problems do not amortize the table set-up.
+  if ((double)g.M * g.K * g.Cout < 4.0e6) return 1;
+  return 0;
+}
+
+// Kernels that take one table at a time and need neither preparation nor scratch.
+static int run_untiled(const Geom& g, const QParams& qp, const Options& o, const uint8_t* x, const uint8_t* w,
+                       const uint16_t* lut, int32_t* acc_out, float* y_out, hipStream_t s) {
+  const bool dw = g.mult && o.variant != 1 && dw_supported(g, x, w, lut);
+  const size_t per_table = (size_t)g.M * g.Cout;
+  for (int t = 0; t < g.T; ++t) {
+    const uint16_t* lt = lut + (size_t)t * 65536;
+    int32_t* at = acc_out ? acc_out + t * per_table : nullptr;
+    float* yt = y_out ? y_out + t * per_table : nullptr;
+    const hipError_t e = dw ? launch_dw(g, qp, x, w, lt, at, yt, s) : launch_direct(g, qp, x, w, lt, at, yt, s);
+    if (e != hipSuccess) return AX_ERR_HIP;
   }
+  return AX_OK;
+}
+
+int run_layer(const Geom& g, const QParams& qp, const Options& o, const uint8_t* x, const uint8_t* w,
+              const uint16_t* lut, int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, hipStream_t s) {
+  const int v = choose_variant(g, o);
+  if (v == 1) return run_untiled(g, qp, o, x, w, lut, acc_out, y_out, s);
+  Options ov = o;
+  ov.variant = v;
+  const TabPlan p = tab_plan(g, ov);
+  if (!ws || ws_bytes < p.prep_total + p.ws_total || ((uintptr_t)ws & 255)) return AX_ERR_WORKSPACE;
+  uint8_t* wsb = static_cast<uint8_t*>(ws);
+  const hipError_t e = launch_tab(g, qp, p, x, w, lut, acc_out, y_out, wsb, wsb + p.prep_total, kPhAll, 1, s);
   return e == hipSuccess ? AX_OK : AX_ERR_HIP;
 }
 
-static int run(const Geom& g, const ax_quant_t* q, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
-               int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, void* stream) {
+static int check_io(const void* x, const void* w, const void* lut, const int32_t* acc_out, const float* y_out) {
   if (!x || !w || !lut || (!acc_out && !y_out)) return AX_ERR_NULL;
   if (((uintptr_t)lut & 1) || ((uintptr_t)acc_out & 3) || ((uintptr_t)y_out & 3)) return AX_ERR_ALIGN;
-  QParams qp;
-  int rc = make_quant(q, &qp, g.sgn);
-  if (rc) return rc;
-  return run_layer(g, qp, x, w, lut, acc_out, y_out, ws, ws_bytes, (hipStream_t)stream);
+  return AX_OK;
 }
 
-size_t layer_workspace(const Geom& g) {
-  // Large enough for whichever variant the options may select later.
-  if (!tab_supported(g)) return 256;
-  size_t need = 256;
-  for (int v = 2; v <= 3; ++v) {
-    Options o = {v, g_opt.split_k, g_opt.tile, 0, g_opt.row_tiles, g_opt.share_order};
-    const size_t t = tab_plan(g, o).total;
-    if (t > need) need = t;
-  }
-  return need;
+static int run(const Geom& g, const ax_quant_t* q, const ax_tune_t* tune, const uint8_t* x, const uint8_t* w,
+               const uint16_t* lut, int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_io(x, w, lut, acc_out, y_out);
+  if (rc) return rc;
+  QParams qp;
+  rc = make_quant(q, &qp, g.sgn);
+  if (rc) return rc;
+  Options o;
+  rc = make_options(tune, &o);
+  if (rc) return rc;
+  return run_layer(g, qp, o, x, w, lut, acc_out, y_out, ws, ws_bytes, (hipStream_t)stream);
+}
+
+size_t layer_workspace(const Geom& g, const Options& o) {
+  const int v = choose_variant(g, o);
+  if (v == 1) return 256;
+  Options ov = o;
+  ov.variant = v;
+  const TabPlan p = tab_plan(g, ov);
+  return p.prep_total + p.ws_total;
+}
+
+static size_t workspace_of(const Geom& g, const ax_tune_t* tune) {
+  Options o;
+  if (make_options(tune, &o)) return 0;
+  return layer_workspace(g, o);
 }
 
 }  // namespace ax
@@ -137,37 +155,30 @@ extern "C" int ax_conv2d(const uint8_t* x, int N, int H, int W, int Cin, const u
   Geom g;
   int rc = make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g);
   if (rc) return rc;
-  return run(g, q, x, w, lut, acc_out, y_out, workspace, workspace_bytes, hip_stream);
+  return run(g, q, nullptr, x, w, lut, acc_out, y_out, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" size_t ax_conv2d_workspace_bytes(int N, int H, int W, int Cin, int KH, int KW, int Cout, int stride_h,
                                             int stride_w, int pad_h, int pad_w) {
   Geom g;
   if (make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g)) return 0;
-  return layer_workspace(g);
+  return workspace_of(g, nullptr);
 }
 
-static int geom_of(const ax_conv_desc_t* d, Geom* g) {
-  if (!d) return AX_ERR_NULL;
-  if ((d->depthwise != 0 && d->depthwise != 1) || (d->signed_codes != 0 && d->signed_codes != 1)) return AX_ERR_OPTION;
-  return make_geom(d->N, d->H, d->W, d->Cin, d->KH, d->KW, d->Cout, d->stride_h, d->stride_w, d->pad_h, d->pad_w, g,
-                   d->dilation_h, d->dilation_w, d->signed_codes, d->depthwise);
-}
-
-extern "C" int ax_conv2d_ex(const ax_conv_desc_t* desc, const void* x, const void* w, const void* lut,
-                            const ax_quant_t* q, int32_t* acc_out, float* y_out, void* workspace,
+extern "C" int ax_conv2d_ex(const ax_conv_desc_t* desc, const ax_tune_t* tune, const void* x, const void* w,
+                            const void* lut, const ax_quant_t* q, int32_t* acc_out, float* y_out, void* workspace,
                             size_t workspace_bytes, void* hip_stream) {
   Geom g;
-  int rc = geom_of(desc, &g);
+  int rc = geom_of_desc(desc, &g);
   if (rc) return rc;
-  return run(g, q, static_cast<const uint8_t*>(x), static_cast<const uint8_t*>(w), static_cast<const uint16_t*>(lut),
-             acc_out, y_out, workspace, workspace_bytes, hip_stream);
+  return run(g, q, tune, static_cast<const uint8_t*>(x), static_cast<const uint8_t*>(w),
+             static_cast<const uint16_t*>(lut), acc_out, y_out, workspace, workspace_bytes, hip_stream);
 }
 
-extern "C" size_t ax_conv2d_ex_workspace_bytes(const ax_conv_desc_t* desc) {
+extern "C" size_t ax_conv2d_ex_workspace_bytes(const ax_conv_desc_t* desc, const ax_tune_t* tune) {
   Geom g;
-  if (geom_of(desc, &g)) return 0;
-  return layer_workspace(g);
+  if (geom_of_desc(desc, &g)) return 0;
+  return workspace_of(g, tune);
 }
 
 extern "C" int ax_conv2d_multi_lut(const uint8_t* x, int N, int H, int W, int Cin, const uint8_t* w, int KH, int KW,
@@ -179,7 +190,7 @@ extern "C" int ax_conv2d_multi_lut(const uint8_t* x, int N, int H, int W, int Ci
   if (rc) return rc;
   if (num_luts < 1 || num_luts > 65536) return AX_ERR_SHAPE;
   g.T = num_luts;
-  return run(g, q, x, w, luts, acc_out, y_out, workspace, workspace_bytes, hip_stream);
+  return run(g, q, nullptr, x, w, luts, acc_out, y_out, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" size_t ax_conv2d_multi_lut_workspace_bytes(int N, int H, int W, int Cin, int KH, int KW, int Cout,
@@ -189,7 +200,7 @@ extern "C" size_t ax_conv2d_multi_lut_workspace_bytes(int N, int H, int W, int C
   if (make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g)) return 0;
   if (num_luts < 1 || num_luts > 65536) return 0;
   g.T = num_luts;
-  return layer_workspace(g);
+  return workspace_of(g, nullptr);
 }
 
 extern "C" int ax_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N, const uint16_t* lut,
@@ -198,13 +209,122 @@ extern "C" int ax_dense(const uint8_t* x, int M, int K, const uint8_t* w, int N,
   Geom g;
   int rc = make_geom(M, 1, 1, K, 1, 1, N, 1, 1, 0, 0, &g);
   if (rc) return rc;
-  return run(g, q, x, w, lut, acc_out, y_out, workspace, workspace_bytes, hip_stream);
+  return run(g, q, nullptr, x, w, lut, acc_out, y_out, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" size_t ax_dense_workspace_bytes(int M, int K, int N) {
   Geom g;
   if (make_geom(M, 1, 1, K, 1, 1, N, 1, 1, 0, 0, &g)) return 0;
-  return layer_workspace(g);
+  return workspace_of(g, nullptr);
+}
+
+// ---- layer handles --------------------------------------------------------------------------
+
+extern "C" int ax_layer_create(const ax_conv_desc_t* desc, int num_luts, const ax_quant_t* q, const ax_tune_t* tune,
+                               ax_layer_t** layer_out) {
+  if (!layer_out) return AX_ERR_NULL;
+  *layer_out = nullptr;
+  Geom g;
+  int rc = geom_of_desc(desc, &g);
+  if (rc) return rc;
+  if (num_luts < 1 || num_luts > 65536) return AX_ERR_SHAPE;
+  g.T = num_luts;
+  QParams qp;
+  rc = make_quant(q, &qp, g.sgn);
+  if (rc) return rc;
+  Options o;
+  rc = make_options(tune, &o);
+  if (rc) return rc;
+  ax_layer* L = new (std::nothrow) ax_layer();
+  if (!L) return AX_ERR_HIP;
+  L->g = g;
+  L->qp = qp;
+  L->o = o;
+  const int v = choose_variant(g, o);
+  L->tab = v != 1;
+  if (L->tab) {
+    Options ov = o;
+    ov.variant = v;
+    L->p = tab_plan(g, ov);
+  } else {
+    L->p = TabPlan{};
+  }
+  L->w = nullptr;
+  L->lut = nullptr;
+  L->prepared = nullptr;
+  L->ready = false;
+  *layer_out = L;
+  return AX_OK;
+}
+
+extern "C" void ax_layer_destroy(ax_layer_t* layer) { delete layer; }
+
+extern "C" size_t ax_layer_prepared_bytes(const ax_layer_t* layer) {
+  return layer && layer->tab ? layer->p.prep_total : 0;
+}
+
+extern "C" size_t ax_layer_workspace_bytes(const ax_layer_t* layer) {
+  return layer && layer->tab ? layer->p.ws_total : 0;
+}
+
+extern "C" int ax_layer_prepare(ax_layer_t* layer, const void* w, const void* luts, void* prepared,
+                                size_t prepared_bytes, void* hip_stream) {
+  if (!layer || !w || !luts) return AX_ERR_NULL;
+  if ((uintptr_t)luts & 1) return AX_ERR_ALIGN;
+  layer->ready = false;
+  if (layer->tab) {
+    if (!prepared || prepared_bytes < layer->p.prep_total || ((uintptr_t)prepared & 255)) return AX_ERR_WORKSPACE;
+    const hipError_t e = launch_tab(layer->g, layer->qp, layer->p, nullptr, static_cast<const uint8_t*>(w),
+                                    static_cast<const uint16_t*>(luts), nullptr, nullptr, prepared, nullptr, kPhConst,
+                                    1, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return AX_ERR_HIP;
+  }
+  layer->w = static_cast<const uint8_t*>(w);
+  layer->lut = static_cast<const uint16_t*>(luts);
+  layer->prepared = prepared;
+  layer->ready = true;
+  return AX_OK;
+}
+
+namespace ax {
+// Shared by ax_layer_run and the kernel-timing probe: the per-call parts of a prepared layer.
+int run_prepared(const ax_layer* layer, const void* x, int32_t* acc_out, float* y_out, void* workspace,
+                 size_t workspace_bytes, int phases, int main_reps, hipStream_t s) {
+  if (!layer) return AX_ERR_NULL;
+  if (!layer->ready) return AX_ERR_STATE;
+  int rc = check_io(x, layer->w, layer->lut, acc_out, y_out);
+  if (rc) return rc;
+  const uint8_t* xb = static_cast<const uint8_t*>(x);
+  if (!layer->tab) {
+    if (!(phases & kPhMain)) return AX_OK;
+    for (int r = 0; r < main_reps; ++r) {
+      rc = run_untiled(layer->g, layer->qp, layer->o, xb, layer->w, layer->lut, acc_out, y_out, s);
+      if (rc) return rc;
+    }
+    return AX_OK;
+  }
+  const TabPlan& p = layer->p;
+  if (p.ws_total && (!workspace || workspace_bytes < p.ws_total || ((uintptr_t)workspace & 255)))
+    return AX_ERR_WORKSPACE;
+  const hipError_t e = launch_tab(layer->g, layer->qp, p, xb, layer->w, layer->lut, acc_out, y_out, layer->prepared,
+                                  workspace, phases, main_reps, s);
+  return e == hipSuccess ? AX_OK : AX_ERR_HIP;
+}
+}  // namespace ax
+
+extern "C" int ax_layer_run(const ax_layer_t* layer, const void* x, int32_t* acc_out, float* y_out, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  return run_prepared(layer, x, acc_out, y_out, workspace, workspace_bytes, kPhCall | kPhMain | kPhFixup, 1,
+                      (hipStream_t)hip_stream);
+}
+
+extern "C" int ax_layer_plan(const ax_layer_t* layer, int* variant, int* tile, int* workgroups, int* pieces) {
+  if (!layer) return AX_ERR_NULL;
+  if (variant) *variant = layer->tab ? layer->p.variant : 1;
+  if (tile) *tile = layer->tab ? layer->p.tile + 1 : 0;
+  if (workgroups) *workgroups = layer->tab ? layer->p.G : 0;
+  if (pieces) *pieces = layer->tab ? layer->p.partials : 0;
+  return AX_OK;
 }
 
 extern "C" const char* ax_strerror(int code) {
@@ -217,85 +337,10 @@ extern "C" const char* ax_strerror(int code) {
     case AX_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
     case AX_ERR_HIP: return "HIP runtime call failed";
     case AX_ERR_ALIGN: return "pointer not aligned";
-    case AX_ERR_OPTION: return "unknown option or value out of range";
+    case AX_ERR_OPTION: return "flag, round mode or tuning value out of range";
+    case AX_ERR_STATE: return "layer handle has not been prepared";
     default: return "unknown error code";
   }
 }
 
-extern "C" int ax_version(void) { return 200; }
-
-extern "C" int ax_set_option(const char* name, int value) {
-  if (!name) return AX_ERR_OPTION;
-  if (!std::strcmp(name, "variant")) {
-    if (value < 0 || value > 3) return AX_ERR_OPTION;
-    g_opt.variant = value;
-    return AX_OK;
-  }
-  if (!std::strcmp(name, "split_k")) {
-    if (value < 0 || value > 64) return AX_ERR_OPTION;
-    g_opt.split_k = value;
-    return AX_OK;
-  }
-  if (!std::strcmp(name, "tile")) {
-    if (value < 0 || value > tab_num_tiles()) return AX_ERR_OPTION;
-    g_opt.tile = value;
-    return AX_OK;
-  }
-  if (!std::strcmp(name, "row_tiles")) {
-    if (value < 0 || value > (1 << 20)) return AX_ERR_OPTION;
-    g_opt.row_tiles = value;
-    return AX_OK;
-  }
-  if (!std::strcmp(name, "share_order")) {
-    if (value < 0 || value > 2) return AX_ERR_OPTION;
-    g_opt.share_order = value;
-    return AX_OK;
-  }
-  if (!std::strcmp(name, "timing")) {
-    if (value < 0 || value > 16) return AX_ERR_OPTION;
-    g_opt.timing = value;
-    return AX_OK;
-  }
-
-  return AX_ERR_OPTION;
-}
-
-extern "C" int ax_get_option(const char* name, int* value) {
-  if (!name || !value) return AX_ERR_OPTION;
-  if (!std::strcmp(name, "variant")) { *value = g_opt.variant; return AX_OK; }
-  if (!std::strcmp(name, "split_k")) { *value = g_opt.split_k; return AX_OK; }
-  if (!std::strcmp(name, "tile")) { *value = g_opt.tile; return AX_OK; }
-  if (!std::strcmp(name, "timing")) { *value = g_opt.timing; return AX_OK; }
-  if (!std::strcmp(name, "row_tiles")) { *value = g_opt.row_tiles; return AX_OK; }
-  if (!std::strcmp(name, "share_order")) { *value = g_opt.share_order; return AX_OK; }
-  return AX_ERR_OPTION;
-}
-
-extern "C" int ax_last_kernel_ms(float* ms) {
-  if (!ms) return AX_ERR_NULL;
-  if (!g_ev_valid || !g_ev0) return AX_ERR_OPTION;
-  if (hipEventSynchronize(g_ev1) != hipSuccess) return AX_ERR_HIP;
-  if (hipEventElapsedTime(ms, g_ev0, g_ev1) != hipSuccess) return AX_ERR_HIP;
-  *ms /= (float)g_ev_reps;
-  return AX_OK;
-}
-
-extern "C" int ax_conv2d_plan(int N, int H, int W, int Cin, int KH, int KW, int Cout, int stride_h, int stride_w,
-                              int pad_h, int pad_w, int* variant, int* tile, int* workgroups, int* pieces) {
-  Geom g;
-  int rc = make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g);
-  if (rc) return rc;
-  const int v = choose_variant(g);
-  int pv = 1, pt = 0, pg = 0, pp = 0;
-  if (v != 1) {
-    Options o = g_opt;
-    o.variant = v;
-    const TabPlan p = tab_plan(g, o);
-    pv = p.variant; pt = p.tile + 1; pg = p.G; pp = p.partials;
-  }
-  if (variant) *variant = pv;
-  if (tile) *tile = pt;
-  if (workgroups) *workgroups = pg;
-  if (pieces) *pieces = pp;
-  return AX_OK;
-}
+extern "C" int ax_version(void) { return 300; }

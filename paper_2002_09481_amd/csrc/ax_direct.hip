@@ -239,7 +239,6 @@ hipError_t launch_dw(const Geom& g, const QParams& qp, const uint8_t* x, const u
   const uint64_t items = (uint64_t)g.M * (g.Cin / 4);
   const uint32_t blocks = (uint32_t)std::min<uint64_t>((uint64_t)cu_count(), (items + 1023) / 1024);
   const int vec_out = ((((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
-  timing_begin(s);
   const bool keeps_channels = 1024 % (g.Cin / 4) == 0;  // the grid stride is then a multiple of the channel groups
   if (g.KH == 3 && g.KW == 3 && keeps_channels)
     hipLaunchKernelGGL((dw_kernel<3, true>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
@@ -249,7 +248,6 @@ hipError_t launch_dw(const Geom& g, const QParams& qp, const uint8_t* x, const u
     hipLaunchKernelGGL((dw_kernel<5, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
   else
     hipLaunchKernelGGL((dw_kernel<0, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
-  timing_end(s);
   return hipGetLastError();
 }
 
@@ -257,9 +255,7 @@ hipError_t launch_direct(const Geom& g, const QParams& qp, const uint8_t* x, con
                          const uint16_t* lut, int32_t* acc_out, float* y_out, hipStream_t s) {
   const uint64_t total = (uint64_t)g.M * g.Cout;
   const uint32_t blocks = (uint32_t)((total + 255) / 256);
-  timing_begin(s);
   hipLaunchKernelGGL(direct_kernel, dim3(blocks), dim3(256), 0, s, g, qp, x, w, lut, acc_out, y_out);
-  timing_end(s);
   return hipGetLastError();
 }
 

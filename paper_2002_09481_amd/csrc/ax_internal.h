@@ -42,39 +42,50 @@ struct QParams {
   int sgn;  // 1: signed codes (zero points and pad code in [-128, 127], also those read through dq)
 };
 
-// Shared tail of ax_conv2d / ax_conv2d_f32 (ax_api.hip): pick a kernel family and enqueue.
-int run_layer(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
-              int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, hipStream_t s);
-size_t layer_workspace(const Geom& g);
-int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw, Geom* g,
-              int dh = 1, int dw = 1, int sgn = 0, int depthwise = 0);
-
+// Tuning overrides of one call or layer handle (ax_tune_t checked and copied); all zero = automatic.
 struct Options {
-  int variant;  // 0 auto, 1 direct, 2 lanes over pixels, 3 lanes over channels
-  int split_k;  // 0 auto
-  int tile;     // index of the table-tile configuration (0 = default)
-  int timing;   // n >= 1: bracket n back-to-back launches of the main kernel of every call with HIP events
-  int row_tiles;  // 0 auto, 1 as few tiles along the lane dimension as fit, n that many (clamped)
+  int variant;      // 0 auto, 1 direct, 2 lanes over pixels, 3 lanes over channels
+  int split_k;      // 0 auto
+  int tile;         // index + 1 of the table-tile configuration (0 = automatic)
+  int row_tiles;    // 0 auto, 1 as few tiles along the lane dimension as fit, n that many (clamped)
   int share_order;  // numbering of the work shares: 0 auto, 1 launch order, 2 XCD by XCD
 };
-extern Options g_opt;
+// AX_OK, or AX_ERR_OPTION for a value out of range.  tune == nullptr gives the automatic choice.
+int make_options(const ax_tune_t* tune, Options* o);
 
-// Event pair around the most recent main-kernel launch (only when g_opt.timing is set).
-void timing_begin(hipStream_t s);
-void timing_end(hipStream_t s, int reps = 1);
+// Parts of a table-tile layer call (bit mask).  A one-shot call runs all of them; a layer handle
+// runs kPhConst once (ax_layer_prepare) and the others per call (ax_layer_run).
+enum : int {
+  kPhConst = 1,  // what depends on filters, table and coefficients only
+  kPhCall = 2,   // per-call operand preparation (depends on the activations)
+  kPhMain = 4,   // the lookup-MAC kernel
+  kPhFixup = 8,  // combination of tiles that several workgroups share
+  kPhAll = 15,
+};
+
+// Shared tail of the integer and the float layer calls (ax_api.hip): pick a kernel family and
+// enqueue all parts.  ws holds the prepared constants followed by the per-call scratch.
+int run_layer(const Geom& g, const QParams& qp, const Options& o, const uint8_t* x, const uint8_t* w,
+              const uint16_t* lut, int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, hipStream_t s);
+size_t layer_workspace(const Geom& g, const Options& o);
+int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw, Geom* g,
+              int dh = 1, int dw = 1, int sgn = 0, int depthwise = 0);
+int geom_of_desc(const ax_conv_desc_t* d, Geom* g);
 
 // Direct kernel (ax_direct.hip): needs no workspace.
 hipError_t launch_direct(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w,
                          const uint16_t* lut, int32_t* acc_out, float* y_out, hipStream_t s);
 
 // Depthwise kernel with the whole table in LDS (ax_direct.hip); dw_supported tells whether the
-// layer and its pointers fit it (channel multiplier 1, Cin a multiple of 4, aligned tensors,
-// enough work to pay for staging the table per workgroup).
+// layer and its pointers fit it.
 bool dw_supported(const Geom& g, const uint8_t* x, const uint8_t* w, const uint16_t* lut);
 hipError_t launch_dw(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
                      int32_t* acc_out, float* y_out, hipStream_t s);
 
-// Table-tile kernels (ax_tab.hip).
+// Table-tile kernels (ax_tab.hip).  Device memory of a layer comes in two blocks: the prepared
+// constants (re-laid-out table, packed filters and their sums, coefficients) and the per-call
+// scratch (materialized activations, pieces of shared tiles).  Offsets are relative to the block
+// the part lives in, which depends on the lane assignment (see tab_plan).
 struct TabPlan {
   int variant;      // 2 or 3
   int tile;         // index of the tile configuration
@@ -83,21 +94,46 @@ struct TabPlan {
   int nti;          // tiles along the lane dimension
   int ih;           // their height in lane elements (multiple of 64, nti * ih >= I)
   int xcd;          // 1: shares of work numbered XCD by XCD, 0: in launch order
-  size_t off_rows;  // workspace offsets (bytes)
-  size_t off_bpack;
-  size_t off_bsum;
-  size_t off_apack;
-  size_t off_part;
-  size_t off_lsum;
-  size_t off_qd;  // QDev block
-  size_t total;
+  size_t off_rows;   // prepared block
+  size_t off_qd;     // prepared block
+  size_t off_bpack;  // prepared block (variant 2) or scratch (variant 3)
+  size_t off_bsum;   // with off_bpack
+  size_t off_apack;  // scratch (variant 2) or prepared block (variant 3)
+  size_t off_part;   // scratch
+  size_t off_lsum;   // scratch
+  size_t prep_total;  // bytes of the prepared block (multiple of 256)
+  size_t ws_total;    // bytes of the scratch block
 };
 int cu_count();  // compute units of the current device
 bool tab_supported(const Geom& g);
 int tab_num_tiles();
 TabPlan tab_plan(const Geom& g, const Options& o);
+// Enqueue the parts named by `phases`; the main kernel `main_reps` times (measurement helpers
+// launch it repeatedly between two events; layer calls pass 1).
 hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const uint8_t* x,
                       const uint8_t* w, const uint16_t* lut, int32_t* acc_out, float* y_out,
-                      void* ws, hipStream_t s);
+                      void* prepared, void* scratch, int phases, int main_reps, hipStream_t s);
 
 }  // namespace ax
+
+struct ax_layer;
+namespace ax {
+// The per-call parts (`phases`) of a prepared layer, the main kernel `main_reps` times: shared by
+// ax_layer_run and the kernel-timing probe.
+int run_prepared(const ax_layer* layer, const void* x, int32_t* acc_out, float* y_out, void* workspace,
+                 size_t workspace_bytes, int phases, int main_reps, hipStream_t s);
+}  // namespace ax
+
+// Layer handle (ax_layer_create): host-side description of one layer, its plan and, once
+// ax_layer_prepare has run, the device block holding its constants.
+struct ax_layer {
+  ax::Geom g;
+  ax::QParams qp;
+  ax::Options o;
+  bool tab;        // table-tile kernels (else the direct / depthwise kernels)
+  ax::TabPlan p;   // valid when tab
+  const uint8_t* w;     // as given to ax_layer_prepare
+  const uint16_t* lut;
+  void* prepared;
+  bool ready;
+};

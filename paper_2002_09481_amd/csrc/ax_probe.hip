@@ -5,6 +5,7 @@
 #include <vector>
 
 #include "ax_internal.h"
+#include "axconv_probe.h"
 
 namespace ax {
 
@@ -157,7 +158,8 @@ extern "C" int ax_probe_lds_gather(int width_bytes, int pattern, int table_bytes
   using namespace ax;
   if (!wave_reads || !cycles || !seconds || !workgroups) return AX_ERR_NULL;
   if (width_bytes != 2 && width_bytes != 4 && width_bytes != 8 && width_bytes != 16) return AX_ERR_OPTION;
-  if (pattern < 0 || pattern > 2 || iters < 1 || iters > (1 << 20)) return AX_ERR_OPTION;
+  if (pattern < 0 || pattern > 6 || iters < 1 || iters > (1 << 20)) return AX_ERR_OPTION;
+  if (pattern >= 3 && (width_bytes != 16 || table_bytes < 4096)) return AX_ERR_OPTION;
   if (threads < 64 || threads > 1024 || threads % 64) return AX_ERR_OPTION;
   if (table_bytes < 1024 || table_bytes > 160 * 1024 || table_bytes % 1024) return AX_ERR_OPTION;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -176,6 +178,14 @@ extern "C" int ax_probe_lds_gather(int width_bytes, int pattern, int table_bytes
       uint32_t e;
       if (pattern == 0) {
         e = (lane + 64u * (uint32_t)j) % elems;
+      } else if (pattern >= 3) {
+        // sixteen tables interleaved entry by entry: element index = 16 * v + slot, v random; the
+        // slot is a function of the lane only, so 16 lanes with distinct slots never share a bank
+        const uint32_t slot = pattern == 3   ? (lane & 15u)
+                              : pattern == 4 ? ((lane >> 2) & 15u)
+                              : pattern == 5 ? ((lane & 7u) | ((lane >> 2) & 8u))
+                                             : ((lane & 3u) | ((lane >> 2) & 12u));
+        e = (rng() % (elems / 16u)) * 16u + slot;
       } else {
         e = rng() % elems;
         if (pattern == 2 && (rng() & 1u)) e = 0;
@@ -307,4 +317,37 @@ extern "C" int ax_probe_mac(int mode, int pattern, int iters, int wgs_per_cu, do
   *ops = mode == 0 ? (double)wgs * 1024 * 128.0 * iters : (double)lanes * 16.0 * NG * 8 * iters;
   *seconds = ms * 1e-3;
   return AX_OK;
+}
+
+// Events are created and destroyed here, outside the layer path, and the stream is waited for.
+extern "C" int ax_probe_layer_kernel_ms(const ax_layer_t* layer, const void* x, int32_t* acc_out, float* y_out,
+                                        void* workspace, size_t workspace_bytes, int reps, float* ms,
+                                        void* hip_stream) {
+  using namespace ax;
+  if (!ms) return AX_ERR_NULL;
+  if (reps < 1 || reps > 64) return AX_ERR_OPTION;
+  hipStream_t s = (hipStream_t)hip_stream;
+  int rc = run_prepared(layer, x, acc_out, y_out, workspace, workspace_bytes, kPhCall, 1, s);
+  if (rc) return rc;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  rc = AX_ERR_HIP;
+  do {
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) break;
+    if (hipEventRecord(e0, s) != hipSuccess) break;
+    rc = run_prepared(layer, x, acc_out, y_out, workspace, workspace_bytes, kPhMain, reps, s);
+    if (rc) break;
+    rc = AX_ERR_HIP;
+    if (hipEventRecord(e1, s) != hipSuccess) break;
+    rc = run_prepared(layer, x, acc_out, y_out, workspace, workspace_bytes, kPhFixup, 1, s);
+    if (rc) break;
+    rc = AX_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) break;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, e0, e1) != hipSuccess) break;
+    *ms = t / (float)reps;
+    rc = AX_OK;
+  } while (0);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  return rc;
 }

@@ -279,7 +279,7 @@ size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct F32Plan {
   size_t off_xpart, off_wpart, off_xq, off_wq, off_layer, total;
 };
-F32Plan f32_plan(const Geom& g) {
+F32Plan f32_plan(const Geom& g, const Options& o) {
   F32Plan p;
   size_t off = 256;
   p.off_xpart = off;
@@ -291,13 +291,13 @@ F32Plan f32_plan(const Geom& g) {
   p.off_wq = off;
   off += up256((size_t)g.K * g.Cout);
   p.off_layer = off;
-  p.total = off + layer_workspace(g);
+  p.total = off + layer_workspace(g, o);
   return p;
 }
 
 // Two launches in front of the convolution: one range launch covering whichever of the two
 // tensors came without a range, one quantization launch covering both tensors.
-int run_f32(const Geom& g, const float* x, const float* w, const uint16_t* lut, const float* x_range,
+int run_f32(const Geom& g, const ax_tune_t* tune, const float* x, const float* w, const uint16_t* lut, const float* x_range,
             const float* w_range, int relu, int mode, int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes,
             void* stream) {
   if (!x || !w || !lut || (!acc_out && !y_out)) return AX_ERR_NULL;
@@ -305,7 +305,9 @@ int run_f32(const Geom& g, const float* x, const float* w, const uint16_t* lut, 
       ((uintptr_t)lut & 1) || ((uintptr_t)acc_out & 3) || ((uintptr_t)y_out & 3))
     return AX_ERR_ALIGN;
   if (mode != 0 && mode != 1) return AX_ERR_OPTION;
-  const F32Plan p = f32_plan(g);
+  Options o;
+  if (make_options(tune, &o)) return AX_ERR_OPTION;
+  const F32Plan p = f32_plan(g, o);
   if (!ws || ws_bytes < p.total || ((uintptr_t)ws & 255)) return AX_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   uint8_t* wsb = static_cast<uint8_t*>(ws);
@@ -327,8 +329,14 @@ int run_f32(const Geom& g, const float* x, const float* w, const uint16_t* lut, 
   hipLaunchKernelGGL(quantize_kernel, dim3(qx.blocks + qw.blocks), dim3(kThreads), 0, s, qx, qw, mode);
   if (launched() != AX_OK) return AX_ERR_HIP;
   QParams qp{0, 0, 0, 1.0f, dq, g.sgn};
-  return run_layer(g, qp, wsb + p.off_xq, wsb + p.off_wq, lut, acc_out, y_out, wsb + p.off_layer,
+  return run_layer(g, qp, o, wsb + p.off_xq, wsb + p.off_wq, lut, acc_out, y_out, wsb + p.off_layer,
                    ws_bytes - p.off_layer, s);
+}
+
+size_t f32_workspace(const Geom& g, const ax_tune_t* tune) {
+  Options o;
+  if (make_options(tune, &o)) return 0;
+  return f32_plan(g, o).total;
 }
 
 }  // namespace
@@ -368,7 +376,7 @@ extern "C" int ax_conv2d_f32(const float* x, int N, int H, int W, int Cin, const
   Geom g;
   int rc = make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g);
   if (rc) return rc;
-  return run_f32(g, x, w, lut, x_range, w_range, relu, round_mode, acc_out, y_out, workspace, workspace_bytes,
+  return run_f32(g, nullptr, x, w, lut, x_range, w_range, relu, round_mode, acc_out, y_out, workspace, workspace_bytes,
                  hip_stream);
 }
 
@@ -376,31 +384,24 @@ extern "C" size_t ax_conv2d_f32_workspace_bytes(int N, int H, int W, int Cin, in
                                                 int stride_w, int pad_h, int pad_w) {
   Geom g;
   if (make_geom(N, H, W, Cin, KH, KW, Cout, stride_h, stride_w, pad_h, pad_w, &g)) return 0;
-  return f32_plan(g).total;
+  return f32_workspace(g, nullptr);
 }
 
-static int geom_of_desc(const ax_conv_desc_t* d, Geom* g) {
-  if (!d) return AX_ERR_NULL;
-  if ((d->depthwise != 0 && d->depthwise != 1) || (d->signed_codes != 0 && d->signed_codes != 1)) return AX_ERR_OPTION;
-  return make_geom(d->N, d->H, d->W, d->Cin, d->KH, d->KW, d->Cout, d->stride_h, d->stride_w, d->pad_h, d->pad_w, g,
-                   d->dilation_h, d->dilation_w, d->signed_codes, d->depthwise);
-}
-
-extern "C" int ax_conv2d_f32_ex(const ax_conv_desc_t* desc, const float* x, const float* w, const void* lut,
-                                const float* x_range, const float* w_range, int relu, int round_mode,
-                                int32_t* acc_out, float* y_out, void* workspace, size_t workspace_bytes,
-                                void* hip_stream) {
+extern "C" int ax_conv2d_f32_ex(const ax_conv_desc_t* desc, const ax_tune_t* tune, const float* x, const float* w,
+                                const void* lut, const float* x_range, const float* w_range, int relu,
+                                int round_mode, int32_t* acc_out, float* y_out, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
   Geom g;
   int rc = geom_of_desc(desc, &g);
   if (rc) return rc;
-  return run_f32(g, x, w, static_cast<const uint16_t*>(lut), x_range, w_range, relu, round_mode, acc_out, y_out,
-                 workspace, workspace_bytes, hip_stream);
+  return run_f32(g, tune, x, w, static_cast<const uint16_t*>(lut), x_range, w_range, relu, round_mode, acc_out,
+                 y_out, workspace, workspace_bytes, hip_stream);
 }
 
-extern "C" size_t ax_conv2d_f32_ex_workspace_bytes(const ax_conv_desc_t* desc) {
+extern "C" size_t ax_conv2d_f32_ex_workspace_bytes(const ax_conv_desc_t* desc, const ax_tune_t* tune) {
   Geom g;
   if (geom_of_desc(desc, &g)) return 0;
-  return f32_plan(g).total;
+  return f32_workspace(g, tune);
 }
 
 extern "C" int ax_dense_f32(const float* x, int M, int K, const float* w, int N, const uint16_t* lut,
@@ -409,12 +410,12 @@ extern "C" int ax_dense_f32(const float* x, int M, int K, const float* w, int N,
   Geom g;
   int rc = make_geom(M, 1, 1, K, 1, 1, N, 1, 1, 0, 0, &g);
   if (rc) return rc;
-  return run_f32(g, x, w, lut, x_range, w_range, relu, round_mode, acc_out, y_out, workspace, workspace_bytes,
+  return run_f32(g, nullptr, x, w, lut, x_range, w_range, relu, round_mode, acc_out, y_out, workspace, workspace_bytes,
                  hip_stream);
 }
 
 extern "C" size_t ax_dense_f32_workspace_bytes(int M, int K, int N) {
   Geom g;
   if (make_geom(M, 1, 1, K, 1, 1, N, 1, 1, 0, 0, &g)) return 0;
-  return f32_plan(g).total;
+  return f32_workspace(g, nullptr);
 }

@@ -213,7 +213,8 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     for (int p = 0; p < P; ++p) {
       const int iy = by[p] + ky * a.dh, ix = bx[p] + kx * a.dw;
       const bool inside = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
-      const uint32_t off = ((uint32_t)(nb[p] + iy) * (uint32_t)a.W + (uint32_t)ix) * (uint32_t)a.Cin + (uint32_t)ci0;
+      // pixel index below 2^31; times the row length it can pass 2^32 for a materialized operand
+      const size_t off = (size_t)((uint32_t)(nb[p] + iy) * (uint32_t)a.W + (uint32_t)ix) * (uint32_t)a.Cin + (uint32_t)ci0;
       v[p] = make_uint4(pad4, pad4, pad4, pad4);
       if (inside && act[p]) v[p] = *reinterpret_cast<const uint4*>(a.A + off);
     }
@@ -682,14 +683,17 @@ __device__ __forceinline__ uint32_t im2col_code(const ConvView& v, uint32_t pad,
 // the rows; block 128 + seg * (Jpad/64) + jb does 64 columns of one segment, thread = (4
 // columns, one of 16 row phases).
 // FROM_X: B[k][j] = im2col(x)[j][k] (lanes are channels) else B[k][j] = w[k*J + j].
+// do_rows = 0 leaves the table rows out (the grid then holds the packing blocks only), a grid of
+// only the row blocks leaves the packing out, do_qd = 0 leaves the coefficients alone: a layer
+// handle prepares what depends on filters and table once and the rest per call.
 constexpr int kRowBlocks = 128;
 template <bool FROM_X>
 __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ lut, uint32_t* __restrict__ rows32,
                                                     const uint8_t* __restrict__ w, ConvView cv, int K, int J, int krows,
                                                     int Jpad, int seg_rows, uint8_t* __restrict__ Bp,
                                                     int32_t* __restrict__ psum, QParams qp, QDev* __restrict__ qd,
-                                                    int tables) {
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
+                                                    int tables, int do_rows, int do_qd) {
+  if (do_qd && blockIdx.x == 0 && threadIdx.x == 0) {
     int xz = qp.x_zp, wz = qp.w_zp, pad = qp.pad_code;
     float sc = qp.scale;
     if (qp.dq) {
@@ -708,7 +712,8 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
     qd->pad4 = (((uint32_t)pad & 0xffu) ^ (qp.sgn ? 0x80u : 0u)) * 0x01010101u;
   }
   const uint32_t sx = qp.sgn ? 0x80u : 0u;  // pattern <-> offset-binary code; also moves int16 entries to offset form
-  if (blockIdx.x < kRowBlocks * tables) {  // kRowBlocks blocks per multiplier table
+  const int row_blocks = do_rows ? kRowBlocks * tables : 0;
+  if ((int)blockIdx.x < row_blocks) {  // kRowBlocks blocks per multiplier table
     const int tbl = blockIdx.x / kRowBlocks;
     lut += (size_t)tbl * 65536;
     rows32 += (size_t)tbl * 32768;
@@ -727,7 +732,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
     return;
   }
   __shared__ int32_t red[16][65];
-  const int b = blockIdx.x - kRowBlocks * tables;
+  const int b = blockIdx.x - row_blocks;
   const int jblocks = Jpad / 64;
   const int seg = b / jblocks, jb = b - seg * jblocks;
   const int c4 = threadIdx.x & 15, r = threadIdx.x >> 4;
@@ -1168,61 +1173,82 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
 
   const size_t Kp = (size_t)nch * kChunk;
   const size_t Jpad = (size_t)cdiv(J, 64) * 64;
-  size_t off = 0;
-  p.off_rows = off;   off += up256((size_t)131072 * g.T);
-  p.off_bpack = off;  off += up256((Kp + 1) * Jpad);
-  p.off_bsum = off;   off += up256(Jpad * 4 * kMaxSeg);
+  // Prepared block: what depends on filters, table and coefficients.  Scratch block: what depends
+  // on the activations.  The packed table-side operand is the filters for pixel lanes and the
+  // transposed patch matrix for channel lanes; the materialized lane-side operand the other way round.
+  const size_t bpack = up256((Kp + 1) * Jpad), bsum = up256(Jpad * 4 * kMaxSeg);
   // materialized lane operand, or (signed codes, implicit patch view) the offset-binary copy of x
-  p.off_apack = off;  off += up256(std::max((size_t)I * Kp, (size_t)g.N * g.H * g.W * g.Cin));
-  p.off_qd = off;     off += 256;
-  p.off_lsum = off;
-  p.off_part = off;
-  if (p.partials) {
-    off += up256((size_t)2 * G * kIT * 4);
-    p.off_part = off;
-    off += up256((size_t)2 * G * kIT * kJT * 4);
+  const size_t apack = up256(std::max((size_t)I * Kp, v == 2 ? (size_t)g.N * g.H * g.W * g.Cin : (size_t)0));
+  size_t prep = 0, ws = 0;
+  p.off_rows = prep;  prep += up256((size_t)131072 * g.T);
+  p.off_qd = prep;    prep += 256;
+  if (v == 2) {
+    p.off_bpack = prep;  prep += bpack;
+    p.off_bsum = prep;   prep += bsum;
+    p.off_apack = ws;    ws += apack;
+  } else {
+    p.off_apack = prep;  prep += apack;
+    p.off_bpack = ws;    ws += bpack;
+    p.off_bsum = ws;     ws += bsum;
   }
-  p.total = off;
+  p.off_lsum = ws;
+  p.off_part = ws;
+  if (p.partials) {
+    ws += up256((size_t)2 * G * kIT * 4);
+    p.off_part = ws;
+    ws += up256((size_t)2 * G * kIT * kJT * 4);
+  }
+  p.prep_total = prep;
+  p.ws_total = ws;
   return p;
 }
 
+// First error of a sequence of launches: every launch is followed by a look at the runtime's
+// error state, and nothing more is enqueued after a failure.
+#define AX_LAUNCHED()                               \
+  do {                                              \
+    const hipError_t e_ = hipGetLastError();        \
+    if (e_ != hipSuccess) return e_;                \
+  } while (0)
+
 template <int THREADS, int P, int NG, int KS, int WPE, bool CH>
-static void launch_cfg(const TabArgs& a, int G, int ntiles, bool fixup, hipStream_t s) {
-  // With the "timing" option n the main kernel is launched n times between the two events (it
-  // rewrites the same outputs and pieces), so that the events' own cost does not weigh on a launch.
-  const int reps = g_opt.timing > 1 ? g_opt.timing : 1;
-  timing_begin(s);
-  for (int r = 0; r < reps; ++r) {
+static hipError_t launch_cfg(const TabArgs& a, int G, int ntiles, int phases, int reps, hipStream_t s) {
+  for (int r = 0; r < reps && (phases & kPhMain); ++r) {
     if (a.K > 16384)
       hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, WPE, CH, true>), dim3(G), dim3(THREADS), 0, s, a);
     else
       hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, WPE, CH, false>), dim3(G), dim3(THREADS), 0, s, a);
+    AX_LAUNCHED();
   }
-  timing_end(s, reps);
-  if (fixup && G >= 16 * ntiles)
+  if (!(phases & kPhFixup)) return hipSuccess;
+  if (G >= 16 * ntiles)
     hipLaunchKernelGGL((tab_fixup_kernel<THREADS * P, NG * 8, CH, true>), dim3(ntiles * (THREADS * P / 64)), dim3(256), 0, s, a, G);
-  else if (fixup)
+  else
     hipLaunchKernelGGL((tab_fixup_kernel<THREADS * P, NG * 8, CH, false>), dim3(ntiles * (THREADS * P / 64)), dim3(256), 0, s, a, G);
+  return hipGetLastError();
 }
 
+// phases: kPhMain and / or kPhFixup (the latter only for plans with partial pieces)
 template <bool CH>
-static void launch_main(const TileCfg& t, const TabArgs& a, int G, int ntiles, bool fixup, hipStream_t s) {
+static hipError_t launch_main(const TileCfg& t, const TabArgs& a, int G, int ntiles, int phases, int reps, hipStream_t s) {
   const int key = t.threads * 10000 + t.P * 1000 + t.NG * 100 + t.KS * 10 + t.wpe;
   switch (key) {
-    case 5120000 + 2812: launch_cfg<512, 2, 8, 1, 2, CH>(a, G, ntiles, fixup, s); break;
-    case 10240000 + 1824: launch_cfg<1024, 1, 8, 2, 4, CH>(a, G, ntiles, fixup, s); break;
-    case 10240000 + 2444: launch_cfg<1024, 2, 4, 4, 4, CH>(a, G, ntiles, fixup, s); break;
-    case 10240000 + 2244: launch_cfg<1024, 2, 2, 4, 4, CH>(a, G, ntiles, fixup, s); break;
-    case 10240000 + 2284: launch_cfg<1024, 2, 2, 8, 4, CH>(a, G, ntiles, fixup, s); break;
-    case 5120000 + 2244: launch_cfg<512, 2, 2, 4, 4, CH>(a, G, ntiles, fixup, s); break;
-    case 5120000 + 2424: launch_cfg<512, 2, 4, 2, 4, CH>(a, G, ntiles, fixup, s); break;
-    default: break;
+    case 5120000 + 2812: return launch_cfg<512, 2, 8, 1, 2, CH>(a, G, ntiles, phases, reps, s);
+    case 10240000 + 1824: return launch_cfg<1024, 1, 8, 2, 4, CH>(a, G, ntiles, phases, reps, s);
+    case 10240000 + 2444: return launch_cfg<1024, 2, 4, 4, 4, CH>(a, G, ntiles, phases, reps, s);
+    case 10240000 + 2244: return launch_cfg<1024, 2, 2, 4, 4, CH>(a, G, ntiles, phases, reps, s);
+    case 10240000 + 2284: return launch_cfg<1024, 2, 2, 8, 4, CH>(a, G, ntiles, phases, reps, s);
+    case 5120000 + 2244: return launch_cfg<512, 2, 2, 4, 4, CH>(a, G, ntiles, phases, reps, s);
+    case 5120000 + 2424: return launch_cfg<512, 2, 4, 2, 4, CH>(a, G, ntiles, phases, reps, s);
+    default: return hipErrorInvalidValue;  // a tile configuration without an instantiated kernel
   }
 }
 
 hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const uint8_t* x, const uint8_t* w,
-                      const uint16_t* lut, int32_t* acc_out, float* y_out, void* ws, hipStream_t s) {
-  uint8_t* wsb = static_cast<uint8_t*>(ws);
+                      const uint16_t* lut, int32_t* acc_out, float* y_out, void* prepared, void* scratch, int phases,
+                      int main_reps, hipStream_t s) {
+  uint8_t* pb = static_cast<uint8_t*>(prepared);
+  uint8_t* sb = static_cast<uint8_t*>(scratch);
   const bool ch = (p.variant == 3);
   const int I = ch ? g.Cout : g.M;
   const int J = ch ? g.M : g.Cout;
@@ -1231,11 +1257,13 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   const TileCfg& tc = kTiles[p.tile];
   const int kJT = tc.NG * 8;
   const int Jpad = cdiv(J, 64) * 64;
-  uint16_t* rows = reinterpret_cast<uint16_t*>(wsb + p.off_rows);
-  uint8_t* Bp = wsb + p.off_bpack;
-  int32_t* bsum = reinterpret_cast<int32_t*>(wsb + p.off_bsum);
-  uint8_t* Ap = wsb + p.off_apack;
-  QDev* qd = reinterpret_cast<QDev*>(wsb + p.off_qd);
+  uint16_t* rows = reinterpret_cast<uint16_t*>(pb + p.off_rows);
+  QDev* qd = reinterpret_cast<QDev*>(pb + p.off_qd);
+  // pixel lanes: packed filters and their sums are constants, the materialized patches per call;
+  // channel lanes: the transposed filters are constants, packed patches and their sums per call
+  uint8_t* Bp = (ch ? sb : pb) + p.off_bpack;
+  int32_t* bsum = reinterpret_cast<int32_t*>((ch ? sb : pb) + p.off_bsum);
+  uint8_t* Ap = (ch ? pb : sb) + p.off_apack;
 
   ConvView cv{x, g.H, g.W, g.Cin, g.KW, g.sh, g.sw, g.ph, g.pw, g.OH, g.OW, g.M, g.K, qp.pad_code, qp.dq,
               g.dh, g.dw, g.sgn ? 0x80u : 0u};
@@ -1246,43 +1274,60 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   const int krows = Kp + 1;
   const int nseg = std::max(1, std::min(kMaxSeg, cdiv(krows, 64)));
   const int seg_rows = cdiv(cdiv(krows, nseg), 16) * 16;
-  const dim3 pgrid(kRowBlocks * g.T + nseg * (Jpad / 64));
-  if (ch)
-    hipLaunchKernelGGL((prep_kernel<true>), pgrid, dim3(256), 0, s, lut, reinterpret_cast<uint32_t*>(rows), w, cv, g.K, J,
-                       krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T);
-  else
-    hipLaunchKernelGGL((prep_kernel<false>), pgrid, dim3(256), 0, s, lut, reinterpret_cast<uint32_t*>(rows), w, cv, g.K, J,
-                       krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T);
+  const int row_blocks = kRowBlocks * g.T, pack_blocks = nseg * (Jpad / 64);
+  const bool implicit_view = !ch && g.Cin % 16 == 0 && ((uintptr_t)x & 15) == 0;
+  uint32_t* rows32 = reinterpret_cast<uint32_t*>(rows);
 
-  TabArgs a{};
-  a.I = I;
   if (ch) {
-    hipLaunchKernelGGL(prep_transpose_kernel, dim3(cdiv(Kp, 64), cdiv(g.Cout, 64)), dim3(256), 0, s, w, g.K,
-                       g.Cout, Kp, Ap, cv.sx);
-    a.A = Ap;
-    a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
-    a.dh = 1; a.dw = 1;
-  } else if (g.Cin % 16 == 0 && ((uintptr_t)x & 15) == 0) {
-    a.A = x;
-    if (g.sgn) {  // N*H*W*Cin is a multiple of 16 here
+    // one launch when both parts are wanted; otherwise rows + coefficients (+ the transposed
+    // filters) as constants, and the packing of the patches per call
+    const bool c = phases & kPhConst, k = phases & kPhCall;
+    if (c || k) {
+      hipLaunchKernelGGL((prep_kernel<true>), dim3((c ? row_blocks : 0) + (k ? pack_blocks : 0)), dim3(256), 0, s, lut,
+                         rows32, w, cv, g.K, J, krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T, c ? 1 : 0, c ? 1 : 0);
+      AX_LAUNCHED();
+    }
+    if (c) {
+      hipLaunchKernelGGL(prep_transpose_kernel, dim3(cdiv(Kp, 64), cdiv(g.Cout, 64)), dim3(256), 0, s, w, g.K,
+                         g.Cout, Kp, Ap, cv.sx);
+      AX_LAUNCHED();
+    }
+  } else {
+    if (phases & kPhConst) {
+      hipLaunchKernelGGL((prep_kernel<false>), dim3(row_blocks + pack_blocks), dim3(256), 0, s, lut, rows32, w, cv, g.K,
+                         J, krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T, 1, 1);
+      AX_LAUNCHED();
+    }
+    if ((phases & kPhCall) && implicit_view && g.sgn) {  // N*H*W*Cin is a multiple of 16 here
       const uint32_t n16 = (uint32_t)(((size_t)g.N * g.H * g.W * g.Cin) / 16);
       hipLaunchKernelGGL(prep_flip_kernel, dim3(cdiv(n16, 256)), dim3(256), 0, s, reinterpret_cast<const uint4*>(x),
                          reinterpret_cast<uint4*>(Ap), n16);
-      a.A = Ap;
+      AX_LAUNCHED();
+    } else if ((phases & kPhCall) && !implicit_view) {
+      if (im2col_staged_fits(cv, g.KH, Kp) && g.OH <= 65535 && g.N <= 65535) {
+        const size_t stage_bytes = im2col_stage_bytes(cv, g.KH);
+        hipLaunchKernelGGL(prep_im2col_lds_kernel, dim3(cdiv(g.OW, kStripe), g.OH, g.N), dim3(256),
+                           (unsigned)(stage_bytes + (size_t)Kp * 4), s, cv, g.KH, Kp, (int)im2col_row_bytes(cv),
+                           (int)stage_bytes, Ap);
+      } else {
+        const long long pieces = (long long)g.M * (Kp / 16);
+        hipLaunchKernelGGL(prep_im2col_kernel, dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, s, cv, Kp, Ap);
+      }
+      AX_LAUNCHED();
     }
+  }
+  const bool fixup = p.partials > 0;
+  const int run = (phases & kPhMain) | (fixup ? (phases & kPhFixup) : 0);
+  if (!run) return hipSuccess;
+
+  TabArgs a{};
+  a.I = I;
+  if (implicit_view) {
+    a.A = g.sgn ? Ap : x;
     a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.KW = g.KW; a.sh = g.sh; a.sw = g.sw; a.ph = g.ph; a.pw = g.pw;
     a.OHW = g.OH * g.OW; a.OW = g.OW;
     a.dh = g.dh; a.dw = g.dw;
-  } else {
-    if (im2col_staged_fits(cv, g.KH, Kp) && g.OH <= 65535 && g.N <= 65535) {
-      const size_t stage_bytes = im2col_stage_bytes(cv, g.KH);
-      hipLaunchKernelGGL(prep_im2col_lds_kernel, dim3(cdiv(g.OW, kStripe), g.OH, g.N), dim3(256),
-                         (unsigned)(stage_bytes + (size_t)Kp * 4), s, cv, g.KH, Kp, (int)im2col_row_bytes(cv),
-                         (int)stage_bytes, Ap);
-    } else {
-      const long long pieces = (long long)g.M * (Kp / 16);
-      hipLaunchKernelGGL(prep_im2col_kernel, dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, s, cv, Kp, Ap);
-    }
+  } else {  // materialized operand: I rows of Kp bytes
     a.A = Ap;
     a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
     a.dh = 1; a.dw = 1;
@@ -1297,15 +1342,14 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.qd = qd;
   a.bias_k = g.sgn ? 32768u * (uint32_t)g.K : 0u;
   a.acc_out = acc_out; a.y_out = y_out;
-  a.part = reinterpret_cast<int32_t*>(wsb + p.off_part);
-  a.lsum = reinterpret_cast<int32_t*>(wsb + p.off_lsum);
+  a.part = reinterpret_cast<int32_t*>(sb + p.off_part);
+  a.lsum = reinterpret_cast<int32_t*>(sb + p.off_lsum);
   a.out_elems = (long long)g.M * g.Cout;
   a.xcd = p.xcd;
   a.vec_out = (!ch && J % 4 == 0 && (((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
 
-  const bool fixup = p.partials > 0;
-  if (ch) launch_main<true>(tc, a, p.G, ntiles, fixup, s); else launch_main<false>(tc, a, p.G, ntiles, fixup, s);
-  return hipGetLastError();
+  return ch ? launch_main<true>(tc, a, p.G, ntiles, run, main_reps, s)
+            : launch_main<false>(tc, a, p.G, ntiles, run, main_reps, s);
 }
 
 }  // namespace ax

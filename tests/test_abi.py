@@ -1,5 +1,5 @@
-"""The C-ABI library loads and exports every function include/axconv.h declares (CPU only:
-no compute call is made)."""
+"""The C-ABI library loads and exports every function include/axconv.h and
+include/axconv_probe.h declare (CPU only: no compute call is made)."""
 
 import ctypes
 import os
@@ -12,21 +12,26 @@ from paper_2002_09481_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    src = open(os.path.join(ROOT, "include", "axconv.h")).read()
+def _declared(header):
+    src = open(os.path.join(ROOT, "include", header)).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(ax_[a-z0-9_]+)\s*\(", src)))
 
 
 def test_header_functions_are_exported():
-    names = _declared()
-    assert "ax_conv2d" in names and "ax_dense" in names and len(names) >= 8
+    names = _declared("axconv.h")
+    probes = _declared("axconv_probe.h")
+    assert "ax_conv2d" in names and "ax_dense" in names and "ax_layer_run" in names and len(names) >= 20
+    assert "ax_probe_lds_gather" in probes and not set(names) & set(probes)
     if not os.path.exists(binding.LIB_PATH):
         pytest.skip("libaxconv.so not built")
     L = ctypes.CDLL(binding.LIB_PATH)
-    for n in names:
+    for n in names + probes:
         assert hasattr(L, n), n
     assert sorted(binding.EXPORTS) == names
+    assert sorted(binding.PROBE_EXPORTS) == probes
+    # no process-wide option state is left in the library
+    assert not hasattr(L, "ax_set_option") and not hasattr(L, "ax_last_kernel_ms")
 
 
 def test_host_side_calls_without_gpu():
@@ -41,7 +46,7 @@ def test_host_side_calls_without_gpu():
         binding.ax_set_option("variant", 99)
     with pytest.raises(binding.AxError):
         binding.ax_set_option("no_such_option", 1)
-    for name, top in (("share_order", 2), ("timing", 16), ("row_tiles", 1 << 20)):
+    for name, top in (("share_order", 2), ("split_k", 64), ("row_tiles", 1 << 20)):
         binding.ax_set_option(name, top)
         assert binding.ax_get_option(name) == top
         with pytest.raises(binding.AxError):
@@ -75,23 +80,31 @@ def test_host_side_validation_of_the_later_entry_points():
     q = binding.ax_quant_t(1.0, 0, 1.0, 0, -1)
     D = binding.ax_conv_desc_t
     ok = D(1, 8, 8, 16, 3, 3, 16, 1, 1, 1, 1, 1, 1, 0, 0)
-    assert L.ax_conv2d_ex_workspace_bytes(ctypes.byref(ok)) >= 256
-    assert L.ax_conv2d_ex(None, one, one, one, ctypes.byref(q), one, one, one, 1 << 20, None) == -1
+    assert L.ax_conv2d_ex_workspace_bytes(ctypes.byref(ok), None) >= 256
+    assert L.ax_conv2d_ex(None, None, one, one, one, ctypes.byref(q), one, one, one, 1 << 20, None) == -1
     bad_dil = D(1, 8, 8, 16, 3, 3, 16, 1, 1, 1, 1, 0, 1, 0, 0)
-    assert L.ax_conv2d_ex(ctypes.byref(bad_dil), one, one, one, ctypes.byref(q), one, one, one, 1 << 20, None) == -2
+    assert L.ax_conv2d_ex(ctypes.byref(bad_dil), None, one, one, one, ctypes.byref(q), one, one, one, 1 << 20, None) == -2
     too_wide = D(1, 8, 8, 16, 3, 3, 16, 1, 1, 1, 1, 5, 5, 0, 0)  # dilated kernel larger than the padded image
-    assert L.ax_conv2d_ex_workspace_bytes(ctypes.byref(too_wide)) == 0
+    assert L.ax_conv2d_ex_workspace_bytes(ctypes.byref(too_wide), None) == 0
     bad_flag = D(1, 8, 8, 16, 3, 3, 16, 1, 1, 1, 1, 1, 1, 0, 3)
-    assert L.ax_conv2d_ex(ctypes.byref(bad_flag), one, one, one, ctypes.byref(q), one, one, one, 1 << 20, None) == -8
+    assert L.ax_conv2d_ex(ctypes.byref(bad_flag), None, one, one, one, ctypes.byref(q), one, one, one, 1 << 20, None) == -8
     bad_dw = D(1, 8, 8, 16, 3, 3, 24, 1, 1, 1, 1, 1, 1, 1, 0)  # Cout not a multiple of Cin
-    assert L.ax_conv2d_ex_workspace_bytes(ctypes.byref(bad_dw)) == 0
+    assert L.ax_conv2d_ex_workspace_bytes(ctypes.byref(bad_dw), None) == 0
     signed = D(1, 8, 8, 16, 3, 3, 16, 1, 1, 1, 1, 1, 1, 0, 1)
     qs = binding.ax_quant_t(1.0, -128, 1.0, 127, binding.AX_PAD_DEFAULT)
-    assert L.ax_conv2d_ex(ctypes.byref(signed), None, one, one, ctypes.byref(qs), one, one, one, 1 << 20, None) == -1
+    assert L.ax_conv2d_ex(ctypes.byref(signed), None, None, one, one, ctypes.byref(qs), one, one, one, 1 << 20, None) == -1
     qbad = binding.ax_quant_t(1.0, 128, 1.0, 0, binding.AX_PAD_DEFAULT)  # 128 is no signed code
-    assert L.ax_conv2d_ex(ctypes.byref(signed), one, one, one, ctypes.byref(qbad), one, one, one, 1 << 20, None) == -3
+    assert L.ax_conv2d_ex(ctypes.byref(signed), None, one, one, one, ctypes.byref(qbad), one, one, one, 1 << 20, None) == -3
+    # tuning values travel with the call and are range-checked there
+    T = binding.ax_tune_t
+    assert L.ax_conv2d_ex_workspace_bytes(ctypes.byref(ok), ctypes.byref(T(2, 0, 0, 0, 0))) >= 131072
+    assert L.ax_conv2d_ex_workspace_bytes(ctypes.byref(ok), ctypes.byref(T(4, 0, 0, 0, 0))) == 0
+    assert L.ax_conv2d_ex(ctypes.byref(ok), ctypes.byref(T(0, 65, 0, 0, 0)), one, one, one, ctypes.byref(q), one, one,
+                          one, 1 << 20, None) == -8
+    assert L.ax_conv2d_ex(ctypes.byref(ok), ctypes.byref(T(0, 0, 99, 0, 0)), one, one, one, ctypes.byref(q), one, one,
+                          one, 1 << 20, None) == -8
     # table counts
-    assert binding.ax_conv2d_multi_lut_workspace_bytes((1, 8, 8, 16), (3, 3, 16, 16), 4, 1, 1) >= 4 * 131072
+    assert binding.ax_conv2d_multi_lut_workspace_bytes((8, 28, 28, 64), (3, 3, 64, 64), 4, 1, 1) >= 4 * 131072
     assert L.ax_conv2d_multi_lut_workspace_bytes(1, 8, 8, 16, 3, 3, 16, 0, 1, 1, 1, 1) == 0
     assert L.ax_conv2d_multi_lut(one, 1, 8, 8, 16, one, 3, 3, 16, one, 0, 1, 1, 1, 1, ctypes.byref(q), one, one, one,
                                  1 << 30, None) == -2
@@ -107,6 +120,63 @@ def test_host_side_validation_of_the_later_entry_points():
                            None) == -8
     assert L.ax_conv2d_f32(one, 1, 8, 8, 16, one, 3, 3, 16, one, 1, 1, 1, 1, None, None, 0, 0, one, one, one, 16,
                            None) == -5
-    assert L.ax_conv2d_f32_ex(None, one, one, one, None, None, 0, 0, one, one, one, 1 << 30, None) == -1
-    assert L.ax_conv2d_f32_ex_workspace_bytes(ctypes.byref(signed)) > 0
-    assert binding.ax_version() >= 200
+    assert L.ax_conv2d_f32_ex(None, None, one, one, one, None, None, 0, 0, one, one, one, 1 << 30, None) == -1
+    assert L.ax_conv2d_f32_ex_workspace_bytes(ctypes.byref(signed), None) > 0
+    assert binding.ax_version() >= 300
+
+
+def test_layer_handles_on_the_host():
+    """Creation, sizes, plan and state checks of a layer handle need no device."""
+    if not os.path.exists(binding.LIB_PATH):
+        pytest.skip("libaxconv.so not built")
+    L = binding.lib()
+    D, T = binding.ax_conv_desc_t, binding.ax_tune_t
+    q = binding.ax_quant_t(1.0, 0, 1.0, 0, -1)
+    one = ctypes.c_void_p(256)
+    h = ctypes.c_void_p()
+    big = D(32, 56, 56, 64, 3, 3, 64, 1, 1, 1, 1, 1, 1, 0, 0)
+    assert L.ax_layer_create(ctypes.byref(big), 1, ctypes.byref(q), None, None) == -1
+    assert L.ax_layer_create(None, 1, ctypes.byref(q), None, ctypes.byref(h)) == -1 and not h
+    assert L.ax_layer_create(ctypes.byref(big), 0, ctypes.byref(q), None, ctypes.byref(h)) == -2 and not h
+    assert L.ax_layer_create(ctypes.byref(big), 1, None, None, ctypes.byref(h)) == -1 and not h
+    assert L.ax_layer_create(ctypes.byref(big), 1, ctypes.byref(q), ctypes.byref(T(9, 0, 0, 0, 0)), ctypes.byref(h)) == -8
+    assert L.ax_layer_create(ctypes.byref(big), 1, ctypes.byref(q), None, ctypes.byref(h)) == 0 and h
+    prep, ws = L.ax_layer_prepared_bytes(h), L.ax_layer_workspace_bytes(h)
+    # re-laid-out table + packed filters (36 chunks of 16 taps + 1 row, 64 columns) + sums + coefficients
+    assert prep >= 131072 + 577 * 64 + 256 and prep % 256 == 0 and ws % 256 == 0
+    # the one-call workspace is the two blocks back to back
+    assert binding.ax_conv2d_workspace_bytes((32, 56, 56, 64), (3, 3, 64, 64), 1, 1) == prep + ws
+    v, t, g, p = (ctypes.c_int() for _ in range(4))
+    assert L.ax_layer_plan(h, ctypes.byref(v), ctypes.byref(t), ctypes.byref(g), ctypes.byref(p)) == 0
+    assert v.value == 2 and t.value >= 1 and 1 <= g.value <= 4096
+    assert L.ax_layer_run(h, one, one, one, one, 1 << 40, None) == -9  # not prepared yet
+    assert L.ax_layer_prepare(h, one, one, one, 16, None) == -5      # prepared block too small
+    assert L.ax_layer_prepare(h, None, one, one, 1 << 40, None) == -1
+    L.ax_layer_destroy(h)
+    L.ax_layer_destroy(None)
+    # forcing the lane assignment changes what is a constant: channel lanes prepare the transposed filters
+    with binding.AxLayer(big, q, tune=dict(variant=3, split_k=0, tile=0, row_tiles=0, share_order=0)) as lay:
+        assert lay.plan()["variant"] == 3 and lay.prepared_bytes >= 131072 + 64 * 576
+    # tiny and depthwise layers take kernels that need neither block
+    with binding.AxLayer(D(1, 4, 4, 8, 3, 3, 8, 1, 1, 1, 1, 1, 1, 0, 0), q) as lay:
+        assert lay.plan() == {"variant": 1, "tile": 0, "workgroups": 0, "pieces": 0}
+        assert lay.prepared_bytes == 0 and lay.workspace_bytes == 0
+    with binding.AxLayer(D(8, 56, 56, 64, 3, 3, 64, 1, 1, 1, 1, 1, 1, 1, 0), q) as lay:
+        assert lay.plan()["variant"] == 1 and lay.prepared_bytes == 0
+    # many tables: one re-laid-out table each
+    with binding.AxLayer(big, q, num_luts=4) as lay:
+        assert lay.prepared_bytes >= 4 * 131072
+
+
+def test_materialized_operand_beyond_four_gib_is_planned_for_the_tile_kernels():
+    """A layer whose materialized patch matrix passes 2^32 bytes (Cin not a multiple of 16, many
+    pixels) stays on the table-tile kernels: its row offsets are 64-bit.  The scratch block must
+    hold that matrix."""
+    if not os.path.exists(binding.LIB_PATH):
+        pytest.skip("libaxconv.so not built")
+    D = binding.ax_conv_desc_t
+    q = binding.ax_quant_t(1.0, 0, 1.0, 0, -1)
+    with binding.AxLayer(D(150, 360, 360, 24, 3, 3, 8, 1, 1, 1, 1, 1, 1, 0, 0), q) as lay:
+        M, Kp = 150 * 360 * 360, 224
+        assert M * Kp > 1 << 32
+        assert lay.plan()["variant"] == 2 and lay.workspace_bytes >= M * Kp

@@ -205,7 +205,7 @@ def test_descriptor_errors():
     # for signed layers -1 is a code, not "default": accepted
     ax.ax_conv2d_ex(x.to(torch.int8), w.to(torch.int8), lut, 1, 1, I.Quant(1.0, 0, 1.0, 0, -1))
     d = ax.ax_conv_desc_t(1, 4, 4, 2, 3, 3, 3, 1, 1, 1, 1, 1, 1, 1, 0)  # depthwise with Cout % Cin != 0
-    assert L_.ax_conv2d_ex_workspace_bytes(d) == 0
+    assert L_.ax_conv2d_ex_workspace_bytes(d, None) == 0
     d = ax.ax_conv_desc_t(1, 4, 4, 2, 3, 3, 2, 1, 1, 1, 1, 1, 1, 2, 0)  # flag that is neither 0 nor 1
-    assert L_.ax_conv2d_ex_workspace_bytes(d) == 0
+    assert L_.ax_conv2d_ex_workspace_bytes(d, None) == 0
     torch.cuda.synchronize()
