@@ -287,6 +287,14 @@ extern "C" int ax_layer_prepare(ax_layer_t* layer, const void* w, const void* lu
 }
 
 namespace ax {
+size_t scratch_need(const ax_layer* layer, const void* x) {
+  if (!layer || !layer->tab) return 0;
+  const TabPlan& p = layer->p;
+  // unsigned activations read in place leave the last part of the scratch unused
+  const bool unused = p.variant == 2 && !layer->g.sgn && reads_in_place(layer->g, x);
+  return p.ws_total - (unused ? p.ws_apack : 0);
+}
+
 // Shared by ax_layer_run and the kernel-timing probe: the per-call parts of a prepared layer.
 int run_prepared(const ax_layer* layer, const void* x, int32_t* acc_out, float* y_out, void* workspace,
                  size_t workspace_bytes, int phases, int main_reps, hipStream_t s) {
@@ -304,8 +312,8 @@ int run_prepared(const ax_layer* layer, const void* x, int32_t* acc_out, float* 
     return AX_OK;
   }
   const TabPlan& p = layer->p;
-  if (p.ws_total && (!workspace || workspace_bytes < p.ws_total || ((uintptr_t)workspace & 255)))
-    return AX_ERR_WORKSPACE;
+  const size_t need = scratch_need(layer, x);
+  if (need && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return AX_ERR_WORKSPACE;
   const hipError_t e = launch_tab(layer->g, layer->qp, p, xb, layer->w, layer->lut, acc_out, y_out, layer->prepared,
                                   workspace, phases, main_reps, s);
   return e == hipSuccess ? AX_OK : AX_ERR_HIP;

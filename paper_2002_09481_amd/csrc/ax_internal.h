@@ -103,6 +103,7 @@ struct TabPlan {
   size_t off_lsum;   // scratch
   size_t prep_total;  // bytes of the prepared block (multiple of 256)
   size_t ws_total;    // bytes of the scratch block
+  size_t ws_apack;    // of which, at its end, the materialized activations (variant 2; else 0)
 };
 int cu_count();  // compute units of the current device
 bool tab_supported(const Geom& g);
@@ -122,6 +123,12 @@ namespace ax {
 // ax_layer_run and the kernel-timing probe.
 int run_prepared(const ax_layer* layer, const void* x, int32_t* acc_out, float* y_out, void* workspace,
                  size_t workspace_bytes, int phases, int main_reps, hipStream_t s);
+// Scratch bytes a call of the prepared layer on activations at `x` really uses: the layer's
+// ax_layer_workspace_bytes, less the room for materialized activations where they are read in place.
+size_t scratch_need(const ax_layer* layer, const void* x);
+// Whether a table-tile layer with pixel lanes reads activations at `x` in place (implicit patch
+// view: 16-byte aligned, channel count a multiple of 16) instead of materializing the patches.
+bool reads_in_place(const Geom& g, const void* x);
 }  // namespace ax
 
 // Layer handle (ax_layer_create): host-side description of one layer, its plan and, once

@@ -950,6 +950,8 @@ static const TileCfg kTiles[] = {
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 int tab_num_tiles() { return kNumTiles; }
 
+bool reads_in_place(const Geom& g, const void* x) { return g.Cin % 16 == 0 && ((uintptr_t)x & 15) == 0; }
+
 // The preparation kernels index their pieces with 32-bit integers.
 bool tab_supported(const Geom& g) {
   if (g.mult) return false;  // depthwise: every output channel has its own lane-side operand
@@ -1185,7 +1187,6 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   if (v == 2) {
     p.off_bpack = prep;  prep += bpack;
     p.off_bsum = prep;   prep += bsum;
-    p.off_apack = ws;    ws += apack;
   } else {
     p.off_apack = prep;  prep += apack;
     p.off_bpack = ws;    ws += bpack;
@@ -1197,6 +1198,13 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
     ws += up256((size_t)2 * G * kIT * 4);
     p.off_part = ws;
     ws += up256((size_t)2 * G * kIT * kJT * 4);
+  }
+  // last, so that a call whose activations can be read in place needs the scratch only up to here
+  p.ws_apack = 0;
+  if (v == 2) {
+    p.off_apack = ws;
+    p.ws_apack = apack;
+    ws += apack;
   }
   p.prep_total = prep;
   p.ws_total = ws;
@@ -1275,7 +1283,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   const int nseg = std::max(1, std::min(kMaxSeg, cdiv(krows, 64)));
   const int seg_rows = cdiv(cdiv(krows, nseg), 16) * 16;
   const int row_blocks = kRowBlocks * g.T, pack_blocks = nseg * (Jpad / 64);
-  const bool implicit_view = !ch && g.Cin % 16 == 0 && ((uintptr_t)x & 15) == 0;
+  const bool implicit_view = !ch && reads_in_place(g, x);
   uint32_t* rows32 = reinterpret_cast<uint32_t*>(rows);
 
   if (ch) {
