@@ -66,9 +66,9 @@ struct TabArgs {
   uint32_t bias_k;   // 32768 * K for signed tables (their entries are stored with that offset), else 0
   int32_t* acc_out;
   float* y_out;
-  int32_t* part;  // [2*G][IT*JT] partial tiles: slot 2w = workgroup w's piece of a tile begun by
+  int32_t* part;  // [2*G][JT][ih] partial tiles: slot 2w = workgroup w's piece of a tile begun by
                   // another workgroup, slot 2w+1 = its piece of a tile it begins but does not end
-  int32_t* lsum;  // [2*G][IT] lane-operand sums of the same pieces
+  int32_t* lsum;  // [2*G][ih] lane-operand sums of the same pieces
   long long out_elems;   // outputs per table (M * Cout)
   int ntiles1;           // tiles of one table; tile index space = table * ntiles1 + tile (several tables: ax_conv2d_multi_lut)
   int vec_out;  // outputs may be written in aligned 16-byte pieces along j
@@ -143,7 +143,6 @@ __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
 template <int THREADS, int P, int NG, int KS, int WPE, bool CH, bool WIDE>
 __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   constexpr int JT = NG * 8;
-  constexpr int IT = P * THREADS;
   constexpr int WAVES = THREADS / 64;
   constexpr int HALVES = 2 * NG * KS;  // half-tables (128 entries) to build per phase
   constexpr int UNITS = (HALVES + WAVES - 1) / WAVES;
@@ -423,16 +422,17 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   if (!whole) {
     // Piece of a tile that several workgroups share: stored column-major ([column][lane
     // element]) so that consecutive lanes write consecutive words straight from their registers.
+    // a slot holds a.ih lane elements (the tile height) of JT columns
     const int slot = 2 * wg + (c_beg > 0 ? 0 : 1);
-    int32_t* part = a.part + (size_t)slot * (IT * JT);
-    int32_t* lsum = a.lsum + (size_t)slot * IT;
+    int32_t* part = a.part + (size_t)slot * ((size_t)a.ih * JT);
+    int32_t* lsum = a.lsum + (size_t)slot * a.ih;
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-      if (!act[p]) continue;  // rows of tile padding: the fix-up never reads them
       const int il = p * THREADS + tid;
+      if (!act[p] || il >= a.ih) continue;  // rows of tile padding: the fix-up never reads them
       lsum[il] = (int32_t)sl[p];
 #pragma unroll
-      for (int j = 0; j < JT; ++j) part[j * IT + il] = (int32_t)acc[p][j];
+      for (int j = 0; j < JT; ++j) part[(size_t)j * a.ih + il] = (int32_t)acc[p][j];
     }
   }
   if (finish && tid < JT) {
@@ -577,10 +577,10 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const int slot = 2 * (w + k) + (w + k == w_first ? 1 : 0);
-        const int32_t* pp = a.part + (size_t)slot * (IT * JT) + il0 + r;
+        const int32_t* pp = a.part + (size_t)slot * ((size_t)a.ih * JT) + il0 + r;
 #pragma unroll
-        for (int c = 0; c < CPT; ++c) tv[k][c] = (uint32_t)pp[(cg * CPT + c) * IT];
-        ts[k] = (uint32_t)a.lsum[(size_t)slot * IT + il0 + r];
+        for (int c = 0; c < CPT; ++c) tv[k][c] = (uint32_t)pp[(size_t)(cg * CPT + c) * a.ih];
+        ts[k] = (uint32_t)a.lsum[(size_t)slot * a.ih + il0 + r];
       }
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
@@ -592,10 +592,10 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
   }
   for (; w <= w_last; ++w) {
     const int slot = 2 * w + (w == w_first ? 1 : 0);
-    const int32_t* pp = a.part + (size_t)slot * (IT * JT) + il0 + r;
+    const int32_t* pp = a.part + (size_t)slot * ((size_t)a.ih * JT) + il0 + r;
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) v[c] += (uint32_t)pp[(cg * CPT + c) * IT];
-    sl += (uint32_t)a.lsum[(size_t)slot * IT + il0 + r];
+    for (int c = 0; c < CPT; ++c) v[c] += (uint32_t)pp[(size_t)(cg * CPT + c) * a.ih];
+    sl += (uint32_t)a.lsum[(size_t)slot * a.ih + il0 + r];
   }
   const uint32_t lterm = (uint32_t)a.qd->z_tab * sl;
   const float scale = a.qd->scale;
@@ -1170,7 +1170,7 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   const int G = best.G;
   const long long I = (v == 2) ? g.M : g.Cout;
   const long long J = (v == 2) ? g.Cout : g.M;
-  const int kIT = tc.threads * tc.P, kJT = tc.NG * 8;
+  const int kJT = tc.NG * 8;
   const int nch = cdiv(g.K, kChunk);
 
   const size_t Kp = (size_t)nch * kChunk;
@@ -1194,10 +1194,10 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   }
   p.off_lsum = ws;
   p.off_part = ws;
-  if (p.partials) {
-    ws += up256((size_t)2 * G * kIT * 4);
+  if (p.partials) {  // two slots per workgroup, each one tile high
+    ws += up256((size_t)2 * G * p.ih * 4);
     p.off_part = ws;
-    ws += up256((size_t)2 * G * kIT * kJT * 4);
+    ws += up256((size_t)2 * G * p.ih * kJT * 4);
   }
   // last, so that a call whose activations can be read in place needs the scratch only up to here
   p.ws_apack = 0;
