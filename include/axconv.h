@@ -203,6 +203,20 @@ int ax_layer_prepare(ax_layer_t* layer, const void* w, const void* luts, void* p
  * AX_ERR_STATE before the first ax_layer_prepare. */
 int ax_layer_run(const ax_layer_t* layer, const void* x, int32_t* acc_out, float* y_out,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
+/*
+ * ax_layer_run for callers that cannot allocate device memory or hand in a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The per-call scratch
+ * is a device array inside the library (ax_static_scratch_bytes() = 64 MiB, held by every GPU the
+ * library runs on until the process ends); the call allocates and frees nothing.  Inputs, outputs
+ * and results as for ax_layer_run.  AX_ERR_WORKSPACE when the call needs more scratch than the
+ * array holds (what it needs is at most ax_layer_workspace_bytes(), less when the activations can
+ * be read in place: 16-byte aligned, unsigned, channel count a multiple of 16).  All calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU (different streams) race.
+ */
+int ax_layer_run_static(const ax_layer_t* layer, const void* x, int32_t* acc_out, float* y_out,
+                        void* hip_stream);
+size_t ax_static_scratch_bytes(void);
+
 /* What the handle's calls run (host arithmetic only): variant as in ax_tune_t (1, 2 or 3), tile
  * configuration (0 for the direct and depthwise kernels), grid size of the main kernel and
  * number of partial tile pieces it produces.  Any output pointer may be NULL. */

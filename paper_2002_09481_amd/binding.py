@@ -47,7 +47,8 @@ EXPORTS = [  # include/axconv.h
     "ax_conv2d_f32_workspace_bytes", "ax_dense_f32", "ax_dense_f32_workspace_bytes", "ax_conv2d_ex",
     "ax_conv2d_ex_workspace_bytes", "ax_conv2d_multi_lut", "ax_conv2d_multi_lut_workspace_bytes", "ax_conv2d_f32_ex",
     "ax_conv2d_f32_ex_workspace_bytes", "ax_layer_create", "ax_layer_destroy", "ax_layer_prepared_bytes",
-    "ax_layer_workspace_bytes", "ax_layer_prepare", "ax_layer_run", "ax_layer_plan",
+    "ax_layer_workspace_bytes", "ax_layer_prepare", "ax_layer_run", "ax_layer_plan", "ax_layer_run_static",
+    "ax_static_scratch_bytes",
 ]
 PROBE_EXPORTS = [  # include/axconv_probe.h
     "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_probe_layer_kernel_ms",
@@ -112,6 +113,10 @@ def lib():
     L.ax_layer_run.restype = ci
     L.ax_layer_plan.argtypes = [vp, ip, ip, ip, ip]
     L.ax_layer_plan.restype = ci
+    L.ax_layer_run_static.argtypes = [vp, vp, vp, vp, vp]
+    L.ax_layer_run_static.restype = ci
+    L.ax_static_scratch_bytes.argtypes = []
+    L.ax_static_scratch_bytes.restype = sz
     L.ax_probe_layer_kernel_ms.argtypes = [vp, vp, vp, vp, vp, sz, ci, ctypes.POINTER(ctypes.c_float), vp]
     L.ax_probe_layer_kernel_ms.restype = ci
     L.ax_probe_copy.argtypes = [vp, vp, sz, vp]
@@ -151,6 +156,10 @@ def lib():
 def _check(rc: int):
     if rc != 0:
         raise AxError(rc, lib().ax_strerror(rc).decode())
+
+
+def ax_static_scratch_bytes() -> int:
+    return int(lib().ax_static_scratch_bytes())
 
 
 def ax_strerror(code: int) -> str:
@@ -501,6 +510,19 @@ class AxLayer:
         _check(lib().ax_layer_run(self._h, _ptr(x), _ptr(None if acc_out is False else acc_out),
                                   _ptr(None if y_out is False else y_out), _ptr(workspace), workspace.numel(),
                                   ctypes.c_void_p(_stream_ptr(stream))))
+        return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+    def run_static(self, x, acc_out, y_out, stream=None):
+        """ax_layer_run_static: scratch from the library's static device array; nothing is
+        allocated, so the outputs must be handed in (False skips one of them)."""
+        cdt = torch.int8 if self.desc.signed_codes else torch.uint8
+        _dev(x, cdt, "x")
+        if acc_out is None or y_out is None:
+            raise ValueError("run_static allocates nothing: pass acc_out and y_out (False to skip one)")
+        acc_out, y_out = _outs(self.out_shape(), x.device, acc_out, y_out)
+        _check(lib().ax_layer_run_static(self._h, _ptr(x), _ptr(None if acc_out is False else acc_out),
+                                         _ptr(None if y_out is False else y_out),
+                                         ctypes.c_void_p(_stream_ptr(stream))))
         return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
 
     def kernel_ms(self, x, acc_out=None, y_out=None, workspace=None, reps: int = 8, stream=None) -> float:
