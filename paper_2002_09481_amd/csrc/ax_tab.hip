@@ -24,6 +24,7 @@
 // combined by a small fix-up kernel (integer addition is associative: same bits).
 #include <algorithm>
 #include <cmath>
+#include <cstddef>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -42,7 +43,10 @@ struct QDev {
   long long kzz;          // K * z_lane * z_tab
   float scale;            // x_scale * w_scale
   uint32_t pad4;          // pad code in all four bytes
+  uint32_t pad_[2];
+  uint32_t padrow[4];     // sixteen pad codes (16-byte aligned): what a tap outside the image reads
 };
+static_assert(sizeof(QDev) == 48 && offsetof(QDev, padrow) == 32, "padrow must be 16-byte aligned");
 
 struct TabArgs {
   // lane-side operand, addressed as an implicit im2col view of an [N,H,W,Cin] tensor
@@ -156,7 +160,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint32_t pad4 = a.qd->pad4;
+  const uint8_t* padrow = reinterpret_cast<const uint8_t*>(a.qd->padrow);
   const int klast = a.nch * kChunk;  // padded K = index of the last (zero) row of Bp
   // Taps K .. klast-1 exist only in materialized operands, where both codes are 0: each adds
   // the table entry (0,0) to every accumulator, which the final epilogue takes off again.
@@ -214,8 +218,12 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
       const bool inside = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
       // pixel index below 2^31; times the row length it can pass 2^32 for a materialized operand
       const size_t off = (size_t)((uint32_t)(nb[p] + iy) * (uint32_t)a.W + (uint32_t)ix) * (uint32_t)a.Cin + (uint32_t)ci0;
-      v[p] = make_uint4(pad4, pad4, pad4, pad4);
-      if (inside && act[p]) v[p] = *reinterpret_cast<const uint4*>(a.A + off);
+      // Every lane loads: taps outside the image (and lanes of tile padding) read sixteen pad codes
+      // kept in device memory.  A load that only some waves issued would leave the number of loads
+      // in flight unknown at compile time, and every later wait for table rows would then have to
+      // wait for all loads, the activation prefetch from HBM included.
+      const uint8_t* src = (inside && act[p]) ? a.A + off : padrow;
+      v[p] = *reinterpret_cast<const uint4*>(src);
     }
   };
 
@@ -356,11 +364,11 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
         if (ph == 0 && q == 0) {
           // operand and codes of the next chunk: fetched behind the first row fetches of this
           // chunk, so that the wait for those rows does not also wait for these
+          // (also after the last chunk of a segment: the addresses stay inside the operands, the
+          // values are not used, and the number of loads in flight stays known to the compiler)
           __builtin_amdgcn_sched_barrier(0);
-          if (c + 1 < nchunks) {
-            load_chunk(k0 + kChunk, xn);
-            tvv = fetch_codes(k0 + kChunk + KS);
-          }
+          load_chunk(k0 + kChunk, xn);
+          tvv = fetch_codes(k0 + kChunk + KS);
         }
         __builtin_amdgcn_sched_barrier(0);
         if (act[p]) {
@@ -710,6 +718,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
     qd->kzz = (long long)K * xz * wz + (qp.sgn ? 128LL * K * (xz + wz) : 0LL);
     qd->scale = sc;
     qd->pad4 = (((uint32_t)pad & 0xffu) ^ (qp.sgn ? 0x80u : 0u)) * 0x01010101u;
+    for (int e = 0; e < 4; ++e) qd->padrow[e] = qd->pad4;
   }
   const uint32_t sx = qp.sgn ? 0x80u : 0u;  // pattern <-> offset-binary code; also moves int16 entries to offset form
   const int row_blocks = do_rows ? kRowBlocks * tables : 0;
