@@ -393,10 +393,44 @@ def main():
         ms = time_calls(fns, 3)
         m4 = sum(l.macs for l in l4) * 64
         extra["config4_lut_sweep_64_tables"] = {"ms": ms, "lut_macs_per_s": m4 / ms * 1e3, "tables_per_s": 64 / ms * 1e3}
-        # the same, with every table's 128 KB host-to-device copy (from pinned host memory) inside the
-        # timed region, enqueued on the same stream in front of the table's two layer calls
-        host_luts = [torch.from_numpy(np.ascontiguousarray(I.lut_random_error(sd)).reshape(-1).view(np.int16).copy())
-                     .pin_memory() for sd in range(64)]
+        # the same, with every table's 128 KB host-to-device copy (from page-locked host memory) inside
+        # the timed region: (a) enqueued on the compute stream in front of the table's two layers,
+        # (b) on a second stream, overlapping the layers that run on the previous table
+        # (sweep.TableSweep: two staging buffers, event-ordered).  Both go through layer handles
+        # (prepare + run per table and layer), like (c), the tables resident in device memory.
+        from paper_2002_09481_amd.sweep import TableSweep
+        host_all = torch.from_numpy(np.stack([np.ascontiguousarray(I.lut_random_error(sd)).reshape(-1)
+                                              for sd in range(64)]).view(np.int16).copy()).pin_memory()
+        sw_layers = []
+        for i, l in enumerate(l4):
+            x, w, q = I.make_operands(l, I.layer_seed(4, i))
+            sw_layers.append((ax._conv_desc(x.shape, w.shape, l.stride, l.pad), q, torch.from_numpy(x).to(dev),
+                              torch.from_numpy(w).to(dev)))
+        for chunk, tag in ((1, "per_table"), (8, "eight_tables_per_call")):
+            sw = TableSweep(sw_layers, chunk=chunk)
+            acc_sw = [torch.empty(sw.out_shape(li, 64), dtype=torch.int32, device=dev) for li in range(len(l4))]
+            y_sw = [torch.empty(sw.out_shape(li, 64), dtype=torch.float32, device=dev) for li in range(len(l4))]
+            ms_ser = time_calls([lambda: sw.run(host_all, acc_sw, y_sw, overlap=False)], 3)
+            ms_ovl = time_calls([lambda: sw.run(host_all, acc_sw, y_sw, overlap=True)], 3)
+            # tables already in device memory: the same handles, prepare + run per chunk
+            resident = host_all.to(dev)
+
+            def run_resident():
+                for t0 in range(0, 64, chunk):
+                    for li in range(len(l4)):
+                        h = sw._handle(li, chunk)
+                        h.prepare(sw_layers[li][3], resident[t0:t0 + chunk], prepared=sw._blocks[(li, chunk, 0)])
+                        a, yy = acc_sw[li][t0:t0 + chunk], y_sw[li][t0:t0 + chunk]
+                        h.run(sw_layers[li][2], a[0] if chunk == 1 else a, yy[0] if chunk == 1 else yy,
+                              workspace=sw._ws[(li, chunk)])
+            ms_res = time_calls([run_resident], 3)
+            extra["config4_lut_sweep_64_tables_handles_" + tag] = {
+                "ms_tables_resident": ms_res, "ms_upload_on_compute_stream": ms_ser, "ms_upload_overlapped": ms_ovl,
+                "overlapped_over_resident": ms_ovl / ms_res, "lut_macs_per_s_overlapped": m4 / ms_ovl * 1e3,
+                "tables_per_s_overlapped": 64 / ms_ovl * 1e3}
+            sw.close()
+            del acc_sw, y_sw, resident
+        host_luts = [host_all[sd] for sd in range(64)]
         stage = torch.empty(65536, dtype=torch.int16, device=dev)
 
         def with_upload(h):
