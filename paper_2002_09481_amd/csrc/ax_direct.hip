@@ -73,29 +73,36 @@ __global__ __launch_bounds__(256) void direct_kernel(Geom g, QParams qp_in, cons
   }
 }
 
-// Depthwise layers (channel multiplier 1, Cin % 4 == 0).  No table-side operand is shared
-// between output channels, so the table-tile scheme does not apply; instead every workgroup
-// keeps the whole 128 KB table in LDS (one workgroup of 1024 threads per compute unit) and
-// gathers 2-byte entries at random addresses.  One thread takes 4 consecutive channels of one
-// output pixel: activations and filters arrive as one dword per tap, the four results leave as
-// one 16-byte store per output tensor.  Signed tables are stored with 32768 added to every
-// entry and activation sums are taken over the byte patterns with the top bit flipped (code +
-// 128); both offsets come off again in the epilogue.
-constexpr int kDwMaxC = 4096;  // channels whose filter sums fit next to the table in LDS
+// Depthwise layers.  No table-side operand is shared between output channels, so the table-tile
+// scheme does not apply; instead every workgroup keeps the whole 128 KB table in LDS (one
+// workgroup of 1024 threads per compute unit) and gathers 2-byte entries at data-dependent
+// addresses.  One thread takes 4 consecutive output channels of one output pixel and stores 16
+// bytes per output tensor.  Signed tables are stored with 32768 added to every entry and activation
+// sums are taken over the byte patterns with the top bit flipped (code + 128); both offsets come
+// off again in the epilogue.
+//
+// Table rows (one per activation code) are kDwRow = 129 dwords apart, not 128: with a stride of
+// 128 dwords the LDS bank of an entry depends on the filter code alone, and the lanes of a wave
+// that work on the same channels of different pixels (same filter codes, different activation
+// codes) would all fall into one bank.  With the odd stride the bank is (activation code +
+// filter code / 2) mod 64, as good as random.
+constexpr int kDwMaxC = 4096;  // output channels whose filter sums fit next to the table in LDS
+constexpr int kDwRow = 129;    // dwords per table row in LDS
 
 // KS: kernel height = width known at compile time (taps fully unrolled, so that the loads of all
 // taps of an item are in flight together), or 0 for any kernel size.
-// HOIST (3x3 only): the grid stride is a multiple of the channel groups, so a thread keeps its four
-// channels for every item: the filter codes are loaded once and kept, pre-shifted, in registers.
-// A lookup then costs four vector instructions (extract the activation code, form the address,
-// add the entry, add the code to the patch sum) next to its LDS read.
-template <int KS, bool HOIST>
+// HOIST (3x3, not GEN): the grid stride is a multiple of the channel groups, so a thread keeps its
+// four channels for every item: the filter codes are loaded once and kept, pre-shifted, in registers.
+// GEN: any channel multiplier and channel count: output channel co reads input channel co / mult and
+// filter code w[tap * Cout + co]; codes are loaded byte by byte and the last group of a pixel may
+// hold fewer than four channels.  Otherwise multiplier 1 and Cin % 4 == 0: one dword per tap and operand.
+template <int KS, bool HOIST, bool GEN>
 __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const uint8_t* __restrict__ x,
                                                    const uint8_t* __restrict__ w, const uint16_t* __restrict__ lut,
                                                    int32_t* __restrict__ acc_out, float* __restrict__ y_out,
                                                    int vec_out) {
-  __shared__ uint16_t tab[65536];
-  __shared__ int32_t sfs[kDwMaxC];  // per channel: sum over the taps of the filter codes (+128 each if signed)
+  __shared__ uint32_t tab[256 * kDwRow];
+  __shared__ int32_t sfs[kDwMaxC];  // per output channel: sum over the taps of the filter codes (+128 each if signed)
   QParams qp = qp_in;
   if (qp.dq) {
     qp.x_zp = qp.dq->x_zp;
@@ -109,29 +116,32 @@ __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const u
   const int K = KH * KW;
   {
     const uint4* __restrict__ src = reinterpret_cast<const uint4*>(lut);
-    uint4* dst = reinterpret_cast<uint4*>(tab);
     // signed activations index the table by code + 128 (the byte with its top bit flipped), the
     // same value the patch sums are taken over: rows are staged in that order (a row = 32 chunks)
     const int rowflip = g.sgn ? (0x80 << 5) : 0;
     for (int i = threadIdx.x; i < 8192; i += 1024) {
       uint4 v = src[i ^ rowflip];
-      v.x ^= flip16; v.y ^= flip16; v.z ^= flip16; v.w ^= flip16;
-      dst[i] = v;
+      uint32_t* dst = tab + (i >> 5) * kDwRow + (i & 31) * 4;
+      dst[0] = v.x ^ flip16; dst[1] = v.y ^ flip16; dst[2] = v.z ^ flip16; dst[3] = v.w ^ flip16;
     }
-    for (int c = threadIdx.x; c < g.Cin; c += 1024) {
+    for (int c = threadIdx.x; c < g.Cout; c += 1024) {
       int32_t t = 0;
-      for (int k = 0; k < K; ++k) t += (int32_t)((uint32_t)w[(size_t)k * g.Cin + c] ^ (flip8 & 0xffu));
+      for (int k = 0; k < K; ++k) t += (int32_t)((uint32_t)w[(size_t)k * g.Cout + c] ^ (flip8 & 0xffu));
       sfs[c] = t;
     }
   }
   __syncthreads();
-  const uint32_t C4 = (uint32_t)g.Cin / 4u;
-  const uint32_t items = (uint32_t)g.M * C4;  // M * Cin < 2^31
-  const uint32_t pad4 = ((uint32_t)qp.pad_code & 0xffu) * 0x01010101u;
+  const uint32_t C4 = ((uint32_t)g.Cout + 3u) / 4u;  // groups of four output channels per pixel
+  const uint32_t items = (uint32_t)g.M * C4;          // M * Cout < 2^31
+  const uint32_t padb = ((uint32_t)qp.pad_code & 0xffu);
+  const uint32_t pad4 = padb * 0x01010101u;
   const uint32_t bias = g.sgn ? 32768u * (uint32_t)K : 0u;
   const int off128 = g.sgn ? 128 * K : 0;
   const long long kzz = (long long)K * qp.x_zp * qp.w_zp;
   const char* tabb = reinterpret_cast<const char*>(tab);
+  auto entry = [&](uint32_t a, uint32_t b2) -> uint32_t {  // b2 = 2 * filter code
+    return *reinterpret_cast<const uint16_t*>(tabb + (a * (uint32_t)(kDwRow * 4) + b2));
+  };
   uint32_t wb2[HOIST ? KS * KS : 1][4];  // 2 * filter code = byte offset within a table row
   if constexpr (HOIST) {
     const uint32_t c4 = (blockIdx.x * 1024u + threadIdx.x) % C4;
@@ -151,8 +161,6 @@ __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const u
     const int oy = m % (uint32_t)g.OH;
     const int n = m / (uint32_t)g.OH;
     const int by = oy * g.sh - g.ph, bx = ox * g.sw - g.pw;
-    const uint8_t* __restrict__ xn = x + (size_t)n * g.H * g.W * g.Cin + 4u * c4;
-    const uint8_t* __restrict__ wc = w + 4u * c4;
     uint32_t acc[4] = {0, 0, 0, 0};
     uint32_t sp[4] = {0, 0, 0, 0};
     auto tap = [&](uint32_t xd, uint32_t wd) {
@@ -160,7 +168,7 @@ __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const u
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const uint32_t a = (xs >> (8 * j)) & 0xffu, b = (wd >> (8 * j)) & 0xffu;
-        acc[j] += *reinterpret_cast<const uint16_t*>(tabb + ((a << 9) | (b << 1)));
+        acc[j] += entry(a, b << 1);
         sp[j] += a;
       }
     };
@@ -169,85 +177,123 @@ __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const u
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const uint32_t a = (xs >> (8 * j)) & 0xffu;
-        acc[j] += *reinterpret_cast<const uint16_t*>(tabb + ((a << 9) | wb2[HOIST ? t : 0][j]));
+        acc[j] += entry(a, wb2[HOIST ? t : 0][j]);
         sp[j] += a;
       }
     };
-    if constexpr (KS > 0) {
-      uint32_t xd[KS * KS], wd[KS * KS];
+    if constexpr (GEN) {
+      // output channels co0 .. co0 + 3 (clamped for the last group), their input channels and the
+      // position of their filter codes within a tap
+      uint32_t co[4], ci[4];
 #pragma unroll
-      for (int ky = 0; ky < KS; ++ky) {
-#pragma unroll
-        for (int kx = 0; kx < KS; ++kx) {
-          const int iy = by + ky * g.dh, ix = bx + kx * g.dw;
-          const bool inside = (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
-          xd[ky * KS + kx] = pad4;
-          if (inside) xd[ky * KS + kx] = *reinterpret_cast<const uint32_t*>(xn + ((size_t)iy * g.W + ix) * g.Cin);
-          if constexpr (!HOIST) wd[ky * KS + kx] = *reinterpret_cast<const uint32_t*>(wc + (size_t)(ky * KS + kx) * g.Cin);
-        }
+      for (int j = 0; j < 4; ++j) {
+        co[j] = min(4u * c4 + (uint32_t)j, (uint32_t)g.Cout - 1u);
+        ci[j] = co[j] / (uint32_t)g.mult;
       }
-#pragma unroll
-      for (int t = 0; t < KS * KS; ++t) {
-        if constexpr (HOIST) tap_hoisted(xd[t], t); else tap(xd[t], wd[t]);
-      }
-    } else {
+      const uint8_t* __restrict__ xn = x + (size_t)n * g.H * g.W * g.Cin;
       for (int ky = 0; ky < KH; ++ky) {
         const int iy = by + ky * g.dh;
         for (int kx = 0; kx < KW; ++kx) {
           const int ix = bx + kx * g.dw;
           const bool inside = (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
-          uint32_t xd = pad4;
-          if (inside) xd = *reinterpret_cast<const uint32_t*>(xn + ((size_t)iy * g.W + ix) * g.Cin);
-          tap(xd, *reinterpret_cast<const uint32_t*>(wc + (size_t)(ky * KW + kx) * g.Cin));
+          const uint8_t* xp = xn + ((size_t)(inside ? iy : 0) * g.W + (inside ? ix : 0)) * g.Cin;
+          const uint8_t* wp = w + (size_t)(ky * KW + kx) * g.Cout;
+          uint32_t xd = 0, wd = 0;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            xd |= (inside ? (uint32_t)xp[ci[j]] : padb) << (8 * j);
+            wd |= (uint32_t)wp[co[j]] << (8 * j);
+          }
+          tap(xd, wd);
+        }
+      }
+    } else {
+      const uint8_t* __restrict__ xn = x + (size_t)n * g.H * g.W * g.Cin + 4u * c4;
+      const uint8_t* __restrict__ wc = w + 4u * c4;
+      if constexpr (KS > 0) {
+        uint32_t xd[KS * KS], wd[KS * KS];
+#pragma unroll
+        for (int ky = 0; ky < KS; ++ky) {
+#pragma unroll
+          for (int kx = 0; kx < KS; ++kx) {
+            const int iy = by + ky * g.dh, ix = bx + kx * g.dw;
+            const bool inside = (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
+            xd[ky * KS + kx] = pad4;
+            if (inside) xd[ky * KS + kx] = *reinterpret_cast<const uint32_t*>(xn + ((size_t)iy * g.W + ix) * g.Cin);
+            if constexpr (!HOIST) wd[ky * KS + kx] = *reinterpret_cast<const uint32_t*>(wc + (size_t)(ky * KS + kx) * g.Cin);
+          }
+        }
+#pragma unroll
+        for (int t = 0; t < KS * KS; ++t) {
+          if constexpr (HOIST) tap_hoisted(xd[t], t); else tap(xd[t], wd[t]);
+        }
+      } else {
+        for (int ky = 0; ky < KH; ++ky) {
+          const int iy = by + ky * g.dh;
+          for (int kx = 0; kx < KW; ++kx) {
+            const int ix = bx + kx * g.dw;
+            const bool inside = (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
+            uint32_t xd = pad4;
+            if (inside) xd = *reinterpret_cast<const uint32_t*>(xn + ((size_t)iy * g.W + ix) * g.Cin);
+            tap(xd, *reinterpret_cast<const uint32_t*>(wc + (size_t)(ky * KW + kx) * g.Cin));
+          }
         }
       }
     }
-    const int4 sf4 = *reinterpret_cast<const int4*>(&sfs[4u * c4]);
-    const int32_t sf[4] = {sf4.x, sf4.y, sf4.z, sf4.w};
     int32_t av[4];
     float yv[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      const int32_t sf = sfs[min(4u * c4 + (uint32_t)j, (uint32_t)g.Cout - 1u)];
       av[j] = (int32_t)(acc[j] - bias);
       const long long corr = (long long)av[j] - (long long)qp.w_zp * ((int32_t)sp[j] - off128) -
-                             (long long)qp.x_zp * (sf[j] - off128) + kzz;
+                             (long long)qp.x_zp * (sf - off128) + kzz;
       yv[j] = (float)corr * qp.scale;
     }
-    const size_t o = (size_t)pix * g.Cout + 4u * c4;  // Cout == Cin
-    if (vec_out) {
+    const size_t o = (size_t)pix * g.Cout + 4u * c4;
+    if (vec_out) {  // Cout % 4 == 0 and 16-byte aligned outputs
       if (acc_out) *reinterpret_cast<int4*>(acc_out + o) = make_int4(av[0], av[1], av[2], av[3]);
       if (y_out) *reinterpret_cast<float4*>(y_out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
     } else {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        if (acc_out) acc_out[o + j] = av[j];
-        if (y_out) y_out[o + j] = yv[j];
+        if (4u * c4 + (uint32_t)j < (uint32_t)g.Cout) {
+          if (acc_out) acc_out[o + j] = av[j];
+          if (y_out) y_out[o + j] = yv[j];
+        }
       }
     }
   }
 }
 
 bool dw_supported(const Geom& g, const uint8_t* x, const uint8_t* w, const uint16_t* lut) {
-  if (g.mult != 1 || g.Cin % 4 != 0 || g.Cin > kDwMaxC) return false;
-  if (((uintptr_t)x & 3) || ((uintptr_t)w & 3) || ((uintptr_t)lut & 15)) return false;
+  (void)x;
+  (void)w;
+  if (g.mult < 1 || g.Cout > kDwMaxC) return false;
+  if ((uintptr_t)lut & 15) return false;
   // staging the table costs every workgroup 128 KB of reads: not worth it for small layers
-  return (double)g.M * g.Cin * g.K >= 4.0e6;
+  return (double)g.M * g.Cout * g.K >= 4.0e6;
 }
 
 hipError_t launch_dw(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
                      int32_t* acc_out, float* y_out, hipStream_t s) {
-  const uint64_t items = (uint64_t)g.M * (g.Cin / 4);
+  const uint32_t C4 = ((uint32_t)g.Cout + 3u) / 4u;
+  const uint64_t items = (uint64_t)g.M * C4;
   const uint32_t blocks = (uint32_t)std::min<uint64_t>((uint64_t)cu_count(), (items + 1023) / 1024);
-  const int vec_out = ((((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
-  const bool keeps_channels = 1024 % (g.Cin / 4) == 0;  // the grid stride is then a multiple of the channel groups
-  if (g.KH == 3 && g.KW == 3 && keeps_channels)
-    hipLaunchKernelGGL((dw_kernel<3, true>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+  const int vec_out = (g.Cout % 4 == 0 && (((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;
+  // one dword per tap and operand needs multiplier 1, whole groups of four channels and aligned tensors
+  const bool fast = g.mult == 1 && g.Cin % 4 == 0 && (((uintptr_t)x | (uintptr_t)w) & 3) == 0;
+  const bool keeps_channels = fast && 1024 % C4 == 0;  // the grid stride is then a multiple of the channel groups
+  if (!fast)
+    hipLaunchKernelGGL((dw_kernel<0, false, true>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+  else if (g.KH == 3 && g.KW == 3 && keeps_channels)
+    hipLaunchKernelGGL((dw_kernel<3, true, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
   else if (g.KH == 3 && g.KW == 3)
-    hipLaunchKernelGGL((dw_kernel<3, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+    hipLaunchKernelGGL((dw_kernel<3, false, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
   else if (g.KH == 5 && g.KW == 5)
-    hipLaunchKernelGGL((dw_kernel<5, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+    hipLaunchKernelGGL((dw_kernel<5, false, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
   else
-    hipLaunchKernelGGL((dw_kernel<0, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+    hipLaunchKernelGGL((dw_kernel<0, false, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
   return hipGetLastError();
 }
 

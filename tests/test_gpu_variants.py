@@ -149,11 +149,15 @@ def test_depthwise_layers(case, signed):
 
 
 DEPTHWISE_LDS = [
-    # large enough for the kernel that keeps the whole table in LDS (multiplier 1, Cin % 4 == 0)
+    # large enough for the kernel that keeps the whole table in LDS
     (8, 56, 56, 64, 3, 3, 1, 1, 1, 1),
     (4, 57, 55, 36, 3, 3, 1, 2, 1, 1),        # ragged everything, stride 2
     (2, 64, 64, 32, 5, 5, 1, 1, 4, 2),        # 5x5, dilation 2
     (16, 28, 28, 128, 3, 3, 1, 1, 0, 1),      # no padding
+    (8, 40, 40, 33, 3, 3, 2, 1, 1, 1),        # channel multiplier 2, 66 output channels: last group of a pixel is ragged
+    (16, 48, 48, 6, 5, 5, 1, 1, 2, 1),        # channel count no multiple of four
+    (16, 56, 56, 24, 3, 3, 4, 2, 1, 1),       # channel multiplier 4: a group of outputs reads one input channel
+    (4, 30, 30, 50, 4, 2, 3, 1, 1, 2),        # 4x2 kernel, multiplier 3, dilation 2
 ]
 
 
