@@ -193,7 +193,7 @@ int ax_oracle_threads(void) {
 /* ---- operator variants ------------------------------------------------------------------
  * The paper's layer carries a dilation parameter next to the strides (Sec. III, Algorithm 1
  * inputs), offers signed multipliers with codes in [-128, 127] next to unsigned ones
- * (Sec. III), and says every kind of 2-D convolution gets an approximate twin (Sec. III); the
+ * (Sec. II), and says every kind of 2-D convolution gets an approximate twin (Sec. II); the
  * depthwise convolution is the one other kind built here.  Same definition as above with:
  *   dilation   tap (ky, kx) reads the pixel (oy*sh - ph + ky*dh, ox*sw - pw + kx*dw);
  *              OH = floor((H + 2*ph - dh*(KH-1) - 1) / sh) + 1.

@@ -3,8 +3,8 @@
  * ONLY, like ax_oracle.c; shares no code with the HIP library.
  *
  * The approximate layer of the paper takes two float tensors and the range (minimum and
- * maximum) of each and returns a float tensor (Sec. III, Algorithm 1 and the layer
- * description before it).  Its steps, in the paper's order:
+ * maximum) of each and returns a float tensor (Sec. II, the description of the approximate
+ * layer; Sec. III, Algorithm 1).  Its steps, in the paper's order:
  *
  *   1. the ranges come from minimum / maximum operators placed in front of the layer,
  *      evaluated once per batch                                   -> ax_oracle_range_f32
@@ -86,7 +86,7 @@ int ax_oracle_quantize_f32(const float* x, int64_t n, int relu, float alpha, int
 }
 
 /* The float layer with the layer's full parameter set (Sec. III, Algorithm 1: strides, dilations,
- * padding; signed or unsigned multiplier; round mode) and the depthwise kind.  Signed form: the
+ * padding; Sec. II: signed or unsigned multiplier, round mode) and the depthwise kind.  Signed form: the
  * same alpha; codes and zero point are the unsigned ones lowered by 128, so that they span
  * [-128, 127] and real zero stays exactly representable; the table (int16 entries) is addressed
  * by the two codes' two's-complement patterns.  xq_out / wq_out receive the code bytes. */

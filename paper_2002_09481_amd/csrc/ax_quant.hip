@@ -1,6 +1,7 @@
 // Float side of the layer: range (min / max) reduction, ComputeCoeffs, float -> 8-bit
 // quantization with a round mode, and the float-in / float-out entry points built on the
-// table-lookup convolution (paper: Sec. III, the layer description and Algorithm 1).
+// table-lookup convolution (paper: Sec. II, the description of the approximate layer, its ranges
+// and round mode; Sec. III, Algorithm 1).
 //
 // Every arithmetic step is one IEEE float32 operation in a fixed order (no contraction into
 // fused multiply-adds), so codes and coefficients are reproducible bit for bit:

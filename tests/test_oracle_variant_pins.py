@@ -197,3 +197,65 @@ def test_signed_layer_is_the_unsigned_layer_in_offset_binary(table):
     # (the float outputs of the two layers differ: the correction terms of Eq. (3) are taken on
     # the signed codes and zero points; the signed correction is pinned by the exact-table test)
     del y, y_u
+
+
+def test_signed_layer_float_output_with_a_pad_code_that_is_not_the_zero_point():
+    """The float output of a signed layer whose padded taps carry a code other than the zero
+    point, pinned twice without the oracle's own correction line: (a) an arbitrary signed table
+    against acc, Sp, Sf gathered in numpy and put through the expansion of Eq. (3) here;
+    (b) the exact table against a float64 library convolution of the dequantized tensors over an
+    input that is explicitly padded with the real value of the pad code, alpha1*(pad - beta1)."""
+    rng = np.random.default_rng(21)
+    N, H, W, Cin, KH, KW, Cout, s, p, d = 2, 7, 6, 5, 3, 3, 4, 1, 2, 1
+    x = rng.integers(-128, 128, (N, H, W, Cin)).astype(np.int8)
+    w = rng.integers(-128, 128, (KH, KW, Cin, Cout)).astype(np.int8)
+    q = I.Quant(0.02, -9, 0.01, 41, 77)  # pad code 77, zero point -9
+    K = KH * KW * Cin
+    lut = I.lut_signed_random(5)
+    acc, y = oracle.conv2d_ex(x, w, lut, s, p, q, dilation=d, signed=True)
+    tab = lut.reshape(256, 256).astype(np.int64)
+    ref, Sp, Sf = _gather(x.astype(np.int64), w.astype(np.int64), lambda a, b: tab[a & 255, b & 255], s, p, d, q.pad_code)
+    np.testing.assert_array_equal(acc, ref)
+    corr = ref - q.w_zp * Sp[..., None] - q.x_zp * Sf + K * q.x_zp * q.w_zp
+    assert Hh.float_ok(y, np.float64(q.x_scale) * np.float64(q.w_scale) * corr)
+    # (b): padded taps are real numbers here, not zeros
+    _, y_exact = oracle.conv2d_ex(x, w, I.lut_signed_exact(), s, p, q, dilation=d, signed=True)
+    xr = q.x_scale * (torch.from_numpy(x.astype(np.float64)) - q.x_zp)
+    wr = q.w_scale * (torch.from_numpy(w.astype(np.float64)) - q.w_zp)
+    pad_real = q.x_scale * (q.pad_code - q.x_zp)
+    xpad = torch.nn.functional.pad(xr.permute(0, 3, 1, 2), (p, p, p, p), value=pad_real)
+    lib = torch.nn.functional.conv2d(xpad, wr.permute(3, 2, 0, 1), stride=s).permute(0, 2, 3, 1).numpy()
+    assert Hh.float_ok(y_exact, lib, rtol=1e-5, atol=1e-4)
+    assert not Hh.float_ok(y_exact, torch.nn.functional.conv2d(xr.permute(0, 3, 1, 2), wr.permute(3, 2, 0, 1), stride=s,
+                                                                padding=p).permute(0, 2, 3, 1).numpy(), rtol=1e-5, atol=1e-4)
+
+
+@pytest.mark.parametrize("mult", [1, 2])
+def test_depthwise_with_dilation_float_output(mult):
+    """Depthwise and dilated at once: accumulators and float outputs per output channel against
+    a numpy gather and the expansion of Eq. (3) written out here (K = KH*KW), and the exact
+    table against the library's grouped, dilated float64 convolution."""
+    rng = np.random.default_rng(23)
+    N, H, W, Cin, KH, KW, s, p, d = 2, 10, 9, 3, 3, 3, 1, 2, 2
+    x = rng.integers(0, 256, (N, H, W, Cin)).astype(np.uint8)
+    w = rng.integers(0, 256, (KH, KW, Cin, mult)).astype(np.uint8)
+    q = I.Quant(0.02, 17, 0.004, 140, 9)  # pad code 9 is not the zero point
+    lut = I.lut_random(8)
+    tab = lut.reshape(256, 256).astype(np.int64)
+    acc, y = oracle.conv2d_ex(x, w, lut, s, p, q, dilation=d, depthwise=True)
+    K = KH * KW
+    for ci in range(Cin):
+        for m in range(mult):
+            a1, Sp, Sf = _gather(x[..., ci:ci + 1].astype(np.int64), w[:, :, ci:ci + 1, m:m + 1].astype(np.int64),
+                                 lambda a, b: tab[a, b], s, p, d, q.pad_code)
+            co = ci * mult + m
+            np.testing.assert_array_equal(acc[..., co], a1[..., 0])
+            corr = a1[..., 0] - q.w_zp * Sp - q.x_zp * Sf[0] + K * q.x_zp * q.w_zp
+            assert Hh.float_ok(y[..., co], np.float64(q.x_scale) * np.float64(q.w_scale) * corr)
+    qz = I.Quant(0.02, 17, 0.004, 140, None)  # padded taps are real zeros
+    _, y_exact = oracle.conv2d_ex(x, w, I.lut_exact(), s, p, qz, dilation=d, depthwise=True)
+    xr = qz.x_scale * (torch.from_numpy(x.astype(np.float64)) - qz.x_zp)
+    wr = qz.w_scale * (torch.from_numpy(w.astype(np.float64)) - qz.w_zp)
+    wt = wr.permute(2, 3, 0, 1).reshape(Cin * mult, 1, KH, KW)
+    lib = torch.nn.functional.conv2d(xr.permute(0, 3, 1, 2), wt, padding=p, dilation=d, groups=Cin).permute(0, 2, 3, 1).numpy()
+    assert Hh.float_ok(y_exact, lib, rtol=1e-5, atol=1e-4)
