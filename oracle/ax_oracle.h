@@ -79,6 +79,17 @@ int ax_oracle_conv2d_f32_ex(const float* x, int N, int H, int W, int Cin, const 
                             uint8_t* xq_out, uint8_t* wq_out, ax_oracle_quant* q_out,
                             int32_t* acc_out, float* y_out);
 
+/* ---- backward pass (ax_oracle_grad.c): gradients of the exact convolution of the dequantized
+ * tensors (straight-through reading), in double precision.  gy: [N,OH,OW,Cout] float.
+ * gx_out / gx_abs: [N,H,W,Cin]; gw_out / gw_abs: [KH,KW,Cin,Cout]; the *_abs arrays receive the
+ * sums of the absolute values of the terms.  Any output pointer may be NULL.  pad_code is given
+ * explicitly. */
+int ax_oracle_conv2d_backward(const void* x, int N, int H, int W, int Cin, const void* w, int KH, int KW,
+                              int Cout, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h,
+                              int dil_w, int is_signed, float x_scale, int x_zp, float w_scale, int w_zp,
+                              int pad_code, const float* gy, double* gx_out, double* gx_abs,
+                              double* gw_out, double* gw_abs);
+
 /* Number of threads the parallel loops use. */
 int ax_oracle_threads(void);
 

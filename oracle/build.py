@@ -8,7 +8,8 @@ LIB = os.path.join(HERE, "libax_oracle.so")
 
 
 def build(force: bool = True) -> str:
-    srcs = [os.path.join(HERE, "ax_oracle.c"), os.path.join(HERE, "ax_oracle_quant.c")]
+    srcs = [os.path.join(HERE, "ax_oracle.c"), os.path.join(HERE, "ax_oracle_quant.c"),
+            os.path.join(HERE, "ax_oracle_grad.c")]
     deps = srcs + [os.path.join(HERE, "ax_oracle.h")]
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(d) for d in deps):
         return LIB

@@ -44,6 +44,9 @@ def lib():
         _lib.ax_oracle_conv2d_f32_ex.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci,
                                                  vp, vp, ci, ci, vp, vp, vp, vp, vp]
         _lib.ax_oracle_conv2d_f32_ex.restype = ci
+        _lib.ax_oracle_conv2d_backward.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci,
+                                                   cf, ci, cf, ci, ci, vp, vp, vp, vp, vp]
+        _lib.ax_oracle_conv2d_backward.restype = ci
         for f in (_lib.ax_oracle_conv2d, _lib.ax_oracle_conv2d_sample, _lib.ax_oracle_dense, _lib.ax_oracle_threads,
                   _lib.ax_oracle_range_f32, _lib.ax_oracle_coeffs, _lib.ax_oracle_quantize_f32,
                   _lib.ax_oracle_conv2d_f32):
@@ -260,6 +263,43 @@ def conv2d_f32_ex(x, w, lut, stride, pad, x_range, w_range, relu=False, round_mo
         xq, wq = xq.view(np.int8), wq.view(np.int8)
     return dict(acc=acc, y=y, xq=xq, wq=wq, x_scale=float(qs.x_scale), x_zp=int(qs.x_zp),
                 w_scale=float(qs.w_scale), w_zp=int(qs.w_zp))
+
+
+def conv2d_backward(x, w, gy, stride, pad, q, dilation=1, signed=False, want_gx=True, want_gw=True):
+    """Backward pass of the layer (straight-through: gradients of the exact convolution of the
+    dequantized tensors).  x, w: codes; gy: float32 [N,OH,OW,Cout].  Returns a dict with float64
+    arrays gx [N,H,W,Cin], gw [KH,KW,Cin,Cout] and gx_abs, gw_abs (sums of the absolute values of
+    the terms of every sum); an entry is None when not wanted."""
+    cdt = np.int8 if signed else np.uint8
+    x, w = _chk(x, cdt, 4), _chk(w, cdt, 4)
+    N, H, W, Cin = x.shape
+    KH, KW, Cin2, Cout = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    sh, sw = (stride, stride) if np.isscalar(stride) else stride
+    ph, pw = (pad, pad) if np.isscalar(pad) else pad
+    dh, dw = (dilation, dilation) if np.isscalar(dilation) else dilation
+    OH = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+    OW = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+    gy = _chk(gy, np.float32, 4)
+    if gy.shape != (N, OH, OW, Cout):
+        raise ValueError("gy must be [N,OH,OW,Cout]")
+    pad_code = q.pad_code
+    if pad_code is None or (not signed and pad_code < 0):
+        pad_code = q.x_zp
+    out = dict(gx=None, gx_abs=None, gw=None, gw_abs=None)
+    if want_gx:
+        out["gx"], out["gx_abs"] = np.empty(x.shape, np.float64), np.empty(x.shape, np.float64)
+    if want_gw:
+        out["gw"], out["gw_abs"] = np.empty(w.shape, np.float64), np.empty(w.shape, np.float64)
+    p = lambda a: None if a is None else a.ctypes.data
+    rc = lib().ax_oracle_conv2d_backward(x.ctypes.data, N, H, W, Cin, w.ctypes.data, KH, KW, Cout, sh, sw, ph, pw,
+                                         dh, dw, int(bool(signed)), float(q.x_scale), int(q.x_zp), float(q.w_scale),
+                                         int(q.w_zp), int(pad_code), gy.ctypes.data, p(out["gx"]), p(out["gx_abs"]),
+                                         p(out["gw"]), p(out["gw_abs"]))
+    if rc:
+        raise RuntimeError("ax_oracle_conv2d_backward failed: %d" % rc)
+    return out
 
 
 def threads() -> int:
