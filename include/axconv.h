@@ -297,6 +297,31 @@ int ax_dense_f32(const float* x, int M, int K, const float* w, int N, const uint
                  void* hip_stream);
 size_t ax_dense_f32_workspace_bytes(int M, int K, int N);
 
+/* ---- backward pass -------------------------------------------------------------------------
+ *
+ * The paper says the transformed network serves training as well as inference (Sec. II, design
+ * flow) but defines no gradient of the approximate layer.  Reading taken (straight-through): the
+ * backward pass treats the layer as the exact convolution of the dequantized tensors of Eq. (1),
+ * xr = x_scale * (x_code - x_zp), wr = w_scale * (w_code - w_zp) -- the layer with the exact
+ * multiplier (Sec. IV) -- where a tap outside the image carries x_scale * (pad_code - x_zp).
+ * Quantization and the multiplier's error are passed straight through.  With gy = dL/dy:
+ *
+ *   gx_out [N, H, W, Cin]       dL/dxr = sum over (ky, kx, co) and the output pixels (oy, ox) whose
+ *                               tap (ky, kx) reads input pixel (iy, ix) of gy * wr[ky, kx, ci, co]
+ *   gw_out [KH, KW, Cin, Cout]  dL/dwr = sum over (n, oy, ox) of xr(tap) * gy[n, oy, ox, co]
+ *
+ * x, w: codes as for ax_conv2d_ex (uint8, or int8 with signed_codes); gy: float [N, OH, OW, Cout].
+ * Either output may be NULL (not both).  Sums are accumulated in float32 on the matrix cores (gy
+ * split exactly into three bf16 pieces, the other operand a small integer that bf16 holds
+ * exactly); each output is within 2e-5 times the sum of the absolute values of its terms of the
+ * exact value.  Depthwise descriptors give AX_ERR_OPTION (not built).  workspace (needed for
+ * gw_out): ax_conv2d_backward_workspace_bytes(desc) bytes, 256-byte aligned.
+ */
+int ax_conv2d_backward(const ax_conv_desc_t* desc, const ax_quant_t* q, const void* x, const void* w,
+                       const float* gy, float* gx_out, float* gw_out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream);
+size_t ax_conv2d_backward_workspace_bytes(const ax_conv_desc_t* desc);
+
 const char* ax_strerror(int code);
 
 /* Library version, major * 10000 + minor * 100 + patch. */

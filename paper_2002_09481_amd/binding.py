@@ -48,7 +48,7 @@ EXPORTS = [  # include/axconv.h
     "ax_conv2d_ex_workspace_bytes", "ax_conv2d_multi_lut", "ax_conv2d_multi_lut_workspace_bytes", "ax_conv2d_f32_ex",
     "ax_conv2d_f32_ex_workspace_bytes", "ax_layer_create", "ax_layer_destroy", "ax_layer_prepared_bytes",
     "ax_layer_workspace_bytes", "ax_layer_prepare", "ax_layer_run", "ax_layer_plan", "ax_layer_run_static",
-    "ax_static_scratch_bytes",
+    "ax_static_scratch_bytes", "ax_conv2d_backward", "ax_conv2d_backward_workspace_bytes",
 ]
 PROBE_EXPORTS = [  # include/axconv_probe.h
     "ax_probe_lds_gather", "ax_probe_copy", "ax_probe_mac", "ax_probe_layer_kernel_ms",
@@ -117,6 +117,10 @@ def lib():
     L.ax_layer_run_static.restype = ci
     L.ax_static_scratch_bytes.argtypes = []
     L.ax_static_scratch_bytes.restype = sz
+    L.ax_conv2d_backward.argtypes = [descp, ctypes.POINTER(ax_quant_t), vp, vp, vp, vp, vp, vp, sz, vp]
+    L.ax_conv2d_backward.restype = ci
+    L.ax_conv2d_backward_workspace_bytes.argtypes = [descp]
+    L.ax_conv2d_backward_workspace_bytes.restype = sz
     L.ax_probe_layer_kernel_ms.argtypes = [vp, vp, vp, vp, vp, sz, ci, ctypes.POINTER(ctypes.c_float), vp]
     L.ax_probe_layer_kernel_ms.restype = ci
     L.ax_probe_copy.argtypes = [vp, vp, sz, vp]
@@ -423,6 +427,43 @@ def ax_conv2d_ex(x, w, lut, stride, pad, q, dilation=1, depthwise=False, acc_out
                         _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
     _check(rc)
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
+def ax_conv2d_backward(x, w, gy, stride, pad, q, dilation=1, gx_out=None, gw_out=None, workspace=None, stream=None):
+    """Backward pass of a layer (straight-through).  x, w: codes (uint8, or int8 for the signed
+    form); gy: float32 [N,OH,OW,Cout].  Returns (gx [N,H,W,Cin], gw [KH,KW,Cin,Cout]) as float32
+    tensors; pass False to skip one of them."""
+    L = lib()
+    signed = x.dtype == torch.int8
+    cdt = torch.int8 if signed else torch.uint8
+    _dev(x, cdt, "x")
+    _dev(w, cdt, "w")
+    _dev(gy, torch.float32, "gy")
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
+        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout]")
+    desc = _conv_desc(x.shape, w.shape, stride, pad, dilation, False, signed)
+    OH, OW = _out_hw(desc)
+    if OH <= 0 or OW <= 0:
+        _check(-2)
+    if tuple(gy.shape) != (desc.N, OH, OW, desc.Cout):
+        raise ValueError("gy must be [N,OH,OW,Cout]")
+    if gx_out is None:
+        gx_out = torch.empty(x.shape, dtype=torch.float32, device=x.device)
+    if gw_out is None:
+        gw_out = torch.empty(w.shape, dtype=torch.float32, device=x.device)
+    for o, ref, name in ((gx_out, x, "gx_out"), (gw_out, w, "gw_out")):
+        if o is not False:
+            _dev(o, torch.float32, name)
+            if o.numel() != ref.numel():
+                raise ValueError("%s has the wrong number of elements" % name)
+    if workspace is None:
+        workspace = _workspace(int(L.ax_conv2d_backward_workspace_bytes(ctypes.byref(desc))), x.device, stream)
+    _dev(workspace, torch.uint8, "workspace")
+    qs = _quant(q)
+    _check(L.ax_conv2d_backward(ctypes.byref(desc), ctypes.byref(qs), _ptr(x), _ptr(w), _ptr(gy),
+                                _ptr(None if gx_out is False else gx_out), _ptr(None if gw_out is False else gw_out),
+                                _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream))))
+    return (None if gx_out is False else gx_out), (None if gw_out is False else gw_out)
 
 
 class AxLayer:

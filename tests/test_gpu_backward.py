@@ -1,0 +1,126 @@
+"""GPU parity of the backward pass (ax_conv2d_backward) against the float64 oracle: every
+element of gx and gw within 2e-5 times the sum of the absolute values of its terms (the bound of
+a float32 accumulation in blocks; the products themselves are exact), plus 1e-30."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2002_09481_amd import binding as ax
+from paper_2002_09481_amd import inputs as I
+
+import gpu_common as G
+
+pytestmark = pytest.mark.gpu
+
+REL = 2e-5
+
+
+def _pair(v):
+    return (v, v) if np.isscalar(v) else tuple(v)
+
+
+def _case(shape, seed, signed=False, pad_code=None, gy_kind="normal"):
+    N, H, W, Cin, KH, KW, Cout, s, p, d = shape
+    rng = np.random.default_rng(seed)
+    lo, hi, dt = (-128, 128, np.int8) if signed else (0, 256, np.uint8)
+    x = rng.integers(lo, hi, (N, H, W, Cin)).astype(dt)
+    x[rng.random(x.shape) < 0.4] = dt(lo + 7)  # many equal codes, like post-ReLU tensors
+    w = rng.integers(lo, hi, (KH, KW, Cin, Cout)).astype(dt)
+    q = I.Quant(float(np.float32(0.021)), int(rng.integers(lo, hi)), float(np.float32(0.0043)), int(rng.integers(lo, hi)),
+                pad_code)
+    (sh, sw), (ph, pw), (dh, dw) = _pair(s), _pair(p), _pair(d)
+    OH = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+    OW = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+    gy = rng.standard_normal((N, OH, OW, Cout)).astype(np.float32)
+    if gy_kind == "wide":  # magnitudes over many binades: every bit of the float32 significand matters
+        gy *= np.exp2(rng.integers(-20, 20, gy.shape)).astype(np.float32)
+    return x, w, q, gy
+
+
+def _check(shape, seed, signed=False, pad_code=None, gy_kind="normal", what=""):
+    x, w, q, gy = _case(shape, seed, signed, pad_code, gy_kind)
+    s, p, d = shape[7:]
+    gx, gw = ax.ax_conv2d_backward(G.to_dev(x), G.to_dev(w), G.to_dev(gy), s, p, q, dilation=d)
+    torch.cuda.synchronize()
+    ref = oracle.conv2d_backward(x, w, gy, s, p, q, dilation=d, signed=signed)
+    for name, got, want, bound in (("gx", gx, ref["gx"], ref["gx_abs"]), ("gw", gw, ref["gw"], ref["gw_abs"])):
+        got = got.cpu().numpy().astype(np.float64)
+        err = np.abs(got - want)
+        tol = REL * bound + 1e-30
+        worst = int(np.argmax(err - tol))
+        assert np.all(err <= tol), "%s %s: element %d got %r want %r (sum of |terms| %r)" % (
+            what, name, worst, got.reshape(-1)[worst], want.reshape(-1)[worst], bound.reshape(-1)[worst])
+
+
+SHAPES = [
+    # N, H, W, Cin, KH, KW, Cout, stride, pad, dilation
+    (1, 1, 1, 1, 1, 1, 1, 1, 0, 1),
+    (2, 9, 7, 5, 3, 3, 6, 2, 1, 1),
+    (1, 12, 12, 4, 3, 3, 5, 1, 2, 2),
+    (2, 11, 9, 3, 3, 2, 4, (2, 1), (3, 0), (3, 1)),
+    (2, 20, 20, 16, 3, 3, 24, 1, (2, 4), (2, 4)),
+    (1, 40, 40, 32, 3, 3, 72, 1, 1, 1),                    # several ragged tiles of both outputs
+    (2, 30, 30, 20, 5, 5, 9, 2, 2, 1),
+    (1, 7, 7, 256, 3, 3, 130, 1, 1, 1),                    # long contraction for gx, short for gw
+    (4, 14, 14, 64, 1, 1, 200, 1, 0, 1),
+    (2, 28, 28, 64, 3, 3, 64, 2, 1, 1),
+    (3, 16, 16, 3, 7, 7, 64, 2, 3, 1),                     # a stem: three input channels
+]
+
+
+@pytest.mark.parametrize("signed", [False, True])
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(str(v) for v in s[:7]))
+def test_backward_matches_oracle(shape, signed):
+    _check(shape, 11, signed=signed, what=str(shape))
+
+
+def test_backward_with_a_pad_code_that_is_not_the_zero_point():
+    _check((2, 10, 9, 6, 3, 3, 10, 1, 2, 1), 13, pad_code=200, what="pad code 200")
+    _check((2, 10, 9, 6, 3, 3, 10, 1, 2, 1), 14, signed=True, pad_code=-100, what="signed pad code -100")
+
+
+def test_backward_uses_every_bit_of_gy():
+    _check((2, 16, 16, 32, 3, 3, 48, 1, 1, 1), 15, gy_kind="wide", what="wide gy")
+
+
+def test_backward_resnet_sized_layers_and_single_outputs():
+    # many pixels: the filter gradient sums over 25088 outputs in several splits
+    _check((8, 56, 56, 64, 3, 3, 64, 1, 1, 1), 17, what="56x56x64")
+    x, w, q, gy = _case((4, 28, 28, 128, 1, 1, 96, 1, 0, 1), 19)
+    xd, wd, gd = G.to_dev(x), G.to_dev(w), G.to_dev(gy)
+    gx, gw = ax.ax_conv2d_backward(xd, wd, gd, 1, 0, q)
+    gx1, none = ax.ax_conv2d_backward(xd, wd, gd, 1, 0, q, gw_out=False)
+    none2, gw1 = ax.ax_conv2d_backward(xd, wd, gd, 1, 0, q, gx_out=False)
+    torch.cuda.synchronize()
+    assert none is None and none2 is None
+    assert torch.equal(gx, gx1) and torch.equal(gw, gw1)  # the same bits in every run
+
+
+def test_backward_argument_errors():
+    """Every call below is rejected on the host before anything is launched (the pointers are
+    never dereferenced); the last one, with real tensors, runs without a workspace because only gx
+    is asked for."""
+    import ctypes
+    L = ax.lib()
+    q = ax.ax_quant_t(1.0, 0, 1.0, 0, -1)
+    one = ctypes.c_void_p(256)
+    d = ax._conv_desc((1, 8, 8, 4), (3, 3, 4, 1), 1, 1, depthwise=True)
+    assert L.ax_conv2d_backward(ctypes.byref(d), ctypes.byref(q), one, one, one, one, one, one, 1 << 20, None) == -8
+    d = ax._conv_desc((1, 8, 8, 4), (3, 3, 4, 8), 1, 1)
+    assert L.ax_conv2d_backward(ctypes.byref(d), ctypes.byref(q), one, one, one, None, None, one, 1 << 20, None) == -1
+    assert L.ax_conv2d_backward(ctypes.byref(d), ctypes.byref(q), one, one, one, one, one, one, 16, None) == -5
+    assert L.ax_conv2d_backward(ctypes.byref(d), ctypes.byref(q), one, one, one, one, one, None, 0, None) == -5
+    bad = ax.ax_quant_t(1.0, 300, 1.0, 0, -1)
+    assert L.ax_conv2d_backward(ctypes.byref(d), ctypes.byref(bad), one, one, one, one, one, one, 1 << 20, None) == -3
+    x = torch.zeros((1, 8, 8, 4), dtype=torch.uint8, device="cuda")
+    w = torch.ones((3, 3, 4, 8), dtype=torch.uint8, device="cuda")
+    gy = torch.ones((1, 8, 8, 8), dtype=torch.float32, device="cuda")
+    gx = torch.empty((1, 8, 8, 4), dtype=torch.float32, device="cuda")
+    rc = L.ax_conv2d_backward(ctypes.byref(d), ctypes.byref(q), ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(w.data_ptr()),
+                              ctypes.c_void_p(gy.data_ptr()), ctypes.c_void_p(gx.data_ptr()), None, None, 0,
+                              ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    assert rc == 0
+    assert float(gx[0, 4, 4, 0]) == 72.0  # nine taps, eight channels, filter value 1, gy 1
