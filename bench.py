@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads (configs 2, 4, 5)")
     ap.add_argument("--probe", action="store_true", help="only run the LDS / copy micro-benchmarks and print a table")
+    ap.add_argument("--per-layer", action="store_true", help="only time every layer of the workload and print a table")
     return ap.parse_args()
 
 
@@ -51,12 +52,16 @@ def probe_table(ax, torch):
     t = time.time()
     while time.time() - t < 1.0:  # let the clocks ramp up
         (a @ a).sum().item()
-    names = {0: "consecutive (conflict-free)", 1: "uniform random", 2: "random, half of the lanes on entry 0"}
+    names = {0: "consecutive (conflict-free)", 1: "uniform random", 2: "random, half of the lanes on entry 0",
+             3: "random entries of 16 interleaved tables, table = lane % 16",
+             4: "random entries of 16 interleaved tables, table = (lane / 4) % 16",
+             5: "random entries of 16 interleaved tables, table = lane % 8 + 8 * ((lane / 32) % 2)",
+             6: "random entries of 16 interleaved tables, table = lane % 4 + 4 * ((lane / 16) % 4)"}
     print("| read width | pattern | table | T lanes/s | TB/s | lookups per lane |")
     print("|---|---|---|---|---|---|")
     for width in (2, 4, 8, 16):
-        for pat in (0, 1, 2):
-            for tb in ((32768,) if pat == 0 else (4096, 131072)):
+        for pat in (0, 1, 2) + ((3, 4, 5, 6) if width == 16 else ()):
+            for tb in ((32768,) if pat == 0 else (65536,) if pat >= 3 else (4096, 131072)):
                 r = ax.ax_probe_lds_gather(width, pat, tb, 1024, 20000 if width < 16 else 10000)
                 lanes = r["wave_reads"] * r["workgroups"] * 64 / r["seconds"]
                 print("| %d B | %s | %d KiB | %.2f | %.1f | %d |" % (width, names[pat], tb // 1024, lanes / 1e12,
@@ -181,6 +186,32 @@ def main():
     kern_ms = np.median(np.array(kern_ms), axis=0)
     main_ms = float(kern_ms.sum())
     n_launch = len(calls)
+
+    if args.per_layer:
+        # every layer on its own: whole call (per-call preparation, main kernel, fix-up) and main kernel
+        print("| layer | M | K | Cout | lookups (G) | plan (variant, tile, workgroups, pieces) | call us | main kernel us | "
+              "T lookups/s (call) | T lookups/s (kernel) |")
+        print("|---|---|---|---|---|---|---|---|---|---|")
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        tot_call = 0.0
+        for (l, h, xd, wd, q, acc, y, ws), km in zip(calls, kern_ms):
+            for _ in range(3):
+                h.run(xd, acc, y, ws)
+            torch.cuda.synchronize()
+            a0.record()
+            for _ in range(20):
+                h.run(xd, acc, y, ws)
+            a1.record()
+            torch.cuda.synchronize()
+            cm = a0.elapsed_time(a1) / 20
+            tot_call += cm
+            p = h.plan()
+            print("| %s | %d | %d | %d | %.3f | %d, %d, %d, %d | %.1f | %.1f | %.2f | %.2f |" % (
+                l.name, l.M, l.K, l.Cout, l.macs / 1e9, p["variant"], p["tile"], p["workgroups"], p["pieces"], cm * 1e3,
+                km * 1e3, l.macs / cm / 1e9, l.macs / km / 1e9))
+        print("\nsum of the calls timed one layer at a time: %.3f ms; the same 54 calls back to back in a step: %.3f ms; "
+              "main kernels: %.3f ms" % (tot_call, ms_per_step, main_ms))
+        return
 
     # measured denominators: LDS lookup rates and copy bandwidth on this device
     r_cf = ax.ax_probe_lds_gather(2, 0, 131072, 1024, 20000)
@@ -511,8 +542,37 @@ def main():
                 "ms": ms, "lut_macs_per_s": n_out * 9 / ms * 1e3,
                 "roofline": {"bound": "hbm", "achieved": byts / ms / 1e6, "peak": 8000.0, "unit": "GB/s",
                              "frac": byts / ms / 1e6 / 8000.0, "algorithmic_bytes": byts,
-                             "lds_random_gather_Glookup_s": lds_rand / 1e9}}
+                             "lds_random_gather_Glookup_s": lds_rand / 1e9,
+                             "frac_of_lds_random_2_byte_gather_rate": n_out * 9 / ms * 1e3 / lds_rand}}
         extra["variants_batch%d" % args.batch] = var
+
+        # backward pass (straight-through: gradients of the exact convolution of the dequantized
+        # tensors) of the 53 convolutions of the sweep, both gradients, on the matrix cores
+        bw = []
+        for l, h, xd, wd, q, acc, y, ws in calls:
+            if l.dense:
+                continue
+            desc = ax._conv_desc((l.N, l.H, l.W, l.Cin), (l.KH, l.KW, l.Cin, l.Cout), l.stride, l.pad)
+            gy = torch.randn((l.N, l.OH, l.OW, l.Cout), device=dev)
+            gx = torch.empty((l.N, l.H, l.W, l.Cin), dtype=torch.float32, device=dev)
+            gw = torch.empty((l.KH, l.KW, l.Cin, l.Cout), dtype=torch.float32, device=dev)
+            wsb = torch.empty(int(ax.lib().ax_conv2d_backward_workspace_bytes(desc)), dtype=torch.uint8, device=dev)
+            bw.append((l, xd, wd, q, gy, gx, gw, wsb))
+
+        def bstep():
+            for l, xd, wd, q, gy, gx, gw, wsb in bw:
+                ax.ax_conv2d_backward(xd, wd, gy, l.stride, l.pad, q, gx_out=gx, gw_out=gw, workspace=wsb)
+        ms_b = time_calls([bstep], 3)
+        flops_b = sum(4.0 * l.macs for l, *_ in bw)  # two gradients, two flops per multiply-add
+        extra["backward_resnet50_convs_batch%d" % args.batch] = {
+            "ms": ms_b, "useful_TFLOP_s": flops_b / ms_b / 1e9,
+            "roofline": {"bound": "mfma", "achieved": flops_b / ms_b / 1e9, "peak": 2500.0 / 3.0, "unit": "TFLOP/s",
+                         "frac": flops_b / ms_b / 1e9 / (2500.0 / 3.0),
+                         "note": "useful float32-equivalent flops; every product takes three bf16 matrix "
+                                 "instructions (gy split into three exact bf16 pieces), so the bound is a third of "
+                                 "the dense bf16 peak of 2.5 PFLOP/s"},
+            "forward_ms_same_layers": ms_per_step}
+        del bw
 
     # ---- float-in / float-out form of the same sweep (range + quantization glue included) ------
     float_layer = None
