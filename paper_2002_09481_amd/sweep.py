@@ -10,7 +10,10 @@ buffers, and events order them against the compute stream:
     upload stream :  wait(free[b])   copy tables of chunk c into staging[b]     record(ready[b])
     compute stream:  wait(ready[b])  prepare + run every layer on staging[b]    record(free[b])
 
-with b = c mod 2, so the copy of chunk c + 1 proceeds while chunk c is being computed.  An
+with b = c mod 3, so the copy of chunk c + 1 proceeds while chunk c is being computed.  Three
+staging buffers rather than two: the host, not the upload stream, waits for free[b] (see run), and
+with three it waits for the chunk before the one the device is working on, so the device never
+runs out of enqueued work while the host waits.  An
 upload chunk holds several tables (eight by default) even when every layer call takes one table:
 an event wait between two streams costs far more than the copy it orders (about 0.1 ms against
 a few microseconds per table on this machine), so it is paid once per eight tables.  Only
@@ -35,6 +38,8 @@ class TableSweep:
     layer; more = the tiles of `chunk` tables share one grid).  tables_per_upload: tables per
     host-to-device copy and per pair of stream synchronizations (a multiple of chunk)."""
 
+    NBUF = 3  # staging buffers
+
     def __init__(self, layers: Sequence, chunk: int = 1, tables_per_upload: Optional[int] = None, device="cuda"):
         self.layers = list(layers)
         self.chunk = int(chunk)
@@ -46,9 +51,9 @@ class TableSweep:
         self._handles = {}   # (layer index, tables per call) -> AxLayer
         self._blocks = {}    # (layer index, tables per call, buffer) -> prepared block
         self._ws = {}        # (layer index, tables per call) -> workspace
-        self.staging = [torch.empty((self.per_upload, 65536), dtype=torch.int16, device=self.device) for _ in range(2)]
-        self.ready = [torch.cuda.Event() for _ in range(2)]
-        self.free = [torch.cuda.Event() for _ in range(2)]
+        self.staging = [torch.empty((self.per_upload, 65536), dtype=torch.int16, device=self.device) for _ in range(self.NBUF)]
+        self.ready = [torch.cuda.Event() for _ in range(self.NBUF)]
+        self.free = [torch.cuda.Event() for _ in range(self.NBUF)]
 
     def _handle(self, li: int, n: int) -> ax.AxLayer:
         key = (li, n)
@@ -74,7 +79,7 @@ class TableSweep:
         False to skip).  overlap=False enqueues the copies on the compute stream instead (the
         serialized form, for comparison).  Returns (acc_out, y_out).  The device is not waited for at
         the end, but with overlap the host paces itself: before it enqueues the copy of upload unit
-        u it waits until unit u - 2 has finished on the device."""
+        u it waits until unit u - 3 has finished on the device."""
         T = int(host_tables.shape[0])
         if host_tables.dim() != 2 or host_tables.shape[1] != 65536 or host_tables.dtype not in (torch.int16, torch.uint16):
             raise ValueError("host_tables must be a 16-bit integer tensor [T, 65536]")
@@ -94,15 +99,16 @@ class TableSweep:
 
         def enqueue_upload(u):
             t0, n = units[u]
-            b = u % 2
+            b = u % self.NBUF
             if not overlap:
                 self.staging[b][:n].copy_(host_tables[t0:t0 + n], non_blocking=True)
                 return
-            if u >= 2:
-                # Unit u - 2 must have stopped reading this staging buffer.  The host waits for that
+            if u >= self.NBUF:
+                # Unit u - 3 must have stopped reading this staging buffer.  The host waits for that
                 # here rather than the upload stream on the device: a queue that sits blocked on an
-                # event slows every kernel launch of the other queue (measured: 40 us per launch),
-                # and the host stays one unit (milliseconds of device work) ahead anyway.
+                # event slows every kernel launch of the other queue (measured: 40 us per launch).
+                # This copy is enqueued before the launches of unit u - 1, so the device is then
+                # still working on unit u - 2 and has that unit's launches ahead of it.
                 self.free[b].synchronize()
             with torch.cuda.stream(self.upload):
                 self.staging[b][:n].copy_(host_tables[t0:t0 + n], non_blocking=True)
@@ -112,7 +118,7 @@ class TableSweep:
             self.upload.wait_stream(compute)  # whatever filled or read the staging buffers before this call
             enqueue_upload(0)
         for u, (t0, nu) in enumerate(units):
-            b = u % 2
+            b = u % self.NBUF
             if overlap:
                 if u + 1 < len(units):
                     enqueue_upload(u + 1)
