@@ -266,6 +266,115 @@ __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const u
   }
 }
 
+// 3 x 3 depthwise layers with multiplier 1 whose channel-group count divides 1024 (every thread
+// keeps its four channels, the filter codes stay pre-shifted in registers) and 16-byte aligned
+// outputs: PX items (pixels) per thread and iteration.  All loads of the PX items are issued
+// before the first lookup, so that a wave has PX times the lookups to cover one memory round trip
+// with (the workgroup fills the compute unit's LDS, so more waves are not to be had).
+template <int PX>
+__global__ __launch_bounds__(1024) void dw3_kernel(Geom g, QParams qp_in, const uint8_t* __restrict__ x,
+                                                    const uint8_t* __restrict__ w, const uint16_t* __restrict__ lut,
+                                                    int32_t* __restrict__ acc_out, float* __restrict__ y_out) {
+  __shared__ uint32_t tab[256 * kDwRow];
+  __shared__ int32_t sfs[kDwMaxC];
+  QParams qp = qp_in;
+  if (qp.dq) {
+    qp.x_zp = qp.dq->x_zp;
+    qp.w_zp = qp.dq->w_zp;
+    qp.pad_code = qp.x_zp;
+    qp.scale = qp.dq->x_scale * qp.dq->w_scale;
+  }
+  const uint32_t flip16 = g.sgn ? 0x80008000u : 0u;
+  const uint32_t flip8 = g.sgn ? 0x80808080u : 0u;
+  {
+    const uint4* __restrict__ src = reinterpret_cast<const uint4*>(lut);
+    const int rowflip = g.sgn ? (0x80 << 5) : 0;  // see dw_kernel
+    for (int i = threadIdx.x; i < 8192; i += 1024) {
+      uint4 v = src[i ^ rowflip];
+      uint32_t* dst = tab + (i >> 5) * kDwRow + (i & 31) * 4;
+      dst[0] = v.x ^ flip16; dst[1] = v.y ^ flip16; dst[2] = v.z ^ flip16; dst[3] = v.w ^ flip16;
+    }
+    for (int c = threadIdx.x; c < g.Cout; c += 1024) {
+      int32_t t = 0;
+      for (int k = 0; k < 9; ++k) t += (int32_t)((uint32_t)w[(size_t)k * g.Cout + c] ^ (flip8 & 0xffu));
+      sfs[c] = t;
+    }
+  }
+  __syncthreads();
+  const uint32_t C4 = (uint32_t)g.Cout / 4u;
+  const uint32_t items = (uint32_t)g.M * C4;
+  const uint32_t pad4 = ((uint32_t)qp.pad_code & 0xffu) * 0x01010101u;
+  const uint32_t bias = g.sgn ? 32768u * 9u : 0u;
+  const int off128 = g.sgn ? 128 * 9 : 0;
+  const long long kzz = 9LL * qp.x_zp * qp.w_zp;
+  const char* tabb = reinterpret_cast<const char*>(tab);
+  const uint32_t gid = blockIdx.x * 1024u + threadIdx.x, stride = gridDim.x * 1024u;
+  const uint32_t c4 = gid % C4;  // the same for every item of this thread: stride % C4 == 0
+  uint32_t wb2[9][4];  // 2 * filter code = byte offset within a table row
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    const uint32_t wd = *reinterpret_cast<const uint32_t*>(w + (size_t)t * g.Cin + 4u * c4);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wb2[t][j] = ((wd >> (8 * j)) & 0xffu) << 1;
+  }
+  int32_t sf[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) sf[j] = sfs[4u * c4 + j] - off128;
+  const uint8_t* __restrict__ xc = x + 4u * c4;
+  for (uint32_t it0 = gid; it0 < items; it0 += PX * stride) {
+    uint32_t xd[PX][9];
+#pragma unroll
+    for (int p = 0; p < PX; ++p) {
+      const uint32_t it = it0 + p * stride;
+      uint32_t m = (it < items ? it : it0) / C4;  // a missing item repeats the first one's loads
+      const int ox = m % (uint32_t)g.OW;
+      m /= (uint32_t)g.OW;
+      const int oy = m % (uint32_t)g.OH;
+      const int n = m / (uint32_t)g.OH;
+      const int by = oy * g.sh - g.ph, bx = ox * g.sw - g.pw;
+      const uint8_t* __restrict__ xn = xc + (size_t)n * g.H * g.W * g.Cin;
+#pragma unroll
+      for (int ky = 0; ky < 3; ++ky) {
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx) {
+          const int iy = by + ky * g.dh, ix = bx + kx * g.dw;
+          const bool inside = (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
+          xd[p][ky * 3 + kx] = pad4;
+          if (inside) xd[p][ky * 3 + kx] = *reinterpret_cast<const uint32_t*>(xn + ((size_t)iy * g.W + ix) * g.Cin);
+        }
+      }
+    }
+#pragma unroll
+    for (int p = 0; p < PX; ++p) {
+      const uint32_t it = it0 + p * stride;
+      if (it >= items) break;
+      uint32_t acc[4] = {0, 0, 0, 0}, sp[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int t = 0; t < 9; ++t) {
+        const uint32_t xs = xd[p][t] ^ flip8;  // code + 128 for signed codes
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t a = (xs >> (8 * j)) & 0xffu;
+          acc[j] += *reinterpret_cast<const uint16_t*>(tabb + (a * (uint32_t)(kDwRow * 4) + wb2[t][j]));
+          sp[j] += a;
+        }
+      }
+      int32_t av[4];
+      float yv[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        av[j] = (int32_t)(acc[j] - bias);
+        const long long corr = (long long)av[j] - (long long)qp.w_zp * ((int32_t)sp[j] - off128) -
+                               (long long)qp.x_zp * sf[j] + kzz;
+        yv[j] = (float)corr * qp.scale;
+      }
+      const size_t o = (size_t)it * 4u;  // = pixel * Cout + 4 * c4
+      if (acc_out) *reinterpret_cast<int4*>(acc_out + o) = make_int4(av[0], av[1], av[2], av[3]);
+      if (y_out) *reinterpret_cast<float4*>(y_out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+    }
+  }
+}
+
 bool dw_supported(const Geom& g, const uint8_t* x, const uint8_t* w, const uint16_t* lut) {
   (void)x;
   (void)w;
@@ -286,6 +395,8 @@ hipError_t launch_dw(const Geom& g, const QParams& qp, const uint8_t* x, const u
   const bool keeps_channels = fast && 1024 % C4 == 0;  // the grid stride is then a multiple of the channel groups
   if (!fast)
     hipLaunchKernelGGL((dw_kernel<0, false, true>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
+  else if (g.KH == 3 && g.KW == 3 && keeps_channels && vec_out)
+    hipLaunchKernelGGL((dw3_kernel<2>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out);
   else if (g.KH == 3 && g.KW == 3 && keeps_channels)
     hipLaunchKernelGGL((dw_kernel<3, true, false>), dim3(blocks), dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, vec_out);
   else if (g.KH == 3 && g.KW == 3)
