@@ -314,8 +314,9 @@ size_t ax_dense_f32_workspace_bytes(int M, int K, int N);
  * Either output may be NULL (not both).  Sums are accumulated in float32 on the matrix cores (gy
  * split exactly into three bf16 pieces, the other operand a small integer that bf16 holds
  * exactly); each output is within 2e-5 times the sum of the absolute values of its terms of the
- * exact value.  Depthwise descriptors give AX_ERR_OPTION (not built).  workspace (needed for
- * gw_out): ax_conv2d_backward_workspace_bytes(desc) bytes, 256-byte aligned.
+ * exact value.  Depthwise descriptors give AX_ERR_OPTION (not built).  workspace (always
+ * needed: it holds the bf16 pieces of gy, the converted filters and the partial filter
+ * gradients): ax_conv2d_backward_workspace_bytes(desc) bytes, 256-byte aligned.
  */
 int ax_conv2d_backward(const ax_conv_desc_t* desc, const ax_quant_t* q, const void* x, const void* w,
                        const float* gy, float* gx_out, float* gw_out, void* workspace,

@@ -100,8 +100,7 @@ def test_backward_resnet_sized_layers_and_single_outputs():
 
 def test_backward_argument_errors():
     """Every call below is rejected on the host before anything is launched (the pointers are
-    never dereferenced); the last one, with real tensors, runs without a workspace because only gx
-    is asked for."""
+    never dereferenced); the last one, with real tensors and a real workspace, asks for gx only."""
     import ctypes
     L = ax.lib()
     q = ax.ax_quant_t(1.0, 0, 1.0, 0, -1)
@@ -118,9 +117,14 @@ def test_backward_argument_errors():
     w = torch.ones((3, 3, 4, 8), dtype=torch.uint8, device="cuda")
     gy = torch.ones((1, 8, 8, 8), dtype=torch.float32, device="cuda")
     gx = torch.empty((1, 8, 8, 4), dtype=torch.float32, device="cuda")
-    rc = L.ax_conv2d_backward(ctypes.byref(d), ctypes.byref(q), ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(w.data_ptr()),
-                              ctypes.c_void_p(gy.data_ptr()), ctypes.c_void_p(gx.data_ptr()), None, None, 0,
-                              ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    nws = int(L.ax_conv2d_backward_workspace_bytes(ctypes.byref(d)))
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    args = (ctypes.byref(d), ctypes.byref(q), ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(w.data_ptr()),
+            ctypes.c_void_p(gy.data_ptr()), ctypes.c_void_p(gx.data_ptr()), None)
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert L.ax_conv2d_backward(*args, None, 0, stream) == -5  # no workspace: rejected, nothing launched
+    assert L.ax_conv2d_backward(*args, ctypes.c_void_p(ws.data_ptr()), nws - 1, stream) == -5
+    rc = L.ax_conv2d_backward(*args, ctypes.c_void_p(ws.data_ptr()), nws, stream)
     torch.cuda.synchronize()
     assert rc == 0
     assert float(gx[0, 4, 4, 0]) == 72.0  # nine taps, eight channels, filter value 1, gy 1
