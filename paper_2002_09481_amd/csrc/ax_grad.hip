@@ -174,11 +174,15 @@ __global__ __launch_bounds__(256) void grad_wint_kernel(const uint8_t* __restric
 // stride 2) instead of multiplying zeros.  blockIdx = (tile within the class, Cin tile, class).
 // A wave takes 32 rows and all TC columns: every piece read from LDS feeds TC / 32 matrix
 // instructions.
-template <int TC>
-__global__ __launch_bounds__(256) void dgrad_kernel(const GradArgs a) {
-  constexpr int NB = TC / 32;   // 32 x 32 blocks per wave
-  constexpr int BE = TC / 8;    // filter elements per thread and stage (8 or 16)
-  constexpr int TPR = 32 / BE;  // threads per filter row
+template <int TC, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void dgrad_kernel(const GradArgs a) {
+  constexpr int THREADS = 64 * WAVES;
+  constexpr int CG = WAVES / 4;                 // waves side by side; four rows of waves cover the 128 tile rows
+  constexpr int NB = TC / (32 * CG);            // 32 x 32 blocks per wave
+  constexpr int AE = kTR * kStage / THREADS;    // gy elements per thread, plane and stage (16 or 8)
+  constexpr int ATPR = kStage / AE;             // threads per gy row
+  constexpr int BE = TC * kStage / THREADS;     // filter elements per thread and stage (8 or 16)
+  constexpr int TPR = kStage / BE;              // threads per filter row
   __shared__ __align__(16) short As[3][kTR][kLd];  // gy pieces: [piece][pixel][co within the stage]
   __shared__ __align__(16) short Bs[TC][kLd];      // filter integers: [ci][co within the stage]
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -189,8 +193,8 @@ __global__ __launch_bounds__(256) void dgrad_kernel(const GradArgs a) {
   const int r0 = blockIdx.x * kTR;
   if (r0 >= rows) return;  // uniform
   const int ci0 = blockIdx.y * TC;
-  // staging roles: gy row ar (a pixel), stage elements ah .. ah+15; filter row br (a channel), elements bh .. bh+BE-1
-  const int ar = t >> 1, ah = (t & 1) * 16;
+  // staging roles: gy row ar (a pixel), stage elements ah .. ah+AE-1; filter row br (a channel), elements bh .. bh+BE-1
+  const int ar = t / ATPR, ah = (t - ar * ATPR) * AE;
   const int br = t / TPR, bh = (t - br * TPR) * BE;
   auto pixel_of = [&](int r, int& n, int& iy, int& ix) {
     n = r / (Hc * Wc);
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(256) void dgrad_kernel(const GradArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
   const int mr = lane & 31, kg = (lane >> 5) * 8;
-  const int wrow = wave * 32;
+  const int wrow = (wave & 3) * 32, wcol = (wave >> 2) * (TC / CG);
 
   // The stages: every reachable tap (ky, kx), and for it the channels co0 .. co0+31 of [0, Cp).
   int ky = -1, kx = a.KW - 1, co0 = a.Cp;
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(256) void dgrad_kernel(const GradArgs a) {
     }
   };
   struct StageRegs {
-    bf16x8 ra[3][2], rb[BE / 8];
+    bf16x8 ra[3][AE / 8], rb[BE / 8];
   };
   auto load_stage = [&](StageRegs& R) {  // the current stage's operands, global memory -> registers
     const int ty = iy + a.ph - ky * a.dh, tx = ix + a.pw - kx * a.dw;  // multiples of the strides (class)
@@ -236,8 +240,8 @@ __global__ __launch_bounds__(256) void dgrad_kernel(const GradArgs a) {
 #pragma unroll
     for (int pl = 0; pl < 3; ++pl) {
       const short* src = a.P + ((size_t)pl * a.M + mrow) * a.Cp + co0 + ah;
-      R.ra[pl][0] = ok ? *reinterpret_cast<const bf16x8*>(src) : zero8();
-      R.ra[pl][1] = ok ? *reinterpret_cast<const bf16x8*>(src + 8) : zero8();
+#pragma unroll
+      for (int v = 0; v < AE / 8; ++v) R.ra[pl][v] = ok ? *reinterpret_cast<const bf16x8*>(src + 8 * v) : zero8();
     }
     const short* wsrc = a.wi + ((size_t)(ky * a.KW + kx) * a.Cin + (ci_ok ? ci : 0)) * a.Cp + co0 + bh;
 #pragma unroll
@@ -245,10 +249,9 @@ __global__ __launch_bounds__(256) void dgrad_kernel(const GradArgs a) {
   };
   auto store_stage = [&](const StageRegs& R) {  // registers -> LDS
 #pragma unroll
-    for (int pl = 0; pl < 3; ++pl) {
-      *reinterpret_cast<bf16x8*>(&As[pl][ar][ah]) = R.ra[pl][0];
-      *reinterpret_cast<bf16x8*>(&As[pl][ar][ah + 8]) = R.ra[pl][1];
-    }
+    for (int pl = 0; pl < 3; ++pl)
+#pragma unroll
+      for (int v = 0; v < AE / 8; ++v) *reinterpret_cast<bf16x8*>(&As[pl][ar][ah + 8 * v]) = R.ra[pl][v];
 #pragma unroll
     for (int v = 0; v < BE / 8; ++v) *reinterpret_cast<bf16x8*>(&Bs[br][bh + 8 * v]) = R.rb[v];
   };
@@ -257,7 +260,7 @@ __global__ __launch_bounds__(256) void dgrad_kernel(const GradArgs a) {
     for (int ks = 0; ks < kStage; ks += 16) {
       bf16x8 bv[NB];
 #pragma unroll
-      for (int b = 0; b < NB; ++b) bv[b] = *reinterpret_cast<const bf16x8*>(&Bs[32 * b + mr][ks + kg]);
+      for (int b = 0; b < NB; ++b) bv[b] = *reinterpret_cast<const bf16x8*>(&Bs[wcol + 32 * b + mr][ks + kg]);
 #pragma unroll
       for (int pl = 0; pl < 3; ++pl) {
         const bf16x8 av = *reinterpret_cast<const bf16x8*>(&As[pl][wrow + mr][ks + kg]);
@@ -321,7 +324,7 @@ __global__ __launch_bounds__(256) void dgrad_kernel(const GradArgs a) {
     float* orow = obase + (((size_t)on * a.H + oiy) * a.W + oix) * a.Cin;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-      const int col = ci0 + 32 * b + mr;
+      const int col = ci0 + wcol + 32 * b + mr;
       if (col < a.Cin) orow[col] = acc[b][i] * oscale;
     }
   }
@@ -329,17 +332,21 @@ __global__ __launch_bounds__(256) void dgrad_kernel(const GradArgs a) {
 
 // gw: output matrix [K taps] x [Cout], contraction over the output pixels of this split.
 // blockIdx = (tap tile, Cout tile, split).  A wave takes 64 taps x TC / 2 channels.
-template <int TC>
-__global__ __launch_bounds__(256) void wgrad_kernel(const GradArgs a) {
-  constexpr int NBC = TC / 64;      // 32-column blocks per wave
-  constexpr int BM = 32 * TC / 256;  // stage pixels per thread on the gy side (16 or 8)
-  __shared__ __align__(16) short As[kTR][kLd];     // activation integers: [tap k][pixel within the stage]
+template <int TR, int TC, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void wgrad_kernel(const GradArgs a) {
+  constexpr int THREADS = 64 * WAVES;
+  constexpr int RG = TR / 64;                  // rows of waves: a wave takes 64 taps
+  constexpr int CG = WAVES / RG;               // waves side by side
+  constexpr int NBC = TC / (32 * CG);          // 32-column blocks per wave
+  constexpr int BM = kStage * TC / THREADS;    // stage pixels per thread on the gy side (16 or 8)
+  static_assert(TR * 16 == THREADS * 8, "a thread stages 16 pixels of one tap row: two threads per row");
+  __shared__ __align__(16) short As[TR][kLd];      // activation integers: [tap k][pixel within the stage]
   __shared__ __align__(16) short Bs[3][TC][kLd];   // gy pieces: [piece][co][pixel within the stage]
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int k0 = blockIdx.x * kTR, co0 = blockIdx.y * TC, split = blockIdx.z;
+  const int k0 = blockIdx.x * TR, co0 = blockIdx.y * TC, split = blockIdx.z;
   // staging roles: tap row ar, stage pixels as .. as+15 (consecutive lanes take consecutive taps, i.e.
   // consecutive input channels: one pixel's bytes are read together); channel bc, stage pixels bs .. bs+BM-1
-  const int ar = t & 127, as = (t >> 7) * 16;
+  const int ar = t % TR, as = (t / TR) * 16;
   const int bc = t % TC, bs = (t / TC) * BM;
   const int k = k0 + ar;
   const bool k_ok = k < a.K;
@@ -362,7 +369,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const GradArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[b][c][i] = 0.f;
   const int mr = lane & 31, kg = (lane >> 5) * 8;
-  const int wrow = (wave & 1) * 64, wcol = (wave >> 1) * (TC / 2);
+  const int wrow = (wave % RG) * 64, wcol = (wave / RG) * (TC / CG);
 
   struct StageRegs {
     uint32_t xa[16];  // raw activation codes of the stage (converted when they go to LDS)
@@ -462,15 +469,27 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const GradArgs a) {
       }
 }
 
-// out = scale * (sum of the partial sums, in slice order: the same bits in every run); used for
-// gw (scale alpha1) and for a gx whose contraction was cut into slices (scale alpha2)
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ part, int splits, size_t n,
-                                                            float scale, float* __restrict__ gw) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
+// out = scale * (sum of the partial sums); used for gw (scale alpha1) and for a gx whose
+// contraction was cut into slices (scale alpha2).  A block takes 32 outputs; its eight groups of
+// threads each add every eighth slice, and the eight sums are added in group order: a fixed
+// order, so the same bits in every run, and no thread walks hundreds of slices alone (the filter
+// gradient of a layer with few filters and many pixels has that many).
+__global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict__ part, int splits, size_t n,
+                                                          float scale, float* __restrict__ out) {
+  __shared__ float red[8][32];
+  const int o = threadIdx.x & 31, sg = threadIdx.x >> 5;
+  const size_t i = (size_t)blockIdx.x * 32 + o;
   float s = 0.f;
-  for (int q = 0; q < splits; ++q) s += part[(size_t)q * n + i];
-  gw[i] = s * scale;
+  if (i < n)
+    for (int q = sg; q < splits; q += 8) s += part[(size_t)q * n + i];
+  red[sg][o] = s;
+  __syncthreads();
+  if (sg == 0 && i < n) {
+    float tot = red[0][o];
+#pragma unroll
+    for (int g = 1; g < 8; ++g) tot += red[g][o];
+    out[i] = tot * scale;
+  }
 }
 
 inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -479,6 +498,7 @@ struct GradPlan {
   int splits, m_per_split;
   int Cp, Mp;
   int tc_d, tc_w;  // column tile of dgrad (over Cin) and of wgrad (over Cout)
+  int tr_w;        // row tile of wgrad (over the taps)
   int dsplits;     // slices of dgrad's contraction
   size_t off_part, off_dpart, off_P, off_PT, off_wi, ws_bytes;
 };
@@ -486,18 +506,21 @@ GradPlan grad_plan(const Geom& g) {
   GradPlan p;
   p.Cp = (g.Cout + kStage - 1) / kStage * kStage;
   p.Mp = (g.M + kStage - 1) / kStage * kStage;
+  // Both kernels are bound by the bytes of the gy pieces (6 per element against 2 for the filter
+  // integers and 1 for the activation codes), so their tiles are wide along the other operand.
   p.tc_w = g.Cout > 64 ? 128 : 64;
-  // dgrad: 128 columns where that still leaves two workgroups per compute unit, then slices of the
-  // contraction (at least eight stages each) until the grid has four per compute unit
+  p.tr_w = (p.tc_w == 128 && g.K > 128) ? 256 : 128;
+  // dgrad: the widest column tile the layer fills, then slices of the contraction (at least eight
+  // stages each) until the grid has four workgroups per compute unit
   const long long rows = (long long)g.N * ((g.H + g.sh - 1) / g.sh) * ((g.W + g.sw - 1) / g.sw);
   const long long rt = (rows + kTR - 1) / kTR * g.sh * g.sw;
-  p.tc_d = (g.Cin > 64 && rt * ((g.Cin + 127) / 128) >= 2LL * cu_count()) ? 128 : 64;
+  p.tc_d = g.Cin > 128 ? 256 : g.Cin > 64 ? 128 : 64;
   const long long dt = rt * ((g.Cin + p.tc_d - 1) / p.tc_d);
   const long long stages_min = (long long)((g.KH + g.sh - 1) / g.sh) * ((g.KW + g.sw - 1) / g.sw) * (p.Cp / kStage);
   long long ds = (4LL * cu_count() + dt - 1) / dt;
   ds = std::max(1LL, std::min(std::min(ds, stages_min / 8), 64LL));
   p.dsplits = (int)ds;
-  const long long tiles = (long long)((g.K + kTR - 1) / kTR) * ((g.Cout + p.tc_w - 1) / p.tc_w);
+  const long long tiles = (long long)((g.K + p.tr_w - 1) / p.tr_w) * ((g.Cout + p.tc_w - 1) / p.tc_w);
   // enough workgroups to fill the machine several times, at least 256 pixels per split
   long long s = (4LL * cu_count() + tiles - 1) / tiles;
   s = std::max(1LL, std::min(s, (long long)(g.M + 255) / 256));
@@ -580,28 +603,32 @@ extern "C" int ax_conv2d_backward(const ax_conv_desc_t* desc, const ax_quant_t* 
     const long long rows = (long long)g.N * ((g.H + g.sh - 1) / g.sh) * ((g.W + g.sw - 1) / g.sw);
     const dim3 grid((unsigned)((rows + kTR - 1) / kTR), (unsigned)((g.Cin + p.tc_d - 1) / p.tc_d),
                     (unsigned)(g.sh * g.sw * p.dsplits));
-    if (p.tc_d == 128)
-      hipLaunchKernelGGL(dgrad_kernel<128>, grid, dim3(256), 0, s, a);
+    if (p.tc_d == 256)
+      hipLaunchKernelGGL((dgrad_kernel<256, 8>), grid, dim3(512), 0, s, a);
+    else if (p.tc_d == 128)
+      hipLaunchKernelGGL((dgrad_kernel<128, 4>), grid, dim3(256), 0, s, a);
     else
-      hipLaunchKernelGGL(dgrad_kernel<64>, grid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL((dgrad_kernel<64, 4>), grid, dim3(256), 0, s, a);
     AX_GRAD_LAUNCHED();
     if (p.dsplits > 1) {
       const size_t n = (size_t)g.N * g.H * g.W * g.Cin;
-      hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+      hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s,
                          reinterpret_cast<const float*>(ws + p.off_dpart), p.dsplits, n, q->w_scale, gx_out);
       AX_GRAD_LAUNCHED();
     }
   }
   if (gw_out) {
     a.out = reinterpret_cast<float*>(ws + p.off_part);
-    const dim3 grid((unsigned)((g.K + kTR - 1) / kTR), (unsigned)((g.Cout + p.tc_w - 1) / p.tc_w), (unsigned)p.splits);
-    if (p.tc_w == 128)
-      hipLaunchKernelGGL(wgrad_kernel<128>, grid, dim3(256), 0, s, a);
+    const dim3 grid((unsigned)((g.K + p.tr_w - 1) / p.tr_w), (unsigned)((g.Cout + p.tc_w - 1) / p.tc_w), (unsigned)p.splits);
+    if (p.tr_w == 256)
+      hipLaunchKernelGGL((wgrad_kernel<256, 128, 8>), grid, dim3(512), 0, s, a);
+    else if (p.tc_w == 128)
+      hipLaunchKernelGGL((wgrad_kernel<128, 128, 4>), grid, dim3(256), 0, s, a);
     else
-      hipLaunchKernelGGL(wgrad_kernel<64>, grid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL((wgrad_kernel<128, 64, 4>), grid, dim3(256), 0, s, a);
     AX_GRAD_LAUNCHED();
     const size_t n = (size_t)g.K * g.Cout;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+    hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s,
                        reinterpret_cast<const float*>(ws + p.off_part), p.splits, n, q->x_scale, gw_out);
     AX_GRAD_LAUNCHED();
   }
