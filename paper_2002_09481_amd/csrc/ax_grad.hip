@@ -64,6 +64,7 @@ struct GradArgs {
   float x_scale, w_scale;
   int splits, m_per_split;  // wgrad: slices of the pixel range
   int dsplits;              // dgrad: slices of the stage sequence
+  uint8_t cls_order[16];    // dgrad: classes in the order the grid takes them (most taps first)
 };
 
 __device__ __forceinline__ short bf16_of_small_int(int v) {  // |v| <= 256: exact
@@ -186,7 +187,8 @@ __global__ __launch_bounds__(64 * WAVES) void dgrad_kernel(const GradArgs a) {
   __shared__ __align__(16) short As[3][kTR][kLd];  // gy pieces: [piece][pixel][co within the stage]
   __shared__ __align__(16) short Bs[TC][kLd];      // filter integers: [ci][co within the stage]
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int cls = blockIdx.z / a.dsplits, split = blockIdx.z - cls * a.dsplits;
+  const int zc = blockIdx.z / a.dsplits, split = blockIdx.z - zc * a.dsplits;
+  const int cls = a.sh * a.sw <= 16 ? a.cls_order[zc] : zc;
   const int cy = cls / a.sw, cx = cls - cy * a.sw;
   const int Hc = (a.H - cy + a.sh - 1) / a.sh, Wc = (a.W - cx + a.sw - 1) / a.sw;  // pixels of the class per image
   const int rows = (Hc > 0 && Wc > 0) ? a.N * Hc * Wc : 0;
@@ -492,6 +494,23 @@ __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict
   }
 }
 
+// The same sum for few slices: one thread per output walks the slices in order.
+__global__ __launch_bounds__(256) void sum_few_slices_kernel(const float* __restrict__ part, int splits, size_t n,
+                                                              float scale, float* __restrict__ out) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int q = 0; q < splits; ++q) s += part[(size_t)q * n + i];
+  out[i] = s * scale;
+}
+
+void launch_sum_slices(const float* part, int splits, size_t n, float scale, float* out, hipStream_t s) {
+  if (splits > 16)
+    hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s, part, splits, n, scale, out);
+  else
+    hipLaunchKernelGGL(sum_few_slices_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, part, splits, n, scale, out);
+}
+
 inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct GradPlan {
@@ -500,6 +519,7 @@ struct GradPlan {
   int tc_d, tc_w;  // column tile of dgrad (over Cin) and of wgrad (over Cout)
   int tr_w;        // row tile of wgrad (over the taps)
   int dsplits;     // slices of dgrad's contraction
+  uint8_t cls_order[16];
   size_t off_part, off_dpart, off_P, off_PT, off_wi, ws_bytes;
 };
 GradPlan grad_plan(const Geom& g) {
@@ -512,13 +532,32 @@ GradPlan grad_plan(const Geom& g) {
   p.tr_w = (p.tc_w == 128 && g.K > 128) ? 256 : 128;
   // dgrad: the widest column tile the layer fills, then slices of the contraction (at least eight
   // stages each) until the grid has four workgroups per compute unit
-  const long long rows = (long long)g.N * ((g.H + g.sh - 1) / g.sh) * ((g.W + g.sw - 1) / g.sw);
-  const long long rt = (rows + kTR - 1) / kTR * g.sh * g.sw;
+  // The classes (iy mod sh, ix mod sw) of input pixels differ in the taps that reach them (none at
+  // all for three of the four classes of a 1 x 1 layer with stride 2): the grid is sized by the
+  // tiles of the classes that have work, and takes the classes with the most taps first, so that
+  // the longest workgroups do not start last.
   p.tc_d = g.Cin > 128 ? 256 : g.Cin > 64 ? 128 : 64;
-  const long long dt = rt * ((g.Cin + p.tc_d - 1) / p.tc_d);
-  const long long stages_min = (long long)((g.KH + g.sh - 1) / g.sh) * ((g.KW + g.sw - 1) / g.sw) * (p.Cp / kStage);
-  long long ds = (4LL * cu_count() + dt - 1) / dt;
-  ds = std::max(1LL, std::min(std::min(ds, stages_min / 8), 64LL));
+  const int ncls = g.sh * g.sw;
+  long long dt = 0;
+  int max_taps = 0;
+  int taps_of[16] = {0};
+  for (int c = 0; c < ncls; ++c) {
+    const int cy = c / g.sw, cx = c - cy * g.sw;
+    int ty = 0, tx = 0;
+    for (int ky = 0; ky < g.KH; ++ky) ty += (((cy + g.ph - ky * g.dh) % g.sh) + g.sh) % g.sh == 0;
+    for (int kx = 0; kx < g.KW; ++kx) tx += (((cx + g.pw - kx * g.dw) % g.sw) + g.sw) % g.sw == 0;
+    const long long Hc = (g.H - cy + g.sh - 1) / g.sh, Wc = (g.W - cx + g.sw - 1) / g.sw;
+    const long long crow = (Hc > 0 && Wc > 0) ? (long long)g.N * Hc * Wc : 0;
+    if (ty * tx > 0) dt += (crow + kTR - 1) / kTR * ((g.Cin + p.tc_d - 1) / p.tc_d);
+    max_taps = std::max(max_taps, ty * tx);
+    if (c < 16) taps_of[c] = ty * tx;
+  }
+  for (int c = 0; c < 16; ++c) p.cls_order[c] = (uint8_t)c;
+  if (ncls <= 16)
+    std::stable_sort(p.cls_order, p.cls_order + ncls, [&](uint8_t x, uint8_t y) { return taps_of[x] > taps_of[y]; });
+  const long long stages_max = (long long)max_taps * (p.Cp / kStage);
+  long long ds = (4LL * cu_count() + std::max(1LL, dt) - 1) / std::max(1LL, dt);
+  ds = std::max(1LL, std::min(std::min(ds, stages_max / 8), 64LL));
   p.dsplits = (int)ds;
   const long long tiles = (long long)((g.K + p.tr_w - 1) / p.tr_w) * ((g.Cout + p.tc_w - 1) / p.tc_w);
   // enough workgroups to fill the machine several times, at least 256 pixels per split
@@ -586,6 +625,7 @@ extern "C" int ax_conv2d_backward(const ax_conv_desc_t* desc, const ax_quant_t* 
   a.x_zp = q->x_zp; a.pad_code = pad_default ? q->x_zp : q->pad_code; a.sgn = g.sgn;
   a.x_scale = q->x_scale; a.w_scale = q->w_scale;
   a.splits = p.splits; a.m_per_split = p.m_per_split; a.dsplits = p.dsplits;
+  for (int c = 0; c < 16; ++c) a.cls_order[c] = p.cls_order[c];
 
   // the pieces of gy: blocks of 64 pixels x 64 channels over the padded extents
   hipLaunchKernelGGL(grad_split_kernel, dim3((unsigned)((p.Mp + 63) / 64), (unsigned)((p.Cp + 63) / 64)), dim3(256), 0, s,
@@ -612,8 +652,7 @@ extern "C" int ax_conv2d_backward(const ax_conv_desc_t* desc, const ax_quant_t* 
     AX_GRAD_LAUNCHED();
     if (p.dsplits > 1) {
       const size_t n = (size_t)g.N * g.H * g.W * g.Cin;
-      hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s,
-                         reinterpret_cast<const float*>(ws + p.off_dpart), p.dsplits, n, q->w_scale, gx_out);
+      launch_sum_slices(reinterpret_cast<const float*>(ws + p.off_dpart), p.dsplits, n, q->w_scale, gx_out, s);
       AX_GRAD_LAUNCHED();
     }
   }
@@ -628,8 +667,7 @@ extern "C" int ax_conv2d_backward(const ax_conv_desc_t* desc, const ax_quant_t* 
       hipLaunchKernelGGL((wgrad_kernel<128, 64, 4>), grid, dim3(256), 0, s, a);
     AX_GRAD_LAUNCHED();
     const size_t n = (size_t)g.K * g.Cout;
-    hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s,
-                       reinterpret_cast<const float*>(ws + p.off_part), p.splits, n, q->x_scale, gw_out);
+    launch_sum_slices(reinterpret_cast<const float*>(ws + p.off_part), p.splits, n, q->x_scale, gw_out, s);
     AX_GRAD_LAUNCHED();
   }
   return AX_OK;
