@@ -54,6 +54,10 @@ struct TabArgs {
   int I;   // valid lane elements
   int ih;  // lane elements per tile (multiple of 64, at most the kernel's tile height)
   int H, W, Cin, KW, sh, sw, ph, pw, OHW, OW;
+  // byte offset of the 16 codes (pixel, channels ci0 .. ci0+15) = pixel * a_ps + ci0 * a_cs:
+  // (Cin, 1) for a tensor read in place; (16, I) for materialized patches, which lie chunk by
+  // chunk ([K16 / 16][I][16]) so that the lanes of a wave read one contiguous kilobyte
+  uint32_t a_ps, a_cs;
   // table-side operand, packed [Krows][Jpad] with zero fill
   const uint8_t* Bp;
   int Jpad, J;
@@ -217,7 +221,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
       const int iy = by[p] + ky * a.dh, ix = bx[p] + kx * a.dw;
       const bool inside = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
       // pixel index below 2^31; times the row length it can pass 2^32 for a materialized operand
-      const size_t off = (size_t)((uint32_t)(nb[p] + iy) * (uint32_t)a.W + (uint32_t)ix) * (uint32_t)a.Cin + (uint32_t)ci0;
+      const size_t off = (size_t)((uint32_t)(nb[p] + iy) * (uint32_t)a.W + (uint32_t)ix) * a.a_ps + (size_t)(uint32_t)ci0 * a.a_cs;
       // Every lane loads: taps outside the image (and lanes of tile padding) read sixteen pad codes
       // kept in device memory.  A load that only some waves issued would leave the number of loads
       // in flight unknown at compile time, and every later wait for table rows would then have to
@@ -779,7 +783,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
   }
 }
 
-// Materialized im2col, Ap[m][Kp] (zero fill for k >= K): used when the implicit view cannot be
+// Materialized im2col, Ap[Kp / 16][m][16] (zero fill for k >= K): used when the implicit view cannot be
 // read in aligned 16-byte pieces (Cin not a multiple of 16, or a misaligned base pointer).
 // Staged form of the same materialization for the usual case (few input channels, e.g. the
 // first layer of a network): a block takes kStripe consecutive output pixels of one output row
@@ -849,33 +853,36 @@ __global__ __launch_bounds__(256) void prep_im2col_lds_kernel(ConvView cv, int K
   __syncthreads();
   const int npix = min(kStripe, cv.OW - ox0);
   const int pix_step = cv.sw * cv.Cin;  // stage bytes between neighbouring output pixels
-  uint32_t* dst = reinterpret_cast<uint32_t*>(Ap + (((size_t)n * cv.OH + oy) * cv.OW + ox0) * Kp);
-  // element idx = pixel * ndw + j, walked in steps of 256 without dividing again
-  int oxl = threadIdx.x / ndw, j = threadIdx.x - oxl * ndw;
-  const int d_ox = 256 / ndw, d_j = 256 - d_ox * ndw;
+  // Ap lies chunk by chunk, [Kp / 16][M][16]: the block's pixels form one run of npix * 16 bytes
+  // per chunk.  Element idx = (chunk c, pixel p, dword jj of the chunk); consecutive threads
+  // write consecutive dwords of a run.
+  const size_t m0 = ((size_t)n * cv.OH + oy) * cv.OW + ox0;
+  uint32_t* dst = reinterpret_cast<uint32_t*>(Ap);
+  const int run = npix * 4;
   for (int idx = threadIdx.x; idx < npix * ndw; idx += 256) {
-    const int4 o = offtab[j];
-    const int base = oxl * pix_step;
+    const int c = idx / run, rem = idx - c * run;
+    const int pl = rem >> 2, jj = rem & 3;
+    const int4 o = offtab[4 * c + jj];
+    const int base = pl * pix_step;
     uint32_t v = 0;
     if (o.x >= 0) v = stage[o.x + base];
     if (o.y >= 0) v |= (uint32_t)stage[o.y + base] << 8;
     if (o.z >= 0) v |= (uint32_t)stage[o.z + base] << 16;
     if (o.w >= 0) v |= (uint32_t)stage[o.w + base] << 24;
-    dst[idx] = v;
-    oxl += d_ox;
-    j += d_j;
-    if (j >= ndw) { j -= ndw; ++oxl; }
+    dst[((size_t)c * (size_t)cv.M + m0 + pl) * 4 + jj] = v;
   }
 }
 
 // One thread per 16-byte piece: the pixel is decoded once and the tap index advanced
-// incrementally; consecutive threads write consecutive pieces.
+// incrementally; consecutive threads take consecutive pixels of one chunk and so write
+// consecutive pieces of the chunk-major Ap.
 __global__ __launch_bounds__(256) void prep_im2col_kernel(ConvView cv, int Kp, uint8_t* __restrict__ Ap) {
   const uint32_t nchunk = (uint32_t)Kp / 16u;
   const uint32_t q = blockIdx.x * 256u + threadIdx.x;
   if (q >= (uint32_t)cv.M * nchunk) return;  // M * Kp/16 < 2^31: see tab_supported
-  const uint32_t m = q / nchunk;
-  const int k0 = (int)(q - m * nchunk) * 16;
+  const uint32_t chunk = q / (uint32_t)cv.M;
+  const uint32_t m = q - chunk * (uint32_t)cv.M;
+  const int k0 = (int)chunk * 16;
   const uint32_t ohw = (uint32_t)(cv.OH * cv.OW);
   const uint32_t n = m / ohw, r = m - n * ohw;
   const int oy = (int)(r / (uint32_t)cv.OW), ox = (int)(r - (r / (uint32_t)cv.OW) * (uint32_t)cv.OW);
@@ -898,7 +905,7 @@ __global__ __launch_bounds__(256) void prep_im2col_kernel(ConvView cv, int Kp, u
       }
     }
   }
-  *reinterpret_cast<uint4*>(Ap + (size_t)m * Kp + k0) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+  *reinterpret_cast<uint4*>(Ap + ((size_t)chunk * (size_t)cv.M + m) * 16) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
 }
 
 // Signed activations read through the implicit patch view: one pass turns the tensor into
@@ -1344,10 +1351,13 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
     a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.KW = g.KW; a.sh = g.sh; a.sw = g.sw; a.ph = g.ph; a.pw = g.pw;
     a.OHW = g.OH * g.OW; a.OW = g.OW;
     a.dh = g.dh; a.dw = g.dw;
-  } else {  // materialized operand: I rows of Kp bytes
+    a.a_ps = (uint32_t)g.Cin; a.a_cs = 1;
+  } else {  // materialized operand: I lane elements of Kp bytes, seen as I pixels of a 1 x 1 image
     a.A = Ap;
     a.H = 1; a.W = 1; a.Cin = Kp; a.KW = 1; a.sh = 1; a.sw = 1; a.ph = 0; a.pw = 0; a.OHW = 1; a.OW = 1;
     a.dh = 1; a.dw = 1;
+    if (ch) { a.a_ps = (uint32_t)Kp; a.a_cs = 1; }        // transposed filters: row by row
+    else    { a.a_ps = 16; a.a_cs = (uint32_t)I; }          // patches: chunk by chunk
   }
   a.Bp = Bp; a.Jpad = Jpad; a.J = J; a.bsum = bsum; a.nseg = cdiv(krows, seg_rows); a.rows = rows;
   a.K = g.K;
