@@ -277,3 +277,80 @@ int ax_oracle_conv2d_ex(const void* x, int N, int H, int W, int Cin, const void*
   }
   return status;
 }
+
+/*
+ * Grouped convolution (Sec. II: every kind of 2-D convolution gets an approximate twin; the
+ * paper does not spell the kinds out.  Reading taken: the grouped form of the common frameworks).
+ * Input and output channels are cut into `groups` contiguous blocks of Cin/groups and Cout/groups
+ * channels; output channel co of block g = co / (Cout/groups) sums over the taps of the input
+ * channels of block g only, so K = KH*KW*Cin/groups in the correction of Eq. (3).
+ *   w [KH, KW, Cin/groups, Cout]  (filter count fastest, as everywhere)
+ * groups = 1 is the ordinary layer; groups = Cin with Cout = Cin*mult is the depthwise layer of
+ * ax_oracle_conv2d_ex (same filter bytes: [KH,KW,Cin,mult] and [KH,KW,1,Cin*mult] coincide).
+ * Written out on its own, not through the other functions.
+ */
+int ax_oracle_conv2d_grouped(const void* x, int N, int H, int W, int Cin, const void* w, int KH, int KW,
+                             int Cout, const void* lut, int stride_h, int stride_w, int pad_h, int pad_w,
+                             int dil_h, int dil_w, int groups, int is_signed, float x_scale, int x_zp,
+                             float w_scale, int w_zp, int pad_code, int32_t* acc_out, float* y_out) {
+  if (!x || !w || !lut || !acc_out || !y_out) return AX_ORACLE_ERR_ARG;
+  if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || KH <= 0 || KW <= 0 || Cout <= 0 || groups <= 0) return AX_ORACLE_ERR_ARG;
+  if (Cin % groups || Cout % groups) return AX_ORACLE_ERR_ARG;
+  if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1) return AX_ORACLE_ERR_ARG;
+  const int lo = is_signed ? -128 : 0, hi = is_signed ? 127 : 255;
+  if (x_zp < lo || x_zp > hi || w_zp < lo || w_zp > hi || pad_code < lo || pad_code > hi) return AX_ORACLE_ERR_ARG;
+  if (!(x_scale > 0.0f) || !(w_scale > 0.0f)) return AX_ORACLE_ERR_ARG;
+  const int eh = H + 2 * pad_h - dil_h * (KH - 1) - 1, ew = W + 2 * pad_w - dil_w * (KW - 1) - 1;
+  if (eh < 0 || ew < 0) return AX_ORACLE_ERR_ARG;
+  const int OH = eh / stride_h + 1, OW = ew / stride_w + 1;
+  const int Cg = Cin / groups;   /* input channels per block  */
+  const int Cog = Cout / groups; /* output channels per block */
+  const uint8_t* xb = (const uint8_t*)x;
+  const uint8_t* wb = (const uint8_t*)w;
+  const uint16_t* lu = (const uint16_t*)lut;
+  int status = 0;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n) {
+    for (int oy = 0; oy < OH; ++oy) {
+      for (int ox = 0; ox < OW; ++ox) {
+        for (int co = 0; co < Cout; ++co) {
+          const int block = co / Cog;
+          int64_t acc = 0, Sp = 0, Sf = 0;
+          for (int ky = 0; ky < KH; ++ky) {
+            for (int kx = 0; kx < KW; ++kx) {
+              const int iy = oy * stride_h - pad_h + ky * dil_h;
+              const int ix = ox * stride_w - pad_w + kx * dil_w;
+              const int inside = (iy >= 0 && iy < H && ix >= 0 && ix < W);
+              for (int cl = 0; cl < Cg; ++cl) {
+                const int ci = block * Cg + cl;
+                /* codes as integers (sign-extended in the signed form), table addressed by their bit patterns */
+                int a = pad_code;
+                if (inside) {
+                  const uint8_t raw = xb[(((size_t)n * H + iy) * W + ix) * Cin + ci];
+                  a = is_signed ? (int)(int8_t)raw : (int)raw;
+                }
+                const uint8_t braw = wb[(((size_t)ky * KW + kx) * Cg + cl) * Cout + co];
+                const int b = is_signed ? (int)(int8_t)braw : (int)braw;
+                const uint16_t e = lu[(a & 0xff) * 256 + (b & 0xff)];
+                acc += is_signed ? (int)(int16_t)e : (int)e;
+                Sp += a;
+                Sf += b;
+              }
+            }
+          }
+          const size_t o = (((size_t)n * OH + oy) * OW + ox) * Cout + co;
+          if (acc > 2147483647LL || acc < -2147483648LL) {
+#pragma omp atomic write
+            status = AX_ORACLE_ERR_OVERFLOW;
+            continue;
+          }
+          const int64_t K = (int64_t)KH * KW * Cg;
+          const int64_t corr = acc - (int64_t)w_zp * Sp - (int64_t)x_zp * Sf + K * x_zp * w_zp;
+          acc_out[o] = (int32_t)acc;
+          y_out[o] = (float)((double)x_scale * (double)w_scale * (double)corr);
+        }
+      }
+    }
+  }
+  return status;
+}

@@ -41,6 +41,9 @@ def lib():
         _lib.ax_oracle_conv2d_ex.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci,
                                              cf, ci, cf, ci, ci, vp, vp]
         _lib.ax_oracle_conv2d_ex.restype = ci
+        _lib.ax_oracle_conv2d_grouped.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci,
+                                             cf, ci, cf, ci, ci, vp, vp]
+        _lib.ax_oracle_conv2d_grouped.restype = ci
         _lib.ax_oracle_conv2d_f32_ex.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci,
                                                  vp, vp, ci, ci, vp, vp, vp, vp, vp]
         _lib.ax_oracle_conv2d_f32_ex.restype = ci
@@ -164,6 +167,39 @@ def conv2d_ex(x, w, lut, stride, pad, q, dilation=1, depthwise=False, signed=Fal
                                    acc.ctypes.data, y.ctypes.data)
     if rc:
         raise RuntimeError("ax_oracle_conv2d_ex failed: %d" % rc)
+    return acc, y
+
+
+def conv2d_grouped(x, w, lut, stride, pad, q, groups, dilation=1, signed=False):
+    """Grouped convolution: w is [KH,KW,Cin/groups,Cout]."""
+    cdt = np.int8 if signed else np.uint8
+    ldt = np.int16 if signed else np.uint16
+    x, w = _chk(x, cdt, 4), _chk(w, cdt, 4)
+    lut = _chk(np.asarray(lut).reshape(-1), ldt, 1)
+    if lut.size != 65536:
+        raise ValueError("table must have 65536 entries")
+    N, H, W, Cin = x.shape
+    KH, KW, Cg, Cout = w.shape
+    if groups < 1 or Cin % groups or Cout % groups or Cg * groups != Cin:
+        raise ValueError("channel counts do not fit the groups")
+    sh, sw = (stride, stride) if np.isscalar(stride) else stride
+    ph, pw = (pad, pad) if np.isscalar(pad) else pad
+    dh, dw = (dilation, dilation) if np.isscalar(dilation) else dilation
+    OH = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+    OW = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+    if OH <= 0 or OW <= 0:
+        raise ValueError("empty output")
+    acc = np.empty((N, OH, OW, Cout), np.int32)
+    y = np.empty((N, OH, OW, Cout), np.float32)
+    pad_code = q.pad_code
+    if pad_code is None or (not signed and pad_code < 0):
+        pad_code = q.x_zp
+    rc = lib().ax_oracle_conv2d_grouped(x.ctypes.data, N, H, W, Cin, w.ctypes.data, KH, KW, Cout, lut.ctypes.data,
+                                        sh, sw, ph, pw, dh, dw, int(groups), int(bool(signed)),
+                                        float(q.x_scale), int(q.x_zp), float(q.w_scale), int(q.w_zp), int(pad_code),
+                                        acc.ctypes.data, y.ctypes.data)
+    if rc:
+        raise RuntimeError("ax_oracle_conv2d_grouped failed: %d" % rc)
     return acc, y
 
 
