@@ -99,7 +99,8 @@ size_t ax_dense_workspace_bytes(int M, int K, int N);
 
 /* ---- operator variants (Sec. III, Algorithm 1: the layer's dilation parameter next to the
  * strides; Sec. II: signed multipliers with codes in [-128, 127] next to unsigned ones, and an
- * approximate twin for each kind of 2-D convolution, of which the depthwise one is built) ----- */
+ * approximate twin for each kind of 2-D convolution, of which the depthwise and the grouped ones
+ * are built) ----- */
 
 /* pad_code value that selects the activation zero point in both the unsigned and the signed
  * form (-1 selects it too, but only for unsigned codes, where -1 is no code). */
@@ -118,6 +119,12 @@ typedef struct {
   int32_t signed_codes; /* 0: x, w uint8, lut uint16.  1: x, w int8, lut int16 with entry index
                            (uint8_t)x_code * 256 + (uint8_t)w_code (the two's-complement patterns
                            stitched together); zero points and pad_code in [-128, 127]         */
+  int32_t groups;       /* 0 or 1: ordinary.  n >= 2 (depthwise must be 0): grouped convolution,
+                           Cin and Cout multiples of n; input and output channels are cut into n
+                           contiguous blocks and output block g sums over the taps of input block
+                           g only: filters [KH, KW, Cin/n, Cout], K = KH*KW*Cin/n in the
+                           correction.  Grouped layers run on the one-thread-per-output kernel
+                           (functional, not tuned); the backward pass does not take them.       */
 } ax_conv_desc_t;
 
 /*

@@ -65,7 +65,7 @@ class ax_tune_t(ctypes.Structure):
 class ax_conv_desc_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "N", "H", "W", "Cin", "KH", "KW", "Cout", "stride_h", "stride_w", "pad_h", "pad_w", "dilation_h", "dilation_w",
-        "depthwise", "signed_codes")]
+        "depthwise", "signed_codes", "groups")]
 
 
 def lib():
@@ -257,14 +257,15 @@ def _workspace(need: int, device, stream) -> torch.Tensor:
     return ws
 
 
-def _conv_desc(x_shape, w_shape, stride, pad, dilation=1, depthwise=False, signed=False) -> ax_conv_desc_t:
+def _conv_desc(x_shape, w_shape, stride, pad, dilation=1, depthwise=False, signed=False, groups=1) -> ax_conv_desc_t:
     N, H, W, Cin = [int(v) for v in x_shape]
     KH, KW, _, last = [int(v) for v in w_shape]
     Cout = Cin * last if depthwise else last
     sh, sw = _pair(stride)
     ph, pw = _pair(pad)
     dh, dw = _pair(dilation)
-    return ax_conv_desc_t(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, dh, dw, int(bool(depthwise)), int(bool(signed)))
+    return ax_conv_desc_t(N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, dh, dw, int(bool(depthwise)), int(bool(signed)),
+                          int(groups))
 
 
 def _dense_desc(M: int, K: int, N: int) -> ax_conv_desc_t:
@@ -401,18 +402,19 @@ def ax_conv2d_multi_lut(x, w, luts, stride, pad, q, acc_out=None, y_out=None, wo
 
 
 def ax_conv2d_ex(x, w, lut, stride, pad, q, dilation=1, depthwise=False, acc_out=None, y_out=None, workspace=None,
-                 stream=None):
+                 stream=None, groups=1):
     """Operator variants.  Signed form: x, w int8 and lut int16 (chosen by x.dtype).  Depthwise:
-    w is [KH,KW,Cin,mult].  q.pad_code None selects the zero point.  Returns (acc_out, y_out)."""
+    w is [KH,KW,Cin,mult].  Grouped: w is [KH,KW,Cin/groups,Cout].  q.pad_code None selects the
+    zero point.  Returns (acc_out, y_out)."""
     L = lib()
     signed = x.dtype == torch.int8
     cdt = torch.int8 if signed else torch.uint8
     _dev(x, cdt, "x")
     _dev(w, cdt, "w")
     _check_lut(lut)
-    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
-        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout] (or [KH,KW,Cin,mult])")
-    desc = _conv_desc(x.shape, w.shape, stride, pad, dilation, depthwise, signed)
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] * int(groups) != x.shape[3]:
+        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin/groups,Cout] (or [KH,KW,Cin,mult])")
+    desc = _conv_desc(x.shape, w.shape, stride, pad, dilation, depthwise, signed, groups)
     OH, OW = _out_hw(desc)
     if OH <= 0 or OW <= 0:
         _check(-2)
@@ -707,13 +709,13 @@ def ax_conv2d_f32(x, w, lut, stride, pad, x_range=None, w_range=None, relu=False
 
 
 def ax_conv2d_f32_ex(x, w, lut, stride, pad, x_range=None, w_range=None, relu=False, round_mode=0, dilation=1,
-                     depthwise=False, signed=False, acc_out=None, y_out=None, workspace=None, stream=None):
-    """Float layer with dilation / signed codes / depthwise filters (w [KH,KW,Cin,mult]).
-    Returns (acc_out, y_out); pass False to skip one of them."""
+                     depthwise=False, signed=False, acc_out=None, y_out=None, workspace=None, stream=None, groups=1):
+    """Float layer with dilation / signed codes / depthwise filters (w [KH,KW,Cin,mult]) / grouped
+    filters (w [KH,KW,Cin/groups,Cout]).  Returns (acc_out, y_out); pass False to skip one of them."""
     _f32_common(x, w, lut, x_range, w_range)
-    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
-        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout] (or [KH,KW,Cin,mult])")
-    desc = _conv_desc(x.shape, w.shape, stride, pad, dilation, depthwise, signed)
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] * int(groups) != x.shape[3]:
+        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin/groups,Cout] (or [KH,KW,Cin,mult])")
+    desc = _conv_desc(x.shape, w.shape, stride, pad, dilation, depthwise, signed, groups)
     OH, OW = _out_hw(desc)
     if OH <= 0 or OW <= 0:
         _check(-2)

@@ -41,7 +41,7 @@ int make_options(const ax_tune_t* t, Options* o) {
 }
 
 int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw, Geom* g,
-              int dh, int dw, int sgn, int depthwise) {
+              int dh, int dw, int sgn, int depthwise, int groups) {
   if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || KH <= 0 || KW <= 0 || Cout <= 0) return AX_ERR_SHAPE;
   if (sh < 1 || sw < 1 || ph < 0 || pw < 0 || dh < 1 || dw < 1) return AX_ERR_SHAPE;
   if (ph > (1 << 20) || pw > (1 << 20) || dh > (1 << 20) || dw > (1 << 20)) return AX_ERR_SHAPE;
@@ -50,25 +50,30 @@ int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, in
   if (eh < 0 || ew < 0) return AX_ERR_SHAPE;
   const long long OH = eh / sh + 1, OW = ew / sw + 1;
   int mult = 0;
+  if (groups < 1) return AX_ERR_SHAPE;
   if (depthwise) {
-    if (Cout % Cin) return AX_ERR_SHAPE;
+    if (Cout % Cin || groups != 1) return AX_ERR_SHAPE;
     mult = Cout / Cin;
+    groups = Cin;  // the depthwise layer is the grouped one with a block per input channel
+  } else if (Cin % groups || Cout % groups) {
+    return AX_ERR_SHAPE;
   }
-  const long long K = (long long)KH * KW * (depthwise ? 1 : Cin);
+  const long long K = (long long)KH * KW * (Cin / groups);
   if (K > 32768) return AX_ERR_K_OVERFLOW;
   const long long lim = 0x7fffffffLL;
   const long long M = (long long)N * OH * OW;
-  const long long wsize = (long long)KH * KW * Cin * (depthwise ? mult : Cout);
+  const long long wsize = K * Cout;
   if ((long long)N * H * W * Cin > lim || wsize > lim || M > lim || M * Cout > lim) return AX_ERR_SHAPE;
-  *g = Geom{N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, (int)OH, (int)OW, (int)M, (int)K, dh, dw, sgn ? 1 : 0, mult, 1};
+  *g = Geom{N, H, W, Cin, KH, KW, Cout, sh, sw, ph, pw, (int)OH, (int)OW, (int)M, (int)K, dh, dw, sgn ? 1 : 0, mult, 1, groups};
   return AX_OK;
 }
 
 int geom_of_desc(const ax_conv_desc_t* d, Geom* g) {
   if (!d) return AX_ERR_NULL;
   if ((d->depthwise != 0 && d->depthwise != 1) || (d->signed_codes != 0 && d->signed_codes != 1)) return AX_ERR_OPTION;
+  if (d->groups < 0 || (d->depthwise && d->groups > 1)) return AX_ERR_OPTION;
   return make_geom(d->N, d->H, d->W, d->Cin, d->KH, d->KW, d->Cout, d->stride_h, d->stride_w, d->pad_h, d->pad_w, g,
-                   d->dilation_h, d->dilation_w, d->signed_codes, d->depthwise);
+                   d->dilation_h, d->dilation_w, d->signed_codes, d->depthwise, d->groups > 1 ? d->groups : 1);
 }
 
 // 1 = direct (or depthwise) kernels, 0 = table-tile kernels with the planner's lane assignment,
@@ -351,4 +356,4 @@ extern "C" const char* ax_strerror(int code) {
   }
 }
 
-extern "C" int ax_version(void) { return 300; }
+extern "C" int ax_version(void) { return 310; }

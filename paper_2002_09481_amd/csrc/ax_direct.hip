@@ -33,12 +33,14 @@ __global__ __launch_bounds__(256) void direct_kernel(Geom g, QParams qp_in, cons
   const int oy = m % (uint32_t)g.OH;
   const int n = m / (uint32_t)g.OH;
 
-  // Depthwise (g.mult >= 1): output channel co sums over the taps of input channel co / mult
-  // only; filters are [KH, KW, Cin, mult].  Otherwise all Cin channels, filters [KH, KW, Cin, Cout].
-  const int c_first = g.mult ? co / g.mult : 0;
-  const int c_count = g.mult ? 1 : g.Cin;
-  const int wcols = g.mult ? g.mult : g.Cout;   // innermost extent of the filter tensor
-  const int wcol = g.mult ? co % g.mult : co;
+  // Channel blocks: output channel co of block co / (Cout / groups) sums over the taps of that
+  // block's Cin / groups input channels; filters are [KH, KW, Cin / groups, Cout].  One block is
+  // the ordinary layer; the depthwise layer is the case of one input channel per block (its
+  // filters [KH, KW, Cin, mult] are the same bytes).
+  const int c_count = g.Cin / g.groups;
+  const int c_first = (co / (g.Cout / g.groups)) * c_count;
+  const int wcols = g.Cout;  // innermost extent of the filter tensor
+  const int wcol = co;
   // Signed codes are sign-extended bytes; the table is addressed by their 8-bit patterns and
   // its entries are sign-extended too.
   int32_t acc = 0, sp = 0, sf = 0;
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(256) void direct_kernel(Geom g, QParams qp_in, cons
       const int ix = ox * g.sw - g.pw + kx * g.dw;
       const bool inside = (iy >= 0) && (iy < g.H) && (ix >= 0) && (ix < g.W);
       const uint8_t* xp = x + (((size_t)n * g.H + (inside ? iy : 0)) * g.W + (inside ? ix : 0)) * g.Cin + c_first;
-      const uint8_t* wp = w + ((size_t)(ky * g.KW + kx) * g.Cin + c_first) * wcols + wcol;
+      const uint8_t* wp = w + (size_t)(ky * g.KW + kx) * c_count * wcols + wcol;
       for (int ci = 0; ci < c_count; ++ci) {
         const uint32_t ap = inside ? (uint32_t)xp[ci] : ((uint32_t)qp.pad_code & 0xffu);
         const uint32_t bp = wp[(size_t)ci * wcols];

@@ -583,7 +583,7 @@ using namespace ax;
 
 extern "C" size_t ax_conv2d_backward_workspace_bytes(const ax_conv_desc_t* desc) {
   Geom g;
-  if (geom_of_desc(desc, &g) || g.mult) return 0;
+  if (geom_of_desc(desc, &g) || g.mult || g.groups > 1) return 0;
   return std::max<size_t>(256, grad_plan(g).ws_bytes);
 }
 
@@ -598,7 +598,7 @@ extern "C" int ax_conv2d_backward(const ax_conv_desc_t* desc, const ax_quant_t* 
   Geom g;
   int rc = geom_of_desc(desc, &g);
   if (rc) return rc;
-  if (g.mult) return AX_ERR_OPTION;  // depthwise layers: backward not built
+  if (g.mult || g.groups > 1) return AX_ERR_OPTION;  // depthwise and grouped layers: backward not built
   if (!q || !x || !w || !gy || (!gx_out && !gw_out)) return AX_ERR_NULL;
   if (((uintptr_t)gy & 3) || ((uintptr_t)gx_out & 3) || ((uintptr_t)gw_out & 3)) return AX_ERR_ALIGN;
   const int lo = g.sgn ? -128 : 0, hi = g.sgn ? 127 : 255;

@@ -22,6 +22,8 @@ struct Geom {
   int sgn;     // 1: codes are int8, table entries int16, addressed by the two's-complement patterns
   int mult;    // 0: ordinary convolution; >= 1: depthwise with this channel multiplier (Cout = Cin*mult)
   int T;       // multiplier tables evaluated by the call (1 except for ax_conv2d_multi_lut)
+  int groups;  // channel blocks: 1 ordinary, Cin for a depthwise layer, else a grouped convolution with
+               // filters [KH, KW, Cin/groups, Cout] (for depthwise the same bytes as [KH, KW, Cin, mult])
 };
 
 // Quantization coefficients kept in device memory (written by the quantization kernels of the
@@ -69,7 +71,7 @@ int run_layer(const Geom& g, const QParams& qp, const Options& o, const uint8_t*
               const uint16_t* lut, int32_t* acc_out, float* y_out, void* ws, size_t ws_bytes, hipStream_t s);
 size_t layer_workspace(const Geom& g, const Options& o);
 int make_geom(int N, int H, int W, int Cin, int KH, int KW, int Cout, int sh, int sw, int ph, int pw, Geom* g,
-              int dh = 1, int dw = 1, int sgn = 0, int depthwise = 0);
+              int dh = 1, int dw = 1, int sgn = 0, int depthwise = 0, int groups = 1);
 int geom_of_desc(const ax_conv_desc_t* d, Geom* g);
 
 // Direct kernel (ax_direct.hip): needs no workspace.

@@ -970,7 +970,8 @@ bool reads_in_place(const Geom& g, const void* x) { return g.Cin % 16 == 0 && ((
 
 // The preparation kernels index their pieces with 32-bit integers.
 bool tab_supported(const Geom& g) {
-  if (g.mult) return false;  // depthwise: every output channel has its own lane-side operand
+  if (g.mult || g.groups > 1) return false;  // depthwise: every output channel has its own lane-side operand;
+                                              // grouped: the channel blocks would each need strided views
   const long long chunks = cdiv(g.K, kChunk);
   // tile indices over all tables and the fix-up grid are 32-bit: tiles hold at least 64 x 16 outputs
   if ((double)g.M * g.Cout * g.T >= 5.0e10) return false;
