@@ -354,3 +354,80 @@ int ax_oracle_conv2d_grouped(const void* x, int N, int H, int W, int Cin, const 
   }
   return status;
 }
+
+/*
+ * Transposed convolution (Sec. II: every kind of 2-D convolution gets an approximate twin; the
+ * paper does not define this one).  Reading taken: the layer as an accelerator with a fixed MAC
+ * array would run it, by zero insertion.  The input is spread out by the strides, every inserted
+ * position holding the code of the real value zero (the activation zero point x_zp), and every
+ * output sums the table entries of ALL its KH*KW*Cin taps: taps that land on an input pixel feed
+ * its code through the multiplier, taps that land on an inserted position feed x_zp, taps outside
+ * the spread-out image feed pad_code, exactly as padded taps of the ordinary layer do.  With the
+ * exact multiplier and the default pad code this is the transposed convolution of the common
+ * frameworks on the dequantized tensors (the adjoint of the ordinary layer).
+ *
+ *   x [N, H, W, Cin], w [KH, KW, Cin, Cout] (filter count fastest)
+ *   OH = (H - 1) * stride_h + 1 + dil_h * (KH - 1) - 2 * pad_h, OW likewise
+ *   tap (ky, kx) of output (oy, ox) looks at position (oy + pad_h - ky * dil_h, ox + pad_w - kx * dil_w)
+ *   of the spread-out image, whose pixel (iy * stride_h, ix * stride_w) is input pixel (iy, ix)
+ *   K = KH * KW * Cin in the correction of Eq. (3)
+ */
+int ax_oracle_conv2d_transpose(const void* x, int N, int H, int W, int Cin, const void* w, int KH, int KW,
+                               int Cout, const void* lut, int stride_h, int stride_w, int pad_h, int pad_w,
+                               int dil_h, int dil_w, int is_signed, float x_scale, int x_zp, float w_scale,
+                               int w_zp, int pad_code, int32_t* acc_out, float* y_out) {
+  if (!x || !w || !lut || !acc_out || !y_out) return AX_ORACLE_ERR_ARG;
+  if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || KH <= 0 || KW <= 0 || Cout <= 0) return AX_ORACLE_ERR_ARG;
+  if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1) return AX_ORACLE_ERR_ARG;
+  const int lo = is_signed ? -128 : 0, hi = is_signed ? 127 : 255;
+  if (x_zp < lo || x_zp > hi || w_zp < lo || w_zp > hi || pad_code < lo || pad_code > hi) return AX_ORACLE_ERR_ARG;
+  if (!(x_scale > 0.0f) || !(w_scale > 0.0f)) return AX_ORACLE_ERR_ARG;
+  const int Hs = (H - 1) * stride_h + 1, Ws = (W - 1) * stride_w + 1; /* the spread-out image */
+  const int OH = Hs + dil_h * (KH - 1) - 2 * pad_h, OW = Ws + dil_w * (KW - 1) - 2 * pad_w;
+  if (OH <= 0 || OW <= 0) return AX_ORACLE_ERR_ARG;
+  const uint8_t* xb = (const uint8_t*)x;
+  const uint8_t* wb = (const uint8_t*)w;
+  const uint16_t* lu = (const uint16_t*)lut;
+  int status = 0;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n) {
+    for (int oy = 0; oy < OH; ++oy) {
+      for (int ox = 0; ox < OW; ++ox) {
+        for (int co = 0; co < Cout; ++co) {
+          int64_t acc = 0, Sp = 0, Sf = 0;
+          for (int ky = 0; ky < KH; ++ky) {
+            for (int kx = 0; kx < KW; ++kx) {
+              const int ty = oy + pad_h - ky * dil_h, tx = ox + pad_w - kx * dil_w;
+              const int in_spread = (ty >= 0 && ty < Hs && tx >= 0 && tx < Ws);
+              const int on_pixel = in_spread && (ty % stride_h == 0) && (tx % stride_w == 0);
+              for (int ci = 0; ci < Cin; ++ci) {
+                int a = in_spread ? x_zp : pad_code;
+                if (on_pixel) {
+                  const uint8_t raw = xb[(((size_t)n * H + ty / stride_h) * W + tx / stride_w) * Cin + ci];
+                  a = is_signed ? (int)(int8_t)raw : (int)raw;
+                }
+                const uint8_t braw = wb[(((size_t)ky * KW + kx) * Cin + ci) * Cout + co];
+                const int b = is_signed ? (int)(int8_t)braw : (int)braw;
+                const uint16_t e = lu[(a & 0xff) * 256 + (b & 0xff)];
+                acc += is_signed ? (int)(int16_t)e : (int)e;
+                Sp += a;
+                Sf += b;
+              }
+            }
+          }
+          const size_t o = (((size_t)n * OH + oy) * OW + ox) * Cout + co;
+          if (acc > 2147483647LL || acc < -2147483648LL) {
+#pragma omp atomic write
+            status = AX_ORACLE_ERR_OVERFLOW;
+            continue;
+          }
+          const int64_t K = (int64_t)KH * KW * Cin;
+          const int64_t corr = acc - (int64_t)w_zp * Sp - (int64_t)x_zp * Sf + K * x_zp * w_zp;
+          acc_out[o] = (int32_t)acc;
+          y_out[o] = (float)((double)x_scale * (double)w_scale * (double)corr);
+        }
+      }
+    }
+  }
+  return status;
+}

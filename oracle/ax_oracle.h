@@ -54,6 +54,12 @@ int ax_oracle_conv2d_grouped(const void* x, int N, int H, int W, int Cin, const 
                              int dil_h, int dil_w, int groups, int is_signed, float x_scale, int x_zp,
                              float w_scale, int w_zp, int pad_code, int32_t* acc_out, float* y_out);
 
+/* Transposed convolution by zero insertion: inserted positions hold x_zp, every tap contributes. */
+int ax_oracle_conv2d_transpose(const void* x, int N, int H, int W, int Cin, const void* w, int KH, int KW,
+                               int Cout, const void* lut, int stride_h, int stride_w, int pad_h, int pad_w,
+                               int dil_h, int dil_w, int is_signed, float x_scale, int x_zp, float w_scale,
+                               int w_zp, int pad_code, int32_t* acc_out, float* y_out);
+
 /* ---- float-in / float-out layer (ax_oracle_quant.c) ------------------------------------ */
 
 /* range_out[0] = min, range_out[1] = max over x[0..n) (after max(.,0) when relu != 0). */

@@ -44,6 +44,9 @@ def lib():
         _lib.ax_oracle_conv2d_grouped.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci,
                                              cf, ci, cf, ci, ci, vp, vp]
         _lib.ax_oracle_conv2d_grouped.restype = ci
+        _lib.ax_oracle_conv2d_transpose.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci,
+                                                    cf, ci, cf, ci, ci, vp, vp]
+        _lib.ax_oracle_conv2d_transpose.restype = ci
         _lib.ax_oracle_conv2d_f32_ex.argtypes = [vp, ci, ci, ci, ci, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci,
                                                  vp, vp, ci, ci, vp, vp, vp, vp, vp]
         _lib.ax_oracle_conv2d_f32_ex.restype = ci
@@ -200,6 +203,38 @@ def conv2d_grouped(x, w, lut, stride, pad, q, groups, dilation=1, signed=False):
                                         acc.ctypes.data, y.ctypes.data)
     if rc:
         raise RuntimeError("ax_oracle_conv2d_grouped failed: %d" % rc)
+    return acc, y
+
+
+def conv2d_transpose(x, w, lut, stride, pad, q, dilation=1, signed=False):
+    """Transposed convolution by zero insertion: w is [KH,KW,Cin,Cout]."""
+    cdt = np.int8 if signed else np.uint8
+    ldt = np.int16 if signed else np.uint16
+    x, w = _chk(x, cdt, 4), _chk(w, cdt, 4)
+    lut = _chk(np.asarray(lut).reshape(-1), ldt, 1)
+    if lut.size != 65536:
+        raise ValueError("table must have 65536 entries")
+    N, H, W, Cin = x.shape
+    KH, KW, Cin2, Cout = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    sh, sw = (stride, stride) if np.isscalar(stride) else stride
+    ph, pw = (pad, pad) if np.isscalar(pad) else pad
+    dh, dw = (dilation, dilation) if np.isscalar(dilation) else dilation
+    OH = (H - 1) * sh + 1 + dh * (KH - 1) - 2 * ph
+    OW = (W - 1) * sw + 1 + dw * (KW - 1) - 2 * pw
+    if OH <= 0 or OW <= 0:
+        raise ValueError("empty output")
+    acc = np.empty((N, OH, OW, Cout), np.int32)
+    y = np.empty((N, OH, OW, Cout), np.float32)
+    pad_code = q.pad_code
+    if pad_code is None or (not signed and pad_code < 0):
+        pad_code = q.x_zp
+    rc = lib().ax_oracle_conv2d_transpose(x.ctypes.data, N, H, W, Cin, w.ctypes.data, KH, KW, Cout, lut.ctypes.data,
+                                          sh, sw, ph, pw, dh, dw, int(bool(signed)), float(q.x_scale), int(q.x_zp),
+                                          float(q.w_scale), int(q.w_zp), int(pad_code), acc.ctypes.data, y.ctypes.data)
+    if rc:
+        raise RuntimeError("ax_oracle_conv2d_transpose failed: %d" % rc)
     return acc, y
 
 
