@@ -100,7 +100,7 @@ size_t ax_dense_workspace_bytes(int M, int K, int N);
 /* ---- operator variants (Sec. III, Algorithm 1: the layer's dilation parameter next to the
  * strides; Sec. II: signed multipliers with codes in [-128, 127] next to unsigned ones, and an
  * approximate twin for each kind of 2-D convolution, of which the depthwise and the grouped ones
- * are built) ----- */
+ * are built here and the transposed one further down) ----- */
 
 /* pad_code value that selects the activation zero point in both the unsigned and the signed
  * form (-1 selects it too, but only for unsigned codes, where -1 is no code). */
@@ -155,6 +155,33 @@ int ax_conv2d_ex(const ax_conv_desc_t* desc, const ax_tune_t* tune, const void* 
                  const void* lut, const ax_quant_t* q, int32_t* acc_out, float* y_out,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 size_t ax_conv2d_ex_workspace_bytes(const ax_conv_desc_t* desc, const ax_tune_t* tune);
+
+/*
+ * Transposed convolution (Sec. II: an approximate twin for every kind of 2-D convolution; the
+ * paper does not define this one).  Reading taken: zero insertion, as an accelerator with a fixed
+ * MAC array runs it.  The input is spread out by the strides, every inserted position holding the
+ * activation zero point (the code of the real value zero), and every output sums the table
+ * entries of all its KH*KW*Cin taps: taps on an input pixel feed its code, taps on an inserted
+ * position feed x_zp, taps outside the spread-out image feed pad_code.  With the exact
+ * multiplier and the default pad code this is the transposed convolution of the common
+ * frameworks on the dequantized tensors (the adjoint of ax_conv2d_ex with the same descriptor).
+ *
+ *   desc      N, H, W, Cin describe the INPUT, Cout the output channels, filters [KH, KW, Cin, Cout];
+ *             depthwise must be 0 and groups 0 or 1 (AX_ERR_OPTION otherwise)
+ *   acc_out / y_out  [N, OH, OW, Cout], OH = (H-1)*stride_h + 1 + dilation_h*(KH-1) - 2*pad_h
+ *             (pad_h <= dilation_h*(KH-1), AX_ERR_SHAPE otherwise), OW likewise
+ *   tap (ky, kx) of output (oy, ox) looks at position (oy + pad_h - ky*dilation_h,
+ *             ox + pad_w - kx*dilation_w) of the spread-out image, whose pixel
+ *             (iy*stride_h, ix*stride_w) is input pixel (iy, ix); K = KH*KW*Cin in the correction
+ *
+ * The workspace also holds the spread-out image and the flipped filters; the layer itself then
+ * runs as an ordinary stride-1 layer (table-tile kernels included).  Other rules as for
+ * ax_conv2d_ex.  Layer handles, the float form and the backward pass do not take this kind.
+ */
+int ax_conv2d_transpose(const ax_conv_desc_t* desc, const ax_tune_t* tune, const void* x, const void* w,
+                        const void* lut, const ax_quant_t* q, int32_t* acc_out, float* y_out,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t ax_conv2d_transpose_workspace_bytes(const ax_conv_desc_t* desc, const ax_tune_t* tune);
 
 /*
  * One layer against several multiplier tables in one call: the use the paper builds the

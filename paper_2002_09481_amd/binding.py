@@ -43,7 +43,7 @@ class ax_quant_t(ctypes.Structure):
 
 EXPORTS = [  # include/axconv.h
     "ax_conv2d", "ax_conv2d_workspace_bytes", "ax_dense", "ax_dense_workspace_bytes", "ax_strerror",
-    "ax_version", "ax_range_f32", "ax_range_workspace_bytes", "ax_quantize_f32", "ax_conv2d_f32",
+    "ax_conv2d_transpose", "ax_conv2d_transpose_workspace_bytes", "ax_version", "ax_range_f32", "ax_range_workspace_bytes", "ax_quantize_f32", "ax_conv2d_f32",
     "ax_conv2d_f32_workspace_bytes", "ax_dense_f32", "ax_dense_f32_workspace_bytes", "ax_conv2d_ex",
     "ax_conv2d_ex_workspace_bytes", "ax_conv2d_multi_lut", "ax_conv2d_multi_lut_workspace_bytes", "ax_conv2d_f32_ex",
     "ax_conv2d_f32_ex_workspace_bytes", "ax_layer_create", "ax_layer_destroy", "ax_layer_prepared_bytes",
@@ -138,6 +138,9 @@ def lib():
     L.ax_conv2d_ex.restype = ci
     L.ax_conv2d_ex_workspace_bytes.argtypes = [descp, tp]
     L.ax_conv2d_ex_workspace_bytes.restype = sz
+    L.ax_conv2d_transpose.argtypes = [descp, tp, vp, vp, vp, ctypes.POINTER(ax_quant_t), vp, vp, vp, sz, vp]
+    L.ax_conv2d_transpose_workspace_bytes.argtypes = [descp, tp]
+    L.ax_conv2d_transpose_workspace_bytes.restype = sz
     L.ax_range_f32.argtypes = [vp, sz, ci, vp, vp, sz, vp]
     L.ax_range_f32.restype = ci
     L.ax_range_workspace_bytes.argtypes = [sz]
@@ -427,6 +430,39 @@ def ax_conv2d_ex(x, w, lut, stride, pad, q, dilation=1, depthwise=False, acc_out
     rc = L.ax_conv2d_ex(ctypes.byref(desc), t, _ptr(x), _ptr(w), _ptr(lut), ctypes.byref(qs),
                         _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
                         _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
+    _check(rc)
+    return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
+
+
+def ax_conv2d_transpose(x, w, lut, stride, pad, q, dilation=1, acc_out=None, y_out=None, workspace=None, stream=None):
+    """Transposed convolution by zero insertion.  x: codes [N,H,W,Cin] (uint8, or int8 for the
+    signed form), w: [KH,KW,Cin,Cout].  Returns (acc_out, y_out) of shape [N,OH,OW,Cout] with
+    OH = (H-1)*stride + 1 + dilation*(KH-1) - 2*pad."""
+    L = lib()
+    signed = x.dtype == torch.int8
+    cdt = torch.int8 if signed else torch.uint8
+    _dev(x, cdt, "x")
+    _dev(w, cdt, "w")
+    _check_lut(lut)
+    if x.dim() != 4 or w.dim() != 4 or w.shape[2] != x.shape[3]:
+        raise ValueError("x must be [N,H,W,Cin] and w [KH,KW,Cin,Cout]")
+    desc = _conv_desc(x.shape, w.shape, stride, pad, dilation, False, signed)
+    OH = (desc.H - 1) * desc.stride_h + 1 + desc.dilation_h * (desc.KH - 1) - 2 * desc.pad_h
+    OW = (desc.W - 1) * desc.stride_w + 1 + desc.dilation_w * (desc.KW - 1) - 2 * desc.pad_w
+    if OH <= 0 or OW <= 0:
+        _check(-2)
+    acc_out, y_out = _outs((desc.N, OH, OW, desc.Cout), x.device, acc_out, y_out)
+    t = _tune_arg()
+    if workspace is None:
+        n = int(L.ax_conv2d_transpose_workspace_bytes(ctypes.byref(desc), t))
+        if n == 0:
+            _check(-2)
+        workspace = _workspace(n, x.device, stream)
+    _dev(workspace, torch.uint8, "workspace")
+    qs = _quant(q)
+    rc = L.ax_conv2d_transpose(ctypes.byref(desc), t, _ptr(x), _ptr(w), _ptr(lut), ctypes.byref(qs),
+                               _ptr(None if acc_out is False else acc_out), _ptr(None if y_out is False else y_out),
+                               _ptr(workspace), workspace.numel(), ctypes.c_void_p(_stream_ptr(stream)))
     _check(rc)
     return (None if acc_out is False else acc_out), (None if y_out is False else y_out)
 

@@ -11,7 +11,7 @@ namespace ax {
 
 // Unsigned codes: zero points and pad code in [0, 255], pad_code -1 (or AX_PAD_DEFAULT) = x_zp.
 // Signed codes: all three in [-128, 127], pad_code AX_PAD_DEFAULT = x_zp.
-static int make_quant(const ax_quant_t* q, QParams* qp, int sgn = 0) {
+int make_quant_params(const ax_quant_t* q, QParams* qp, int sgn) {
   if (!q) return AX_ERR_NULL;
   const int lo = sgn ? -128 : 0, hi = sgn ? 127 : 255;
   if (q->x_zp < lo || q->x_zp > hi || q->w_zp < lo || q->w_zp > hi) return AX_ERR_QUANT;
@@ -126,7 +126,7 @@ static int run(const Geom& g, const ax_quant_t* q, const ax_tune_t* tune, const 
   int rc = check_io(x, w, lut, acc_out, y_out);
   if (rc) return rc;
   QParams qp;
-  rc = make_quant(q, &qp, g.sgn);
+  rc = make_quant_params(q, &qp, g.sgn);
   if (rc) return rc;
   Options o;
   rc = make_options(tune, &o);
@@ -235,7 +235,7 @@ extern "C" int ax_layer_create(const ax_conv_desc_t* desc, int num_luts, const a
   if (num_luts < 1 || num_luts > 65536) return AX_ERR_SHAPE;
   g.T = num_luts;
   QParams qp;
-  rc = make_quant(q, &qp, g.sgn);
+  rc = make_quant_params(q, &qp, g.sgn);
   if (rc) return rc;
   Options o;
   rc = make_options(tune, &o);

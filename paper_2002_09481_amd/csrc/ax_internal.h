@@ -54,6 +54,8 @@ struct Options {
 };
 // AX_OK, or AX_ERR_OPTION for a value out of range.  tune == nullptr gives the automatic choice.
 int make_options(const ax_tune_t* tune, Options* o);
+// Checks the host-side quantization parameters (AX_ERR_NULL / AX_ERR_QUANT) and resolves the default pad code.
+int make_quant_params(const ax_quant_t* q, QParams* qp, int sgn);
 
 // Parts of a table-tile layer call (bit mask).  A one-shot call runs all of them; a layer handle
 // runs kPhConst once (ax_layer_prepare) and the others per call (ax_layer_run).
