@@ -112,3 +112,43 @@ def test_random_float_layers(seed):
                                round_mode=mode, dilation=d, signed=signed)
     G.assert_parity(acc.cpu().numpy(), y.cpu().numpy(), ref["acc"], ref["y"], "seed %d" % seed)
     np.testing.assert_array_equal(y.cpu().numpy(), ref["y"])
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_grouped_and_transposed_layers(seed):
+    """Random geometries through the grouped form of ax_conv2d_ex and through ax_conv2d_transpose
+    (with random tuning for the inner stride-1 layer of the latter)."""
+    rng = np.random.default_rng(9000 + seed)
+    signed = bool(rng.integers(0, 2))
+    lo, hi, dt = (-128, 128, np.int8) if signed else (0, 256, np.uint8)
+    lut = I.lut_signed_random(seed) if signed else I.lut_random(seed)
+    q = I.Quant(0.013, int(rng.integers(lo, hi)), 0.0071, int(rng.integers(lo, hi)),
+                None if rng.integers(0, 2) else int(rng.integers(lo, hi)))
+    if seed % 2 == 0:
+        n, H, W, _, kh, kw, _, s, p, d = _geometry(rng)
+        groups = int(rng.choice([2, 3, 4, 8]))
+        cin, cout = groups * int(rng.integers(1, 9)), groups * int(rng.integers(1, 7))
+        x = rng.integers(lo, hi, (n, H, W, cin)).astype(dt)
+        w = rng.integers(lo, hi, (kh, kw, cin // groups, cout)).astype(dt)
+        acc, y = ax.ax_conv2d_ex(G.to_dev(x), G.to_dev(w), ax.lut_to_device(lut), s, p, q, dilation=d, groups=groups)
+        torch.cuda.synchronize()
+        acc_ref, y_ref = oracle.conv2d_grouped(x, w, lut, s, p, q, groups=groups, dilation=d, signed=signed)
+    else:
+        kh, kw = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        d = (int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+        s = (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+        p = (int(rng.integers(0, d[0] * (kh - 1) + 1)), int(rng.integers(0, d[1] * (kw - 1) + 1)))
+        n, H, W = int(rng.integers(1, 4)), int(rng.integers(1, 12)), int(rng.integers(1, 12))
+        cin = int(rng.choice([1, 3, 16, 20, 32, 64]))
+        cout = int(rng.choice([1, 4, 8, 24, 40]))
+        x = rng.integers(lo, hi, (n, H, W, cin)).astype(dt)
+        w = rng.integers(lo, hi, (kh, kw, cin, cout)).astype(dt)
+        if (H - 1) * s[0] + 1 + d[0] * (kh - 1) - 2 * p[0] <= 0 or (W - 1) * s[1] + 1 + d[1] * (kw - 1) - 2 * p[1] <= 0:
+            pytest.skip("empty output")
+        ax.ax_set_option("variant", int(rng.choice([0, 0, 2, 3, 1])))
+        ax.ax_set_option("tile", int(rng.integers(0, 8)))
+        ax.ax_set_option("split_k", int(rng.choice([0, 0, 2, 3])))
+        acc, y = ax.ax_conv2d_transpose(G.to_dev(x), G.to_dev(w), ax.lut_to_device(lut), s, p, q, dilation=d)
+        torch.cuda.synchronize()
+        acc_ref, y_ref = oracle.conv2d_transpose(x, w, lut, s, p, q, dilation=d, signed=signed)
+    G.assert_parity(acc.cpu().numpy(), y.cpu().numpy(), acc_ref, y_ref, "seed %d" % seed)
