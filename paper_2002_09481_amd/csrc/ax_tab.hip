@@ -197,6 +197,14 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   // slot il = p*THREADS + tid of the tile is lane element i0 + il; slots at or beyond a.ih (or
   // beyond the operand) are padding.  act[p]: some lane of this wave's slot p is real.
   int by[P], bx[P], nb[P];
+  auto set_prio = [](int v) {  // the instruction takes a constant; v is one after unrolling
+    switch (v < 0 ? 0 : v > 3 ? 3 : v) {
+      case 0: __builtin_amdgcn_s_setprio(0); break;
+      case 1: __builtin_amdgcn_s_setprio(1); break;
+      case 2: __builtin_amdgcn_s_setprio(2); break;
+      default: __builtin_amdgcn_s_setprio(3); break;
+    }
+  };
   bool act[P];
 #pragma unroll
   for (int p = 0; p < P; ++p) {
@@ -326,6 +334,9 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     return *reinterpret_cast<const uint2*>(a.Bp + (size_t)min(kfirst + l_ph * KS + l_s, klast) * a.Jpad + l_col);
   };
   uint2 tvv = fetch_codes(kbeg + KS);
+  // rows of unit 0 for the tables that the first phase of the loop builds
+  build_issue(0, make_uint2((uint32_t)__builtin_amdgcn_readlane((int)tvv.x, 0),
+                            (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, 0)));
 
   for (int c = 0; c < nchunks; ++c) {
     const int k0 = kbeg + c * kChunk;
@@ -362,8 +373,9 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
       for (int q = 0; q < SEGS; ++q) {
         const int p = q / SUB;
         const int s0 = (q % SUB) * TAPS;
+        // (the rows of unit 0 were requested at the end of the phase before, see below)
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u)
+        for (int u = 1; u < UNITS; ++u)
           if (q == u * (SEGS / UNITS)) build_issue(u, tv_cur[u >> 1][ph]);
         if (ph == 0 && q == 0) {
           // operand and codes of the next chunk: fetched behind the first row fetches of this
@@ -375,6 +387,12 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
           tvv = fetch_codes(k0 + kChunk + KS);
         }
         __builtin_amdgcn_sched_barrier(0);
+        // Waves that are behind go first: the priority of a wave falls as it works through the
+        // phase (3 for the first three eighths of its gathers, then 2, 1 and, for the last
+        // eighth, 0), so that the waves of a SIMD reach the barrier together instead of one after
+        // the other.  With the default order the oldest wave finishes the phase early and the
+        // youngest runs its last segment alone, with nobody to cover its LDS latency.
+        set_prio(2 * (SEGS - 1 - q) + 2);
         if (act[p]) {
           uint4 ring[DEPTH + 1];
           // Address of a gather = table base + group * 4096 + 16 * code.  The constant part goes
@@ -399,6 +417,8 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
 #pragma unroll
           for (int i = 0; i < NR; ++i) {
             __builtin_amdgcn_sched_barrier(0);
+            if (i == NR / 4) set_prio(2 * (SEGS - 1 - q) + 1);
+            if (i == (3 * NR) / 4) set_prio(2 * (SEGS - 1 - q));
             if (i + DEPTH < NR) issue(i + DEPTH);
             const int g = i % NG;
             const uint4 e = ring[i % (DEPTH + 1)];
@@ -410,6 +430,17 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
         for (int u = 0; u < UNITS; ++u)
           if (q == (u + 1) * (SEGS / UNITS) - 1) build_commit(u, (ph + 1) & 1);
       }
+      // Rows of unit 0 for the tables that the NEXT phase builds: requested here, before the
+      // barrier, so that after it every wave starts with gathers.  (Requested at the start of a
+      // phase, the row fetches of all sixteen waves queue up in the vector memory pipe while the
+      // vector ALUs have nothing to do.)  Past the last phase of a chunk the codes are those of
+      // the next chunk's first phase, which tvv has held since the start of this chunk; past the
+      // last chunk they are clamped to the operand and the rows are never used.
+      if (ph + 1 < PHASES)
+        build_issue(0, tv_cur[0][ph + 1]);
+      else
+        build_issue(0, make_uint2((uint32_t)__builtin_amdgcn_readlane((int)tvv.x, 0),
+                                  (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, 0)));
       __syncthreads();
     }
   }
