@@ -237,6 +237,24 @@ def main():
 
     alg_bytes = sum(l.algorithmic_bytes for l in layers)
     kern_rate = total_macs / (main_ms * 1e-3)  # lookup-MACs per second inside the dominant kernel
+    # Vector-instruction issue.  In the K loop of the compiled kernel a wave executes, per 16-tap
+    # chunk, 1200 vector instructions for 1024 lookups per lane (32-column tile; 614 of them in
+    # 64-bit encodings: v_sad_u16, v_perm_b32 ...) or 652 for 512 lookups (16-column tile; 326 in
+    # 64-bit encodings).  Issue rates measured on this machine with every SIMD full (4 waves each):
+    # 60.9 T lane-instructions/s for a 32-bit encoded add, 32.5 T/s for the 64-bit encoded forms.
+    # valu_issue.frac = time those rates need for the K loops of all layers / measured kernel time.
+    r32, r64 = 60.9e12, 32.5e12
+    per_lookup = {3: (586 / 1024.0, 614 / 1024.0), 5: (326 / 512.0, 326 / 512.0)}
+    need_s = 0.0
+    for l, h, xd, wd, q, acc, y, ws in calls:
+        n32, n64 = per_lookup.get(h.plan()["tile"], per_lookup[5])
+        need_s += l.macs * (n32 / r32 + n64 / r64)
+    valu_issue = {"frac": need_s / (main_ms * 1e-3),
+                  "lane_instructions_per_lookup": {"tile_3": sum(per_lookup[3]), "tile_5": sum(per_lookup[5])},
+                  "measured_issue_T_per_s": {"32_bit_encoded": r32 / 1e12, "64_bit_encoded": r64 / 1e12},
+                  "note": "time the K loops of all main kernels need at the vector issue rates measured on this "
+                          "machine, over the measured kernel time; the rest is barrier rendezvous, table building "
+                          "waits, prologues and epilogues"}
     # HBM-side traffic of the dominant kernel comes from two rocprofv3 counter runs (FETCH_SIZE,
     # WRITE_SIZE) and cannot be read inside this process; the committed figure is only reported
     # while it belongs to the kernel sources that are running (it records their hash).
@@ -277,6 +295,7 @@ def main():
         # 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz (the 157.3 TFLOP/s fp32 vector figure is
         # two flops on each of these lanes); one integer add per lookup-MAC is the algorithmic minimum
         "alu": {"achieved": kern_rate / 1e12, "peak": 78.64, "unit": "Tint32-add/s", "frac": kern_rate / 78.64e12},
+        "valu_issue": valu_issue,
         "hbm": {"achieved": alg_bytes / (main_ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
                 "frac": alg_bytes / (main_ms * 1e-3) / 8e12, "measured_copy_GBps": copy_gbs,
                 "algorithmic_bytes_per_launch": alg_bytes / n_launch},

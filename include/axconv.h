@@ -142,10 +142,13 @@ typedef struct {
  *                what the layer allows; at most 2^20)
  *   share_order  1 = workgroups take their shares of the work in launch order, 2 = XCD by XCD
  *                (every XCD, with its own L2, gets a contiguous run of tiles)
+ *   combine      output tiles whose sum over the taps is shared by several workgroups:
+ *                1 = a second kernel adds the pieces, 2 = the workgroup that finishes a tile's
+ *                last piece adds the others inside the main kernel
  * A value out of range gives AX_ERR_OPTION.
  */
 typedef struct {
-  int32_t variant, split_k, tile, row_tiles, share_order;
+  int32_t variant, split_k, tile, row_tiles, share_order, combine;
 } ax_tune_t;
 
 /* ax_conv2d generalized by the descriptor; outputs, workspace rules and errors as for ax_conv2d
@@ -218,8 +221,10 @@ size_t ax_conv2d_multi_lut_workspace_bytes(int N, int H, int W, int Cin, int KH,
  *   workspace  ax_layer_workspace_bytes() bytes of per-call scratch, as for ax_conv2d.
  * w and luts given to ax_layer_prepare must stay valid and unchanged while the handle is used:
  * layers that take the direct or the depthwise kernel read them in every call.
- * A handle may be used from one host thread at a time; runs of one handle on different streams
- * need separate workspaces.
+ * A handle may be used from one host thread at a time.  Runs that use the same prepared block
+ * must not overlap in time on the device (one stream, or streams ordered by events): where
+ * several workgroups share an output tile the main kernel keeps the tile's arrival counter in
+ * the prepared block, at zero between runs.
  */
 typedef struct ax_layer ax_layer_t;
 

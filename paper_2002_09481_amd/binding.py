@@ -59,7 +59,7 @@ AX_PAD_DEFAULT = -(1 << 31)
 
 
 class ax_tune_t(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("variant", "split_k", "tile", "row_tiles", "share_order")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("variant", "split_k", "tile", "row_tiles", "share_order", "combine")]
 
 
 class ax_conv_desc_t(ctypes.Structure):
@@ -177,16 +177,16 @@ def ax_version() -> int:
     return int(lib().ax_version())
 
 
-_TUNE_FIELDS = ("variant", "split_k", "tile", "row_tiles", "share_order")
+_TUNE_FIELDS = ("variant", "split_k", "tile", "row_tiles", "share_order", "combine")
 _tune = {n: 0 for n in _TUNE_FIELDS}  # this module's default ax_tune_t (all zero = automatic)
 
 
 def _tune_arg(tune=None):
     """ctypes argument for a `const ax_tune_t*` parameter: NULL when everything is automatic."""
     t = _tune if tune is None else tune
-    if not any(t[n] for n in _TUNE_FIELDS):
+    if not any(t.get(n, 0) for n in _TUNE_FIELDS):
         return None
-    return ctypes.byref(ax_tune_t(*[int(t[n]) for n in _TUNE_FIELDS]))
+    return ctypes.byref(ax_tune_t(*[int(t.get(n, 0)) for n in _TUNE_FIELDS]))
 
 
 def ax_set_option(name: str, value: int) -> None:

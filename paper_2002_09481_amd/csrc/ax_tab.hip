@@ -77,6 +77,7 @@ struct TabArgs {
   int32_t* part;  // [2*G][JT][ih] partial tiles: slot 2w = workgroup w's piece of a tile begun by
                   // another workgroup, slot 2w+1 = its piece of a tile it begins but does not end
   int32_t* lsum;  // [2*G][ih] lane-operand sums of the same pieces
+  uint32_t* cnt;  // non-null: [tiles] arrival counters, pieces are combined inside tab_kernel (see there)
   long long out_elems;   // outputs per table (M * Cout)
   int ntiles1;           // tiles of one table; tile index space = table * ntiles1 + tile (several tables: ax_conv2d_multi_lut)
   int vec_out;  // outputs may be written in aligned 16-byte pieces along j
@@ -177,6 +178,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   long long it_beg = (long long)wg * a.total_iters / gridDim.x;
   const long long it_end = (long long)(wg + 1) * a.total_iters / gridDim.x;
   __shared__ long long cterm[JT];  // column constants of the current tile, see the epilogue
+  __shared__ int comb[3];          // last piece of a shared tile? / first and last share of the tile
 
   while (it_beg < it_end) {
   const int gtile = (int)(it_beg / a.nch);
@@ -461,7 +463,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   // 2^31 in magnitude; for K <= 16384 so is every partial sum, and 32-bit wrap-around
   // arithmetic is exact.  Longer K takes the 64-bit form.
   const uint32_t padfix = (uint32_t)(klast - a.K) * (uint32_t)rows[0] + a.bias_k;
-  const bool finish = whole;  // this workgroup writes the tile's outputs
+  bool finish = whole;  // this workgroup writes the tile's outputs
   if (!whole) {
     // Piece of a tile that several workgroups share: stored column-major ([column][lane
     // element]) so that consecutive lanes write consecutive words straight from their registers.
@@ -473,9 +475,71 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     for (int p = 0; p < P; ++p) {
       const int il = p * THREADS + tid;
       if (!act[p] || il >= a.ih) continue;  // rows of tile padding: the fix-up never reads them
-      lsum[il] = (int32_t)sl[p];
+      if (a.cnt) {  // read by another workgroup of this launch: stores that go through to memory
+        __hip_atomic_store(lsum + il, (int32_t)sl[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-      for (int j = 0; j < JT; ++j) part[(size_t)j * a.ih + il] = (int32_t)acc[p][j];
+        for (int j = 0; j < JT; ++j)
+          __hip_atomic_store(part + (size_t)j * a.ih + il, (int32_t)acc[p][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {
+        lsum[il] = (int32_t)sl[p];
+#pragma unroll
+        for (int j = 0; j < JT; ++j) part[(size_t)j * a.ih + il] = (int32_t)acc[p][j];
+      }
+    }
+    if (a.cnt) {
+      // Combination inside this kernel: every workgroup that has stored a piece counts itself in
+      // at the tile's counter, and the one that arrives last adds the other pieces to its
+      // registers and writes the outputs like the owner of a whole tile.  Nobody waits for
+      // anybody.  The counter wraps to 0 with the last arrival, ready for the next launch.
+      // Pieces travel between workgroups on different XCDs, each with an L2 of its own, so they
+      // are stored and loaded with device-scope atomic accesses, which pass through the L2s to
+      // memory; a device-scope fence would instead write back and invalidate whole L2s (measured:
+      // 60 % more kernel time).  A piece store is complete once the wave's store counter has run
+      // out, which is awaited before the barrier that precedes the count.
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      if (tid == 0) {
+        const long long G = gridDim.x, t_beg = (long long)gtile * a.nch;
+        auto owner = [&](long long it) {  // the share w with w*total/G <= it < (w+1)*total/G
+          long long w = it * G / a.total_iters;
+          while ((w + 1) * a.total_iters / G <= it) ++w;
+          while (w * a.total_iters / G > it) --w;
+          return (int)w;
+        };
+        const int w_first = owner(t_beg), w_last = owner(t_beg + a.nch - 1);
+        const unsigned old = atomicInc(a.cnt + gtile, (unsigned)(w_last - w_first));
+        comb[0] = (old == (unsigned)(w_last - w_first)) ? 1 : 0;
+        comb[1] = w_first;
+        comb[2] = w_last;
+      }
+      __syncthreads();
+      if (comb[0]) {
+        const int w_first = comb[1], w_last = comb[2];
+        for (int w = w_first; w <= w_last; ++w) {
+          if (w == wg) continue;
+          const int so = 2 * w + (w == w_first ? 1 : 0);
+          const int32_t* po = a.part + (size_t)so * ((size_t)a.ih * JT);
+          const int32_t* lo = a.lsum + (size_t)so * a.ih;
+#pragma unroll
+          for (int p = 0; p < P; ++p) {
+            const int il = p * THREADS + tid;
+            if (!act[p] || il >= a.ih) continue;
+            sl[p] += (uint32_t)__hip_atomic_load(lo + il, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            constexpr int NB = JT < 32 ? JT : 32;  // loads in flight
+#pragma unroll
+            for (int jb = 0; jb < JT; jb += NB) {
+              uint32_t t[NB];
+#pragma unroll
+              for (int j = 0; j < NB; ++j)
+                t[j] = (uint32_t)__hip_atomic_load(po + (size_t)(jb + j) * a.ih + il, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+              for (int j = 0; j < NB; ++j) acc[p][jb + j] += t[j];
+            }
+          }
+        }
+        finish = true;
+      }
     }
   }
   if (finish && tid < JT) {
@@ -735,7 +799,11 @@ __global__ __launch_bounds__(256) void prep_kernel(const uint16_t* __restrict__ 
                                                     const uint8_t* __restrict__ w, ConvView cv, int K, int J, int krows,
                                                     int Jpad, int seg_rows, uint8_t* __restrict__ Bp,
                                                     int32_t* __restrict__ psum, QParams qp, QDev* __restrict__ qd,
-                                                    int tables, int do_rows, int do_qd) {
+                                                    int tables, int do_rows, int do_qd, uint32_t* __restrict__ cnt,
+                                                    int ncnt) {
+  // arrival counters of tiles that workgroups share (tab_kernel): zero before the first launch
+  if (do_qd && blockIdx.x == 0)
+    for (int i = threadIdx.x; i < ncnt; i += 256) cnt[i] = 0u;
   if (do_qd && blockIdx.x == 0 && threadIdx.x == 0) {
     int xz = qp.x_zp, wz = qp.w_zp, pad = qp.pad_code;
     float sc = qp.scale;
@@ -1022,20 +1090,30 @@ int cu_count() {
   return n;
 }
 
-// Number of partial tile pieces that a grid of G workgroups produces (see tab_kernel).
-static int count_partials(int ntiles, int nch, int G) {
+// Number of partial tile pieces that a grid of G workgroups produces (see tab_kernel); the
+// largest number of pieces that one tile is cut into, and the number of tiles cut into pieces.
+static int count_partials(int ntiles, int nch, int G, int* most_per_tile = nullptr, int* shared_tiles = nullptr) {
   const long long total = (long long)ntiles * nch;
-  int n = 0;
+  int n = 0, most = 0, run = 0, shared = 0;
+  long long run_tile = -1;
   for (int w = 0; w < G; ++w) {
     long long b = (long long)w * total / G;
     const long long e = (long long)(w + 1) * total / G;
     while (b < e) {
       const long long t = b / nch;
       const long long c0 = b - t * nch, c1 = std::min<long long>(nch, c0 + (e - b));
-      if (!(c0 == 0 && c1 == nch)) ++n;
+      if (!(c0 == 0 && c1 == nch)) {
+        ++n;
+        if (t != run_tile) ++shared;
+        run = (t == run_tile) ? run + 1 : 1;
+        run_tile = t;
+        most = std::max(most, run);
+      }
       b += c1 - c0;
     }
   }
+  if (most_per_tile) *most_per_tile = most;
+  if (shared_tiles) *shared_tiles = shared;
   return n;
 }
 
@@ -1047,7 +1125,15 @@ static int count_partials(int ntiles, int nch, int G) {
 //   - grids larger than the machine run in rounds.
 //   - the lane dimension may be cut into more (lower) tiles than it needs, when that makes the
 //     tile count fill whole rounds of the machine.
-struct PlanChoice { int tile, variant, G, partials, nti, ih; double cost; };
+struct PlanChoice { int tile, variant, G, partials, nti, ih; double cost; int most, shared; };
+// Tiles cut into few pieces are combined inside tab_kernel by the workgroup that finishes last:
+// up to three pieces per tile, or four unless every workgroup holds just one short piece (under
+// kCombineLong chunks) and all of them therefore end at the same moment (measured on the ResNet-50
+// layers: 3-9 us per layer less than with the second launch; that last case loses 10 us, since
+// the one workgroup reads the others' pieces one after another at the very end of the launch).  More pieces per tile (short, wide layers cut into many K slices) go
+// through tab_fixup_kernel, which spreads the sums of one tile over many blocks.
+constexpr int kCombineMost = 4;
+constexpr int kCombineLong = 24;
 
 static PlanChoice plan_choice_nti(const Geom& g, int tile, int v, int forced_split, int nti);
 
@@ -1095,30 +1181,30 @@ static PlanChoice plan_choice_nti(const Geom& g, int tile, int v, int forced_spl
   const double rate = (tc.NG >= 4 ? 80e9 : 75e9) / per_cu;  // wider tiles spend less on gather addresses
   const double t_chunk = 16.0 * (0.3 * kIT + 0.7 * ih) * kJT / rate;
   const double t_piece = 2.0 * kIT * kJT * 4.0 / 6.0e12;
-  auto cost = [&](int Gc, int* np_out) {
+  auto cost = [&](int Gc, int* np_out, int* most_out, int* shared_out) {
     const double rounds = std::ceil((double)Gc / slots);
     const double iters = std::ceil((double)total / Gc);
     const double segs = std::ceil(iters / nch) + (Gc == ntiles ? 0.0 : 1.0);
-    const int np = count_partials(ntiles, nch, Gc);
+    const int np = count_partials(ntiles, nch, Gc, most_out, shared_out);
     *np_out = np;
     return rounds * (iters * t_chunk + segs * 5e-6) + np * t_piece + (np ? 8e-6 : 0.0);
   };
-  PlanChoice best{tile, v, ntiles, 0, nti, ih, 0.0};
+  PlanChoice best{tile, v, ntiles, 0, nti, ih, 0.0, 0, 0};
   if (forced_split > 0) {
     best.G = (int)std::max<long long>(1, std::min<long long>(std::min<long long>(total, 4LL * slots), (long long)ntiles * forced_split));
-    best.cost = cost(best.G, &best.partials);
+    best.cost = cost(best.G, &best.partials, &best.most, &best.shared);
     return best;
   }
-  best.cost = cost(ntiles, &best.partials);
+  best.cost = cost(ntiles, &best.partials, &best.most, &best.shared);
   std::vector<int> cand;
   if (total >= 2) cand.push_back((int)std::min<long long>(slots, total / 2));
   for (int sdiv = 2; sdiv <= 16; ++sdiv)
     if ((long long)ntiles * sdiv <= slots && nch / sdiv >= 2) cand.push_back(ntiles * sdiv);
   for (int Gc : cand) {
     if (Gc < 1) continue;
-    int np = 0;
-    const double c = cost(Gc, &np);
-    if (c < best.cost * 0.97) { best.cost = c; best.G = Gc; best.partials = np; }
+    int np = 0, most = 0, shared = 0;
+    const double c = cost(Gc, &np, &most, &shared);
+    if (c < best.cost * 0.97) { best.cost = c; best.G = Gc; best.partials = np; best.most = most; best.shared = shared; }
   }
   return best;
 }
@@ -1164,13 +1250,13 @@ static double xcd_fetch_bytes(int xcd, int G, int nti, int ntj, int nch, int T, 
 // (geometry, options); the table is small and cleared when it grows past a bound.
 TabPlan tab_plan(const Geom& g, const Options& o) {
   struct Key {
-    int v[22];
+    int v[23];
     bool operator<(const Key& other) const { return std::memcmp(v, other.v, sizeof(v)) < 0; }
   };
   static std::mutex mu;
   static std::map<Key, TabPlan> cache;
   const Key k{{g.N, g.H, g.W, g.Cin, g.KH, g.KW, g.Cout, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.sgn, g.mult, o.variant,
-               o.split_k, o.tile, o.row_tiles, cu_count(), g.T, o.share_order}};
+               o.split_k, o.tile, o.row_tiles, cu_count(), g.T, o.share_order, o.combine}};
   std::lock_guard<std::mutex> lock(mu);
   auto it = cache.find(k);
   if (it != cache.end()) return it->second;
@@ -1189,7 +1275,7 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
     v = (fill(g.Cout) > fill(g.M) + 0.30) ? 3 : 2;
   }
   // Tile and grid: the forced tile, else the cheaper of the two 2048-lane tiles by the cost model.
-  PlanChoice best{0, 0, 0, 0, 0, 0, 1e30};
+  PlanChoice best{0, 0, 0, 0, 0, 0, 1e30, 0, 0};
   for (int tile = 0; tile < kNumTiles; ++tile) {
     if (o.tile >= 1 ? tile != o.tile - 1 : (tile != 2 && tile != 4)) continue;
     const PlanChoice c = plan_choice(g, tile, v, o.split_k, o.row_tiles);
@@ -1199,6 +1285,7 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   p.tile = best.tile;
   p.G = best.G;
   p.partials = best.partials;
+  p.combine = (best.partials > 0 && (o.combine ? o.combine == 2 : (best.most < kCombineMost || (best.most == kCombineMost && (best.partials > best.G || cdiv(g.K, kChunk) >= kCombineMost * kCombineLong))))) ? 1 : 0;
   p.nti = best.nti;
   p.ih = best.ih;
   const TileCfg& tc = kTiles[best.tile];
@@ -1232,6 +1319,8 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   size_t prep = 0, ws = 0;
   p.off_rows = prep;  prep += up256((size_t)131072 * g.T);
   p.off_qd = prep;    prep += 256;
+  p.off_cnt = prep;
+  if (p.combine) prep += up256((size_t)p.nti * cdiv(J, kJT) * g.T * 4);
   if (v == 2) {
     p.off_bpack = prep;  prep += bpack;
     p.off_bsum = prep;   prep += bsum;
@@ -1276,7 +1365,7 @@ static hipError_t launch_cfg(const TabArgs& a, int G, int ntiles, int phases, in
       hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, WPE, CH, false>), dim3(G), dim3(THREADS), 0, s, a);
     AX_LAUNCHED();
   }
-  if (!(phases & kPhFixup)) return hipSuccess;
+  if (!(phases & kPhFixup) || a.cnt) return hipSuccess;
   if (G >= 16 * ntiles)
     hipLaunchKernelGGL((tab_fixup_kernel<THREADS * P, NG * 8, CH, true>), dim3(ntiles * (THREADS * P / 64)), dim3(256), 0, s, a, G);
   else
@@ -1333,6 +1422,8 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   const int row_blocks = kRowBlocks * g.T, pack_blocks = nseg * (Jpad / 64);
   const bool implicit_view = !ch && reads_in_place(g, x);
   uint32_t* rows32 = reinterpret_cast<uint32_t*>(rows);
+  uint32_t* cnt = reinterpret_cast<uint32_t*>(pb + p.off_cnt);
+  const int ncnt = p.combine ? ntiles : 0;
 
   if (ch) {
     // one launch when both parts are wanted; otherwise rows + coefficients (+ the transposed
@@ -1340,7 +1431,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
     const bool c = phases & kPhConst, k = phases & kPhCall;
     if (c || k) {
       hipLaunchKernelGGL((prep_kernel<true>), dim3((c ? row_blocks : 0) + (k ? pack_blocks : 0)), dim3(256), 0, s, lut,
-                         rows32, w, cv, g.K, J, krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T, c ? 1 : 0, c ? 1 : 0);
+                         rows32, w, cv, g.K, J, krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T, c ? 1 : 0, c ? 1 : 0, cnt, ncnt);
       AX_LAUNCHED();
     }
     if (c) {
@@ -1351,7 +1442,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   } else {
     if (phases & kPhConst) {
       hipLaunchKernelGGL((prep_kernel<false>), dim3(row_blocks + pack_blocks), dim3(256), 0, s, lut, rows32, w, cv, g.K,
-                         J, krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T, 1, 1);
+                         J, krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T, 1, 1, cnt, ncnt);
       AX_LAUNCHED();
     }
     if ((phases & kPhCall) && implicit_view && g.sgn) {  // N*H*W*Cin is a multiple of 16 here
@@ -1403,6 +1494,7 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.acc_out = acc_out; a.y_out = y_out;
   a.part = reinterpret_cast<int32_t*>(sb + p.off_part);
   a.lsum = reinterpret_cast<int32_t*>(sb + p.off_lsum);
+  a.cnt = p.combine ? reinterpret_cast<uint32_t*>(pb + p.off_cnt) : nullptr;
   a.out_elems = (long long)g.M * g.Cout;
   a.xcd = p.xcd;
   a.vec_out = (!ch && J % 4 == 0 && (((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;

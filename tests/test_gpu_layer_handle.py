@@ -36,7 +36,8 @@ LAYERS = [
     L(3, 28, 28, 64, 3, 3, 64, 1, 1),
 ]
 TUNES = [_tune(), _tune(variant=2, split_k=3), _tune(variant=3), _tune(variant=3, split_k=2, share_order=1),
-         _tune(variant=2, tile=3, row_tiles=2), _tune(variant=1)]
+         _tune(variant=2, tile=3, row_tiles=2), _tune(variant=1), _tune(variant=2, split_k=5, combine=1),
+         _tune(variant=2, split_k=5, combine=2), _tune(variant=3, split_k=9, combine=2)]
 
 
 @pytest.mark.parametrize("li", range(len(LAYERS)))

@@ -24,6 +24,7 @@ def _reset_options():
     ax.ax_set_option("tile", 0)
     ax.ax_set_option("row_tiles", 0)
     ax.ax_set_option("share_order", 0)
+    ax.ax_set_option("combine", 0)
 
 
 def L(N, H, W, Cin, KH, KW, Cout, s=1, p=0, dense=False, x_dist="uniform", w_dist="uniform", name=None):
@@ -111,6 +112,24 @@ def test_share_numberings(variant, order, split_k):
     G.check_layer(L(1, 20, 20, 48, 1, 1, 30, 2, 0), 52, lut)           # a single tile
     G.check_layer(L(37, 1, 1, 600, 1, 1, 333, dense=True), 53, lut)
     G.check_layer(L(2, 33, 33, 16, 5, 5, 24, 2, 2, x_dist="relu", w_dist="normal"), 54, I.lut_truncated(6))
+
+
+@pytest.mark.parametrize("variant", [2, 3])
+@pytest.mark.parametrize("combine", [1, 2])
+@pytest.mark.parametrize("split_k", [0, 2, 3, 7, 16])
+def test_shared_tiles_combined_by_either_kernel(variant, combine, split_k):
+    """Tiles whose sum over the taps is shared by several workgroups: pieces added by the second
+    kernel or by the workgroup that finishes a tile last, from two to sixteen pieces per tile;
+    twice in a row, since the arrival counters must be back at zero after a call."""
+    ax.ax_set_option("variant", variant)
+    ax.ax_set_option("combine", combine)
+    ax.ax_set_option("split_k", split_k)
+    lut = I.lut_random(33)
+    for rep in range(2):
+        G.check_layer(L(3, 40, 41, 32, 3, 3, 72, 1, 1), 61 + rep, lut)
+        G.check_layer(L(1, 7, 7, 512, 3, 3, 512, 1, 1), 63 + rep, lut)      # few pixels: K slices by default
+        G.check_layer(L(37, 1, 1, 600, 1, 1, 333, dense=True), 65 + rep, lut)
+        G.check_layer(L(2, 33, 33, 16, 5, 5, 24, 2, 2, x_dist="relu", w_dist="normal"), 67 + rep, I.lut_truncated(6))
 
 
 TILES = list(range(1, 8))
