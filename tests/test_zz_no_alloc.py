@@ -83,3 +83,50 @@ def test_static_scratch_limit_and_state_errors():
             h.run_static(x, acc, False)
         assert e.value.code == -5
     torch.cuda.synchronize()
+
+
+def test_static_entry_under_graph_capture_replays_like_eager_calls():
+    """What the allocation-free entry point is for: three layers (materialized patches with a
+    fix-up pass, shared tiles combined inside the main kernel, activations read in place) recorded
+    once into a HIP graph and replayed on new activations.  Every replay is compared with eager
+    calls on the same activations, with eager work of the library between the replays."""
+    cases = [(CASES[0][0], CASES[0][2]), (_layer(8, 7, 7, 512, 3, 3, 512, 1, 1), _tune(variant=2, split_k=2, combine=2)),
+             (CASES[3][0], CASES[3][2])]
+    lut_d = ax.lut_to_device(I.lut_random_error(97))
+    hs = []
+    for i, (layer, tune) in enumerate(cases):
+        x, w, q = I.make_operands(layer, 9100 + i)
+        h = ax.AxLayer(ax._conv_desc(x.shape, w.shape, layer.stride, layer.pad), q, tune=tune)
+        h.prepare(G.to_dev(w), lut_d)
+        xd = G.to_dev(x)
+        acc = torch.empty(h.out_shape(), dtype=torch.int32, device="cuda")
+        y = torch.empty(h.out_shape(), dtype=torch.float32, device="cuda")
+        hs.append((layer, h, xd, acc, y))
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):  # once eagerly on the capture stream, as torch asks
+            for layer, h, xd, acc, y in hs:
+                h.run_static(xd, acc, y)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for layer, h, xd, acc, y in hs:
+                h.run_static(xd, acc, y)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for i, (layer, h, xd, acc, y) in enumerate(hs):  # new activations in the recorded buffers
+                xd.copy_(G.to_dev(I.make_operands(layer, 9200 + 10 * rep + i)[0]))
+                acc.fill_(-1)
+                y.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            for i, (layer, h, xd, acc, y) in enumerate(hs):
+                acc_e, y_e = h.run(xd)  # eager, caller workspace
+                torch.cuda.synchronize()
+                assert torch.equal(acc, acc_e), "replay %d layer %d: accumulators differ" % (rep, i)
+                assert torch.equal(y, y_e), "replay %d layer %d: float outputs differ" % (rep, i)
+    finally:
+        for _, h, _, _, _ in hs:
+            h.close()
+    torch.cuda.synchronize()
