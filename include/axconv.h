@@ -145,10 +145,14 @@ typedef struct {
  *   combine      output tiles whose sum over the taps is shared by several workgroups:
  *                1 = a second kernel adds the pieces, 2 = the workgroup that finishes a tile's
  *                last piece adds the others inside the main kernel
+ *   tables       the per-tap lookup tables of the table-tile kernel (variant 2, one multiplier
+ *                table): 1 = assembled inside the kernel from the rows of the multiplier table,
+ *                2 = ready-made in the prepared block (4 KiB per tap and eight output channels;
+ *                taken where the tile configuration has a kernel for it, else ignored)
  * A value out of range gives AX_ERR_OPTION.
  */
 typedef struct {
-  int32_t variant, split_k, tile, row_tiles, share_order, combine;
+  int32_t variant, split_k, tile, row_tiles, share_order, combine, tables;
 } ax_tune_t;
 
 /* ax_conv2d generalized by the descriptor; outputs, workspace rules and errors as for ax_conv2d

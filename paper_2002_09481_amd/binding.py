@@ -59,7 +59,7 @@ AX_PAD_DEFAULT = -(1 << 31)
 
 
 class ax_tune_t(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("variant", "split_k", "tile", "row_tiles", "share_order", "combine")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("variant", "split_k", "tile", "row_tiles", "share_order", "combine", "tables")]
 
 
 class ax_conv_desc_t(ctypes.Structure):
@@ -177,7 +177,7 @@ def ax_version() -> int:
     return int(lib().ax_version())
 
 
-_TUNE_FIELDS = ("variant", "split_k", "tile", "row_tiles", "share_order", "combine")
+_TUNE_FIELDS = ("variant", "split_k", "tile", "row_tiles", "share_order", "combine", "tables")
 _tune = {n: 0 for n in _TUNE_FIELDS}  # this module's default ax_tune_t (all zero = automatic)
 
 

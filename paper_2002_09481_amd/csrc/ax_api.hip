@@ -29,7 +29,7 @@ int make_quant_params(const ax_quant_t* q, QParams* qp, int sgn) {
 }
 
 int make_options(const ax_tune_t* t, Options* o) {
-  *o = Options{0, 0, 0, 0, 0, 0};
+  *o = Options{0, 0, 0, 0, 0, 0, 0};
   if (!t) return AX_OK;
   if (t->variant < 0 || t->variant > 3) return AX_ERR_OPTION;
   if (t->split_k < 0 || t->split_k > 64) return AX_ERR_OPTION;
@@ -37,7 +37,8 @@ int make_options(const ax_tune_t* t, Options* o) {
   if (t->row_tiles < 0 || t->row_tiles > (1 << 20)) return AX_ERR_OPTION;
   if (t->share_order < 0 || t->share_order > 2) return AX_ERR_OPTION;
   if (t->combine < 0 || t->combine > 2) return AX_ERR_OPTION;
-  *o = Options{t->variant, t->split_k, t->tile, t->row_tiles, t->share_order, t->combine};
+  if (t->tables < 0 || t->tables > 2) return AX_ERR_OPTION;
+  *o = Options{t->variant, t->split_k, t->tile, t->row_tiles, t->share_order, t->combine, t->tables};
   return AX_OK;
 }
 

@@ -52,6 +52,7 @@ struct Options {
   int row_tiles;    // 0 auto, 1 as few tiles along the lane dimension as fit, n that many (clamped)
   int share_order;  // numbering of the work shares: 0 auto, 1 launch order, 2 XCD by XCD
   int combine;      // pieces of shared tiles: 0 auto, 1 summed by a second kernel, 2 inside the main kernel
+  int tables;       // per-tap tables: 0 auto, 1 assembled in the kernel from table rows, 2 ready-made by ax_layer_prepare
 };
 // AX_OK, or AX_ERR_OPTION for a value out of range.  tune == nullptr gives the automatic choice.
 int make_options(const ax_tune_t* tune, Options* o);
@@ -97,12 +98,14 @@ struct TabPlan {
   int G;            // workgroups of the main kernel
   int partials;     // partial tile pieces that grid produces
   int combine;      // 1: the main kernel combines them itself (arrival counters), 0: fix-up pass
+  int pre;          // 1: the main kernel copies ready-made tables from the prepared block
   int nti;          // tiles along the lane dimension
   int ih;           // their height in lane elements (multiple of 64, nti * ih >= I)
   int xcd;          // 1: shares of work numbered XCD by XCD, 0: in launch order
   size_t off_rows;   // prepared block
   size_t off_qd;     // prepared block
   size_t off_cnt;    // prepared block: arrival counters, one per tile (combine only)
+  size_t off_tabs;   // prepared block: ready-made tables (pre only)
   size_t off_bpack;  // prepared block (variant 2) or scratch (variant 3)
   size_t off_bsum;   // with off_bpack
   size_t off_apack;  // scratch (variant 2) or prepared block (variant 3)

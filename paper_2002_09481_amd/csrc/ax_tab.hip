@@ -78,6 +78,8 @@ struct TabArgs {
                   // another workgroup, slot 2w+1 = its piece of a tile it begins but does not end
   int32_t* lsum;  // [2*G][ih] lane-operand sums of the same pieces
   uint32_t* cnt;  // non-null: [tiles] arrival counters, pieces are combined inside tab_kernel (see there)
+  const uint4* tabs;  // kernels with PRE: [nch*16 + 1][Jpad/8][256] ready-made table entries (prep_tables_kernel)
+  uint32_t tabs_bytes;
   long long out_elems;   // outputs per table (M * Cout)
   int ntiles1;           // tiles of one table; tile index space = table * ntiles1 + tile (several tables: ax_conv2d_multi_lut)
   int vec_out;  // outputs may be written in aligned 16-byte pieces along j
@@ -149,7 +151,10 @@ __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
 // global loads of the table rows for the NEXT phase, (b) gathers from the current buffer and
 // accumulates, (c) interleaves the loaded rows into 16-byte entries and stores them into
 // the other buffer, (d) joins the barrier.
-template <int THREADS, int P, int NG, int KS, int WPE, bool CH, bool WIDE>
+// PRE: the 4 KiB tables are not built from table rows but copied from global memory, where
+// prep_tables_kernel has laid them out ready-made for every (tap, column group) of the layer: two
+// 16-byte loads per lane and half table instead of eight 4-byte row loads and eight permutes.
+template <int THREADS, int P, int NG, int KS, int WPE, bool CH, bool WIDE, bool PRE = false>
 __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   constexpr int JT = NG * 8;
   constexpr int WAVES = THREADS / 64;
@@ -264,8 +269,23 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     return *reinterpret_cast<const uint2*>(a.Bp + (size_t)min(k + us[2 * cu < UNITS ? 2 * cu : 0], klast) * a.Jpad + j0 +
                                            8 * ug[2 * cu < UNITS ? 2 * cu : 0]);
   };
-  auto build_issue = [&](int u, const uint2 tv) {
+  const __amdgpu_buffer_rsrc_t tabs_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4*>(a.tabs), 0, PRE ? a.tabs_bytes : 0, 0x00020000);
+  const uint32_t tabs_stride = (uint32_t)(a.Jpad >> 3);  // tables per tap
+  // tv: the eight table-side codes of the unit; ktap: first tap of the phase the unit belongs to
+  auto build_issue = [&](int u, const uint2 tv, int ktap) {
     if (!uvalid[u]) return;
+    if constexpr (PRE) {
+      // entries e = lane + 64 * half and e + 128 of table (tap, column group), 16 bytes each
+      const uint32_t k = (uint32_t)min(ktap + us[u], klast);
+      const uint32_t soff = (k * tabs_stride + (uint32_t)(j0 >> 3) + (uint32_t)ug[u]) * 4096u;
+      const int voff = (lane + 64 * uh[u]) * 16;
+      const u32x4 q0 = __builtin_amdgcn_raw_buffer_load_b128(tabs_rsrc, voff, (int)soff, 0);
+      const u32x4 q1 = __builtin_amdgcn_raw_buffer_load_b128(tabs_rsrc, voff + 2048, (int)soff, 0);
+      d[0] = q0.x; d[1] = q0.y; d[2] = q0.z; d[3] = q0.w;
+      d[4] = q1.x; d[5] = q1.y; d[6] = q1.z; d[7] = q1.w;
+      return;
+    }
     const int voff = (lane + 64 * uh[u]) * 4;
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
@@ -276,14 +296,19 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   auto build_commit = [&](int u, int buf) {
     if (!uvalid[u]) return;
     uint4 lo, hi;
-    lo.x = __builtin_amdgcn_perm(d[1], d[0], 0x05040100u);
-    lo.y = __builtin_amdgcn_perm(d[3], d[2], 0x05040100u);
-    lo.z = __builtin_amdgcn_perm(d[5], d[4], 0x05040100u);
-    lo.w = __builtin_amdgcn_perm(d[7], d[6], 0x05040100u);
-    hi.x = __builtin_amdgcn_perm(d[1], d[0], 0x07060302u);
-    hi.y = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
-    hi.z = __builtin_amdgcn_perm(d[5], d[4], 0x07060302u);
-    hi.w = __builtin_amdgcn_perm(d[7], d[6], 0x07060302u);
+    if constexpr (PRE) {
+      lo = make_uint4(d[0], d[1], d[2], d[3]);
+      hi = make_uint4(d[4], d[5], d[6], d[7]);
+    } else {
+      lo.x = __builtin_amdgcn_perm(d[1], d[0], 0x05040100u);
+      lo.y = __builtin_amdgcn_perm(d[3], d[2], 0x05040100u);
+      lo.z = __builtin_amdgcn_perm(d[5], d[4], 0x05040100u);
+      lo.w = __builtin_amdgcn_perm(d[7], d[6], 0x05040100u);
+      hi.x = __builtin_amdgcn_perm(d[1], d[0], 0x07060302u);
+      hi.y = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
+      hi.z = __builtin_amdgcn_perm(d[5], d[4], 0x07060302u);
+      hi.w = __builtin_amdgcn_perm(d[7], d[6], 0x07060302u);
+    }
     const int e = lane + 64 * uh[u];
     tab[buf][us[u]][ug[u]][e] = lo;
     tab[buf][us[u]][ug[u]][e + 128] = hi;
@@ -308,7 +333,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     uint32_t d0[UNITS][8];
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) {
-      build_issue(u, load_codes(u >> 1, kbeg));
+      build_issue(u, PRE ? make_uint2(0u, 0u) : load_codes(u >> 1, kbeg), kbeg);
 #pragma unroll
       for (int c = 0; c < 8; ++c) d0[u][c] = d[c];
     }
@@ -338,7 +363,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   uint2 tvv = fetch_codes(kbeg + KS);
   // rows of unit 0 for the tables that the first phase of the loop builds
   build_issue(0, make_uint2((uint32_t)__builtin_amdgcn_readlane((int)tvv.x, 0),
-                            (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, 0)));
+                            (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, 0)), kbeg + KS);
 
   for (int c = 0; c < nchunks; ++c) {
     const int k0 = kbeg + c * kChunk;
@@ -378,7 +403,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
         // (the rows of unit 0 were requested at the end of the phase before, see below)
 #pragma unroll
         for (int u = 1; u < UNITS; ++u)
-          if (q == u * (SEGS / UNITS)) build_issue(u, tv_cur[u >> 1][ph]);
+          if (q == u * (SEGS / UNITS)) build_issue(u, tv_cur[u >> 1][ph], k0 + (ph + 1) * KS);
         if (ph == 0 && q == 0) {
           // operand and codes of the next chunk: fetched behind the first row fetches of this
           // chunk, so that the wait for those rows does not also wait for these
@@ -439,10 +464,10 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
       // the next chunk's first phase, which tvv has held since the start of this chunk; past the
       // last chunk they are clamped to the operand and the rows are never used.
       if (ph + 1 < PHASES)
-        build_issue(0, tv_cur[0][ph + 1]);
+        build_issue(0, tv_cur[0][ph + 1], k0 + (ph + 2) * KS);
       else
         build_issue(0, make_uint2((uint32_t)__builtin_amdgcn_readlane((int)tvv.x, 0),
-                                  (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, 0)));
+                                  (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, 0)), k0 + (ph + 2) * KS);
       __syncthreads();
     }
   }
@@ -755,6 +780,27 @@ __global__ __launch_bounds__(256) void tab_fixup_kernel(const TabArgs a, int G) 
 }
 
 // ---- operand preparation ---------------------------------------------------------------
+
+// Ready-made tables for tab_kernel<.., PRE>: for every row k of the packed table-side operand
+// (krows of them, the last one all zero codes) and every group g of eight columns the 256 entries
+// T[v] = (R[b_0][v] .. R[b_7][v]), b_c = Bp[k][8g + c], 16 bytes each: exactly what the kernel
+// otherwise assembles in LDS from eight table rows.  One block per table, one thread per entry.
+__global__ __launch_bounds__(256) void prep_tables_kernel(const uint16_t* __restrict__ rows, const uint8_t* __restrict__ Bp,
+                                                           int Jpad, uint4* __restrict__ tabs) {
+  const int groups = Jpad >> 3;
+  const int k = blockIdx.x / groups, g = blockIdx.x - k * groups;
+  const int v = threadIdx.x;
+  // rows[t] holds R[t][P] at 2P and R[t][P + 128] at 2P + 1 (see prep_kernel)
+  const int col = v < 128 ? 2 * v : 2 * (v - 128) + 1;
+  const uint2 codes = *reinterpret_cast<const uint2*>(Bp + (size_t)k * Jpad + 8 * g);
+  uint32_t e[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const uint32_t b = ((c < 4 ? codes.x : codes.y) >> (8 * (c & 3))) & 0xffu;
+    e[c] = rows[b * 256u + col];
+  }
+  tabs[(size_t)blockIdx.x * 256 + v] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+}
 
 struct ConvView {  // im2col addressing of x
   const uint8_t* x;
@@ -1134,6 +1180,11 @@ struct PlanChoice { int tile, variant, G, partials, nti, ih; double cost; int mo
 // through tab_fixup_kernel, which spreads the sums of one tile over many blocks.
 constexpr int kCombineMost = 4;
 constexpr int kCombineLong = 24;
+// Ready-made tables that a layer gets without being asked to: any set that fits an L2, larger
+// sets (up to kPreTablesMax bytes) for layers with at least kPreRowTiles tiles along the lanes.
+constexpr size_t kPreTablesSmall = (size_t)3 << 20;
+constexpr size_t kPreTablesMax = (size_t)32 << 20;
+constexpr int kPreRowTiles = 8;
 
 static PlanChoice plan_choice_nti(const Geom& g, int tile, int v, int forced_split, int nti);
 
@@ -1250,13 +1301,13 @@ static double xcd_fetch_bytes(int xcd, int G, int nti, int ntj, int nch, int T, 
 // (geometry, options); the table is small and cleared when it grows past a bound.
 TabPlan tab_plan(const Geom& g, const Options& o) {
   struct Key {
-    int v[23];
+    int v[24];
     bool operator<(const Key& other) const { return std::memcmp(v, other.v, sizeof(v)) < 0; }
   };
   static std::mutex mu;
   static std::map<Key, TabPlan> cache;
   const Key k{{g.N, g.H, g.W, g.Cin, g.KH, g.KW, g.Cout, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.sgn, g.mult, o.variant,
-               o.split_k, o.tile, o.row_tiles, cu_count(), g.T, o.share_order, o.combine}};
+               o.split_k, o.tile, o.row_tiles, cu_count(), g.T, o.share_order, o.combine, o.tables}};
   std::lock_guard<std::mutex> lock(mu);
   auto it = cache.find(k);
   if (it != cache.end()) return it->second;
@@ -1321,6 +1372,20 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   p.off_qd = prep;    prep += 256;
   p.off_cnt = prep;
   if (p.combine) prep += up256((size_t)p.nti * cdiv(J, kJT) * g.T * 4);
+  // Ready-made tables (one 4 KiB table per tap and group of eight columns) where the filters are
+  // the table side, one multiplier table is used and the tile has a kernel for them.  Every
+  // workgroup reads the tables of its taps and columns from global memory, so they pay where
+  // many tiles along the lane dimension read the same tables at about the same time (the reads
+  // then meet in the L2s) or where all of them fit into an L2; measured on the ResNet-50 layers
+  // at batch 32: 2-9 % faster with 13 or more row tiles and whole tiles per workgroup, 5-40 %
+  // slower with four row tiles or K slices.
+  const size_t tabs_bytes = (Kp + 1) * (Jpad / 8) * 4096;
+  const bool pre_pays = tabs_bytes <= kPreTablesSmall ||
+                        (best.partials == 0 && best.nti >= kPreRowTiles && tabs_bytes <= kPreTablesMax);
+  p.pre = (v == 2 && g.T == 1 && g.K <= 16384 && (best.tile == 2 || best.tile == 4) && tabs_bytes <= ((size_t)1 << 30) &&
+           (o.tables ? o.tables == 2 : pre_pays)) ? 1 : 0;
+  p.off_tabs = prep;
+  if (p.pre) prep += up256(tabs_bytes);
   if (v == 2) {
     p.off_bpack = prep;  prep += bpack;
     p.off_bsum = prep;   prep += bsum;
@@ -1356,9 +1421,17 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
     if (e_ != hipSuccess) return e_;                \
   } while (0)
 
-template <int THREADS, int P, int NG, int KS, int WPE, bool CH>
+template <int THREADS, int P, int NG, int KS, int WPE, bool CH, bool CANPRE = false>
 static hipError_t launch_cfg(const TabArgs& a, int G, int ntiles, int phases, int reps, hipStream_t s) {
   for (int r = 0; r < reps && (phases & kPhMain); ++r) {
+    if constexpr (CANPRE) {
+      if (a.tabs) {  // planned only for K <= 16384
+        hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, WPE, CH, false, true>), dim3(G), dim3(THREADS), 0, s, a);
+        AX_LAUNCHED();
+        continue;
+      }
+    }
+    if (a.tabs) return hipErrorInvalidValue;  // a plan with ready-made tables for a kernel without them
     if (a.K > 16384)
       hipLaunchKernelGGL((tab_kernel<THREADS, P, NG, KS, WPE, CH, true>), dim3(G), dim3(THREADS), 0, s, a);
     else
@@ -1380,9 +1453,9 @@ static hipError_t launch_main(const TileCfg& t, const TabArgs& a, int G, int nti
   switch (key) {
     case 5120000 + 2812: return launch_cfg<512, 2, 8, 1, 2, CH>(a, G, ntiles, phases, reps, s);
     case 10240000 + 1824: return launch_cfg<1024, 1, 8, 2, 4, CH>(a, G, ntiles, phases, reps, s);
-    case 10240000 + 2444: return launch_cfg<1024, 2, 4, 4, 4, CH>(a, G, ntiles, phases, reps, s);
+    case 10240000 + 2444: return launch_cfg<1024, 2, 4, 4, 4, CH, !CH>(a, G, ntiles, phases, reps, s);
     case 10240000 + 2244: return launch_cfg<1024, 2, 2, 4, 4, CH>(a, G, ntiles, phases, reps, s);
-    case 10240000 + 2284: return launch_cfg<1024, 2, 2, 8, 4, CH>(a, G, ntiles, phases, reps, s);
+    case 10240000 + 2284: return launch_cfg<1024, 2, 2, 8, 4, CH, !CH>(a, G, ntiles, phases, reps, s);
     case 5120000 + 2244: return launch_cfg<512, 2, 2, 4, 4, CH>(a, G, ntiles, phases, reps, s);
     case 5120000 + 2424: return launch_cfg<512, 2, 4, 2, 4, CH>(a, G, ntiles, phases, reps, s);
     default: return hipErrorInvalidValue;  // a tile configuration without an instantiated kernel
@@ -1445,6 +1518,11 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
                          J, krows, Jpad, seg_rows, Bp, bsum, qp, qd, g.T, 1, 1, cnt, ncnt);
       AX_LAUNCHED();
     }
+    if ((phases & kPhConst) && p.pre) {
+      hipLaunchKernelGGL(prep_tables_kernel, dim3((unsigned)(krows * (Jpad / 8))), dim3(256), 0, s, rows, Bp, Jpad,
+                         reinterpret_cast<uint4*>(pb + p.off_tabs));
+      AX_LAUNCHED();
+    }
     if ((phases & kPhCall) && implicit_view && g.sgn) {  // N*H*W*Cin is a multiple of 16 here
       const uint32_t n16 = (uint32_t)(((size_t)g.N * g.H * g.W * g.Cin) / 16);
       hipLaunchKernelGGL(prep_flip_kernel, dim3(cdiv(n16, 256)), dim3(256), 0, s, reinterpret_cast<const uint4*>(x),
@@ -1495,6 +1573,8 @@ hipError_t launch_tab(const Geom& g, const QParams& qp, const TabPlan& p, const 
   a.part = reinterpret_cast<int32_t*>(sb + p.off_part);
   a.lsum = reinterpret_cast<int32_t*>(sb + p.off_lsum);
   a.cnt = p.combine ? reinterpret_cast<uint32_t*>(pb + p.off_cnt) : nullptr;
+  a.tabs = p.pre ? reinterpret_cast<const uint4*>(pb + p.off_tabs) : nullptr;
+  a.tabs_bytes = p.pre ? (uint32_t)((size_t)krows * (Jpad / 8) * 4096) : 0u;
   a.out_elems = (long long)g.M * g.Cout;
   a.xcd = p.xcd;
   a.vec_out = (!ch && J % 4 == 0 && (((uintptr_t)acc_out | (uintptr_t)y_out) & 15) == 0) ? 1 : 0;

@@ -46,7 +46,7 @@ def test_host_side_calls_without_gpu():
         binding.ax_set_option("variant", 99)
     with pytest.raises(binding.AxError):
         binding.ax_set_option("no_such_option", 1)
-    for name, top in (("share_order", 2), ("combine", 2), ("split_k", 64), ("row_tiles", 1 << 20)):
+    for name, top in (("share_order", 2), ("combine", 2), ("tables", 2), ("split_k", 64), ("row_tiles", 1 << 20)):
         binding.ax_set_option(name, top)
         assert binding.ax_get_option(name) == top
         with pytest.raises(binding.AxError):

@@ -37,7 +37,8 @@ LAYERS = [
 ]
 TUNES = [_tune(), _tune(variant=2, split_k=3), _tune(variant=3), _tune(variant=3, split_k=2, share_order=1),
          _tune(variant=2, tile=3, row_tiles=2), _tune(variant=1), _tune(variant=2, split_k=5, combine=1),
-         _tune(variant=2, split_k=5, combine=2), _tune(variant=3, split_k=9, combine=2)]
+         _tune(variant=2, split_k=5, combine=2), _tune(variant=3, split_k=9, combine=2),
+         _tune(variant=2, tables=2), _tune(variant=2, tile=3, tables=2, split_k=2), _tune(variant=2, tables=1)]
 
 
 @pytest.mark.parametrize("li", range(len(LAYERS)))

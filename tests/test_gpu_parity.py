@@ -25,6 +25,7 @@ def _reset_options():
     ax.ax_set_option("row_tiles", 0)
     ax.ax_set_option("share_order", 0)
     ax.ax_set_option("combine", 0)
+    ax.ax_set_option("tables", 0)
 
 
 def L(N, H, W, Cin, KH, KW, Cout, s=1, p=0, dense=False, x_dist="uniform", w_dist="uniform", name=None):
@@ -130,6 +131,25 @@ def test_shared_tiles_combined_by_either_kernel(variant, combine, split_k):
         G.check_layer(L(1, 7, 7, 512, 3, 3, 512, 1, 1), 63 + rep, lut)      # few pixels: K slices by default
         G.check_layer(L(37, 1, 1, 600, 1, 1, 333, dense=True), 65 + rep, lut)
         G.check_layer(L(2, 33, 33, 16, 5, 5, 24, 2, 2, x_dist="relu", w_dist="normal"), 67 + rep, I.lut_truncated(6))
+
+
+@pytest.mark.parametrize("tables", [1, 2])
+@pytest.mark.parametrize("tile", [3, 5])
+@pytest.mark.parametrize("split_k", [0, 3])
+def test_tables_assembled_in_the_kernel_or_ready_made(tables, tile, split_k):
+    """The per-tap tables of the table-tile kernel: built in LDS from the rows of the multiplier
+    table, or copied ready-made from the prepared block; ragged K (taps past the end of the sum),
+    ragged channel tiles, materialized patches, K slices."""
+    ax.ax_set_option("variant", 2)
+    ax.ax_set_option("tables", tables)
+    ax.ax_set_option("tile", tile)
+    ax.ax_set_option("split_k", split_k)
+    lut = I.lut_random(35)
+    G.check_layer(L(3, 40, 41, 32, 3, 3, 72, 1, 1), 71, lut)
+    G.check_layer(L(2, 30, 30, 20, 5, 5, 9, 2, 2), 72, lut)             # Cin % 16 != 0: K padded to 512
+    G.check_layer(L(1, 7, 7, 512, 3, 3, 130, 1, 1), 73, I.lut_truncated(6))
+    G.check_layer(L(40, 1, 1, 100, 1, 1, 64, dense=True), 74, lut)
+    G.check_layer(L(128, 32, 32, 16, 3, 3, 16, 1, 1, x_dist="relu", w_dist="normal"), 75, I.lut_random_error(7))
 
 
 TILES = list(range(1, 8))

@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def _reset_options():
     yield
-    for name in ("variant", "split_k", "tile", "row_tiles", "share_order", "combine"):
+    for name in ("variant", "split_k", "tile", "row_tiles", "share_order", "combine", "tables"):
         ax.ax_set_option(name, 0)
 
 
@@ -53,6 +53,7 @@ def test_random_layers_and_options(seed):
     ax.ax_set_option("row_tiles", int(rng.choice([0, 0, 1, 2, 7])))
     ax.ax_set_option("share_order", seed % 3)  # not drawn from rng: the cases above stay what they were
     ax.ax_set_option("combine", (seed // 3) % 3)
+    ax.ax_set_option("tables", (seed // 2) % 3)
     # now and then operands and outputs that are not 16-byte aligned
     off = int(rng.choice([0, 0, 1, 4]))
     xbuf = torch.zeros(x.size + 16, dtype=torch.int8 if signed else torch.uint8, device="cuda")
