@@ -376,15 +376,31 @@ def main():
             y = torch.empty(acc.shape, dtype=torch.float32, device=dev)
             return lambda lt=lut_dev: ax.ax_conv2d(xd, wd, lt, l.stride, l.pad, q, acc, y, ws)
 
+        kept = []  # handles of the secondary workloads (freed with the process)
+
+        def make_handle_call(l, seed, lut_dev):
+            # the layer as a prepared handle, like the headline: constants laid out once, outside the timing
+            x, w, q = I.make_operands(l, seed)
+            xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
+            h = ax.AxLayer(ax._conv_desc(x.shape, w.shape, l.stride, l.pad), q)
+            h.prepare(wd, lut_dev)
+            acc = torch.empty(h.out_shape(), dtype=torch.int32, device=dev)
+            y = torch.empty(acc.shape, dtype=torch.float32, device=dev)
+            ws = torch.empty(max(256, h.workspace_bytes), dtype=torch.uint8, device=dev)
+            kept.append(h)
+            return lambda: h.run(xd, acc, y, ws)
+
         # config 2: CIFAR-shaped stack, batch 128, random-error table
         l2 = I.config_resnet8_cifar(128)
         lut2 = ax.lut_to_device(I.lut_random_error(2000))
-        ms = time_calls([make_call(l, I.layer_seed(2, i), lut2) for i, l in enumerate(l2)], 50)
+        ms = time_calls([make_handle_call(l, I.layer_seed(2, i), lut2) for i, l in enumerate(l2)], 50)
+        ms_1c = time_calls([make_call(l, I.layer_seed(2, i), lut2) for i, l in enumerate(l2)], 50)
         m2 = sum(l.macs for l in l2)
-        extra["config2_cifar_stack_b128"] = {"ms": ms, "lut_macs_per_s": m2 / ms * 1e3, "images_per_s": 128 / ms * 1e3}
+        extra["config2_cifar_stack_b128"] = {"ms": ms, "lut_macs_per_s": m2 / ms * 1e3, "images_per_s": 128 / ms * 1e3,
+                                             "ms_one_call_entry_points": ms_1c}
         # the same stack at the batch size the paper used for its CIFAR-10 runs (1000 images)
         l2k = I.config_resnet8_cifar(1000)
-        ms_k = time_calls([make_call(l, I.layer_seed(2, i), lut2) for i, l in enumerate(l2k)], 10)
+        ms_k = time_calls([make_handle_call(l, I.layer_seed(2, i), lut2) for i, l in enumerate(l2k)], 10)
         m2k = sum(l.macs for l in l2k)
         extra["config2_cifar_stack_b1000"] = {
             "ms": ms_k, "lut_macs_per_s": m2k / ms_k * 1e3, "images_per_s": 1000 / ms_k * 1e3,
@@ -417,7 +433,7 @@ def main():
         # the same seven calls captured once into a HIP graph and replayed (the calls only enqueue
         # kernels, so nothing but launch overhead changes)
         try:
-            c2 = [make_call(l, I.layer_seed(2, i), lut2) for i, l in enumerate(l2)]
+            c2 = [make_handle_call(l, I.layer_seed(2, i), lut2) for i, l in enumerate(l2)]
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(side):
