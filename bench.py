@@ -189,7 +189,7 @@ def main():
 
     if args.per_layer:
         # every layer on its own: whole call (per-call preparation, main kernel, fix-up) and main kernel
-        print("| layer | M | K | Cout | lookups (G) | plan (variant, tile, workgroups, pieces) | call us | main kernel us | "
+        print("| layer | M | K | Cout | lookups (G) | plan (variant, tile, workgroups, pieces, combine, tables) | call us | main kernel us | "
               "T lookups/s (call) | T lookups/s (kernel) |")
         print("|---|---|---|---|---|---|---|---|---|---|")
         a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -206,8 +206,9 @@ def main():
             cm = a0.elapsed_time(a1) / 20
             tot_call += cm
             p = h.plan()
-            print("| %s | %d | %d | %d | %.3f | %d, %d, %d, %d | %.1f | %.1f | %.2f | %.2f |" % (
-                l.name, l.M, l.K, l.Cout, l.macs / 1e9, p["variant"], p["tile"], p["workgroups"], p["pieces"], cm * 1e3,
+            print("| %s | %d | %d | %d | %.3f | %d, %d, %d, %d, %d, %d | %.1f | %.1f | %.2f | %.2f |" % (
+                l.name, l.M, l.K, l.Cout, l.macs / 1e9, p["variant"], p["tile"], p["workgroups"], p["pieces"],
+                p["combine"], p["tables"], cm * 1e3,
                 km * 1e3, l.macs / cm / 1e9, l.macs / km / 1e9))
         print("\nsum of the calls timed one layer at a time: %.3f ms; the same 54 calls back to back in a step: %.3f ms; "
               "main kernels: %.3f ms" % (tot_call, ms_per_step, main_ms))

@@ -264,6 +264,10 @@ size_t ax_static_scratch_bytes(void);
  * configuration (0 for the direct and depthwise kernels), grid size of the main kernel and
  * number of partial tile pieces it produces.  Any output pointer may be NULL. */
 int ax_layer_plan(const ax_layer_t* layer, int* variant, int* tile, int* workgroups, int* pieces);
+/* The two remaining choices of the plan, in the values of ax_tune_t: combine (0: no shared tiles,
+ * 1: second kernel, 2: inside the main kernel) and tables (0: not a table-tile layer, 1: assembled
+ * in the kernel, 2: ready-made in the prepared block).  Any output pointer may be NULL. */
+int ax_layer_plan_paths(const ax_layer_t* layer, int* combine, int* tables);
 
 /* ---- float-in / float-out form of the layer (Sec. II: the approximate layer reads two float
  * tensors plus the range of each and returns a float tensor; Sec. III, Algorithm 1:

@@ -47,7 +47,7 @@ EXPORTS = [  # include/axconv.h
     "ax_conv2d_f32_workspace_bytes", "ax_dense_f32", "ax_dense_f32_workspace_bytes", "ax_conv2d_ex",
     "ax_conv2d_ex_workspace_bytes", "ax_conv2d_multi_lut", "ax_conv2d_multi_lut_workspace_bytes", "ax_conv2d_f32_ex",
     "ax_conv2d_f32_ex_workspace_bytes", "ax_layer_create", "ax_layer_destroy", "ax_layer_prepared_bytes",
-    "ax_layer_workspace_bytes", "ax_layer_prepare", "ax_layer_run", "ax_layer_plan", "ax_layer_run_static",
+    "ax_layer_workspace_bytes", "ax_layer_prepare", "ax_layer_run", "ax_layer_plan", "ax_layer_plan_paths", "ax_layer_run_static",
     "ax_static_scratch_bytes", "ax_conv2d_backward", "ax_conv2d_backward_workspace_bytes",
 ]
 PROBE_EXPORTS = [  # include/axconv_probe.h
@@ -113,6 +113,8 @@ def lib():
     L.ax_layer_run.restype = ci
     L.ax_layer_plan.argtypes = [vp, ip, ip, ip, ip]
     L.ax_layer_plan.restype = ci
+    L.ax_layer_plan_paths.argtypes = [vp, ip, ip]
+    L.ax_layer_plan_paths.restype = ci
     L.ax_layer_run_static.argtypes = [vp, vp, vp, vp, vp]
     L.ax_layer_run_static.restype = ci
     L.ax_static_scratch_bytes.argtypes = []
@@ -557,7 +559,10 @@ class AxLayer:
     def plan(self) -> dict:
         out = [ctypes.c_int(0) for _ in range(4)]
         _check(lib().ax_layer_plan(self._h, *[ctypes.byref(o) for o in out]))
-        return {"variant": out[0].value, "tile": out[1].value, "workgroups": out[2].value, "pieces": out[3].value}
+        paths = [ctypes.c_int(0) for _ in range(2)]
+        _check(lib().ax_layer_plan_paths(self._h, *[ctypes.byref(o) for o in paths]))
+        return {"variant": out[0].value, "tile": out[1].value, "workgroups": out[2].value, "pieces": out[3].value,
+                "combine": paths[0].value, "tables": paths[1].value}
 
     def prepare(self, w, luts, prepared=None, stream=None):
         cdt = torch.int8 if self.desc.signed_codes else torch.uint8

@@ -342,6 +342,13 @@ extern "C" int ax_layer_plan(const ax_layer_t* layer, int* variant, int* tile, i
   return AX_OK;
 }
 
+extern "C" int ax_layer_plan_paths(const ax_layer_t* layer, int* combine, int* tables) {
+  if (!layer) return AX_ERR_NULL;
+  if (combine) *combine = (layer->tab && layer->p.partials > 0) ? (layer->p.combine ? 2 : 1) : 0;
+  if (tables) *tables = layer->tab ? (layer->p.pre ? 2 : 1) : 0;
+  return AX_OK;
+}
+
 extern "C" const char* ax_strerror(int code) {
   switch (code) {
     case AX_OK: return "ok";
@@ -358,4 +365,4 @@ extern "C" const char* ax_strerror(int code) {
   }
 }
 
-extern "C" int ax_version(void) { return 320; }
+extern "C" int ax_version(void) { return 330; }

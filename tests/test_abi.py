@@ -149,6 +149,15 @@ def test_layer_handles_on_the_host():
     v, t, g, p = (ctypes.c_int() for _ in range(4))
     assert L.ax_layer_plan(h, ctypes.byref(v), ctypes.byref(t), ctypes.byref(g), ctypes.byref(p)) == 0
     assert v.value == 2 and t.value >= 1 and 1 <= g.value <= 4096
+    cmb, tb = ctypes.c_int(-1), ctypes.c_int(-1)
+    assert L.ax_layer_plan_paths(h, ctypes.byref(cmb), ctypes.byref(tb)) == 0 and L.ax_layer_plan_paths(None, None, None) == -1
+    # 49 or more row tiles of whole K ranges: ready-made tables (4 KiB per tap and eight channels) in the prepared block
+    assert tb.value == 2 and prep >= 577 * 8 * 4096 and cmb.value == (0 if p.value == 0 else cmb.value)
+    h1 = ctypes.c_void_p()
+    assert L.ax_layer_create(ctypes.byref(big), 1, ctypes.byref(q), ctypes.byref(T(0, 0, 0, 0, 0, 0, 1)), ctypes.byref(h1)) == 0
+    assert L.ax_layer_plan_paths(h1, None, ctypes.byref(tb)) == 0 and tb.value == 1
+    assert L.ax_layer_prepared_bytes(h1) < 577 * 8 * 4096
+    L.ax_layer_destroy(h1)
     assert L.ax_layer_run(h, one, one, one, one, 1 << 40, None) == -9  # not prepared yet
     assert L.ax_layer_prepare(h, one, one, one, 16, None) == -5      # prepared block too small
     assert L.ax_layer_prepare(h, None, one, one, 1 << 40, None) == -1
@@ -159,7 +168,7 @@ def test_layer_handles_on_the_host():
         assert lay.plan()["variant"] == 3 and lay.prepared_bytes >= 131072 + 64 * 576
     # tiny and depthwise layers take kernels that need neither block
     with binding.AxLayer(D(1, 4, 4, 8, 3, 3, 8, 1, 1, 1, 1, 1, 1, 0, 0), q) as lay:
-        assert lay.plan() == {"variant": 1, "tile": 0, "workgroups": 0, "pieces": 0}
+        assert lay.plan() == {"variant": 1, "tile": 0, "workgroups": 0, "pieces": 0, "combine": 0, "tables": 0}
         assert lay.prepared_bytes == 0 and lay.workspace_bytes == 0
     with binding.AxLayer(D(8, 56, 56, 64, 3, 3, 64, 1, 1, 1, 1, 1, 1, 1, 0), q) as lay:
         assert lay.plan()["variant"] == 1 and lay.prepared_bytes == 0
