@@ -153,7 +153,9 @@ __device__ __forceinline__ uint32_t byte_of(const uint4& v, int kk) {
 // the other buffer, (d) joins the barrier.
 // PRE: the 4 KiB tables are not built from table rows but copied from global memory, where
 // prep_tables_kernel has laid them out ready-made for every (tap, column group) of the layer: two
-// 16-byte loads per lane and half table instead of eight 4-byte row loads and eight permutes.
+// 16-byte loads per lane and half table instead of eight 4-byte row loads and eight permutes.  The
+// loads write straight into LDS (buffer loads with the lds modifier), so the copy takes no
+// registers, no LDS store instructions and no wait in the middle of a phase.
 template <int THREADS, int P, int NG, int KS, int WPE, bool CH, bool WIDE, bool PRE = false>
 __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   constexpr int JT = NG * 8;
@@ -269,23 +271,33 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     return *reinterpret_cast<const uint2*>(a.Bp + (size_t)min(k + us[2 * cu < UNITS ? 2 * cu : 0], klast) * a.Jpad + j0 +
                                            8 * ug[2 * cu < UNITS ? 2 * cu : 0]);
   };
-  const __amdgpu_buffer_rsrc_t tabs_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4*>(a.tabs), 0, PRE ? a.tabs_bytes : 0, 0x00020000);
+  // PRE: buffer descriptor of the ready-made tables (raw buffer, bounds-checked against their size)
+  u32x4 tabs_words;
+  tabs_words.x = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)a.tabs);
+  tabs_words.y = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)((uintptr_t)a.tabs >> 32) & 0xffffu));
+  tabs_words.z = (uint32_t)__builtin_amdgcn_readfirstlane((int)(PRE ? a.tabs_bytes : 0u));
+  tabs_words.w = 0x00020000u;
   const uint32_t tabs_stride = (uint32_t)(a.Jpad >> 3);  // tables per tap
-  // tv: the eight table-side codes of the unit; ktap: first tap of the phase the unit belongs to
-  auto build_issue = [&](int u, const uint2 tv, int ktap) {
+  // PRE: copy the half table of unit u for the phase that starts at tap ktap into buffer buf.  Lane
+  // l moves entries l + 64 * half and, 128 entries on, the second one: two loads of 1 KiB per wave,
+  // which the hardware writes to LDS at M0 + instruction offset + 16 * lane (the instruction offset
+  // counts for the memory address and for the LDS address alike).  Written as instructions: the
+  // compiler would make every later LDS read wait for a copy it knows of, since it cannot tell the
+  // two table buffers apart; the waves wait for their copies once, before the barrier of the phase.
+  auto table_copy = [&](int u, int ktap, int buf) {
     if (!uvalid[u]) return;
-    if constexpr (PRE) {
-      // entries e = lane + 64 * half and e + 128 of table (tap, column group), 16 bytes each
-      const uint32_t k = (uint32_t)min(ktap + us[u], klast);
-      const uint32_t soff = (k * tabs_stride + (uint32_t)(j0 >> 3) + (uint32_t)ug[u]) * 4096u;
-      const int voff = (lane + 64 * uh[u]) * 16;
-      const u32x4 q0 = __builtin_amdgcn_raw_buffer_load_b128(tabs_rsrc, voff, (int)soff, 0);
-      const u32x4 q1 = __builtin_amdgcn_raw_buffer_load_b128(tabs_rsrc, voff + 2048, (int)soff, 0);
-      d[0] = q0.x; d[1] = q0.y; d[2] = q0.z; d[3] = q0.w;
-      d[4] = q1.x; d[5] = q1.y; d[6] = q1.z; d[7] = q1.w;
-      return;
-    }
+    const uint32_t k = (uint32_t)min(ktap + us[u], klast);
+    const uint32_t soff = (k * tabs_stride + (uint32_t)(j0 >> 3) + (uint32_t)ug[u]) * 4096u;
+    const uint32_t voff = (uint32_t)(lane + 64 * uh[u]) * 16u;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)&tab[buf][us[u]][ug[u]][64 * uh[u]];
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds\n\t"
+                 "buffer_load_dwordx4 %1, %2, %3 offen offset:2048 lds"
+                 :: "s"(lds0), "v"(voff), "s"(tabs_words), "s"(soff) : "memory");
+  };
+  auto copies_done = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+  // tv: the eight table-side codes of the unit
+  auto build_issue = [&](int u, const uint2 tv) {
+    if (PRE || !uvalid[u]) return;
     const int voff = (lane + 64 * uh[u]) * 4;
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
@@ -294,21 +306,16 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     }
   };
   auto build_commit = [&](int u, int buf) {
-    if (!uvalid[u]) return;
+    if (PRE || !uvalid[u]) return;
     uint4 lo, hi;
-    if constexpr (PRE) {
-      lo = make_uint4(d[0], d[1], d[2], d[3]);
-      hi = make_uint4(d[4], d[5], d[6], d[7]);
-    } else {
-      lo.x = __builtin_amdgcn_perm(d[1], d[0], 0x05040100u);
-      lo.y = __builtin_amdgcn_perm(d[3], d[2], 0x05040100u);
-      lo.z = __builtin_amdgcn_perm(d[5], d[4], 0x05040100u);
-      lo.w = __builtin_amdgcn_perm(d[7], d[6], 0x05040100u);
-      hi.x = __builtin_amdgcn_perm(d[1], d[0], 0x07060302u);
-      hi.y = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
-      hi.z = __builtin_amdgcn_perm(d[5], d[4], 0x07060302u);
-      hi.w = __builtin_amdgcn_perm(d[7], d[6], 0x07060302u);
-    }
+    lo.x = __builtin_amdgcn_perm(d[1], d[0], 0x05040100u);
+    lo.y = __builtin_amdgcn_perm(d[3], d[2], 0x05040100u);
+    lo.z = __builtin_amdgcn_perm(d[5], d[4], 0x05040100u);
+    lo.w = __builtin_amdgcn_perm(d[7], d[6], 0x05040100u);
+    hi.x = __builtin_amdgcn_perm(d[1], d[0], 0x07060302u);
+    hi.y = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
+    hi.z = __builtin_amdgcn_perm(d[5], d[4], 0x07060302u);
+    hi.w = __builtin_amdgcn_perm(d[7], d[6], 0x07060302u);
     const int e = lane + 64 * uh[u];
     tab[buf][us[u]][ug[u]][e] = lo;
     tab[buf][us[u]][ug[u]][e + 128] = hi;
@@ -333,7 +340,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
     uint32_t d0[UNITS][8];
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) {
-      build_issue(u, PRE ? make_uint2(0u, 0u) : load_codes(u >> 1, kbeg), kbeg);
+      build_issue(u, PRE ? make_uint2(0u, 0u) : load_codes(u >> 1, kbeg));
 #pragma unroll
       for (int c = 0; c < 8; ++c) d0[u][c] = d[c];
     }
@@ -342,6 +349,11 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
 #pragma unroll
       for (int c = 0; c < 8; ++c) d[c] = d0[u][c];
       build_commit(u, 0);
+    }
+    if constexpr (PRE) {
+#pragma unroll
+      for (int u = 0; u < UNITS; ++u) table_copy(u, kbeg, 0);
+      copies_done();
     }
   }
   __syncthreads();
@@ -363,7 +375,7 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
   uint2 tvv = fetch_codes(kbeg + KS);
   // rows of unit 0 for the tables that the first phase of the loop builds
   build_issue(0, make_uint2((uint32_t)__builtin_amdgcn_readlane((int)tvv.x, 0),
-                            (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, 0)), kbeg + KS);
+                            (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, 0)));
 
   for (int c = 0; c < nchunks; ++c) {
     const int k0 = kbeg + c * kChunk;
@@ -403,7 +415,15 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
         // (the rows of unit 0 were requested at the end of the phase before, see below)
 #pragma unroll
         for (int u = 1; u < UNITS; ++u)
-          if (q == u * (SEGS / UNITS)) build_issue(u, tv_cur[u >> 1][ph], k0 + (ph + 1) * KS);
+          if (q == u * (SEGS / UNITS)) build_issue(u, tv_cur[u >> 1][ph]);
+        if constexpr (PRE) {
+          // the tables of the next phase: one unit at the start of the phase, the other half way
+          // through (all copies at the start were 1 % slower); the buffer they go to was last read
+          // in the phase before, which every wave has left (barrier)
+#pragma unroll
+          for (int u = 0; u < UNITS; ++u)
+            if (q == u * (SEGS / UNITS)) table_copy(u, k0 + (ph + 1) * KS, (ph + 1) & 1);
+        }
         if (ph == 0 && q == 0) {
           // operand and codes of the next chunk: fetched behind the first row fetches of this
           // chunk, so that the wait for those rows does not also wait for these
@@ -464,10 +484,11 @@ __global__ __launch_bounds__(THREADS, WPE) void tab_kernel(const TabArgs a) {
       // the next chunk's first phase, which tvv has held since the start of this chunk; past the
       // last chunk they are clamped to the operand and the rows are never used.
       if (ph + 1 < PHASES)
-        build_issue(0, tv_cur[0][ph + 1], k0 + (ph + 2) * KS);
+        build_issue(0, tv_cur[0][ph + 1]);
       else
         build_issue(0, make_uint2((uint32_t)__builtin_amdgcn_readlane((int)tvv.x, 0),
-                                  (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, 0)), k0 + (ph + 2) * KS);
+                                  (uint32_t)__builtin_amdgcn_readlane((int)tvv.y, 0)));
+      if constexpr (PRE) copies_done();
       __syncthreads();
     }
   }
