@@ -1226,7 +1226,7 @@ static PlanChoice plan_choice(const Geom& g, int tile, int v, int forced_split, 
   for (int r = 1; r <= 64; ++r) {
     const long long n = (long long)r * slots / ntj;
     if (n <= base) continue;
-    if (n > cdiv(I, 64) || n > 4LL * base + 1) break;
+    if (n > cdiv(I, 64) || n > 8LL * base + 1) break;
     const PlanChoice c = plan_choice_nti(g, tile, v, 0, (int)n);
     if (c.cost < best.cost * 0.97) best = c;
     break;
