@@ -86,6 +86,8 @@ static int choose_variant(const Geom& g, const Options& o) {
   if (o.variant == 2 || o.variant == 3) return o.variant;
   // Tiny problems do not amortize the table set-up.
   if ((double)g.M * g.K * g.Cout < 4.0e6) return 1;
+  // A dense layer of few rows fills 1/32 of the lanes of a table tile: whole table in LDS instead.
+  if (g.T == 1 && fewrows_shape(g)) return 1;
   return 0;
 }
 
@@ -93,12 +95,15 @@ static int choose_variant(const Geom& g, const Options& o) {
 static int run_untiled(const Geom& g, const QParams& qp, const Options& o, const uint8_t* x, const uint8_t* w,
                        const uint16_t* lut, int32_t* acc_out, float* y_out, hipStream_t s) {
   const bool dw = g.mult && o.variant != 1 && dw_supported(g, x, w, lut);
+  const bool rows = !dw && o.variant != 1 && (double)g.M * g.K * g.Cout >= 4.0e6 && fewrows_supported(g, lut);
   const size_t per_table = (size_t)g.M * g.Cout;
   for (int t = 0; t < g.T; ++t) {
     const uint16_t* lt = lut + (size_t)t * 65536;
     int32_t* at = acc_out ? acc_out + t * per_table : nullptr;
     float* yt = y_out ? y_out + t * per_table : nullptr;
-    const hipError_t e = dw ? launch_dw(g, qp, x, w, lt, at, yt, s) : launch_direct(g, qp, x, w, lt, at, yt, s);
+    const hipError_t e = dw     ? launch_dw(g, qp, x, w, lt, at, yt, s)
+                         : rows ? launch_fewrows(g, qp, x, w, lt, at, yt, s)
+                                : launch_direct(g, qp, x, w, lt, at, yt, s);
     if (e != hipSuccess) return AX_ERR_HIP;
   }
   return AX_OK;

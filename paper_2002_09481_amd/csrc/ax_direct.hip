@@ -377,6 +377,135 @@ __global__ __launch_bounds__(1024) void dw3_kernel(Geom g, QParams qp_in, const 
   }
 }
 
+// Dense layers with few rows (a fully connected layer on a small batch: M <= 64 rows of x [M, K],
+// filters [K, Cout]).  The table-tile kernels would fill 1/32 of their lanes; here a workgroup
+// keeps the whole table in LDS, as the depthwise kernel does, and takes four output columns: lane
+// l of every wave walks the taps k = l, l + 64, ..., wave v the rows v, v + 16, ...  Per tap a
+// lane reads its four filter codes (one dword) and, per row, one activation code (consecutive
+// lanes, consecutive bytes) and gathers four 2-byte entries; the 64 partial sums of a wave meet
+// in a butterfly of lane exchanges.  One launch, no preparation, no scratch.
+// MPW: rows per wave (M <= 16 * MPW).
+template <int MPW>
+__global__ __launch_bounds__(1024) void fewrows_kernel(Geom g, QParams qp_in, const uint8_t* __restrict__ x,
+                                                        const uint8_t* __restrict__ w, const uint16_t* __restrict__ lut,
+                                                        int32_t* __restrict__ acc_out, float* __restrict__ y_out,
+                                                        int w_dwords) {
+  __shared__ uint32_t tab[256 * kDwRow];
+  QParams qp = qp_in;
+  if (qp.dq) {
+    qp.x_zp = qp.dq->x_zp;
+    qp.w_zp = qp.dq->w_zp;
+    qp.scale = qp.dq->x_scale * qp.dq->w_scale;
+  }
+  const uint32_t flip16 = g.sgn ? 0x80008000u : 0u;
+  const uint32_t flip8 = g.sgn ? 0x80u : 0u;
+  {
+    const uint4* __restrict__ src = reinterpret_cast<const uint4*>(lut);
+    const int rowflip = g.sgn ? (0x80 << 5) : 0;  // see dw_kernel
+    for (int i = threadIdx.x; i < 8192; i += 1024) {
+      uint4 v = src[i ^ rowflip];
+      uint32_t* dst = tab + (i >> 5) * kDwRow + (i & 31) * 4;
+      dst[0] = v.x ^ flip16; dst[1] = v.y ^ flip16; dst[2] = v.z ^ flip16; dst[3] = v.w ^ flip16;
+    }
+  }
+  __syncthreads();
+  const char* tabb = reinterpret_cast<const char*>(tab);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int K = g.K, M = g.M, J = g.Cout;
+  const int n0 = blockIdx.x * 4;
+  uint32_t acc[MPW][4], sp[MPW], sf[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int i = 0; i < MPW; ++i) {
+    sp[i] = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0;
+  }
+  const uint8_t* xr[MPW];
+  bool live[MPW];
+#pragma unroll
+  for (int i = 0; i < MPW; ++i) {
+    live[i] = wave + 16 * i < M;  // wave-uniform
+    xr[i] = x + (size_t)min(wave + 16 * i, M - 1) * K;
+  }
+#pragma unroll 4
+  for (int k = lane; k < K; k += 64) {
+    uint32_t wd;
+    const uint8_t* wp = w + (size_t)k * J + n0;
+    if (w_dwords) {
+      wd = *reinterpret_cast<const uint32_t*>(wp);
+    } else {
+      wd = (uint32_t)wp[0] | ((uint32_t)wp[1] << 8) | ((uint32_t)wp[2] << 16) | ((uint32_t)wp[3] << 24);
+    }
+    uint32_t wb2[4];  // 2 * filter code pattern = byte offset within a table row
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t b = (wd >> (8 * j)) & 0xffu;
+      wb2[j] = b << 1;
+      sf[j] += b ^ flip8;  // code + 128 for signed codes
+    }
+#pragma unroll
+    for (int i = 0; i < MPW; ++i) {
+      if (!live[i]) continue;
+      const uint32_t a = (uint32_t)xr[i][k] ^ flip8;
+      sp[i] += a;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] += *reinterpret_cast<const uint16_t*>(tabb + (a * (uint32_t)(kDwRow * 4) + wb2[j]));
+    }
+  }
+  // sums over the 64 lanes of the wave
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) sf[j] += (uint32_t)__shfl_xor((int)sf[j], s, 64);
+#pragma unroll
+    for (int i = 0; i < MPW; ++i) {
+      sp[i] += (uint32_t)__shfl_xor((int)sp[i], s, 64);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] += (uint32_t)__shfl_xor((int)acc[i][j], s, 64);
+    }
+  }
+  if (lane != 0) return;
+  const uint32_t bias = g.sgn ? 32768u * (uint32_t)K : 0u;
+  const int off128 = g.sgn ? 128 * K : 0;
+  const long long kzz = (long long)K * qp.x_zp * qp.w_zp;
+#pragma unroll
+  for (int i = 0; i < MPW; ++i) {
+    if (!live[i]) continue;
+    const size_t o = (size_t)(wave + 16 * i) * J + n0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int32_t av = (int32_t)(acc[i][j] - bias);
+      if (acc_out) acc_out[o + j] = av;
+      if (y_out) {
+        const long long corr = (long long)av - (long long)qp.w_zp * ((int32_t)sp[i] - off128) -
+                               (long long)qp.x_zp * ((int32_t)sf[j] - off128) + kzz;
+        y_out[o + j] = (float)corr * qp.scale;
+      }
+    }
+  }
+}
+
+bool fewrows_shape(const Geom& g) {
+  return g.mult == 0 && g.groups == 1 && g.KH == 1 && g.KW == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0 &&
+         g.M <= 64 && g.Cout % 4 == 0 && g.Cout >= 256 && g.K >= 64 && g.K <= 32768;
+}
+
+bool fewrows_supported(const Geom& g, const uint16_t* lut) { return fewrows_shape(g) && ((uintptr_t)lut & 15) == 0; }
+
+hipError_t launch_fewrows(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
+                          int32_t* acc_out, float* y_out, hipStream_t s) {
+  const int w_dwords = ((uintptr_t)w & 3) == 0 ? 1 : 0;  // Cout % 4 == 0: every group of four codes is then a dword
+  const dim3 grid((unsigned)(g.Cout / 4));
+  if (g.M <= 16)
+    hipLaunchKernelGGL((fewrows_kernel<1>), grid, dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, w_dwords);
+  else if (g.M <= 32)
+    hipLaunchKernelGGL((fewrows_kernel<2>), grid, dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, w_dwords);
+  else
+    hipLaunchKernelGGL((fewrows_kernel<4>), grid, dim3(1024), 0, s, g, qp, x, w, lut, acc_out, y_out, w_dwords);
+  return hipGetLastError();
+}
+
 bool dw_supported(const Geom& g, const uint8_t* x, const uint8_t* w, const uint16_t* lut) {
   (void)x;
   (void)w;

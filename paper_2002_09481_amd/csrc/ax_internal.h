@@ -88,6 +88,13 @@ bool dw_supported(const Geom& g, const uint8_t* x, const uint8_t* w, const uint1
 hipError_t launch_dw(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
                      int32_t* acc_out, float* y_out, hipStream_t s);
 
+// Dense layers of at most 64 rows with the whole table in LDS (ax_direct.hip): fewrows_shape says
+// whether the geometry is one, fewrows_supported whether the table pointer fits as well.
+bool fewrows_shape(const Geom& g);
+bool fewrows_supported(const Geom& g, const uint16_t* lut);
+hipError_t launch_fewrows(const Geom& g, const QParams& qp, const uint8_t* x, const uint8_t* w, const uint16_t* lut,
+                          int32_t* acc_out, float* y_out, hipStream_t s);
+
 // Table-tile kernels (ax_tab.hip).  Device memory of a layer comes in two blocks: the prepared
 // constants (re-laid-out table, packed filters and their sums, coefficients) and the per-call
 // scratch (materialized activations, pieces of shared tiles).  Offsets are relative to the block

@@ -213,3 +213,34 @@ def test_descriptor_errors():
     d = ax.ax_conv_desc_t(1, 4, 4, 2, 3, 3, 2, 1, 1, 1, 1, 1, 1, 2, 0)  # flag that is neither 0 nor 1
     assert L_.ax_conv2d_ex_workspace_bytes(d, None) == 0
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("signed", [False, True])
+@pytest.mark.parametrize("M", [1, 16, 17, 32, 33, 64])
+def test_dense_layers_of_few_rows(M, signed):
+    """Dense layers of at most 64 rows take the kernel with the whole table in LDS (four output
+    columns per workgroup, taps over the lanes): every rows-per-wave form, K that is and is not a
+    multiple of 64, filters that are and are not dword aligned; as a 1 x 1 convolution, through
+    the descriptor entry point and through a handle."""
+    rng = np.random.default_rng(500 + M)
+    lo, hi, dt = (-128, 128, np.int8) if signed else (0, 256, np.uint8)
+    lut = I.lut_signed_random(M) if signed else I.lut_random_error(M)
+    for K, Cout, off in ((2048, 1000, 0), (100, 256, 0), (640, 260, 1)):
+        x = rng.integers(lo, hi, (M, 1, 1, K)).astype(dt)
+        x[rng.random(x.shape) < 0.5] = dt(lo + 7)
+        w = rng.integers(lo, hi, (1, 1, K, Cout)).astype(dt)
+        q = I.Quant(0.017, int(rng.integers(lo, hi)), 0.0031, int(rng.integers(lo, hi)), None)
+        wbuf = torch.zeros(w.size + 8, dtype=torch.int8 if signed else torch.uint8, device="cuda")
+        wd = wbuf[off:off + w.size].view(w.shape)
+        wd.copy_(G.to_dev(w))
+        acc, y = ax.ax_conv2d_ex(G.to_dev(x), wd, ax.lut_to_device(lut), 1, 0, q)
+        torch.cuda.synchronize()
+        acc_ref, y_ref = oracle.conv2d_ex(x, w, lut, 1, 0, q, signed=signed)
+        G.assert_parity(acc.cpu().numpy(), y.cpu().numpy(), acc_ref, y_ref, "M %d K %d Cout %d" % (M, K, Cout))
+        desc = ax._conv_desc(x.shape, w.shape, 1, 0, 1, False, signed)
+        with ax.AxLayer(desc, q) as h:
+            assert h.plan()["variant"] == 1  # not a table-tile layer
+            h.prepare(wd, ax.lut_to_device(lut))
+            acc2, y2 = h.run(G.to_dev(x))
+            torch.cuda.synchronize()
+            assert torch.equal(acc2, acc) and torch.equal(y2, y)
