@@ -319,9 +319,11 @@ __global__ __launch_bounds__(1024) void dw3_kernel(Geom g, QParams qp_in, const 
 #pragma unroll
     for (int j = 0; j < 4; ++j) wb2[t][j] = ((wd >> (8 * j)) & 0xffu) << 1;
   }
-  int32_t sf[4];
+  int32_t xz_sf[4];  // x_zp * (sum of the channel's filter codes): constant per thread
 #pragma unroll
-  for (int j = 0; j < 4; ++j) sf[j] = sfs[4u * c4 + j] - off128;
+  for (int j = 0; j < 4; ++j) xz_sf[j] = (int32_t)qp.x_zp * (sfs[4u * c4 + j] - off128);
+  const int32_t kzz32 = (int32_t)kzz;
+  const uint32_t rowbytes = (uint32_t)(kDwRow * 4);
   const uint8_t* __restrict__ xc = x + 4u * c4;
   for (uint32_t it0 = gid; it0 < items; it0 += PX * stride) {
     uint32_t xd[PX][9];
@@ -350,24 +352,34 @@ __global__ __launch_bounds__(1024) void dw3_kernel(Geom g, QParams qp_in, const 
     for (int p = 0; p < PX; ++p) {
       const uint32_t it = it0 + p * stride;
       if (it >= items) break;
-      uint32_t acc[4] = {0, 0, 0, 0}, sp[4] = {0, 0, 0, 0};
+      // Per lookup: row offset = code * 516 taken straight from byte j of the packed codes (one
+      // sub-dword multiply), + column offset, gather, add.  The activation sum of a channel is the
+      // sum of its row offsets over 516: one more add per lookup instead of extracting the code.
+      uint32_t acc[4] = {0, 0, 0, 0}, rsum[4] = {0, 0, 0, 0};
 #pragma unroll
       for (int t = 0; t < 9; ++t) {
         const uint32_t xs = xd[p][t] ^ flip8;  // code + 128 for signed codes
+        uint32_t row[4];
+        asm("v_mul_u32_u24_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD" : "=v"(row[0]) : "v"(xs), "v"(rowbytes));
+        asm("v_mul_u32_u24_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD" : "=v"(row[1]) : "v"(xs), "v"(rowbytes));
+        asm("v_mul_u32_u24_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD" : "=v"(row[2]) : "v"(xs), "v"(rowbytes));
+        asm("v_mul_u32_u24_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD" : "=v"(row[3]) : "v"(xs), "v"(rowbytes));
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const uint32_t a = (xs >> (8 * j)) & 0xffu;
-          acc[j] += *reinterpret_cast<const uint16_t*>(tabb + (a * (uint32_t)(kDwRow * 4) + wb2[t][j]));
-          sp[j] += a;
+          acc[j] += *reinterpret_cast<const uint16_t*>(tabb + (row[j] + wb2[t][j]));
+          rsum[j] += row[j];
         }
       }
+      uint32_t sp[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) sp[j] = rsum[j] / (uint32_t)(kDwRow * 4);
       int32_t av[4];
       float yv[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         av[j] = (int32_t)(acc[j] - bias);
-        const long long corr = (long long)av[j] - (long long)qp.w_zp * ((int32_t)sp[j] - off128) -
-                               (long long)qp.x_zp * sf[j] + kzz;
+        // nine taps: every term is below 2^20, 32-bit arithmetic is exact
+        const int32_t corr = av[j] - (int32_t)qp.w_zp * ((int32_t)sp[j] - off128) - xz_sf[j] + kzz32;
         yv[j] = (float)corr * qp.scale;
       }
       const size_t o = (size_t)it * 4u;  // = pixel * Cout + 4 * c4
