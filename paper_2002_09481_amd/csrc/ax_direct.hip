@@ -248,9 +248,14 @@ __global__ __launch_bounds__(1024) void dw_kernel(Geom g, QParams qp_in, const u
     for (int j = 0; j < 4; ++j) {
       const int32_t sf = sfs[min(4u * c4 + (uint32_t)j, (uint32_t)g.Cout - 1u)];
       av[j] = (int32_t)(acc[j] - bias);
-      const long long corr = (long long)av[j] - (long long)qp.w_zp * ((int32_t)sp[j] - off128) -
-                             (long long)qp.x_zp * (sf - off128) + kzz;
-      yv[j] = (float)corr * qp.scale;
+      if (g.K <= 4096) {  // every term below 2^29: 32-bit arithmetic is exact
+        const int32_t corr = av[j] - (int32_t)qp.w_zp * ((int32_t)sp[j] - off128) - (int32_t)qp.x_zp * (sf - off128) + (int32_t)kzz;
+        yv[j] = (float)corr * qp.scale;
+      } else {
+        const long long corr = (long long)av[j] - (long long)qp.w_zp * ((int32_t)sp[j] - off128) -
+                               (long long)qp.x_zp * (sf - off128) + kzz;
+        yv[j] = (float)corr * qp.scale;
+      }
     }
     const size_t o = (size_t)pix * g.Cout + 4u * c4;
     if (vec_out) {  // Cout % 4 == 0 and 16-byte aligned outputs
