@@ -1201,9 +1201,11 @@ struct PlanChoice { int tile, variant, G, partials, nti, ih; double cost; int mo
 // through tab_fixup_kernel, which spreads the sums of one tile over many blocks.
 constexpr int kCombineMost = 4;
 constexpr int kCombineLong = 24;
-// Ready-made tables that a layer gets without being asked to: any set that fits an L2, larger
-// sets (up to kPreTablesMax bytes) for layers with at least kPreRowTiles tiles along the lanes.
-constexpr size_t kPreTablesSmall = (size_t)3 << 20;
+// Ready-made tables that a layer gets without being asked to: any set of up to kPreTablesSmall
+// bytes (it stays in the L2s and the memory-side cache whichever workgroup reads which part:
+// the CIFAR-shaped layers with K slices gain 25 %), larger sets (up to kPreTablesMax bytes) for
+// layers with at least kPreRowTiles tiles along the lanes and no K slices.
+constexpr size_t kPreTablesSmall = (size_t)20 << 20;
 constexpr size_t kPreTablesMax = (size_t)32 << 20;
 constexpr int kPreRowTiles = 8;
 
@@ -1397,7 +1399,7 @@ static TabPlan tab_plan_uncached(const Geom& g, const Options& o) {
   // the table side, one multiplier table is used and the tile has a kernel for them.  Every
   // workgroup reads the tables of its taps and columns from global memory, so they pay where
   // many tiles along the lane dimension read the same tables at about the same time (the reads
-  // then meet in the L2s) or where all of them fit into an L2; measured on the ResNet-50 layers
+  // then meet in the L2s) or where all of them stay in the caches; measured on the ResNet-50 layers
   // at batch 32: 2-9 % faster with 13 or more row tiles and whole tiles per workgroup, 5-40 %
   // slower with four row tiles or K slices.
   const size_t tabs_bytes = (Kp + 1) * (Jpad / 8) * 4096;
