@@ -87,6 +87,28 @@ def test_prepare_again_with_other_filters_and_table_and_another_block():
         assert torch.equal(snap, p1)
 
 
+def test_prepare_into_a_dirty_block_with_counters_and_ready_made_tables():
+    """ax_layer_prepare owns everything in the prepared block: a block full of ones (arrival
+    counters of shared tiles, ready-made tables) prepared twice with different filters gives the
+    oracle's results both times, on two runs each."""
+    layer = L(2, 28, 28, 32, 3, 3, 48, 1, 1)
+    x, w1, q = I.make_operands(layer, 7311)
+    w2 = I.make_operands(layer, 7312)[1]
+    lut1, lut2 = I.lut_random_error(3), I.lut_truncated(4)
+    desc = ax._conv_desc(x.shape, w1.shape, 1, 1)
+    xd = G.to_dev(x)
+    with ax.AxLayer(desc, q, tune=_tune(variant=2, split_k=3, combine=2, tables=2)) as h:
+        plan = h.plan()
+        assert plan["combine"] == 2 and plan["tables"] == 2 and plan["pieces"] > 0
+        block = torch.full((h.prepared_bytes,), 255, dtype=torch.uint8, device="cuda")
+        for w, lut in ((w1, lut1), (w2, lut2)):
+            h.prepare(G.to_dev(w), ax.lut_to_device(lut), prepared=block)
+            for call in range(2):
+                acc, y = h.run(xd)
+                torch.cuda.synchronize()
+                G.assert_parity(acc.cpu().numpy(), y.cpu().numpy(), *oracle.conv2d(x, w, lut, 1, 1, q), "call %d" % call)
+
+
 def test_handle_with_operator_variants_and_several_tables():
     rng = np.random.default_rng(77)
     # signed codes, dilation 2, implicit patch view (the activations are flipped per call)
